@@ -1,0 +1,148 @@
+/*
+ * hybridkv -- C ABI of the per-layer hybrid-cache decode step on AMD MI355X (gfx950).
+ *
+ * The step is the "KV Gen -> concat -> MHA" slice of the execution engine of
+ * arXiv 2501.01792 (Sec. 4.2.2): keys and values of the context tokens that
+ * are held as activation checkpoints are regenerated from those checkpoints
+ * (Sec. 3.3, Eq. 7), joined with the keys and values that are held directly
+ * in the KV cache (Eq. 3), and the decode query of each sequence attends over
+ * the union (Eq. 4).
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller and must be
+ *     16-byte aligned.  hk_shape / hk_layer_params themselves are HOST structs
+ *     passed by pointer and read before the call returns.
+ *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16); accumulation is fp32.
+ *   - The library allocates nothing.  Scratch memory is the caller's
+ *     `workspace` (device, 256-byte aligned, at least hk_workspace_bytes()).
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising.  Calls that share a
+ *     workspace must be ordered by the caller (same stream, or events).
+ *   - Return value: HK_OK (0) or a negative hk_status.  All argument checks run
+ *     on the host before anything is launched, so a rejected call has touched
+ *     no device memory.
+ *
+ * Tensor layouts (row-major, last index fastest)
+ *   act      [B, L_act, d]     activation checkpoints A_c: the layer's input
+ *                              hidden states of the tokens not held as KV
+ *   ln_w, ln_b [d]             LayerNorm weight and bias of the layer's
+ *                              pre-attention LayerNorm
+ *   Wkv      [2d, d]           fused projection, "output feature x input":
+ *                              rows 0..d-1 are the columns of W_K, rows d..2d-1
+ *                              the columns of W_V in Eq. 7
+ *   bkv      [2d]              K bias, then V bias
+ *   K, V     [B, H, L, dh]     head-major: one (sequence, head) is one
+ *                              contiguous L*dh run; feature n of a token is
+ *                              head n / dh, element n % dh
+ *   q, out   [B, H, dh]        (= [B, d])
+ */
+#ifndef HYBRIDKV_H
+#define HYBRIDKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hk_status {
+    HK_OK = 0,
+    HK_ERR_NULL = -1,      /* a required pointer is NULL */
+    HK_ERR_SHAPE = -2,     /* d != n_heads*head_dim, head_dim not in {64,128}, negative or overflowing sizes */
+    HK_ERR_RATIO = -3,     /* ratio outside [0,1] or inconsistent with L_kv, L_act */
+    HK_ERR_ALIGN = -4,     /* a data pointer is not 16-byte aligned (workspace: 256) */
+    HK_ERR_WORKSPACE = -5, /* workspace_bytes smaller than hk_workspace_bytes() */
+    HK_ERR_DTYPE = -6,     /* dtype other than HK_DTYPE_F16 */
+    HK_ERR_LAUNCH = -7     /* the HIP runtime reported an error at launch */
+} hk_status;
+
+enum { HK_DTYPE_F16 = 0 };
+
+/* Shape and numerics of one decoder layer.  Host struct. */
+typedef struct hk_shape {
+    int32_t d;             /* hidden size */
+    int32_t n_heads;       /* H */
+    int32_t head_dim;      /* dh, 64 or 128; d == n_heads * head_dim */
+    int32_t dtype;         /* HK_DTYPE_F16 */
+    float ln_eps;          /* LayerNorm epsilon (inside the square root); OPT uses 1e-5 */
+    float softmax_scale;   /* multiplies q.k before the softmax; <= 0 selects head_dim^-1/2 */
+    int32_t attn_splits;   /* token-axis splits per (sequence, head) in the attention kernel;
+                              0 lets the library choose, otherwise 1..HK_MAX_SPLITS */
+    int32_t reserved;      /* must be 0 */
+} hk_shape;
+
+enum { HK_MAX_SPLITS = 64 };
+
+/* Device pointers to the parameters the step needs from one decoder layer. */
+typedef struct hk_layer_params {
+    const void *ln_w;      /* [d]     */
+    const void *ln_b;      /* [d]     */
+    const void *Wkv;       /* [2d, d] */
+    const void *bkv;       /* [2d]    */
+} hk_layer_params;
+
+/*
+ * Bytes of device workspace that hk_regen_kv / hk_hybrid_decode_attn need for
+ * a batch of B sequences with L_kv cached and L_act checkpointed tokens each
+ * (per-row LayerNorm statistics, the regenerated K/V of the hybrid call, and
+ * the attention partials).  Returns 0 when the shape is invalid.
+ */
+size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);
+
+/*
+ * "KV Gen" (Sec. 4.2.2; Sec. 3.3, Eq. 7): regenerate keys and values from
+ * activation checkpoints,
+ *     [K V] = LayerNorm(act; ln_w, ln_b, ln_eps) x [W_K W_V] + [b_K b_V],
+ * skipping everything the layer does after QKV generation.  The LayerNorm is
+ * the layer's own pre-attention one: a checkpoint is the layer's input tensor.
+ *
+ *   act          [B, L_act, d] fp16, read only
+ *   K_out, V_out [B, H, L_cap, dh] fp16; token t of sequence b is written to
+ *                row tok_off + t of every head of b, other rows are untouched
+ *                (0 <= tok_off, tok_off + L_act <= L_cap)
+ *   workspace    needs hk_workspace_bytes(shape, B, 0, L_act)
+ * B == 0 or L_act == 0 is a successful no-op.
+ */
+int hk_regen_kv(const hk_shape *shape,
+                const void *act, int32_t B, int32_t L_act,
+                const hk_layer_params *params,
+                void *K_out, void *V_out, int32_t L_cap, int32_t tok_off,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The whole step (Sec. 4.2.2; Eq. 7, 3, 4): regenerate K/V from `act`,
+ * treat them as the continuation of the cached K/V along the token axis
+ * (no copy is made), and compute for the one decode query of every
+ * (sequence, head)
+ *     out = softmax(softmax_scale * q K^T) V
+ * over all L = L_kv + L_act context tokens.  No mask: the query attends to
+ * every context token.  Softmax attention does not depend on token order, so
+ * which tokens sit in which store does not matter.
+ *
+ *   q            [B, H, dh] fp16, unscaled
+ *   K_cache, V_cache [B, H, L_kv, dh] fp16; may be NULL when L_kv == 0
+ *   act          [B, L_act, d] fp16; may be NULL when L_act == 0
+ *   ratio        fraction of the context held as KV; checked against the
+ *                lengths: L_kv must equal round(ratio * (L_kv + L_act))
+ *   out          [B, H, dh] fp16
+ *   workspace    needs hk_workspace_bytes(shape, B, L_kv, L_act); on return
+ *                (after the stream has run) its head holds the regenerated
+ *                K [B,H,L_act,dh] then V [B,H,L_act,dh]
+ * L_kv + L_act == 0 is rejected with HK_ERR_SHAPE (softmax over nothing).
+ */
+int hk_hybrid_decode_attn(const hk_shape *shape,
+                          const void *q,
+                          const void *K_cache, const void *V_cache, int32_t L_kv,
+                          const void *act, int32_t L_act, int32_t B,
+                          const hk_layer_params *params, float ratio,
+                          void *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *hk_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYBRIDKV_H */
