@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer hybrid-cache decode step on one MI355X.
+
+A step is one pass of the whole hot path (LayerNorm statistics -> K/V regeneration GEMM ->
+single-query attention over cached ++ regenerated K/V -> merge) over one synthetic batch of the
+OPT-6.7B-shaped workload (d=4096, 32 heads x 128, B=32, context 1024 at ratio 0.5), through the
+C ABI.  Inputs are resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config opt6.7b] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks used for the roofline fractions
+PEAK_MFMA_F16_TFLOPS = 2500.0     # dense fp16 matrix, 256 CUs
+PEAK_HBM_GBPS = 8000.0
+
+
+def algorithmic_counts(cfg):
+    """Algorithmic work of one step: regeneration GEMM flops (2*M*d*2d) and the bytes the
+    attention must stream (K and V of every context token once: B*L*4d in fp16)."""
+    gemm_flops = 4.0 * cfg.M * cfg.d * cfg.d
+    attn_bytes = float(cfg.B) * cfg.L * 4 * cfg.d
+    return gemm_flops, attn_bytes
+
+
+def cpu_baseline(cfg, budget_s=15.0):
+    """The CPU oracle (fp32 build, as it stands) timed on a bounded sample of the same workload:
+    whole sequences of the batch, as many as fit the time budget."""
+    from oracle import hybridkv_oracle as oracle
+    from paper_2501_01792_amd import synth
+    oracle.build()
+
+    def run(n):
+        b = synth.make_batch(cfg, sequences=range(n))
+        t0 = time.perf_counter()
+        out, _, _ = oracle.hybrid_decode_attn(b["q"], b["K_cache"] if cfg.L_kv else None,
+                                              b["V_cache"] if cfg.L_kv else None,
+                                              b["act"] if cfg.L_act else None,
+                                              b["ln_w"], b["ln_b"], b["Wkv"], b["bkv"], cfg.n_heads,
+                                              precision="f32")
+        return time.perf_counter() - t0, out
+
+    t1, out = run(1)
+    n = int(max(1, min(cfg.B, budget_s // max(t1, 1e-3))))
+    if n > 1:
+        t, out = run(n)
+    else:
+        t = t1
+    unit_tokens = max(cfg.L_act, 1)
+    return {
+        "value": n * unit_tokens / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "fp32 oracle, whole step on %d of %d sequences of the same workload (%d checkpoint + %d cached "
+                  "tokens each), %.1f s" % (n, cfg.B, cfg.L_act, cfg.L_kv, t),
+    }, n, out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="opt6.7b")
+    ap.add_argument("--ratio", type=float, default=None, help="override the KV fraction of the context")
+    ap.add_argument("--gemm-tile", type=int, default=0)
+    ap.add_argument("--attn-splits", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the step has no cross-GPU part); "
+              "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2501_01792_amd import binding as hk, synth
+    from paper_2501_01792_amd.hipevents import EventSet
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    hk.lib()
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    if args.ratio is not None:
+        cfg = cfg.with_ratio(args.ratio)
+
+    batch = synth.make_batch(cfg, threads=16)
+    g = {k: torch.from_numpy(v).cuda() for k, v in batch.items()}
+    lp = (g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"])
+    Kc = g["K_cache"] if cfg.L_kv else None
+    Vc = g["V_cache"] if cfg.L_kv else None
+    act = g["act"] if cfg.L_act else None
+    shape = hk.make_shape(cfg.d, cfg.n_heads, attn_splits=args.attn_splits, gemm_tile=args.gemm_tile)
+    ws = hk.new_workspace(hk.hk_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
+    out = torch.empty((cfg.B, cfg.n_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        hk.hybrid_decode_attn(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream,
+                              attn_splits=args.attn_splits, gemm_tile=args.gemm_tile, events=events)
+
+    for _ in range(args.warmup):
+        step()
+    events = [EventSet(5) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # per-kernel durations from the events recorded on the launch stream inside the timed region
+    names = ["ln_stats", "kv_gemm", "flash_decode", "merge_partials"]
+    dur = {n: float(np.mean([e.elapsed_ms(i, i + 1) for e in events])) for i, n in enumerate(names)}
+    for e in events:
+        e.destroy()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    gemm_flops, attn_bytes = algorithmic_counts(cfg)
+    roofline = None
+    if cfg.M > 0 and dur["kv_gemm"] > 0:
+        ach = gemm_flops / (dur["kv_gemm"] * 1e-3) / 1e12
+        roofline = {"kernel": "kv_gemm", "bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_F16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F16_TFLOPS, "traffic": None,
+                    "avg_ms": dur["kv_gemm"]}
+    ach_bw = attn_bytes / (dur["flash_decode"] * 1e-3) / 1e9
+    roofline_attn = {"kernel": "flash_decode", "bound": "hbm", "achieved": ach_bw, "peak": PEAK_HBM_GBPS,
+                     "unit": "GB/s", "frac": ach_bw / PEAK_HBM_GBPS, "traffic": None,
+                     "avg_ms": dur["flash_decode"]}
+    if roofline is None:
+        roofline = roofline_attn
+
+    result = {
+        "metric": "regenerated_kv_tokens_per_s",
+        "value": cfg.M / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "%s: d=%d H=%d dh=%d B=%d L=%d ratio=%g (L_kv=%d, L_act=%d), hybrid-cache decode step "
+                               "of one layer" % (cfg.name, cfg.d, cfg.n_heads, cfg.head_dim, cfg.B, cfg.L, cfg.ratio,
+                                                 cfg.L_kv, cfg.L_act),
+                   "regen_gemm": "M=%d K=%d N=%d" % (cfg.M, cfg.d, 2 * cfg.d)},
+        "decode_layer_latency_ms": ms_per_step,
+        "decode_tokens_per_s": cfg.B / (ms_per_step * 1e-3),
+        "regen_only_tokens_per_s": (cfg.M / ((dur["ln_stats"] + dur["kv_gemm"]) * 1e-3)) if cfg.M else None,
+        "kernel_ms": dur,
+        "roofline": roofline,
+        "roofline_attn": roofline_attn,
+    }
+
+    if not args.no_cpu_baseline:
+        base, n, ref = cpu_baseline(cfg)
+        result["cpu_baseline"] = base
+        got = out[:n].float().cpu().numpy()
+        result["parity_vs_cpu_sample"] = {"max_abs": float(np.abs(got - ref).max()),
+                                          "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -69,7 +69,8 @@ typedef struct hk_shape {
     float softmax_scale;   /* multiplies q.k before the softmax; <= 0 selects head_dim^-1/2 */
     int32_t attn_splits;   /* token-axis splits per (sequence, head) in the attention kernel;
                               0 lets the library choose, otherwise 1..HK_MAX_SPLITS */
-    int32_t reserved;      /* must be 0 */
+    int32_t gemm_tile;     /* output tile edge of the projection kernel: 0 lets the library
+                              choose, otherwise 128 or 256 */
 } hk_shape;
 
 enum { HK_MAX_SPLITS = 64 };
@@ -83,12 +84,18 @@ typedef struct hk_layer_params {
 } hk_layer_params;
 
 /*
- * Bytes of device workspace that hk_regen_kv / hk_hybrid_decode_attn need for
- * a batch of B sequences with L_kv cached and L_act checkpointed tokens each
- * (per-row LayerNorm statistics, the regenerated K/V of the hybrid call, and
- * the attention partials).  Returns 0 when the shape is invalid.
+ * Bytes of device workspace that hk_hybrid_decode_attn needs for a batch of B
+ * sequences with L_kv cached and L_act checkpointed tokens each (the
+ * regenerated K/V, per-row LayerNorm statistics, and the attention partials
+ * for shape->attn_splits).  Returns 0 when the shape is invalid.
  */
 size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);
+
+/*
+ * Bytes of device workspace that hk_regen_kv needs (per-row LayerNorm
+ * statistics only).  Returns 0 when the shape is invalid.
+ */
+size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act);
 
 /*
  * "KV Gen" (Sec. 4.2.2; Sec. 3.3, Eq. 7): regenerate keys and values from
@@ -101,7 +108,7 @@ size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_
  *   K_out, V_out [B, H, L_cap, dh] fp16; token t of sequence b is written to
  *                row tok_off + t of every head of b, other rows are untouched
  *                (0 <= tok_off, tok_off + L_act <= L_cap)
- *   workspace    needs hk_workspace_bytes(shape, B, 0, L_act)
+ *   workspace    needs hk_regen_workspace_bytes(shape, B, L_act)
  * B == 0 or L_act == 0 is a successful no-op.
  */
 int hk_regen_kv(const hk_shape *shape,
@@ -138,6 +145,26 @@ int hk_hybrid_decode_attn(const hk_shape *shape,
                           const hk_layer_params *params, float ratio,
                           void *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hk_hybrid_decode_attn with per-kernel time stamps, for measurement: the same
+ * step (Sec. 4.2.2; Eq. 7, 3, 4) and the same arguments, plus `events`, a HOST
+ * array of n_events hipEvent_t handles (passed as void*; NULL entries are
+ * skipped) owned by the caller.  The library records, on `stream`,
+ *   events[0] before the first kernel,      events[1] after the LayerNorm statistics,
+ *   events[2] after the K/V projection,     events[3] after the attention streaming kernel,
+ *   events[4] after the merge of the attention partials (end of the step).
+ * Stages that do not run (L_act == 0, a single attention chunk) leave their
+ * event recorded back to back with the previous one.
+ */
+int hk_hybrid_decode_attn_marked(const hk_shape *shape,
+                                 const void *q,
+                                 const void *K_cache, const void *V_cache, int32_t L_kv,
+                                 const void *act, int32_t L_act, int32_t B,
+                                 const hk_layer_params *params, float ratio,
+                                 void *out,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 void **events, int32_t n_events);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *hk_status_string(int status);

@@ -79,15 +79,17 @@ def layernorm(x, gamma, beta, eps=1e-5, precision="f64"):
 
 
 def kv_projection(xhat, Wkv, bkv, precision="f64"):
-    """Eq. 7 plus biases: ``xhat[M, d]``, ``Wkv[2d, d]``, ``bkv[2d]`` -> ``KV[M, 2d]``."""
+    """Eq. 7 plus biases: ``xhat[M, d]``, ``Wkv[N, d]``, ``bkv[N]`` -> ``KV[M, N]``
+    (N = 2d for the full fused weight; any subset of its rows gives those features only)."""
     np_t, _ = _PREC[precision]
     xhat = _arr(xhat, np_t)
     M, d = xhat.shape
     Wkv, bkv = _arr(Wkv, np_t), _arr(bkv, np_t)
-    assert Wkv.shape == (2 * d, d) and bkv.shape == (2 * d,)
-    out = np.empty((M, 2 * d), dtype=np_t)
+    N = Wkv.shape[0]
+    assert Wkv.shape == (N, d) and bkv.shape == (N,)
+    out = np.empty((M, N), dtype=np_t)
     fn = getattr(_load(), "hko_kv_projection_" + precision)
-    fn(_ptr(xhat), _ptr(Wkv), _ptr(bkv), _i64(M), _i64(d), _ptr(out))
+    fn(_ptr(xhat), _ptr(Wkv), _ptr(bkv), _i64(M), _i64(d), _i64(N), _ptr(out))
     return out
 
 

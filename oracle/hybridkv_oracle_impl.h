@@ -70,12 +70,13 @@ void HKO(hko_layernorm)(const REAL *x, const REAL *gamma, const REAL *beta,
     }
 }
 
-/* Eq. 7 with biases: KV[r, n] = sum_j xhat[r, j] * Wkv[n, j] + bkv[n], n in [0, 2d).
- * Columns 0..d-1 of a row are that token's key, d..2d-1 its value. */
+/* Eq. 7 with biases: KV[r, n] = sum_j xhat[r, j] * Wkv[n, j] + bkv[n], n in [0, N).
+ * With the full weight (N = 2d) columns 0..d-1 of a row are that token's key and
+ * d..2d-1 its value; a caller may pass any subset of the weight rows (and the
+ * matching biases) to get only those output features. */
 void HKO(hko_kv_projection)(const REAL *xhat, const REAL *Wkv, const REAL *bkv,
-                            int64_t M, int64_t d, REAL *KV)
+                            int64_t M, int64_t d, int64_t N, REAL *KV)
 {
-    const int64_t N = 2 * d;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < M; ++r) {
         const REAL *xr = xhat + r * d;
@@ -101,7 +102,7 @@ void HKO(hko_regen_kv)(const REAL *act, const REAL *gamma, const REAL *beta,
     const int64_t M = B * L_act;
     const int64_t dh = d / n_heads;
     HKO(hko_layernorm)(act, gamma, beta, M, d, eps, scratch_xhat);
-    HKO(hko_kv_projection)(scratch_xhat, Wkv, bkv, M, d, scratch_kv);
+    HKO(hko_kv_projection)(scratch_xhat, Wkv, bkv, M, d, 2 * d, scratch_kv);
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < M; ++r) {
         const int64_t b = r / L_act, t = r % L_act;

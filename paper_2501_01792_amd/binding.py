@@ -1,0 +1,180 @@
+"""ctypes binding of libhybridkv.so: same names as the C ABI, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the library's
+HIP kernels.  There is no fallback: if the library cannot be loaded the import of a symbol
+raises, and a call with a non-GPU tensor raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhybridkv.so")
+
+HK_OK = 0
+HK_ERR_NULL, HK_ERR_SHAPE, HK_ERR_RATIO, HK_ERR_ALIGN = -1, -2, -3, -4
+HK_ERR_WORKSPACE, HK_ERR_DTYPE, HK_ERR_LAUNCH = -5, -6, -7
+HK_DTYPE_F16 = 0
+HK_MAX_SPLITS = 64
+
+
+class hk_shape(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("ln_eps", ctypes.c_float), ("softmax_scale", ctypes.c_float),
+                ("attn_splits", ctypes.c_int32), ("gemm_tile", ctypes.c_int32)]
+
+
+class hk_layer_params(ctypes.Structure):
+    _fields_ = [("ln_w", ctypes.c_void_p), ("ln_b", ctypes.c_void_p),
+                ("Wkv", ctypes.c_void_p), ("bkv", ctypes.c_void_p)]
+
+
+class HybridKVError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built (no silent fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: run `python -m paper_2501_01792_amd.build` "
+                               "(or __graft_entry__.build()) first" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        shp, lpp = ctypes.POINTER(hk_shape), ctypes.POINTER(hk_layer_params)
+        L.hk_workspace_bytes.restype = sz
+        L.hk_workspace_bytes.argtypes = [shp, i32, i32, i32]
+        L.hk_regen_workspace_bytes.restype = sz
+        L.hk_regen_workspace_bytes.argtypes = [shp, i32, i32]
+        L.hk_regen_kv.restype = ctypes.c_int
+        L.hk_regen_kv.argtypes = [shp, vp, i32, i32, lpp, vp, vp, i32, i32, vp, sz, vp]
+        L.hk_hybrid_decode_attn.restype = ctypes.c_int
+        L.hk_hybrid_decode_attn.argtypes = [shp, vp, vp, vp, i32, vp, i32, i32, lpp, ctypes.c_float,
+                                            vp, vp, sz, vp]
+        L.hk_hybrid_decode_attn_marked.restype = ctypes.c_int
+        L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
+        L.hk_status_string.restype = ctypes.c_char_p
+        L.hk_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().hk_status_string(int(status)).decode()
+
+
+def make_shape(d, n_heads, ln_eps=1e-5, softmax_scale=0.0, attn_splits=0, gemm_tile=0) -> hk_shape:
+    return hk_shape(d, n_heads, d // n_heads, HK_DTYPE_F16, ln_eps, softmax_scale, attn_splits, gemm_tile)
+
+
+def hk_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int) -> int:
+    return int(lib().hk_workspace_bytes(ctypes.byref(shape), B, L_kv, L_act))
+
+
+def hk_regen_workspace_bytes(shape: hk_shape, B: int, L_act: int) -> int:
+    return int(lib().hk_regen_workspace_bytes(ctypes.byref(shape), B, L_act))
+
+
+# ----------------------------------------------------------------------------- torch-facing calls
+def _dev_ptr(t, name, dtype=None):
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a GPU tensor (there is no CPU path)" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s" % (name, dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _params(ln_w, ln_b, Wkv, bkv):
+    import torch
+    f16 = torch.float16
+    return hk_layer_params(_dev_ptr(ln_w, "ln_w", f16).value, _dev_ptr(ln_b, "ln_b", f16).value,
+                           _dev_ptr(Wkv, "Wkv", f16).value, _dev_ptr(bkv, "bkv", f16).value)
+
+
+def new_workspace(nbytes: int, device="cuda"):
+    """A device buffer for the ``workspace`` argument (torch's allocator aligns to >= 256 B)."""
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def regen_kv(act, ln_w, ln_b, Wkv, bkv, n_heads, K_out=None, V_out=None, tok_off=0,
+             ln_eps=1e-5, gemm_tile=0, workspace=None, stream=None):
+    """hk_regen_kv: ``act[B, L_act, d]`` fp16 -> ``(K, V)``, each ``[B, H, L_cap, dh]`` fp16, rows
+    ``tok_off .. tok_off+L_act`` written.  Allocates the outputs (L_cap = L_act) and the
+    workspace when they are not given."""
+    import torch
+    B, L_act, d = act.shape
+    shape = make_shape(d, n_heads, ln_eps, gemm_tile=gemm_tile)
+    dh = d // n_heads
+    if K_out is None:
+        K_out = torch.empty((B, n_heads, L_act, dh), dtype=torch.float16, device=act.device)
+        V_out = torch.empty_like(K_out)
+    L_cap = K_out.shape[2]
+    if workspace is None:
+        workspace = new_workspace(hk_regen_workspace_bytes(shape, B, L_act), act.device)
+    lp = _params(ln_w, ln_b, Wkv, bkv)
+    st = lib().hk_regen_kv(ctypes.byref(shape), _dev_ptr(act, "act", torch.float16), B, L_act,
+                           ctypes.byref(lp), _dev_ptr(K_out, "K_out", torch.float16),
+                           _dev_ptr(V_out, "V_out", torch.float16), L_cap, tok_off,
+                           _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_regen_kv")
+    return K_out, V_out
+
+
+def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, ln_eps=1e-5,
+                       softmax_scale=0.0, attn_splits=0, gemm_tile=0, workspace=None, stream=None,
+                       return_regen=False, events=None):
+    """hk_hybrid_decode_attn: ``q[B,H,dh]``, ``K_cache,V_cache[B,H,L_kv,dh]`` (or None), ``act[B,L_act,d]``
+    (or None), ``layer_params = (ln_w, ln_b, Wkv, bkv)`` -> ``out[B,H,dh]`` (all fp16 GPU tensors).
+    With ``return_regen`` also returns views of the regenerated K, V ``[B,H,L_act,dh]`` that
+    the call left at the head of the workspace.  ``events`` (a ``hipevents.EventSet`` of 5)
+    selects hk_hybrid_decode_attn_marked, which time-stamps the kernels of the step."""
+    import torch
+    B, H, dh = q.shape
+    d = H * dh
+    L_kv = 0 if K_cache is None else K_cache.shape[2]
+    L_act = 0 if act is None else act.shape[1]
+    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, gemm_tile)
+    if out is None:
+        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+    if workspace is None:
+        workspace = new_workspace(hk_workspace_bytes(shape, B, L_kv, L_act), q.device)
+    lp = _params(*layer_params)
+    f16 = torch.float16
+    args = [ctypes.byref(shape), _dev_ptr(q, "q", f16),
+            _dev_ptr(K_cache, "K_cache", f16), _dev_ptr(V_cache, "V_cache", f16), L_kv,
+            _dev_ptr(act, "act", f16), L_act, B, ctypes.byref(lp), float(ratio),
+            _dev_ptr(out, "out", f16), _dev_ptr(workspace, "workspace"),
+            workspace.numel(), _stream_ptr(stream)]
+    if events is None:
+        st = lib().hk_hybrid_decode_attn(*args)
+    else:
+        st = lib().hk_hybrid_decode_attn_marked(*args, events.array, events.n)
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_hybrid_decode_attn")
+    if return_regen:
+        n = B * H * L_act * dh
+        v_off = (2 * n + 255) // 256 * 256
+        K = workspace[:2 * n].view(f16).view(B, H, L_act, dh)
+        V = workspace[v_off:v_off + 2 * n].view(f16).view(B, H, L_act, dh)
+        return out, K, V
+    return out

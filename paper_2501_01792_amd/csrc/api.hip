@@ -1,0 +1,241 @@
+// C-ABI layer of libhybridkv: argument validation (host only, before any launch), workspace
+// layout, and the sequencing of the kernels of the hybrid-cache decode step
+// (KV Gen -> concat -> MHA; Sec. 4.2.2, Eq. 7, 3, 4).
+#include "../../include/hybridkv.h"
+#include "hk_internal.h"
+
+#include <cmath>
+#include <cstdint>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+struct Plan {
+    // sizes
+    int64_t M;            // B * L_act
+    int64_t BH;           // B * n_heads
+    int chunk;            // attention tokens per chunk
+    int total_chunks;
+    float scale;
+    // workspace offsets (bytes)
+    size_t off_k, off_v, off_stats, off_partial, total;
+};
+
+int check_shape(const hk_shape *s)
+{
+    if (!s) return HK_ERR_NULL;
+    if (s->dtype != HK_DTYPE_F16) return HK_ERR_DTYPE;
+    if (s->d <= 0 || s->n_heads <= 0) return HK_ERR_SHAPE;
+    if (s->gemm_tile != 0 && s->gemm_tile != 128 && s->gemm_tile != 256) return HK_ERR_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128) return HK_ERR_SHAPE;
+    if ((int64_t)s->n_heads * s->head_dim != s->d) return HK_ERR_SHAPE;
+    if (s->d > (1 << 20)) return HK_ERR_SHAPE;
+    if (s->attn_splits < 0 || s->attn_splits > HK_MAX_SPLITS) return HK_ERR_SHAPE;
+    if (!(s->ln_eps >= 0.f) || !std::isfinite(s->ln_eps) || !std::isfinite(s->softmax_scale)) return HK_ERR_SHAPE;
+    return HK_OK;
+}
+
+// Tokens per attention chunk.  One workgroup streams one chunk; a chunk is a multiple of the
+// 256 tokens that the 4 wavefronts of a workgroup consume per step.  Without a request the
+// chunk is chosen so that the launch has at least ~8 workgroups per compute unit.
+int choose_chunk(const hk_shape *s, int64_t BH, int64_t L)
+{
+    int64_t splits = s->attn_splits;
+    if (splits <= 0) {
+        const int64_t want = 8 * 256;
+        splits = (want + BH - 1) / BH;
+        if (splits < 1) splits = 1;
+        if (splits > HK_MAX_SPLITS) splits = HK_MAX_SPLITS;
+    }
+    int64_t chunk = (L + splits - 1) / splits;
+    chunk = (chunk + 255) / 256 * 256;
+    if (chunk < 256) chunk = 256;
+    return (int)chunk;
+}
+
+// Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
+int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p)
+{
+    int st = check_shape(s);
+    if (st != HK_OK) return st;
+    if (B < 0 || L_kv < 0 || L_act < 0) return HK_ERR_SHAPE;
+    if (B > (1 << 24) || L_kv > (1 << 28) || L_act > (1 << 28)) return HK_ERR_SHAPE;
+    p->M = B * L_act;
+    p->BH = B * s->n_heads;
+    // element counts must stay addressable and grids launchable
+    const long double elems = (long double)B * (long double)(L_kv + L_act) * (long double)s->d;
+    if (elems > 4.0e12L || p->M > 0x7fffffffLL || p->BH > 0x7fffffffLL) return HK_ERR_SHAPE;
+    p->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)s->head_dim);
+    const size_t kv_bytes = regen_only ? 0 : align_up((size_t)p->M * s->d * 2);
+    p->off_k = 0;
+    p->off_v = kv_bytes;
+    p->off_stats = 2 * kv_bytes;
+    size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
+    p->off_partial = end;
+    p->chunk = 256;
+    p->total_chunks = 0;
+    if (!regen_only && L_kv + L_act > 0 && p->BH > 0) {
+        p->chunk = choose_chunk(s, p->BH, L_kv + L_act);
+        p->total_chunks = hk::attn_total_chunks((int)L_kv, (int)L_act, p->chunk);
+        if (p->BH * (int64_t)p->total_chunks > 0x7fffffffLL) return HK_ERR_SHAPE;
+        if (p->total_chunks > 1)
+            end += align_up((size_t)p->BH * p->total_chunks * (s->head_dim + 2) * sizeof(float));
+    }
+    p->total = end;
+    return HK_OK;
+}
+
+int check_params(const hk_layer_params *lp)
+{
+    if (!lp) return HK_ERR_NULL;
+    if (!lp->ln_w || !lp->ln_b || !lp->Wkv || !lp->bkv) return HK_ERR_NULL;
+    if (!aligned(lp->ln_w, 16) || !aligned(lp->ln_b, 16) || !aligned(lp->Wkv, 16) || !aligned(lp->bkv, 16))
+        return HK_ERR_ALIGN;
+    return HK_OK;
+}
+
+// Optional per-kernel time stamps: events recorded on the call's stream between the kernels.
+struct Marks {
+    hipEvent_t *ev;
+    int n;
+    hipStream_t stream;
+    bool put(int i) const { return !(ev && i < n && ev[i]) || hipEventRecord(ev[i], stream) == hipSuccess; }
+};
+
+int regen_impl(const hk_shape *s, const void *act, int64_t B, int64_t L_act, const hk_layer_params *lp,
+               void *K_out, void *V_out, int L_cap, int tok_off, float2 *stats, const Plan &p, hipStream_t stream,
+               const Marks &mk)
+{
+    if (hk::launch_ln_stats(act, stats, p.M, s->d, s->ln_eps, stream) != hipSuccess) return HK_ERR_LAUNCH;
+    if (!mk.put(1)) return HK_ERR_LAUNCH;
+    hk::KvGemmArgs g;
+    g.act = act; g.stats = stats; g.ln_w = lp->ln_w; g.ln_b = lp->ln_b; g.Wkv = lp->Wkv; g.bkv = lp->bkv;
+    g.K_out = K_out; g.V_out = V_out; g.M = p.M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
+    g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile;
+    if (hk::launch_kv_gemm(g, stream) != hipSuccess) return HK_ERR_LAUNCH;
+    return HK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act)
+{
+    Plan p;
+    if (make_plan(shape, B, 0, L_act, true, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act)
+{
+    Plan p;
+    if (make_plan(shape, B, L_kv, L_act, false, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+int hk_regen_kv(const hk_shape *shape, const void *act, int32_t B, int32_t L_act,
+                const hk_layer_params *params, void *K_out, void *V_out, int32_t L_cap, int32_t tok_off,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan p;
+    int st = make_plan(shape, B, 0, L_act, true, &p);
+    if (st != HK_OK) return st;
+    if (tok_off < 0 || L_cap < 0 || (int64_t)tok_off + L_act > L_cap) return HK_ERR_SHAPE;
+    if ((long double)B * L_cap * shape->d > 4.0e12L) return HK_ERR_SHAPE;
+    if (p.M == 0) return HK_OK;
+    st = check_params(params);
+    if (st != HK_OK) return st;
+    if (!act || !K_out || !V_out || !workspace) return HK_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(K_out, 16) || !aligned(V_out, 16) || !aligned(workspace, kAlign))
+        return HK_ERR_ALIGN;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    return regen_impl(shape, act, B, L_act, params, K_out, V_out, L_cap, tok_off,
+                      reinterpret_cast<float2 *>(ws + p.off_stats), p, static_cast<hipStream_t>(stream),
+                      Marks{nullptr, 0, nullptr});
+}
+
+int hk_hybrid_decode_attn(const hk_shape *shape, const void *q,
+                          const void *K_cache, const void *V_cache, int32_t L_kv,
+                          const void *act, int32_t L_act, int32_t B,
+                          const hk_layer_params *params, float ratio,
+                          void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return hk_hybrid_decode_attn_marked(shape, q, K_cache, V_cache, L_kv, act, L_act, B, params, ratio, out,
+                                        workspace, workspace_bytes, stream, nullptr, 0);
+}
+
+int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
+                                 const void *K_cache, const void *V_cache, int32_t L_kv,
+                                 const void *act, int32_t L_act, int32_t B,
+                                 const hk_layer_params *params, float ratio,
+                                 void *out, void *workspace, size_t workspace_bytes, void *stream,
+                                 void **events, int32_t n_events)
+{
+    Plan p;
+    int st = make_plan(shape, B, L_kv, L_act, false, &p);
+    if (st != HK_OK) return st;
+    const int64_t L = (int64_t)L_kv + L_act;
+    if (L == 0) return HK_ERR_SHAPE;
+    if (!(ratio >= 0.f && ratio <= 1.f)) return HK_ERR_RATIO;
+    if (std::fabs((double)ratio * (double)L - (double)L_kv) > 0.5 + 1e-6 * (double)L) return HK_ERR_RATIO;
+    if (B == 0) return HK_OK;
+    if (!q || !out || !workspace) return HK_ERR_NULL;
+    if (L_kv > 0 && (!K_cache || !V_cache)) return HK_ERR_NULL;
+    if (L_act > 0) {
+        st = check_params(params);
+        if (st != HK_OK) return st;
+        if (!act) return HK_ERR_NULL;
+        if (!aligned(act, 16)) return HK_ERR_ALIGN;
+    }
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign)) return HK_ERR_ALIGN;
+    if (L_kv > 0 && (!aligned(K_cache, 16) || !aligned(V_cache, 16))) return HK_ERR_ALIGN;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    void *K_regen = ws + p.off_k, *V_regen = ws + p.off_v;
+    const Marks mk{reinterpret_cast<hipEvent_t *>(events), events ? n_events : 0, hs};
+    if (!mk.put(0)) return HK_ERR_LAUNCH;
+    if (L_act > 0) {
+        st = regen_impl(shape, act, B, L_act, params, K_regen, V_regen, L_act, 0,
+                        reinterpret_cast<float2 *>(ws + p.off_stats), p, hs, mk);
+        if (st != HK_OK) return st;
+    } else if (!mk.put(1)) {
+        return HK_ERR_LAUNCH;
+    }
+    if (!mk.put(2)) return HK_ERR_LAUNCH;
+    hk::AttnArgs a;
+    a.q = q;
+    a.K0 = K_cache; a.V0 = V_cache; a.L0 = L_kv;
+    a.K1 = K_regen; a.V1 = V_regen; a.L1 = L_act;
+    a.BH = (int)p.BH; a.head_dim = shape->head_dim; a.scale = p.scale;
+    a.n_split = p.total_chunks; a.chunk = p.chunk;
+    a.partial = reinterpret_cast<float *>(ws + p.off_partial);
+    a.out = out;
+    a.after_main = (mk.ev && mk.n > 3) ? mk.ev[3] : nullptr;
+    if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    if (!mk.put(4)) return HK_ERR_LAUNCH;
+    return HK_OK;
+}
+
+const char *hk_status_string(int status)
+{
+    switch (status) {
+    case HK_OK: return "HK_OK";
+    case HK_ERR_NULL: return "HK_ERR_NULL: a required pointer is NULL";
+    case HK_ERR_SHAPE: return "HK_ERR_SHAPE: unsupported or inconsistent sizes";
+    case HK_ERR_RATIO: return "HK_ERR_RATIO: ratio outside [0,1] or inconsistent with L_kv, L_act";
+    case HK_ERR_ALIGN: return "HK_ERR_ALIGN: pointer not sufficiently aligned";
+    case HK_ERR_WORKSPACE: return "HK_ERR_WORKSPACE: workspace too small";
+    case HK_ERR_DTYPE: return "HK_ERR_DTYPE: unsupported dtype";
+    case HK_ERR_LAUNCH: return "HK_ERR_LAUNCH: HIP reported a launch error";
+    default: return "unknown hk_status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the gfx950 kernels.
+// Everything here is host-callable; pointers are device pointers unless said otherwise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hk {
+
+// Per-row LayerNorm statistics of act[M, d] (fp16) in fp32.
+// stats[r] = (rstd_r, -mean_r * rstd_r), so that (x - mean) * rstd == fma(x, stats.x, stats.y).
+hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s);
+
+struct KvGemmArgs {
+    const void *act;       // [M, d] fp16
+    const float2 *stats;   // [M]
+    const void *ln_w;      // [d] fp16
+    const void *ln_b;      // [d] fp16
+    const void *Wkv;       // [2d, d] fp16
+    const void *bkv;       // [2d] fp16
+    void *K_out;           // [B, H, L_cap, dh] fp16
+    void *V_out;
+    int64_t M;             // B * L_act
+    int d, n_heads, head_dim;
+    int L_act, L_cap, tok_off;
+    int tile;              // 0 = choose, else 128 or 256
+};
+// LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
+hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
+
+struct AttnArgs {
+    const void *q;         // [B, H, dh] fp16
+    const void *K0, *V0;   // first token segment  [B*H, L0, dh] fp16 (may be null when L0 == 0)
+    const void *K1, *V1;   // second token segment [B*H, L1, dh] fp16 (may be null when L1 == 0)
+    int L0, L1;
+    int BH;                // B * H
+    int head_dim;          // 64 or 128
+    float scale;           // multiplies q.k
+    int n_split;           // >= 1; token chunks per (b, h)
+    int chunk;             // tokens per chunk, multiple of 64; n_split * chunk >= L0 and L1 handled per segment
+    float *partial;        // [BH, n_split_total, dh + 2] fp32 (unused when n_split_total == 1)
+    void *out;             // [BH, dh] fp16
+    hipEvent_t after_main; // optional: recorded after the streaming kernel, before the merge
+};
+// Number of token chunks the attention kernel uses for segments of length L0, L1.
+int attn_total_chunks(int L0, int L1, int chunk);
+// Single-query attention over the two token segments taken as one context.
+hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s);
+
+}  // namespace hk

@@ -1,0 +1,69 @@
+// Row-parallel LayerNorm statistics for gfx950: one 64-lane wavefront per checkpoint row.
+//
+// The checkpoint is the decoder layer's input (Sec. 3.3), so the layer's pre-attention
+// LayerNorm has to be applied before Eq. 7.  This kernel only produces the two fp32
+// numbers per row that the projection kernel needs to normalise the row on the fly:
+//     stats[r] = (rstd, -mean * rstd),   rstd = 1 / sqrt(var + eps), var biased.
+// Mean and variance are taken in two passes over the row (the second pass hits L2), both
+// summed in fp32 with wavefront shuffles.
+#include "hk_internal.h"
+#include <hip/hip_fp16.h>
+
+namespace hk {
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+constexpr int kRowsPerBlock = 4;   // 256 threads = 4 wavefronts
+
+__global__ __launch_bounds__(256) void ln_stats_kernel(const _Float16 *__restrict__ act,
+                                                       float2 *__restrict__ stats,
+                                                       int64_t M, int d, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    if (row >= M) return;   // whole wavefront leaves together; no barrier in this kernel
+    const half8_t *p = reinterpret_cast<const half8_t *>(act + row * (int64_t)d);
+    const int nvec = d >> 3;   // host guarantees d % 8 == 0
+
+    float s = 0.f;
+    for (int i = lane; i < nvec; i += 64) {
+        const half8_t v = p[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += (float)v[j];
+    }
+    const float mean = wave_sum(s) / (float)d;
+
+    float ss = 0.f;
+    for (int i = lane; i < nvec; i += 64) {
+        const half8_t v = p[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float c = (float)v[j] - mean;
+            ss += c * c;
+        }
+    }
+    const float var = wave_sum(ss) / (float)d;
+    const float rstd = 1.0f / sqrtf(var + eps);
+    if (lane == 0) stats[row] = make_float2(rstd, -mean * rstd);
+}
+
+}  // namespace
+
+hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s)
+{
+    if (M <= 0) return hipSuccess;
+    const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
+    hipLaunchKernelGGL(ln_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       static_cast<const _Float16 *>(act), stats, M, d, eps);
+    return hipGetLastError();
+}
+
+}  // namespace hk

@@ -1,0 +1,126 @@
+"""Host-side checks of the C ABI that need no GPU: the shared library loads, exports every
+function include/hybridkv.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_01792_amd import binding as hk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000      # never dereferenced: every call below must fail validation first
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "hybridkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hk_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"hk_regen_kv", "hk_hybrid_decode_attn", "hk_workspace_bytes",
+            "hk_regen_workspace_bytes", "hk_status_string"} <= set(names)
+    L = hk.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(hk.hk_shape) == 32
+    assert ctypes.sizeof(hk.hk_layer_params) == 32
+
+
+def test_status_strings():
+    for code in range(0, -8, -1):
+        assert hk.status_string(code).startswith("HK_")
+    assert "unknown" in hk.status_string(-99)
+
+
+def test_workspace_bytes():
+    s = hk.make_shape(4096, 32)
+    B, L_kv, L_act = 32, 512, 512
+    w = hk.hk_workspace_bytes(s, B, L_kv, L_act)
+    regen = 2 * B * L_act * 4096 * 2
+    assert regen + B * L_act * 8 <= w < regen + (64 << 20)
+    assert hk.hk_regen_workspace_bytes(s, B, L_act) >= B * L_act * 8
+    assert hk.hk_workspace_bytes(hk.make_shape(4096, 31), B, L_kv, L_act) == 0     # invalid shape
+    assert hk.hk_workspace_bytes(s, 4, 100, 0) > 0
+    # more splits -> more partials
+    s64 = hk.make_shape(4096, 32, attn_splits=64)
+    assert hk.hk_workspace_bytes(s64, 1, 0, 16384) > hk.hk_workspace_bytes(hk.make_shape(4096, 32, attn_splits=1), 1, 0, 16384)
+
+
+def _attn(shape, q=FAKE, Kc=FAKE, Vc=FAKE, L_kv=128, act=FAKE, L_act=128, B=4, lp=None, ratio=0.5,
+          out=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    if lp is None:
+        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE)
+    return hk.lib().hk_hybrid_decode_attn(ctypes.byref(shape), q, Kc, Vc, L_kv, act, L_act, B,
+                                          ctypes.byref(lp) if lp != 0 else None, ratio, out, ws, ws_bytes, None)
+
+
+def test_hybrid_decode_attn_rejects_bad_arguments():
+    ok = hk.make_shape(768, 12)
+    assert _attn(hk.make_shape(768, 11)) == hk.HK_ERR_SHAPE                 # d != H*dh
+    assert _attn(hk.make_shape(768, 24)) == hk.HK_ERR_SHAPE                 # head_dim 32 unsupported
+    bad = hk.make_shape(768, 12); bad.dtype = 1
+    assert _attn(bad) == hk.HK_ERR_DTYPE
+    assert _attn(hk.make_shape(768, 12, attn_splits=65)) == hk.HK_ERR_SHAPE
+    assert _attn(hk.make_shape(768, 12, gemm_tile=64)) == hk.HK_ERR_SHAPE
+    assert _attn(ok, ratio=1.5) == hk.HK_ERR_RATIO
+    assert _attn(ok, ratio=-0.1) == hk.HK_ERR_RATIO
+    assert _attn(ok, ratio=float("nan")) == hk.HK_ERR_RATIO
+    assert _attn(ok, ratio=0.25) == hk.HK_ERR_RATIO                         # 128 of 256 is not 0.25
+    assert _attn(ok, L_kv=0, L_act=0, ratio=0.0) == hk.HK_ERR_SHAPE         # empty context
+    assert _attn(ok, L_kv=-1) == hk.HK_ERR_SHAPE
+    assert _attn(ok, q=None) == hk.HK_ERR_NULL
+    assert _attn(ok, out=None) == hk.HK_ERR_NULL
+    assert _attn(ok, Kc=None) == hk.HK_ERR_NULL
+    assert _attn(ok, act=None) == hk.HK_ERR_NULL
+    assert _attn(ok, ws=None) == hk.HK_ERR_NULL
+    assert _attn(ok, lp=hk.hk_layer_params(FAKE, None, FAKE, FAKE)) == hk.HK_ERR_NULL
+    assert _attn(ok, q=FAKE + 8) == hk.HK_ERR_ALIGN
+    assert _attn(ok, Vc=FAKE + 2) == hk.HK_ERR_ALIGN
+    assert _attn(ok, ws=FAKE + 16) == hk.HK_ERR_ALIGN
+    assert _attn(ok, ws_bytes=1024) == hk.HK_ERR_WORKSPACE
+    need = hk.hk_workspace_bytes(ok, 4, 128, 128)
+    assert _attn(ok, ws_bytes=need - 1) == hk.HK_ERR_WORKSPACE
+    assert hk.lib().hk_hybrid_decode_attn(None, FAKE, FAKE, FAKE, 1, FAKE, 1, 1, None, 0.5,
+                                          FAKE, FAKE, 1 << 30, None) == hk.HK_ERR_NULL
+    # B == 0 is a no-op that still validates shape and ratio first
+    assert _attn(ok, B=0) == hk.HK_OK
+    assert _attn(ok, B=0, ratio=0.9) == hk.HK_ERR_RATIO
+
+
+def _regen(shape, act=FAKE, B=4, L_act=128, lp=None, K=FAKE, V=FAKE, L_cap=128, tok_off=0, ws=FAKE, ws_bytes=1 << 40):
+    if lp is None:
+        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE)
+    return hk.lib().hk_regen_kv(ctypes.byref(shape), act, B, L_act, ctypes.byref(lp), K, V, L_cap, tok_off,
+                                ws, ws_bytes, None)
+
+
+def test_regen_kv_rejects_bad_arguments():
+    ok = hk.make_shape(768, 12)
+    assert _regen(hk.make_shape(770, 12)) == hk.HK_ERR_SHAPE
+    assert _regen(ok, L_cap=100) == hk.HK_ERR_SHAPE                         # rows would not fit
+    assert _regen(ok, tok_off=1) == hk.HK_ERR_SHAPE
+    assert _regen(ok, tok_off=-1, L_cap=256) == hk.HK_ERR_SHAPE
+    assert _regen(ok, act=None) == hk.HK_ERR_NULL
+    assert _regen(ok, K=None) == hk.HK_ERR_NULL
+    assert _regen(ok, V=FAKE + 4) == hk.HK_ERR_ALIGN
+    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, None, FAKE)) == hk.HK_ERR_NULL
+    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, FAKE + 6, FAKE)) == hk.HK_ERR_ALIGN
+    assert _regen(ok, ws_bytes=16) == hk.HK_ERR_WORKSPACE
+    assert _regen(ok, L_act=0, L_cap=0) == hk.HK_OK                         # nothing to do
+    assert _regen(ok, B=0) == hk.HK_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 4, 768, dtype=torch.float16)
+    w = torch.zeros(768, dtype=torch.float16)
+    with pytest.raises(TypeError):
+        hk.regen_kv(x, w, w, torch.zeros(1536, 768, dtype=torch.float16), torch.zeros(1536, dtype=torch.float16), 12,
+                    K_out=torch.zeros(1, 12, 4, 64, dtype=torch.float16), V_out=torch.zeros(1, 12, 4, 64, dtype=torch.float16),
+                    workspace=torch.zeros(1024, dtype=torch.uint8))

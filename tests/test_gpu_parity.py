@@ -1,0 +1,224 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded fp16 inputs.
+
+Tolerances (the contract of the benchmark): max abs error <= 2e-2 and relative L2 error
+<= 5e-3, for the attention output and, elementwise, for the regenerated K/V.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_01792_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-2
+REL_L2 = 5e-3
+
+
+@pytest.fixture(scope="module")
+def hk():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    from paper_2501_01792_amd import binding
+    binding.lib()        # raises if the HIP library has not been built
+    return binding
+
+
+def _gpu(x):
+    return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _check(name, got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.isfinite(got).all(), name + ": non-finite values"
+    max_abs = np.abs(got - ref).max() if got.size else 0.0
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30) if got.size else 0.0
+    print("%s: max_abs=%.3e rel_l2=%.3e" % (name, max_abs, rel), flush=True)
+    assert max_abs <= MAX_ABS, "%s: max abs error %.3e" % (name, max_abs)
+    assert rel <= REL_L2, "%s: relative L2 error %.3e" % (name, rel)
+
+
+def _cfg(name, d, H, B, L, ratio, seed):
+    return synth.LayerConfig(name, d, H, B, L, ratio, seed)
+
+
+def _run_hybrid(hk, cfg, batch, **kw):
+    lp = tuple(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    Kc = _gpu(batch["K_cache"]) if cfg.L_kv else None
+    Vc = _gpu(batch["V_cache"]) if cfg.L_kv else None
+    act = _gpu(batch["act"]) if cfg.L_act else None
+    out, K, V = hk.hybrid_decode_attn(_gpu(batch["q"]), Kc, Vc, act, lp, cfg.ratio, return_regen=True, **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), K.cpu().numpy(), V.cpu().numpy()
+
+
+def _oracle_hybrid(oracle, cfg, batch):
+    return oracle.hybrid_decode_attn(batch["q"], batch["K_cache"] if cfg.L_kv else None,
+                                     batch["V_cache"] if cfg.L_kv else None,
+                                     batch["act"] if cfg.L_act else None,
+                                     batch["ln_w"], batch["ln_b"], batch["Wkv"], batch["bkv"], cfg.n_heads)
+
+
+# shapes chosen to span several tiles of every kernel and leave ragged tails:
+#   rows M = B*L_act not a multiple of 128/256, token counts not multiples of 64/256
+SMALL = [
+    _cfg("tiny", 768, 12, 4, 256, 0.5, 0),                 # the small benchmark config
+    _cfg("ragged64", 768, 12, 3, 101, 37 / 101, 11),       # dh = 64, M = 192, L_kv = 37
+    _cfg("ragged128", 1024, 8, 2, 427, 127 / 427, 12),     # dh = 128, M = 600
+    _cfg("all_regen", 512, 4, 5, 77, 0.0, 13),             # ratio 0
+    _cfg("all_cached", 512, 8, 3, 333, 1.0, 14),           # ratio 1: no regeneration
+    _cfg("one_token_each", 256, 2, 2, 2, 0.5, 15),         # 1 cached + 1 checkpoint
+    _cfg("single_act", 256, 4, 1, 1, 0.0, 16),             # a single context token
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+@pytest.mark.parametrize("tile", [128, 256])
+def test_hybrid_step_matches_oracle(hk, oracle, cfg, tile):
+    print("case", cfg, "tile", tile, flush=True)
+    batch = synth.make_batch(cfg)
+    out, K, V = _run_hybrid(hk, cfg, batch, gemm_tile=tile)
+    ref_out, ref_K, ref_V = _oracle_hybrid(oracle, cfg, batch)
+    if cfg.L_act:
+        _check("K_regen", K, ref_K[:, :, cfg.L_kv:])
+        _check("V_regen", V, ref_V[:, :, cfg.L_kv:])
+    _check("out", out, ref_out)
+
+
+@pytest.mark.parametrize("cfg", SMALL[:4], ids=lambda c: c.name)
+def test_regen_kv_into_cache_slot(hk, oracle, cfg):
+    """hk_regen_kv writes rows [tok_off, tok_off + L_act) of a larger cache and nothing else."""
+    print("case", cfg, flush=True)
+    batch = synth.make_batch(cfg)
+    B, H, dh, L_act = cfg.B, cfg.n_heads, cfg.head_dim, cfg.L_act
+    L_cap, off = L_act + 9, 5
+    K = torch.full((B, H, L_cap, dh), 7.0, dtype=torch.float16, device="cuda")
+    V = torch.full((B, H, L_cap, dh), -7.0, dtype=torch.float16, device="cuda")
+    hk.regen_kv(_gpu(batch["act"]), *(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv")), H,
+                K_out=K, V_out=V, tok_off=off)
+    torch.cuda.synchronize()
+    K, V = K.cpu().numpy(), V.cpu().numpy()
+    ref_K, ref_V = oracle.regen_kv(batch["act"], batch["ln_w"], batch["ln_b"], batch["Wkv"], batch["bkv"], H)
+    _check("K", K[:, :, off:off + L_act], ref_K)
+    _check("V", V[:, :, off:off + L_act], ref_V)
+    # canaries outside the slot are intact
+    assert (K[:, :, :off] == 7.0).all() and (K[:, :, off + L_act:] == 7.0).all()
+    assert (V[:, :, :off] == -7.0).all() and (V[:, :, off + L_act:] == -7.0).all()
+
+
+def test_layernorm_statistics_under_offset_and_scale(hk, oracle):
+    """Rows with a large mean and a non-unit spread: the fused LayerNorm must still match."""
+    cfg = _cfg("shifted", 1024, 8, 2, 130, 0.0, 21)
+    batch = synth.make_batch(cfg)
+    rng = np.random.default_rng(5)
+    act = batch["act"].astype(np.float32) * rng.uniform(0.1, 6.0, size=(cfg.B, cfg.L, 1)) + rng.uniform(-20, 20, size=(cfg.B, cfg.L, 1))
+    batch["act"] = act.astype(np.float16)
+    out, K, V = _run_hybrid(hk, cfg, batch)
+    ref_out, ref_K, ref_V = _oracle_hybrid(oracle, cfg, batch)
+    _check("K_regen", K, ref_K)
+    _check("V_regen", V, ref_V)
+    _check("out", out, ref_out)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 64])
+def test_attention_split_count_invariance(hk, oracle, splits):
+    """Any split of the token axis must give the oracle's result (log-sum-exp merge)."""
+    cfg = _cfg("splits", 512, 4, 2, 1500, 700 / 1500, 22)
+    batch = synth.make_batch(cfg)
+    out, _, _ = _run_hybrid(hk, cfg, batch, attn_splits=splits)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+    _check("out[splits=%d]" % splits, out, ref_out)
+
+
+def test_attention_peaked_and_flat_scores(hk, oracle):
+    """Softmax extremes: one dominating token (huge score) and q = 0 (uniform weights)."""
+    cfg = _cfg("extremes", 512, 4, 2, 600, 0.5, 23)
+    batch = synth.make_batch(cfg)
+    q = batch["q"].copy()
+    q[0] = 0                                     # sequence 0: uniform attention -> mean of V
+    batch["K_cache"][1, :, 17] = (q[1] * 4).astype(np.float16)   # sequence 1: token 17 dominates
+    batch["q"] = q
+    out, _, _ = _run_hybrid(hk, cfg, batch)
+    ref_out, _, ref_V = _oracle_hybrid(oracle, cfg, batch)
+    _check("out", out, ref_out)
+    _check("out[uniform] vs mean V", out[0], ref_V[0].mean(axis=1))
+
+
+def test_ratio_invariance_on_gpu(hk):
+    """Sec. 3.3: with the cache filled by the same regeneration, every KV:activation split of
+    the context gives the same output.  On the GPU the regenerated rows are bit-identical to
+    the cached ones, so outputs may differ only through the summation order of the partials."""
+    cfg = _cfg("ratio_inv", 1024, 8, 3, 512, 0.0, 24)
+    batch = synth.make_batch(cfg)
+    lp = tuple(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    act, q = _gpu(batch["act"]), _gpu(batch["q"])
+    K_full, V_full = hk.regen_kv(act, *lp, cfg.n_heads)
+    outs = []
+    for L_kv in (0, 128, 256, 300, 512):
+        Kc = K_full[:, :, :L_kv].contiguous() if L_kv else None
+        Vc = V_full[:, :, :L_kv].contiguous() if L_kv else None
+        a = act[:, L_kv:].contiguous() if L_kv < cfg.L else None
+        out, K, V = hk.hybrid_decode_attn(q, Kc, Vc, a, lp, L_kv / cfg.L, return_regen=True)
+        torch.cuda.synchronize()
+        if L_kv < cfg.L:
+            assert torch.equal(K, K_full[:, :, L_kv:]) and torch.equal(V, V_full[:, :, L_kv:])
+        outs.append(out.float().cpu().numpy())
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() <= 2e-3
+
+
+def test_repeatable(hk):
+    """Two runs on the same inputs give the same bits (no atomics, fixed reduction order)."""
+    cfg = _cfg("repeat", 768, 12, 4, 300, 0.25, 25)
+    batch = synth.make_batch(cfg)
+    a = _run_hybrid(hk, cfg, batch)
+    b = _run_hybrid(hk, cfg, batch)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------ full benchmark sizes, sampled
+def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99):
+    """Runs the GPU path on the whole config and checks (a) regenerated K/V of randomly sampled
+    checkpoint rows and (b) the attention output of sampled (sequence, head) pairs against the
+    oracle, which computes exactly those outputs from the same inputs (all K/V rows of the
+    sampled head, via Eq. 7 restricted to that head's weight rows)."""
+    batch = synth.make_batch(cfg, threads=16)
+    out, K, V = _run_hybrid(hk, cfg, batch)
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
+    rng = np.random.default_rng(seed)
+    if cfg.L_act:
+        rows = [(int(rng.integers(cfg.B)), int(rng.integers(cfg.L_act))) for _ in range(n_rows)]
+        rows += [(0, 0), (cfg.B - 1, cfg.L_act - 1)]
+        x = np.stack([batch["act"][b, t] for b, t in rows])
+        xh = oracle.layernorm(x, batch["ln_w"], batch["ln_b"])
+        kv = oracle.kv_projection(xh, batch["Wkv"], batch["bkv"])           # [rows, 2d]
+        got_k = np.stack([K[b, :, t, :].reshape(d) for b, t in rows])
+        got_v = np.stack([V[b, :, t, :].reshape(d) for b, t in rows])
+        _check("K_regen[sampled rows]", got_k, kv[:, :d])
+        _check("V_regen[sampled rows]", got_v, kv[:, d:])
+    pairs = [(int(rng.integers(cfg.B)), int(rng.integers(H))) for _ in range(n_pairs)]
+    pairs += [(cfg.B - 1, H - 1)]
+    got, ref = [], []
+    for b, h in pairs:
+        Kb = batch["K_cache"][b, h].astype(np.float64)
+        Vb = batch["V_cache"][b, h].astype(np.float64)
+        if cfg.L_act:
+            xh = oracle.layernorm(batch["act"][b], batch["ln_w"], batch["ln_b"])
+            sel = np.r_[h * dh:(h + 1) * dh, d + h * dh:d + (h + 1) * dh]
+            kv = oracle.kv_projection(xh, batch["Wkv"][sel], batch["bkv"][sel])   # Eq. 7, head h's features
+            Kb = np.concatenate([Kb, kv[:, :dh]], axis=0)
+            Vb = np.concatenate([Vb, kv[:, dh:]], axis=0)
+        ref.append(oracle.decode_attention(batch["q"][b:b + 1, h:h + 1], Kb[None, None], Vb[None, None])[0, 0])
+        got.append(out[b, h])
+    _check("out[sampled (b,h)]", np.stack(got), np.stack(ref))
+
+
+def test_full_size_opt6p7b_sampled(hk, oracle):
+    """The configuration the benchmark times (OPT-6.7B-shaped layer, B=32, L=1024, ratio 0.5)."""
+    _sampled_oracle_check(hk, oracle, synth.CONFIGS["opt6.7b"])
