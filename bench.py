@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--gemm-tile", type=int, default=0)
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain device copy of 1 GiB (3 launches) so that profiler byte counters "
+                         "can be scaled against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the step has no cross-GPU part); "
@@ -106,6 +109,14 @@ def main():
     def step(events=None):
         hk.hybrid_decode_attn(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream,
                               attn_splits=args.attn_splits, gemm_tile=args.gemm_tile, events=events)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -26,6 +26,8 @@ struct KvGemmArgs {
 };
 // LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
+// The 256 x 256 software-pipelined kernel behind launch_kv_gemm for large problems.
+hipError_t launch_kv_gemm_pipe(const KvGemmArgs &a, hipStream_t s);
 
 struct AttnArgs {
     const void *q;         // [B, H, dh] fp16
