@@ -81,6 +81,7 @@ typedef struct hk_layer_params {
     const void *ln_b;      /* [d]     */
     const void *Wkv;       /* [2d, d] */
     const void *bkv;       /* [2d]    */
+    const void *prepared;  /* NULL, or the buffer hk_prepare_layer filled from these four */
 } hk_layer_params;
 
 /*
@@ -96,6 +97,22 @@ size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_
  * statistics only).  Returns 0 when the shape is invalid.
  */
 size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act);
+
+/*
+ * Optional one-time preparation of a layer (its parameters are fixed during
+ * inference).  Eq. 7 applied to LayerNorm-ed checkpoints can be regrouped as
+ *     [K V][t, n] = rstd_t * (a_t . W'[n, :]) - mean_t * rstd_t * c[n] + b'[n],
+ *     W'[n, k] = ln_w[k] * Wkv[n, k],  c[n] = sum_k W'[n, k],  b'[n] = bkv[n] + sum_k ln_b[k] * Wkv[n, k],
+ * which lets the raw checkpoint rows feed the matrix cores while the row
+ * statistics are applied to the accumulators.  hk_prepare_layer computes W'
+ * (fp16), c and b' (fp32) into `prepared` (device, 256-byte aligned, at least
+ * hk_prepared_bytes(shape) bytes, owned by the caller, valid as long as it is
+ * referenced from hk_layer_params.prepared).  Calls given a prepared layer use
+ * it for large batches; results agree with the unprepared path to rounding.
+ */
+size_t hk_prepared_bytes(const hk_shape *shape);
+int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params,
+                     void *prepared, size_t prepared_bytes, void *stream);
 
 /*
  * "KV Gen" (Sec. 4.2.2; Sec. 3.3, Eq. 7): regenerate keys and values from

@@ -27,7 +27,7 @@ class hk_shape(ctypes.Structure):
 
 class hk_layer_params(ctypes.Structure):
     _fields_ = [("ln_w", ctypes.c_void_p), ("ln_b", ctypes.c_void_p),
-                ("Wkv", ctypes.c_void_p), ("bkv", ctypes.c_void_p)]
+                ("Wkv", ctypes.c_void_p), ("bkv", ctypes.c_void_p), ("prepared", ctypes.c_void_p)]
 
 
 class HybridKVError(RuntimeError):
@@ -53,6 +53,10 @@ def lib():
         L.hk_workspace_bytes.argtypes = [shp, i32, i32, i32]
         L.hk_regen_workspace_bytes.restype = sz
         L.hk_regen_workspace_bytes.argtypes = [shp, i32, i32]
+        L.hk_prepared_bytes.restype = sz
+        L.hk_prepared_bytes.argtypes = [shp]
+        L.hk_prepare_layer.restype = ctypes.c_int
+        L.hk_prepare_layer.argtypes = [shp, lpp, vp, sz, vp]
         L.hk_regen_kv.restype = ctypes.c_int
         L.hk_regen_kv.argtypes = [shp, vp, i32, i32, lpp, vp, vp, i32, i32, vp, sz, vp]
         L.hk_hybrid_decode_attn.restype = ctypes.c_int
@@ -102,11 +106,31 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _params(ln_w, ln_b, Wkv, bkv):
+def _params(ln_w, ln_b, Wkv, bkv, prepared=None):
     import torch
     f16 = torch.float16
+    pp = _dev_ptr(prepared, "prepared")
     return hk_layer_params(_dev_ptr(ln_w, "ln_w", f16).value, _dev_ptr(ln_b, "ln_b", f16).value,
-                           _dev_ptr(Wkv, "Wkv", f16).value, _dev_ptr(bkv, "bkv", f16).value)
+                           _dev_ptr(Wkv, "Wkv", f16).value, _dev_ptr(bkv, "bkv", f16).value,
+                           pp.value if pp is not None else None)
+
+
+def hk_prepared_bytes(shape: hk_shape) -> int:
+    return int(lib().hk_prepared_bytes(ctypes.byref(shape)))
+
+
+def prepare_layer(ln_w, ln_b, Wkv, bkv, n_heads, stream=None):
+    """hk_prepare_layer: returns the prepared-layer buffer (a uint8 GPU tensor) to pass as the fifth
+    element of ``layer_params`` / the ``prepared`` argument."""
+    d = ln_w.shape[0]
+    shape = make_shape(d, n_heads)
+    buf = new_workspace(hk_prepared_bytes(shape), ln_w.device)
+    lp = _params(ln_w, ln_b, Wkv, bkv)
+    st = lib().hk_prepare_layer(ctypes.byref(shape), ctypes.byref(lp), _dev_ptr(buf, "prepared"), buf.numel(),
+                                _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_prepare_layer")
+    return buf
 
 
 def new_workspace(nbytes: int, device="cuda"):
@@ -116,7 +140,7 @@ def new_workspace(nbytes: int, device="cuda"):
 
 
 def regen_kv(act, ln_w, ln_b, Wkv, bkv, n_heads, K_out=None, V_out=None, tok_off=0,
-             ln_eps=1e-5, gemm_tile=0, workspace=None, stream=None):
+             ln_eps=1e-5, gemm_tile=0, workspace=None, stream=None, prepared=None):
     """hk_regen_kv: ``act[B, L_act, d]`` fp16 -> ``(K, V)``, each ``[B, H, L_cap, dh]`` fp16, rows
     ``tok_off .. tok_off+L_act`` written.  Allocates the outputs (L_cap = L_act) and the
     workspace when they are not given."""
@@ -130,7 +154,7 @@ def regen_kv(act, ln_w, ln_b, Wkv, bkv, n_heads, K_out=None, V_out=None, tok_off
     L_cap = K_out.shape[2]
     if workspace is None:
         workspace = new_workspace(hk_regen_workspace_bytes(shape, B, L_act), act.device)
-    lp = _params(ln_w, ln_b, Wkv, bkv)
+    lp = _params(ln_w, ln_b, Wkv, bkv, prepared)
     st = lib().hk_regen_kv(ctypes.byref(shape), _dev_ptr(act, "act", torch.float16), B, L_act,
                            ctypes.byref(lp), _dev_ptr(K_out, "K_out", torch.float16),
                            _dev_ptr(V_out, "V_out", torch.float16), L_cap, tok_off,
@@ -144,7 +168,7 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
                        softmax_scale=0.0, attn_splits=0, gemm_tile=0, workspace=None, stream=None,
                        return_regen=False, events=None):
     """hk_hybrid_decode_attn: ``q[B,H,dh]``, ``K_cache,V_cache[B,H,L_kv,dh]`` (or None), ``act[B,L_act,d]``
-    (or None), ``layer_params = (ln_w, ln_b, Wkv, bkv)`` -> ``out[B,H,dh]`` (all fp16 GPU tensors).
+    (or None), ``layer_params = (ln_w, ln_b, Wkv, bkv[, prepared])`` -> ``out[B,H,dh]`` (all fp16 GPU tensors).
     With ``return_regen`` also returns views of the regenerated K, V ``[B,H,L_act,dh]`` that
     the call left at the head of the workspace.  ``events`` (a ``hipevents.EventSet`` of 5)
     selects hk_hybrid_decode_attn_marked, which time-stamps the kernels of the step."""

@@ -94,7 +94,22 @@ int check_params(const hk_layer_params *lp)
     if (!lp->ln_w || !lp->ln_b || !lp->Wkv || !lp->bkv) return HK_ERR_NULL;
     if (!aligned(lp->ln_w, 16) || !aligned(lp->ln_b, 16) || !aligned(lp->Wkv, 16) || !aligned(lp->bkv, 16))
         return HK_ERR_ALIGN;
+    if (lp->prepared && !aligned(lp->prepared, kAlign)) return HK_ERR_ALIGN;
     return HK_OK;
+}
+
+// Layout of a prepared layer: W' [2d, d] fp16, then c [2d] fp32, then b' [2d] fp32, each 256-byte aligned.
+struct PreparedLayout {
+    size_t off_w, off_c, off_b, total;
+};
+PreparedLayout prepared_layout(int d)
+{
+    PreparedLayout L;
+    L.off_w = 0;
+    L.off_c = align_up((size_t)2 * d * d * 2);
+    L.off_b = L.off_c + align_up((size_t)2 * d * sizeof(float));
+    L.total = L.off_b + align_up((size_t)2 * d * sizeof(float));
+    return L;
 }
 
 // Optional per-kernel time stamps: events recorded on the call's stream between the kernels.
@@ -113,6 +128,14 @@ int regen_impl(const hk_shape *s, const void *act, int64_t B, int64_t L_act, con
     if (!mk.put(1)) return HK_ERR_LAUNCH;
     hk::KvGemmArgs g;
     g.act = act; g.stats = stats; g.ln_w = lp->ln_w; g.ln_b = lp->ln_b; g.Wkv = lp->Wkv; g.bkv = lp->bkv;
+    g.Wp = nullptr; g.cvec = nullptr; g.bvec = nullptr;
+    if (lp->prepared) {
+        const PreparedLayout L = prepared_layout(s->d);
+        const char *pp = static_cast<const char *>(lp->prepared);
+        g.Wp = pp + L.off_w;
+        g.cvec = reinterpret_cast<const float *>(pp + L.off_c);
+        g.bvec = reinterpret_cast<const float *>(pp + L.off_b);
+    }
     g.K_out = K_out; g.V_out = V_out; g.M = p.M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
     g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile;
     if (hk::launch_kv_gemm(g, stream) != hipSuccess) return HK_ERR_LAUNCH;
@@ -122,6 +145,31 @@ int regen_impl(const hk_shape *s, const void *act, int64_t B, int64_t L_act, con
 }  // namespace
 
 extern "C" {
+
+size_t hk_prepared_bytes(const hk_shape *shape)
+{
+    if (check_shape(shape) != HK_OK) return 0;
+    return prepared_layout(shape->d).total;
+}
+
+int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params, void *prepared, size_t prepared_bytes,
+                     void *stream)
+{
+    int st = check_shape(shape);
+    if (st != HK_OK) return st;
+    st = check_params(params);
+    if (st != HK_OK) return st;
+    if (!prepared) return HK_ERR_NULL;
+    if (!aligned(prepared, kAlign)) return HK_ERR_ALIGN;
+    const PreparedLayout L = prepared_layout(shape->d);
+    if (prepared_bytes < L.total) return HK_ERR_WORKSPACE;
+    char *pp = static_cast<char *>(prepared);
+    if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, pp + L.off_w,
+                                 reinterpret_cast<float *>(pp + L.off_c), reinterpret_cast<float *>(pp + L.off_b),
+                                 shape->d, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return HK_ERR_LAUNCH;
+    return HK_OK;
+}
 
 size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act)
 {

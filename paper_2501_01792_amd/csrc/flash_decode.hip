@@ -62,8 +62,12 @@ __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane / LPR, c = lane % LPR;
-    const int bh = blockIdx.x / total_chunks;
-    const int ck = blockIdx.x % total_chunks;
+    // Workgroups are numbered so that the launch walks the (sequence, head) pairs from the last to the
+    // first and, within a pair, the second (regenerated) segment before the first: the rows that the
+    // projection kernel wrote most recently are read first, while they are still in the last-level cache.
+    const int rev = gridDim.x - 1 - blockIdx.x;
+    const int bh = rev / total_chunks;
+    const int ck = rev % total_chunks;
 
     // which segment, which token range
     const bool second = ck >= chunks0;

@@ -17,6 +17,9 @@ struct KvGemmArgs {
     const void *ln_b;      // [d] fp16
     const void *Wkv;       // [2d, d] fp16
     const void *bkv;       // [2d] fp16
+    const void *Wp;        // prepared layer (null when not given): [2d, d] fp16 gamma-scaled weights,
+    const float *cvec;     //   [2d] row sums of Wp,
+    const float *bvec;     //   [2d] bias with the LayerNorm bias folded in
     void *K_out;           // [B, H, L_cap, dh] fp16
     void *V_out;
     int64_t M;             // B * L_act
@@ -26,6 +29,11 @@ struct KvGemmArgs {
 };
 // LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
+// The 256 x 256 kernel for prepared layers (LayerNorm folded around the product; needs Wp, cvec, bvec).
+hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s);
+// Fills Wp, cvec, bvec from the layer's parameters.
+hipError_t launch_prepare_layer(const void *Wkv, const void *bkv, const void *ln_w, const void *ln_b,
+                                void *Wp, float *cvec, float *bvec, int d, hipStream_t s);
 // The 256 x 256 software-pipelined kernel behind launch_kv_gemm for large problems.
 hipError_t launch_kv_gemm_pipe(const KvGemmArgs &a, hipStream_t s);
 

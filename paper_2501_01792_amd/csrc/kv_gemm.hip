@@ -25,7 +25,6 @@
 //     tiles; the workgroups resident on one XCD share weight panels in that XCD's L2.
 #include "hk_internal.h"
 #include "kv_gemm_common.h"
-#include <cstdlib>
 
 namespace hk {
 namespace {
@@ -183,12 +182,9 @@ hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s)
     // tiles to occupy the 256 compute units fall back to 128x128 tiles.
     const int64_t big_tiles = ((a.M + 255) / 256) * ((2 * (int64_t)a.d + 255) / 256);
     const int tile = a.tile ? a.tile : (big_tiles >= 512 ? 256 : 128);
-    static const int variant = getenv("HK_GEMM_VARIANT") ? atoi(getenv("HK_GEMM_VARIANT")) : 0;
     if (tile == 256) {
-        if (variant == 1) return launch_tile<256, 256, 4, 2, 8>(a, s);
-        if (variant == 2) return launch_tile<256, 256, 2, 4, 8>(a, s);
-        if (variant == 3) return launch_kv_gemm_pipe(a, s);
-        return launch_tile<256, 256, 2, 2, 8>(a, s);
+        // prepared layer: LayerNorm folded around the product; otherwise LayerNorm as the GEMM prologue
+        return a.Wp ? launch_kv_gemm_fold(a, s) : launch_kv_gemm_pipe(a, s);
     }
     return launch_tile<128, 128, 2, 2, 8>(a, s);
 }

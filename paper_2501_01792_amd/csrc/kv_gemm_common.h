@@ -132,5 +132,51 @@ __device__ __forceinline__ void store_head_split(const float16_t (&acc)[TM][TN],
     }
 }
 
+// Epilogue of one wavefront for the folded-LayerNorm kernel: the accumulators hold x . W'[n,:] of
+// the raw rows; out = rstd * acc + (nmr * c[n] + b'[n]) with (rstd, nmr) = stats[row], in fp32,
+// then fp16 and the head-split store.  Register / row / feature layout as in store_head_split.
+template <int BM, int TM, int TN>
+__device__ __forceinline__ void store_head_split_fold(const float16_t (&acc)[TM][TN], int lane,
+                                                      int64_t m0, int wrow0, int nb, int64_t M, int d,
+                                                      int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
+                                                      const float2 *__restrict__ stats,
+                                                      const float *__restrict__ cvec, const float *__restrict__ bvec,
+                                                      _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
+{
+    static_assert(TN == 4, "packs four features per store");
+    if (nb >= 2 * d) return;
+    float cn[TN], bn[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) { cn[j] = cvec[nb + j]; bn[j] = bvec[nb + j]; }
+    const bool is_v = nb >= d;
+    const int nn = is_v ? nb - d : nb;
+    const int h = nn / head_dim, e = nn % head_dim;
+    _Float16 *dst_base = (is_v ? V_out : K_out) + e;
+    const uint32_t b0 = (uint32_t)m0 / (uint32_t)L_act, t0 = (uint32_t)m0 % (uint32_t)L_act;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int dm = wrow0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (m0 + dm < M) {
+                const float2 st = stats[m0 + dm];
+                uint32_t b = b0, t = t0 + (uint32_t)dm;
+                if (L_act >= BM) {
+                    if (t >= (uint32_t)L_act) { t -= (uint32_t)L_act; ++b; }
+                } else {
+                    b += t / (uint32_t)L_act;
+                    t %= (uint32_t)L_act;
+                }
+                _Float16 *dst = dst_base + (((int64_t)b * n_heads + h) * (int64_t)L_cap + tok_off + t) * head_dim;
+                half4_t v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], st.x, __builtin_fmaf(st.y, cn[j], bn[j]));
+                *reinterpret_cast<half4_t *>(dst) = v;
+            }
+        }
+    }
+}
+
 }  // namespace gemm
 }  // namespace hk

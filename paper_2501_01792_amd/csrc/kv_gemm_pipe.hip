@@ -24,7 +24,6 @@
 // way into LDS.  LDS: 2 activation buffers + 3 weight buffers of 32 KiB = 160 KiB.
 #include "hk_internal.h"
 #include "kv_gemm_common.h"
-#include <cstdlib>
 
 namespace hk {
 namespace {
@@ -55,7 +54,7 @@ struct Frags {
     half8_t a[PTM], b[PTN];
 };
 
-template <int GROUP_M, int ABL>
+template <int GROUP_M>
 __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
     const _Float16 *__restrict__ act, const float2 *__restrict__ stats,
     const _Float16 *__restrict__ ln_w, const _Float16 *__restrict__ ln_b,
@@ -129,17 +128,14 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
     // form is counted in order with the other vector loads, so waits can be exact.
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<_Float16 *>(b_base), 0, (int)(((int64_t)N - n0) * d * 2), 0x00020000);
-    auto issue_weight_load = [&](int k0, int bslot, int i, bool main_loop = false) {
-        if ((ABL & 2) && main_loop) return;
+    auto issue_weight_load = [&](int k0, int bslot, int i) {
         unsigned char *dst = smem + kLdsB + bslot * kStageBytes + b_dma_wave + i * (PLROWS * BK * 2);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)dst, 16, (int)(b_off[i] * 2), k0 * 2, 0, 0);
     };
-    auto issue_act_load = [&](int k0, RawSet &r, int i, bool main_loop = false) {
-        if ((ABL & 2) && main_loop) return;
+    auto issue_act_load = [&](int k0, RawSet &r, int i) {
         r.a[i] = *reinterpret_cast<const half8_t *>(a_base + k0 + a_off[i]);
     };
-    auto issue_ln_param_loads = [&](int k0, RawSet &r, bool main_loop = false) {
-        if ((ABL & 2) && main_loop) return;
+    auto issue_ln_param_loads = [&](int k0, RawSet &r) {
         r.g = *reinterpret_cast<const half8_t *>(ln_w + k0 + lc * 8);
         r.be = *reinterpret_cast<const half8_t *>(ln_b + k0 + lc * 8);
     };
@@ -148,12 +144,11 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
     auto ln_quarter = [&](const RawSet &r, int abuf, int i, int w) {
         const uint4_t g = __builtin_bit_cast(uint4_t, r.g), be = __builtin_bit_cast(uint4_t, r.be);
         const uint4_t x = __builtin_bit_cast(uint4_t, r.a[i]);
-        ln_y[w] = (ABL & 1) ? x[w] : ln_pair(x[w], a_stat[i].x, a_stat[i].y, g[w], be[w]);
-        if (w == 3 && !(ABL & 8))
+        ln_y[w] = ln_pair(x[w], a_stat[i].x, a_stat[i].y, g[w], be[w]);
+        if (w == 3)
             *reinterpret_cast<uint4_t *>(smem + kLdsA + abuf * kStageBytes + a_st_off + i * (PLROWS * BK * 2)) = ln_y;
     };
-    auto read_frags = [&](Frags &f, int abuf, int bslot, int ks, int which, bool main_loop = true) {
-        if ((ABL & 4) && main_loop) return;
+    auto read_frags = [&](Frags &f, int abuf, int bslot, int ks, int which) {
         // which: 0..3 -> a[which], 4..7 -> b[which - 4]
         if (which < 4)
             f.a[which] = *reinterpret_cast<const half8_t *>(smem + a_rd_wave + abuf * kStageBytes + frag_off[ks] + which * (32 * BK * 2));
@@ -184,9 +179,9 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
         for (int q = 0; q < 16; ++q) {
             acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f0.a[q >> 2], f0.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
             if (q < 8) read_frags(f1, abuf, bs, 1, q);
-            if (q == 0) issue_ln_param_loads(k2, ld, true);
-            if (q < 8) issue_act_load(k2, ld, q, true);
-            if (q >= 8) issue_weight_load(k2, bs2, q - 8, true);
+            if (q == 0) issue_ln_param_loads(k2, ld);
+            if (q < 8) issue_act_load(k2, ld, q);
+            if (q >= 8) issue_weight_load(k2, bs2, q - 8);
             if (q >= 12) ln_quarter(nx, abuf_n, 0, q - 12);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -245,8 +240,7 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) read_frags(f0, 0, 0, 0, q, false);
-        if (ABL & 4) f1 = f0;
+        for (int q = 0; q < 8; ++q) read_frags(f0, 0, 0, 0, q);
     }
 
     int kt = 0, bs = 0;
@@ -263,14 +257,15 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
                                     head_dim, L_act, L_cap, tok_off, bkv, K_out, V_out);
 }
 
-template <int ABL>
-hipError_t launch_pipe_abl(const KvGemmArgs &a, hipStream_t s)
+}  // namespace
+
+hipError_t launch_kv_gemm_pipe(const KvGemmArgs &a, hipStream_t s)
 {
     const int64_t tiles_m64 = (a.M + PBM - 1) / PBM;
     const int tiles_n = (2 * a.d + PBN - 1) / PBN;
     if (tiles_m64 * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
     const int tiles_m = (int)tiles_m64;
-    auto kern = kv_gemm_pipe_kernel<8, ABL>;
+    auto kern = kv_gemm_pipe_kernel<8>;
     static_assert(kLdsTotal == 160 * 1024, "the pipeline uses the whole 160 KiB LDS of a CU");
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
@@ -282,23 +277,6 @@ hipError_t launch_pipe_abl(const KvGemmArgs &a, hipStream_t s)
                        static_cast<_Float16 *>(a.K_out), static_cast<_Float16 *>(a.V_out),
                        a.M, a.d, a.n_heads, a.head_dim, a.L_act, a.L_cap, a.tok_off, tiles_m, tiles_n);
     return hipGetLastError();
-}
-
-}  // namespace
-
-hipError_t launch_kv_gemm_pipe(const KvGemmArgs &a, hipStream_t s)
-{
-    static const int abl = getenv("HK_ABL") ? atoi(getenv("HK_ABL")) : 0;
-    switch (abl) {
-    case 1: return launch_pipe_abl<1>(a, s);
-    case 2: return launch_pipe_abl<2>(a, s);
-    case 4: return launch_pipe_abl<4>(a, s);
-    case 8: return launch_pipe_abl<8>(a, s);
-    case 9: return launch_pipe_abl<9>(a, s);
-    case 6: return launch_pipe_abl<6>(a, s);
-    case 15: return launch_pipe_abl<15>(a, s);
-    default: return launch_pipe_abl<0>(a, s);
-    }
 }
 
 }  // namespace hk

@@ -21,7 +21,8 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hk_regen_kv", "hk_hybrid_decode_attn", "hk_workspace_bytes",
-            "hk_regen_workspace_bytes", "hk_status_string"} <= set(names)
+            "hk_regen_workspace_bytes", "hk_status_string", "hk_prepare_layer", "hk_prepared_bytes",
+            "hk_hybrid_decode_attn_marked"} <= set(names)
     L = hk.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -29,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(hk.hk_shape) == 32
-    assert ctypes.sizeof(hk.hk_layer_params) == 32
+    assert ctypes.sizeof(hk.hk_layer_params) == 40
 
 
 def test_status_strings():
@@ -55,7 +56,7 @@ def test_workspace_bytes():
 def _attn(shape, q=FAKE, Kc=FAKE, Vc=FAKE, L_kv=128, act=FAKE, L_act=128, B=4, lp=None, ratio=0.5,
           out=FAKE, ws=FAKE, ws_bytes=1 << 40):
     if lp is None:
-        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE)
+        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
     return hk.lib().hk_hybrid_decode_attn(ctypes.byref(shape), q, Kc, Vc, L_kv, act, L_act, B,
                                           ctypes.byref(lp) if lp != 0 else None, ratio, out, ws, ws_bytes, None)
 
@@ -79,7 +80,7 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
     assert _attn(ok, Kc=None) == hk.HK_ERR_NULL
     assert _attn(ok, act=None) == hk.HK_ERR_NULL
     assert _attn(ok, ws=None) == hk.HK_ERR_NULL
-    assert _attn(ok, lp=hk.hk_layer_params(FAKE, None, FAKE, FAKE)) == hk.HK_ERR_NULL
+    assert _attn(ok, lp=hk.hk_layer_params(FAKE, None, FAKE, FAKE, None)) == hk.HK_ERR_NULL
     assert _attn(ok, q=FAKE + 8) == hk.HK_ERR_ALIGN
     assert _attn(ok, Vc=FAKE + 2) == hk.HK_ERR_ALIGN
     assert _attn(ok, ws=FAKE + 16) == hk.HK_ERR_ALIGN
@@ -95,7 +96,7 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
 
 def _regen(shape, act=FAKE, B=4, L_act=128, lp=None, K=FAKE, V=FAKE, L_cap=128, tok_off=0, ws=FAKE, ws_bytes=1 << 40):
     if lp is None:
-        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE)
+        lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
     return hk.lib().hk_regen_kv(ctypes.byref(shape), act, B, L_act, ctypes.byref(lp), K, V, L_cap, tok_off,
                                 ws, ws_bytes, None)
 
@@ -109,11 +110,27 @@ def test_regen_kv_rejects_bad_arguments():
     assert _regen(ok, act=None) == hk.HK_ERR_NULL
     assert _regen(ok, K=None) == hk.HK_ERR_NULL
     assert _regen(ok, V=FAKE + 4) == hk.HK_ERR_ALIGN
-    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, None, FAKE)) == hk.HK_ERR_NULL
-    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, FAKE + 6, FAKE)) == hk.HK_ERR_ALIGN
+    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, None, FAKE, None)) == hk.HK_ERR_NULL
+    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, FAKE + 6, FAKE, None)) == hk.HK_ERR_ALIGN
     assert _regen(ok, ws_bytes=16) == hk.HK_ERR_WORKSPACE
     assert _regen(ok, L_act=0, L_cap=0) == hk.HK_OK                         # nothing to do
     assert _regen(ok, B=0) == hk.HK_OK
+
+
+def test_prepare_layer_rejects_bad_arguments():
+    ok = hk.make_shape(768, 12)
+    need = hk.hk_prepared_bytes(ok)
+    assert need >= 2 * 768 * 768 * 2 + 2 * 2 * 768 * 4
+    assert hk.hk_prepared_bytes(hk.make_shape(768, 11)) == 0
+    lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+    call = lambda shape, lp, buf, n: hk.lib().hk_prepare_layer(ctypes.byref(shape), ctypes.byref(lp), buf, n, None)
+    assert call(hk.make_shape(768, 11), lp, FAKE, need) == hk.HK_ERR_SHAPE
+    assert call(ok, hk.hk_layer_params(FAKE, FAKE, None, FAKE, None), FAKE, need) == hk.HK_ERR_NULL
+    assert call(ok, lp, None, need) == hk.HK_ERR_NULL
+    assert call(ok, lp, FAKE + 16, need) == hk.HK_ERR_ALIGN
+    assert call(ok, lp, FAKE, need - 1) == hk.HK_ERR_WORKSPACE
+    # a misaligned prepared buffer inside the layer parameters is caught by the consumers
+    assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, FAKE + 16)) == hk.HK_ERR_ALIGN
 
 
 def test_binding_refuses_cpu_tensors():

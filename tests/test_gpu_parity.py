@@ -47,8 +47,10 @@ def _cfg(name, d, H, B, L, ratio, seed):
     return synth.LayerConfig(name, d, H, B, L, ratio, seed)
 
 
-def _run_hybrid(hk, cfg, batch, **kw):
+def _run_hybrid(hk, cfg, batch, prepared=False, **kw):
     lp = tuple(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    if prepared:            # one-time layer preparation; selects the folded-LayerNorm kernel for 256 tiles
+        lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
     Kc = _gpu(batch["K_cache"]) if cfg.L_kv else None
     Vc = _gpu(batch["V_cache"]) if cfg.L_kv else None
     act = _gpu(batch["act"]) if cfg.L_act else None
@@ -78,11 +80,11 @@ SMALL = [
 
 
 @pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
-@pytest.mark.parametrize("tile", [128, 256])
-def test_hybrid_step_matches_oracle(hk, oracle, cfg, tile):
-    print("case", cfg, "tile", tile, flush=True)
+@pytest.mark.parametrize("tile,prepared", [(128, False), (256, False), (256, True)])
+def test_hybrid_step_matches_oracle(hk, oracle, cfg, tile, prepared):
+    print("case", cfg, "tile", tile, "prepared", prepared, flush=True)
     batch = synth.make_batch(cfg)
-    out, K, V = _run_hybrid(hk, cfg, batch, gemm_tile=tile)
+    out, K, V = _run_hybrid(hk, cfg, batch, prepared=prepared, gemm_tile=tile)
     ref_out, ref_K, ref_V = _oracle_hybrid(oracle, cfg, batch)
     if cfg.L_act:
         _check("K_regen", K, ref_K[:, :, cfg.L_kv:])
@@ -111,14 +113,16 @@ def test_regen_kv_into_cache_slot(hk, oracle, cfg):
     assert (V[:, :, :off] == -7.0).all() and (V[:, :, off + L_act:] == -7.0).all()
 
 
-def test_layernorm_statistics_under_offset_and_scale(hk, oracle):
-    """Rows with a large mean and a non-unit spread: the fused LayerNorm must still match."""
+@pytest.mark.parametrize("tile,prepared", [(0, False), (256, False), (256, True)])
+def test_layernorm_statistics_under_offset_and_scale(hk, oracle, tile, prepared):
+    """Rows with a large mean and a non-unit spread: the fused LayerNorm must still match, also
+    when it is applied to the accumulators (prepared layer), where mean * c[n] has to cancel."""
     cfg = _cfg("shifted", 1024, 8, 2, 130, 0.0, 21)
     batch = synth.make_batch(cfg)
     rng = np.random.default_rng(5)
     act = batch["act"].astype(np.float32) * rng.uniform(0.1, 6.0, size=(cfg.B, cfg.L, 1)) + rng.uniform(-20, 20, size=(cfg.B, cfg.L, 1))
     batch["act"] = act.astype(np.float16)
-    out, K, V = _run_hybrid(hk, cfg, batch)
+    out, K, V = _run_hybrid(hk, cfg, batch, prepared=prepared, gemm_tile=tile)
     ref_out, ref_K, ref_V = _oracle_hybrid(oracle, cfg, batch)
     _check("K_regen", K, ref_K)
     _check("V_regen", V, ref_V)
@@ -183,13 +187,13 @@ def test_repeatable(hk):
 
 
 # ------------------------------------------------------------------ full benchmark sizes, sampled
-def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99):
+def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99, prepared=False):
     """Runs the GPU path on the whole config and checks (a) regenerated K/V of randomly sampled
     checkpoint rows and (b) the attention output of sampled (sequence, head) pairs against the
     oracle, which computes exactly those outputs from the same inputs (all K/V rows of the
     sampled head, via Eq. 7 restricted to that head's weight rows)."""
     batch = synth.make_batch(cfg, threads=16)
-    out, K, V = _run_hybrid(hk, cfg, batch)
+    out, K, V = _run_hybrid(hk, cfg, batch, prepared=prepared)
     H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
     rng = np.random.default_rng(seed)
     if cfg.L_act:
@@ -219,6 +223,7 @@ def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99):
     _check("out[sampled (b,h)]", np.stack(got), np.stack(ref))
 
 
-def test_full_size_opt6p7b_sampled(hk, oracle):
+@pytest.mark.parametrize("prepared", [False, True])
+def test_full_size_opt6p7b_sampled(hk, oracle, prepared):
     """The configuration the benchmark times (OPT-6.7B-shaped layer, B=32, L=1024, ratio 0.5)."""
-    _sampled_oracle_check(hk, oracle, synth.CONFIGS["opt6.7b"])
+    _sampled_oracle_check(hk, oracle, synth.CONFIGS["opt6.7b"], prepared=prepared)
