@@ -31,6 +31,23 @@ def algorithmic_counts(cfg):
     return gemm_flops, attn_bytes
 
 
+def profiled_traffic(cfg_name):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE / WRITE_SIZE, scaled against a plain copy of known size), or {} if there is none."""
+    path = os.path.join(ROOT, "profiles", "hybrid_step_%s.txt" % cfg_name)
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("TRAFFIC "):
+                    parts = line.split()
+                    kv = dict(p.split("=") for p in parts[2:])
+                    out[parts[1]] = (float(kv["fetch_kib"]) + float(kv["write_kib"])) * 1024.0
+    except OSError:
+        pass
+    return out
+
+
 def cpu_baseline(cfg, budget_s=15.0):
     """The CPU oracle (fp32 build, as it stands) timed on a bounded sample of the same workload:
     whole sequences of the batch, as many as fit the time budget."""
@@ -149,15 +166,17 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     gemm_flops, attn_bytes = algorithmic_counts(cfg)
+    traffic = profiled_traffic(cfg.name) if args.ratio is None else {}
+    gemm_kernel = "kv_gemm_pipe_kernel" if args.unprepared else "kv_gemm_fold_kernel"
     roofline = None
     if cfg.M > 0 and dur["kv_gemm"] > 0:
         ach = gemm_flops / (dur["kv_gemm"] * 1e-3) / 1e12
         roofline = {"kernel": "kv_gemm", "bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_F16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F16_TFLOPS, "traffic": None,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F16_TFLOPS, "traffic": traffic.get(gemm_kernel),
                     "avg_ms": dur["kv_gemm"]}
     ach_bw = attn_bytes / (dur["flash_decode"] * 1e-3) / 1e9
     roofline_attn = {"kernel": "flash_decode", "bound": "hbm", "achieved": ach_bw, "peak": PEAK_HBM_GBPS,
-                     "unit": "GB/s", "frac": ach_bw / PEAK_HBM_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": ach_bw / PEAK_HBM_GBPS, "traffic": traffic.get("flash_decode_kernel"),
                      "avg_ms": dur["flash_decode"]}
     if roofline is None:
         roofline = roofline_attn
@@ -183,6 +202,12 @@ def main():
         "roofline": roofline,
         "roofline_attn": roofline_attn,
     }
+
+    # What a loop of nothing but fp16 MFMAs sustains on this GPU: with random operands the shader
+    # clock drops, so that rate (not the published peak) is the practical ceiling of the GEMM.
+    result["mfma_rate_probe_tflops"] = {"zero_operands": hk.probe_mfma_rate(False), "random_operands": hk.probe_mfma_rate(True)}
+    if roofline.get("bound") == "mfma":
+        roofline["frac_of_probe_random"] = roofline["achieved"] / result["mfma_rate_probe_tflops"]["random_operands"]
 
     if not args.no_cpu_baseline:
         base, n, ref = cpu_baseline(cfg)

@@ -183,6 +183,19 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape,
                                  void *workspace, size_t workspace_bytes, void *stream,
                                  void **events, int32_t n_events);
 
+/*
+ * Measurement aid (no operation of the paper): runs a loop of back-to-back
+ * v_mfma_f32_32x32x16_f16 on every compute unit (4 wavefronts each, `iters`
+ * x 16 instructions per wavefront) with all-zero (random_operands == 0) or
+ * random fp16 operands and returns the sustained rate in TFLOP/s through
+ * `tflops_out` (HOST pointer).  `sink` is device scratch of at least
+ * (number of compute units) * 1024 bytes.  Synchronises the stream.  The rate
+ * with random operands is the practical ceiling of any fp16 MFMA kernel on the
+ * GPU at hand; it is reported next to the projection kernel's roofline figure.
+ */
+int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
+                       float *tflops_out, void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *hk_status_string(int status);
 

@@ -64,6 +64,8 @@ def lib():
                                             vp, vp, sz, vp]
         L.hk_hybrid_decode_attn_marked.restype = ctypes.c_int
         L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
+        L.hk_probe_mfma_rate.restype = ctypes.c_int
+        L.hk_probe_mfma_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         L.hk_status_string.restype = ctypes.c_char_p
         L.hk_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -84,6 +86,17 @@ def hk_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int) -> int:
 
 def hk_regen_workspace_bytes(shape: hk_shape, B: int, L_act: int) -> int:
     return int(lib().hk_regen_workspace_bytes(ctypes.byref(shape), B, L_act))
+
+
+def probe_mfma_rate(random_operands: bool, iters: int = 20000, stream=None) -> float:
+    """hk_probe_mfma_rate: sustained TFLOP/s of a pure fp16 MFMA loop with zero / random operands."""
+    sink = new_workspace(1 << 20)
+    out = ctypes.c_float()
+    st = lib().hk_probe_mfma_rate(1 if random_operands else 0, iters, _dev_ptr(sink, "sink"), sink.numel(),
+                                  ctypes.byref(out), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_probe_mfma_rate")
+    return float(out.value)
 
 
 # ----------------------------------------------------------------------------- torch-facing calls

@@ -1,0 +1,77 @@
+// Measurement aid: the matrix-core rate this GPU sustains on a loop of nothing but
+// v_mfma_f32_32x32x16_f16, with all-zero or with random operands.  On MI355X the two differ widely
+// (the shader clock drops under random fp16 operands), so the second number is the practical
+// ceiling against which the projection kernel's fraction of the published peak should be read.
+#include "../../include/hybridkv.h"
+#include <hip/hip_runtime.h>
+
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters, int random_operands)
+{
+    float16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    half8_t a[4], b[4];
+    unsigned x = 12345u + threadIdx.x * 7919u + blockIdx.x * 104729u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            x = x * 1664525u + 1013904223u;
+            a[i][e] = random_operands ? (_Float16)(((int)(x >> 8) % 2001 - 1000) * 0.001f) : (_Float16)0.f;
+            x = x * 1664525u + 1013904223u;
+            b[i][e] = random_operands ? (_Float16)(((int)(x >> 8) % 2001 - 1000) * 0.00002f) : (_Float16)0.f;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[q >> 2], b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace
+
+extern "C" int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
+                                  float *tflops_out, void *stream)
+{
+    if (!sink || !tflops_out) return HK_ERR_NULL;
+    if (iters <= 0 || iters > (1 << 22)) return HK_ERR_SHAPE;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return HK_ERR_LAUNCH;
+    if (sink_bytes < (size_t)cus * 256 * sizeof(float)) return HK_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return HK_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return HK_ERR_LAUNCH; }
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(cus), dim3(256), 0, s, sink, iters / 8 + 1, random_operands);   // warm up
+    hipEventRecord(e0, s);
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(cus), dim3(256), 0, s, sink, iters, random_operands);
+    hipEventRecord(e1, s);
+    int rc = HK_OK;
+    float ms = 0.f;
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f)
+        rc = HK_ERR_LAUNCH;
+    else
+        *tflops_out = (float)((double)cus * 4 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return rc;
+}
