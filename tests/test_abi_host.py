@@ -141,3 +141,23 @@ def test_binding_refuses_cpu_tensors():
         hk.regen_kv(x, w, w, torch.zeros(1536, 768, dtype=torch.float16), torch.zeros(1536, dtype=torch.float16), 12,
                     K_out=torch.zeros(1, 12, 4, 64, dtype=torch.float16), V_out=torch.zeros(1, 12, 4, 64, dtype=torch.float16),
                     workspace=torch.zeros(1024, dtype=torch.uint8))
+
+
+def test_algorithmic_byte_and_flop_counts():
+    """The roofline's per-unit figures: a cached token costs 4d bytes per layer in fp16 (K and V),
+    a checkpoint half of that (Sec. 4.1: an ACT block is half a KV block), and regenerating a
+    token costs 4 d^2 flops (Eq. 7: d x 2d multiply-adds).  The 4d-byte figure is pinned by the
+    KV traffic the paper quotes for OPT-30B with 1024-token inputs (Sec. 3.1): 21 GB per token
+    step at batch 16 and 168 GB at batch 128, i.e. B * 1024 tokens * 48 layers * 4d bytes, d = 7168."""
+    import bench
+    from paper_2501_01792_amd import synth
+    cfg = synth.CONFIGS["opt30b"]
+    flops, attn_bytes = bench.algorithmic_counts(cfg)
+    per_token_layer = attn_bytes / (cfg.B * cfg.L)
+    assert per_token_layer == 4 * cfg.d
+    assert flops == 4.0 * cfg.M * cfg.d ** 2
+    gib = 1024.0 ** 3
+    assert round(16 * 1024 * 48 * per_token_layer / gib, 1) == 21.0
+    assert round(128 * 1024 * 48 * per_token_layer / gib, 1) == 168.0
+    # the checkpoint of a token is d fp16 values: half of its K/V
+    assert cfg.d * 2 * 2 == per_token_layer
