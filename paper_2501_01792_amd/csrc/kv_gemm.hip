@@ -147,9 +147,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void kv_gemm_kernel(
         __syncthreads();
     }
 
-    // ---- epilogue: bias, fp16, head split
-    store_head_split<BM, TM, TN>(acc, lane, m0, wm * WM, n0 + wn * WN + TN * (lane & 31), M, d, n_heads, head_dim,
-                                 L_act, L_cap, tok_off, bkv, K_out, V_out);
+    // ---- epilogue: bias, fp16, head split (the loop's last barrier has retired every read of the stages)
+    RowDst *tab = reinterpret_cast<RowDst *>(smem_raw);
+    fill_row_table<BM, 64 * WAVES_M * WAVES_N>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, nullptr);
+    const int nb = n0 + wn * WN + TN * (lane & 31);
+    float cn[TN], bn[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        cn[j] = 0.f;
+        bn[j] = nb < 2 * d ? (float)bkv[nb + j] : 0.f;
+    }
+    __syncthreads();
+    store_head_split<TM, TN>(acc, lane, tab, wm * WM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int GROUP_M>

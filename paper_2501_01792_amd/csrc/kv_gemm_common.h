@@ -79,100 +79,73 @@ __device__ __forceinline__ int weight_row_of_lds_row(int rho)
     return w * WN + TN * (r & 31) + (r >> 5);
 }
 
-// Epilogue of one wavefront: bias in fp32, round to fp16, head-split store into [B, H, L_cap, dh].
-// acc[i][j][r] is MFMA block (i, j), register r: token row m0 + wrow0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,
+// Where a token row of an output tile goes, and the LayerNorm statistics that its accumulators
+// are to be combined with.  One entry per tile row, built once per tile in LDS (the operand
+// stages are dead by then) so that the store loop itself has no division, no global load and
+// no divergent control flow.
+struct __align__(16) RowDst {
+    float rstd, nmr;      // (1, 0) when the accumulators already hold the projection of LayerNorm-ed rows
+    int64_t base;         // element offset of K[b, 0, tok_off + t, 0]; negative: row is past the end, store nothing
+};
+
+// Fills tab[0 .. BM) for the tile whose first row is m0.  Call between two workgroup barriers.
+template <int BM, int NT>
+__device__ __forceinline__ void fill_row_table(RowDst *tab, int tid, int64_t m0, int64_t M,
+                                               int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
+                                               const float2 *__restrict__ stats)
+{
+    for (int row = tid; row < BM; row += NT) {
+        const int64_t m = m0 + row;
+        RowDst e;
+        e.rstd = 1.f; e.nmr = 0.f; e.base = -1;
+        if (m < M) {
+            const uint32_t b = (uint32_t)m / (uint32_t)L_act, t = (uint32_t)m % (uint32_t)L_act;   // M < 2^31
+            e.base = (((int64_t)b * n_heads) * L_cap + tok_off + t) * head_dim;
+            if (stats) { const float2 st = stats[m]; e.rstd = st.x; e.nmr = st.y; }
+        }
+        tab[row] = e;
+    }
+}
+
+// Epilogue of one wavefront: out = rstd * acc + (nmr * cn + bn) in fp32, round to fp16, head-split
+// store into [B, H, L_cap, dh].  With the row table's (rstd, nmr) = (1, 0) this is acc + bn, the plain
+// bias add; with the row statistics it is the folded LayerNorm (cn = c[n], bn = b'[n]).
+// acc[i][j][r] is MFMA block (i, j), register r: tile row wrow0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,
 // output feature nb + j with nb = n0 + wcol0 + TN * (lane % 32).
-template <int BM, int TM, int TN>
-__device__ __forceinline__ void store_head_split(const float16_t (&acc)[TM][TN], int lane,
-                                                 int64_t m0, int wrow0, int nb, int64_t M, int d,
-                                                 int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
-                                                 const _Float16 *__restrict__ bkv,
+template <int TM, int TN>
+__device__ __forceinline__ void store_head_split(const float16_t (&acc)[TM][TN], int lane, const RowDst *tab,
+                                                 int wrow0, int nb, int d, int head_dim, int L_cap,
+                                                 const float (&cn)[TN], const float (&bn)[TN],
                                                  _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
 {
     if (nb >= 2 * d) return;                       // 2d % TN == 0: the lane's features are all in or all out
-    float bias[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bias[j] = (float)bkv[nb + j];
     const bool is_v = nb >= d;
     const int nn = is_v ? nb - d : nb;
     const int h = nn / head_dim, e = nn % head_dim;
-    _Float16 *dst_base = (is_v ? V_out : K_out) + e;
-    // (sequence, token) of the tile's first row, once per workgroup; rows below it are reached
-    // by adding the row offset and carrying into the sequence index.
-    const uint32_t b0 = (uint32_t)m0 / (uint32_t)L_act, t0 = (uint32_t)m0 % (uint32_t)L_act;
+    _Float16 *dst_base = (is_v ? V_out : K_out) + ((int64_t)h * L_cap * head_dim + e);
+    const RowDst *my = tab + wrow0 + 4 * (lane >> 5);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int dm = wrow0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m0 + dm < M) {
-                uint32_t b = b0, t = t0 + (uint32_t)dm;
-                if (L_act >= BM) {                 // at most one carry inside a tile
-                    if (t >= (uint32_t)L_act) { t -= (uint32_t)L_act; ++b; }
-                } else {
-                    b += t / (uint32_t)L_act;
-                    t %= (uint32_t)L_act;
-                }
-                _Float16 *dst = dst_base + (((int64_t)b * n_heads + h) * (int64_t)L_cap + tok_off + t) * head_dim;
+            const RowDst row = my[i * 32 + 8 * (r >> 2) + (r & 3)];
+            if (row.base >= 0) {
+                _Float16 *dst = dst_base + row.base;
                 if constexpr (TN == 4) {
                     half4_t v;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = (_Float16)(acc[i][j][r] + bias[j]);
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
                     *reinterpret_cast<half4_t *>(dst) = v;
                 } else if constexpr (TN == 2) {
                     half2_t v;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) v[j] = (_Float16)(acc[i][j][r] + bias[j]);
+                    for (int j = 0; j < 2; ++j)
+                        v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
                     *reinterpret_cast<half2_t *>(dst) = v;
                 } else {
-                    *dst = (_Float16)(acc[i][0][r] + bias[0]);
+                    *dst = (_Float16)__builtin_fmaf(acc[i][0][r], row.rstd, __builtin_fmaf(row.nmr, cn[0], bn[0]));
                 }
-            }
-        }
-    }
-}
-
-// Epilogue of one wavefront for the folded-LayerNorm kernel: the accumulators hold x . W'[n,:] of
-// the raw rows; out = rstd * acc + (nmr * c[n] + b'[n]) with (rstd, nmr) = stats[row], in fp32,
-// then fp16 and the head-split store.  Register / row / feature layout as in store_head_split.
-template <int BM, int TM, int TN>
-__device__ __forceinline__ void store_head_split_fold(const float16_t (&acc)[TM][TN], int lane,
-                                                      int64_t m0, int wrow0, int nb, int64_t M, int d,
-                                                      int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
-                                                      const float2 *__restrict__ stats,
-                                                      const float *__restrict__ cvec, const float *__restrict__ bvec,
-                                                      _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
-{
-    static_assert(TN == 4, "packs four features per store");
-    if (nb >= 2 * d) return;
-    float cn[TN], bn[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) { cn[j] = cvec[nb + j]; bn[j] = bvec[nb + j]; }
-    const bool is_v = nb >= d;
-    const int nn = is_v ? nb - d : nb;
-    const int h = nn / head_dim, e = nn % head_dim;
-    _Float16 *dst_base = (is_v ? V_out : K_out) + e;
-    const uint32_t b0 = (uint32_t)m0 / (uint32_t)L_act, t0 = (uint32_t)m0 % (uint32_t)L_act;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int dm = wrow0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m0 + dm < M) {
-                const float2 st = stats[m0 + dm];
-                uint32_t b = b0, t = t0 + (uint32_t)dm;
-                if (L_act >= BM) {
-                    if (t >= (uint32_t)L_act) { t -= (uint32_t)L_act; ++b; }
-                } else {
-                    b += t / (uint32_t)L_act;
-                    t %= (uint32_t)L_act;
-                }
-                _Float16 *dst = dst_base + (((int64_t)b * n_heads + h) * (int64_t)L_cap + tok_off + t) * head_dim;
-                half4_t v;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], st.x, __builtin_fmaf(st.y, cn[j], bn[j]));
-                *reinterpret_cast<half4_t *>(dst) = v;
             }
         }
     }

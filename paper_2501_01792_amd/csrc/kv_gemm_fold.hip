@@ -182,8 +182,18 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // drain the loads issued past the end before LDS is released
 
     // ---- epilogue: LayerNorm statistics, constants of the layer, fp16, head split
-    store_head_split_fold<FBM, FTM, FTN>(acc, lane, m0, wm * FWM, n0 + wn * FWN + FTN * (lane & 31), M, d, n_heads,
-                                         head_dim, L_act, L_cap, tok_off, stats, cvec, bvec, K_out, V_out);
+    __syncthreads();                                           // every wavefront is done with the ring
+    RowDst *tab = reinterpret_cast<RowDst *>(smem);
+    fill_row_table<FBM, FNT>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
+    const int nb = n0 + wn * FWN + FTN * (lane & 31);
+    float cn[FTN], bn[FTN];
+#pragma unroll
+    for (int j = 0; j < FTN; ++j) {
+        cn[j] = nb < N ? cvec[nb + j] : 0.f;
+        bn[j] = nb < N ? bvec[nb + j] : 0.f;
+    }
+    __syncthreads();
+    store_head_split<FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
 }
 
 // One wavefront per output feature n: W'[n,:] = fp16(gamma * W[n,:]), c[n] = sum_k W'[n,k],

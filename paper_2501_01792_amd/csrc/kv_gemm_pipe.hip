@@ -253,8 +253,18 @@ __global__ __launch_bounds__(PNT) void kv_gemm_pipe_kernel(
     if (kt < nk) step(kt, bs, raw0, raw1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // drain the loads issued past the end before LDS is released
 
-    store_head_split<PBM, PTM, PTN>(acc, lane, m0, wm * PWM, n0 + wn * PWN + PTN * (lane & 31), M, d, n_heads,
-                                    head_dim, L_act, L_cap, tok_off, bkv, K_out, V_out);
+    __syncthreads();                                       // every wavefront is done with the stages
+    RowDst *tab = reinterpret_cast<RowDst *>(smem);
+    fill_row_table<PBM, PNT>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, nullptr);
+    const int nb = n0 + wn * PWN + PTN * (lane & 31);
+    float cn[PTN], bn[PTN];
+#pragma unroll
+    for (int j = 0; j < PTN; ++j) {
+        cn[j] = 0.f;
+        bn[j] = nb < 2 * d ? (float)bkv[nb + j] : 0.f;
+    }
+    __syncthreads();
+    store_head_split<PTM, PTN>(acc, lane, tab, wm * PWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
 }
 
 }  // namespace
