@@ -10,43 +10,95 @@
 // the per-row statistics of ln_stats.  The raw fp16 checkpoint rows feed the matrix cores as
 // they are; the row statistics enter in the epilogue, in fp32.
 //
-// Kernel shape (CDNA4): 256 x 256 output tile, 4 wavefronts (128 x 128 accumulators each, in
-// AGPRs), k advanced 32 at a time through a ring of 5 LDS stages (activations 16 KiB + weights
-// 16 KiB each = 160 KiB).  Both operands are fetched with buffer_load ... lds (16 bytes per lane,
-// a wavefront fills 16 consecutive 64-byte rows), four stages ahead of their use; the XOR
-// swizzle of the 16-byte chunk index is applied on the global side.  No operand passes through
-// a vector register before its fragment read, and the only vector-memory waits are the explicit
-// per-step "stage kt+1 has landed" waits.  Fragments are double-buffered in registers; every
-// MFMA slot carries at most one LDS read or one direct load.
+// Kernel shape (CDNA4).  One workgroup per compute unit, resident for the whole launch (grid =
+// number of compute units); it walks its share of the 256 x 256 output tiles.  4 wavefronts,
+// 128 x 128 accumulators each (AGPRs).  The reduction axis advances in k blocks of 64; a k block
+// of one operand is a "unit" of 256 rows x 128 bytes = 32 KiB, and the 160 KiB of LDS are a ring of
+// 5 units through which the units of all the workgroup's tiles stream in consumption order
+// (activations of block g, weights of block g, activations of block g+1, ...): the loads run
+// across tile boundaries, so only the first tile of a workgroup sees a cold pipeline.
+//   * Loads are buffer_load ... lds, 16 bytes per lane; the 8 lanes of an LDS row fetch one whole
+//     128-byte line of a global row (half-line requests halve the useful rate of the L2 channels).
+//     The XOR swizzle of the 16-byte chunk index, (row / 2) % 8, is applied on the global side; it
+//     makes the 32-row x 16-byte fragment reads (ds_read_b128) conflict-free.
+//   * While k block g is consumed (64 MFMAs per wavefront) the activations of block g+2 are issued
+//     during its first half and the weights of block g+2 right after the barrier in its last
+//     quarter, into the slot that barrier has just freed.  One barrier per k block.
+//   * Fragments are double-buffered in registers; every MFMA slot carries at most one LDS read
+//     and one direct load.
+//   * End of a tile: a row table (destination offset + statistics per row) is built in the one
+//     slot that is free at that moment; accumulators are read out of the AGPRs four rows at a
+//     time, combined with the statistics, rounded to fp16 and stored head-split.  The next
+//     tile's first MFMAs start from a zero C operand instead of cleared accumulators.
 #include "hk_internal.h"
 #include "kv_gemm_common.h"
+
+#include <type_traits>
 
 namespace hk {
 namespace {
 
 using namespace gemm;
 
-constexpr int FBM = 256, FBN = 256, FBK = 32;
+constexpr int FBM = 256, FBN = 256, FBK = 64;
 constexpr int FNT = 256;                                    // 4 wavefronts, 2 x 2
 constexpr int FWM = 128, FWN = 128, FTM = 4, FTN = 4;
-constexpr int kStages = 5;
-constexpr int kOperandBytes = 256 * FBK * 2;                // 16 KiB: one operand of one stage
-constexpr int kRingStageBytes = 2 * kOperandBytes;          // 32 KiB
-constexpr int kRingBytes = kStages * kRingStageBytes;       // 160 KiB
-constexpr int kRowBytes = FBK * 2;                          // 64-byte LDS rows, 4 chunks of 16 bytes
-constexpr int kDmaPerStage = 8;                             // direct loads one lane issues per stage (4 + 4)
-constexpr int kAhead = 4;                                   // stages in flight ahead of the one being consumed
-// At the per-step wait, stages kt+2 .. kt+4 (3 x 8 loads) may still be in flight.
-#define HK_FOLD_WAIT_NEXT_STAGE() asm volatile("s_waitcnt vmcnt(24)" ::: "memory")
-static_assert((kAhead - 1) * kDmaPerStage == 24, "the wait above is written for 24 loads in flight");
-// Inside a step the wait sits after 4 of the step's 8 loads: stages kt+2, kt+3 and half of kt+4 may fly.
-#define HK_FOLD_WAIT_IN_STEP() asm volatile("s_waitcnt vmcnt(20)" ::: "memory")
+constexpr int kSlots = 5;
+constexpr int kRowBytes = FBK * 2;                          // 128-byte LDS rows: 8 chunks of 16 bytes
+constexpr int kUnitBytes = 256 * kRowBytes;                 // 32 KiB: one operand of one k block
+constexpr int kRingBytes = kSlots * kUnitBytes;             // 160 KiB
+constexpr int kLoadsPerUnit = 8;                            // direct loads one lane issues per unit
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 struct Frags {
     half8_t a[FTM], b[FTN];
 };
+
+__device__ __forceinline__ int next2(int s) { s += 2; return s >= kSlots ? s - kSlots : s; }
+
+
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile(const float16_t (&acc)[TM][TN], int lane, const RowDst *tab,
+                                                  int wrow0, int nb, int d, int head_dim, int L_cap,
+                                                  const float (&cn)[TN], const float (&bn)[TN],
+                                                  _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
+{
+    if (nb >= 2 * d) return;
+    const bool is_v = nb >= d;
+    const int nn = is_v ? nb - d : nb;
+    const int h = nn / head_dim, e = nn % head_dim;
+    _Float16 *dst_base = (is_v ? V_out : K_out) + ((int64_t)h * L_cap * head_dim + e);
+    const RowDst *my = tab + wrow0 + 4 * (lane >> 5);
+    // groups of 4 consecutive rows (one r / 4 of one block row); the table rows of the next group are
+    // fetched while the current group is converted and stored
+    RowDst rows[2][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) rows[0][k] = my[k];
+#pragma unroll
+    for (int gi = 0; gi < TM * 4; ++gi) {
+        const int i = gi >> 2, rg = gi & 3;
+        if (gi + 1 < TM * 4) {
+            const int i1 = (gi + 1) >> 2, rg1 = (gi + 1) & 3;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) rows[(gi + 1) & 1][k] = my[i1 * 32 + 8 * rg1 + k];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const RowDst row = rows[gi & 1][k];
+            const int r = 4 * rg + k;
+            half4_t v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float a;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));
+                v[j] = (_Float16)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
+            }
+            if (row.base >= 0) *reinterpret_cast<half4_t *>(dst_base + row.base) = v;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
 
 template <int GROUP_M>
 __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
@@ -64,136 +116,171 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    int tile_m, tile_n;
-    tile_coords<GROUP_M>(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int64_t m0 = (int64_t)tile_m * FBM;
-    const int n0 = tile_n * FBN;
+    const int n_tiles = tiles_m * tiles_n;
+    const int my_tiles = (n_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // >= 1: grid <= n_tiles
+    const int nks = d / FBK;                                   // host guarantees d % 64 == 0 and nks >= 2
+    const int G = my_tiles * nks;                              // k blocks this workgroup consumes, over all its tiles
 
-    // ---- direct-load roles.  The i-th load of a wavefront fills LDS rows 64 i + 16 wave .. + 15 of an
-    // operand stage; lane l writes row (l / 4), physical chunk (l % 4), so it fetches the logical
-    // chunk (l % 4) ^ ((row / 4) % 4) of that row: a ds_read_b128 is served 16 lanes (256 bytes, 64
-    // banks) at a time, and 16 consecutive rows of one logical chunk then fall into 16 distinct slots.
-    const int dr = lane >> 2;                                  // row inside the 16-row group
-    const int dchunk = (lane & 3) ^ ((lane >> 4) & 3);         // logical 16-byte chunk to fetch
-    int a_voff[4], b_voff[4];                                  // byte offsets from the tile bases
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rho = 64 * i + 16 * wave + dr;
-        int64_t m = m0 + rho;
-        if (m >= M) m = M - 1;                                 // clamp: rows past the end are computed, never stored
-        a_voff[i] = ((int)(m - m0) * d + dchunk * 8) * 2;
-        int n = n0 + weight_row_of_lds_row<FWN, FTN>(rho);
-        if (n >= N) n = N - 1;
-        b_voff[i] = ((n - n0) * d + dchunk * 8) * 2;
-    }
-    const _Float16 *a_base = act + m0 * (int64_t)d;
-    const _Float16 *b_base = Wp + (int64_t)n0 * d;
-    int64_t a_bytes = (M - m0) * (int64_t)d * 2, b_bytes = ((int64_t)N - n0) * d * 2;
-    if (a_bytes > 0x7fffffff) a_bytes = 0x7fffffff;            // a tile spans < 2^23 bytes
-    if (b_bytes > 0x7fffffff) b_bytes = 0x7fffffff;
-    const __amdgpu_buffer_rsrc_t a_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(a_base), 0, (int)a_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t b_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(b_base), 0, (int)b_bytes, 0x00020000);
-    const int dma_wave = 16 * wave * kRowBytes;                // + 64 i rows, + stage, + operand
+    // ---- direct-load roles.  One load of a wavefront fills 8 consecutive 128-byte LDS rows (1 KiB): lane l
+    // writes row l / 8, physical chunk l % 8, and fetches the logical chunk (l % 8) ^ ((row / 2) % 8) of that
+    // row, so that the 8 lanes of a row fetch one whole 128-byte line.  Load i of wavefront w covers LDS
+    // rows 8 (w + 4 i) .. + 7; (row / 2) % 8 = (4 (w % 2) + l / 16) % 8 for all of them.
+    const int l_row = lane >> 3;
+    const int l_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    const int a_voff0 = ((8 * wave + l_row) * d + l_chunk * 8) * 2;          // activation row 8 w + l/8 (+ 32 i)
+    const int b_voff0 = ((32 * wave + 4 * l_row) * d + l_chunk * 8) * 2;     // weight row 32 w + 4 (l/8) (+ 128 (i/4) + i%4)
+    const int dma_wave = wave * 1024;                                        // + 4096 i, + slot
 
-    // ---- fragment reads: row (lane % 32) + 32 i of the wavefront's sub-tile, chunk 2 ks + lane / 32
+    // state of the load cursor: the k block whose units are issued next
+    __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
+    int a_vmax = 0, b_vmax = 0;                                // clamp: rows past the end read the last valid row
+    int ld_j = 0, ld_kb = 0, ld_g = 0;
+    auto set_load_tile = [&](int j) {
+        int tm, tn;
+        tile_coords<GROUP_M>((int)blockIdx.x + j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
+        const int64_t m0 = (int64_t)tm * FBM;
+        const int n0 = tn * FBN;
+        int64_t a_bytes = (M - m0) * (int64_t)d * 2, b_bytes = ((int64_t)N - n0) * d * 2;
+        if (a_bytes > 0x7fffffff) a_bytes = 0x7fffffff;        // a tile spans < 2^30 bytes
+        if (b_bytes > 0x7fffffff) b_bytes = 0x7fffffff;
+        a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(act + m0 * (int64_t)d), 0, (int)a_bytes, 0x00020000);
+        b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(Wp + (int64_t)n0 * d), 0, (int)b_bytes, 0x00020000);
+        const int ra = (M - m0 < FBM) ? (int)(M - m0) - 1 : FBM - 1;
+        const int rb = (N - n0 < FBN) ? (N - n0) - 1 : FBN - 1;
+        a_vmax = (ra * d + l_chunk * 8) * 2;
+        b_vmax = (rb * d + l_chunk * 8) * 2;
+    };
+    auto advance_load = [&]() {                                // past the last k block the cursor stays on it
+        if (ld_g + 1 < G) {
+            ++ld_g;
+            if (++ld_kb == nks) { ld_kb = 0; ++ld_j; set_load_tile(ld_j); }
+        }
+    };
+    auto issue_a = [&](int slot, int i) {
+        int v = a_voff0 + i * 32 * d * 2;
+        v = v < a_vmax ? v : a_vmax;
+        unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
+    };
+    auto issue_b = [&](int slot, int i) {
+        int v = b_voff0 + ((i >> 2) * 128 + (i & 3)) * d * 2;
+        v = v < b_vmax ? v : b_vmax;
+        unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
+    };
+
+    // ---- fragment reads: row (lane % 32) + 32 i of the wavefront's sub-tile, logical chunk 2 ks + lane / 32
     const int fr = lane & 31, fc = lane >> 5;
-    int frag_off[2];
+    int frag_off[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) frag_off[ks] = fr * kRowBytes + (((2 * ks + fc) ^ ((fr >> 2) & 3)) << 4);
+    for (int ks = 0; ks < 4; ++ks) frag_off[ks] = fr * kRowBytes + (((2 * ks + fc) ^ ((fr >> 1) & 7)) << 4);
     const int a_rd_wave = wm * FWM * kRowBytes;
-    const int b_rd_wave = kOperandBytes + wn * FWN * kRowBytes;
-
-    const int nk = d / FBK;                                    // host guarantees d % 64 == 0
-    // k offset of stage s; stages past the end wrap to valid addresses and are never consumed
-    auto k_of_stage = [&](int s) { while (s >= nk) s -= nk; return s * FBK; };
-
-    // j = 0..3: activations, j = 4..7: weights, of the stage at k offset k0 into ring slot `slot`
-    auto issue_dma = [&](int k0, int slot, int j) {
-        unsigned char *dst = smem + slot * kRingStageBytes + dma_wave + (j & 3) * (64 * kRowBytes);
-        if (j < 4)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)dst, 16, a_voff[j], k0 * 2, 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)(dst + kOperandBytes), 16, b_voff[j - 4], k0 * 2, 0, 0);
-    };
-    // which = 0..3: a[which], 4..7: b[which - 4]
-    auto read_frag = [&](Frags &f, int slot, int ks, int which) {
-        const unsigned char *base = smem + slot * kRingStageBytes + frag_off[ks];
+    const int b_rd_wave = wn * FWN * kRowBytes;
+    // which = 0..3: a[which] from the unit in slot sa, 4..7: b[which - 4] from the unit in slot sb
+    auto read_frag = [&](Frags &f, int sa, int sb, int ks, int which) {
         if (which < 4)
-            f.a[which] = *reinterpret_cast<const half8_t *>(base + a_rd_wave + which * (32 * kRowBytes));
+            f.a[which] = *reinterpret_cast<const half8_t *>(smem + sa * kUnitBytes + a_rd_wave + frag_off[ks] + which * (32 * kRowBytes));
         else
-            f.b[which - 4] = *reinterpret_cast<const half8_t *>(base + b_rd_wave + (which - 4) * (32 * kRowBytes));
+            f.b[which - 4] = *reinterpret_cast<const half8_t *>(smem + sb * kUnitBytes + b_rd_wave + frag_off[ks] + (which - 4) * (32 * kRowBytes));
     };
-
-    float16_t acc[FTM][FTN];
-#pragma unroll
-    for (int i = 0; i < FTM; ++i)
-#pragma unroll
-        for (int j = 0; j < FTN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     Frags f0, f1;
 
-    // ---- prologue: stages 0 .. 3 in flight, stage 0 landed, its first fragments read
+    // ---- prologue: k blocks 0 and 1 in flight (units 0..3 -> slots 0..3), block 0 landed, its first fragments read
+    set_load_tile(0);
 #pragma unroll
-    for (int s = 0; s < kAhead; ++s) {
-        const int k0 = k_of_stage(s);
+    for (int s = 0; s < 2; ++s) {
 #pragma unroll
-        for (int j = 0; j < kDmaPerStage; ++j) issue_dma(k0, s, j);
+        for (int i = 0; i < kLoadsPerUnit; ++i) issue_a(2 * s, i);
+#pragma unroll
+        for (int i = 0; i < kLoadsPerUnit; ++i) issue_b(2 * s + 1, i);
+        advance_load();
     }
-    HK_FOLD_WAIT_NEXT_STAGE();
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) read_frag(f0, 0, 0, q);
+    for (int q = 0; q < 8; ++q) read_frag(f0, 0, 1, 0, q);
 
-    int slot = 0;                                              // ring slot of stage kt
-    for (int kt = 0; kt < nk; ++kt) {
-        const int k4 = k_of_stage(kt + kAhead);
-        const int slot1 = slot + 1 == kStages ? 0 : slot + 1;
-        const int slot4 = slot + kAhead >= kStages ? slot + kAhead - kStages : slot + kAhead;
-        // ---- P0: MFMAs of sub-step 0 (f0); fragments of sub-step 1 -> f1; one direct load of stage kt+4 every 4th slot
+    int sA = 0, sB = 1;                                        // slots of the units of k block g
+    for (int c_j = 0; c_j < my_tiles; ++c_j) {                 // tiles of this workgroup
+    float16_t acc[FTM][FTN];
+    // one k block; `first`: the tile's first block, whose first MFMAs start from zero accumulators
+    auto stage = [&](auto first) {
+        constexpr bool FIRST = decltype(first)::value;
+        float16_t zero;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+        const int sA1 = next2(sA), sB1 = next2(sB);            // k block g + 1
+        const int sA2 = next2(sA1), sB2 = sA;                  // k block g + 2: units 2g+4, 2g+5
+        // ---- sub-step 0 (f0): fragments of sub-step 1 -> f1; activations of block g+2, loads 0..3
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f0.a[q >> 2], f0.b[q & 3], FIRST ? zero : acc[q >> 2][q & 3], 0, 0, 0);
+            if (q < 8) read_frag(f1, sA, sB, 1, q);
+            if ((q & 3) == 3) issue_a(sA2, q >> 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- sub-step 1 (f1): fragments of sub-step 2 -> f0; activations of block g+2, loads 4..7
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f1.a[q >> 2], f1.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
+            if (q < 8) read_frag(f0, sA, sB, 2, q);
+            if ((q & 3) == 3) issue_a(sA2, 4 + (q >> 2));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- sub-step 2 (f0): fragments of sub-step 3 -> f1
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f0.a[q >> 2], f0.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
-            if (q < 8) read_frag(f1, slot, 1, q);
-            if ((q & 3) == 3) issue_dma(k4, slot4, q >> 2);          // activations of stage kt+4
+            if (q < 8) read_frag(f1, sA, sB, 3, q);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // ---- P1: MFMAs of sub-step 1 (f1); the step's wait + barrier; fragments of sub-step 0 of stage kt+1 -> f0
+        // ---- sub-step 3 (f1): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; weights of block g+2
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f1.a[q >> 2], f1.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
             if (q == 1) {
-                // Every LDS read of stage kt has been issued (P0).  Wait for them and for this
-                // wavefront's loads of stage kt+1, then meet the others: after the barrier stage kt+1
-                // is complete in LDS and the slot of stage kt may be refilled (by stage kt+5, next step).
-                HK_FOLD_WAIT_IN_STEP();
+                // Every LDS read of block g has been issued.  Wait for them and for this wavefront's loads
+                // of block g+1 (the 8 activation loads of block g+2 may fly), then meet the others: after
+                // the barrier block g+1 is complete in LDS and the slots of block g may be refilled.
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
-            if (q >= 2 && q < 10) read_frag(f0, slot1, 0, q - 2);
-            if ((q & 3) == 3) issue_dma(k4, slot4, 4 + (q >> 2));    // weights of stage kt+4
+            if (q >= 2 && q < 10) read_frag(f0, sA1, sB1, 0, q - 2);
+            if (q >= 2 && (q & 1) == 0) issue_b(sB2, (q - 2) >> 1);      // q = 2, 4, .., 14: loads 0..6
+            if (q == 15) issue_b(sB2, 7);
             __builtin_amdgcn_sched_barrier(0);
         }
-        slot = slot1;
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // drain the loads issued past the end before LDS is released
-
-    // ---- epilogue: LayerNorm statistics, constants of the layer, fp16, head split
-    __syncthreads();                                           // every wavefront is done with the ring
-    RowDst *tab = reinterpret_cast<RowDst *>(smem);
-    fill_row_table<FBM, FNT>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
-    const int nb = n0 + wn * FWN + FTN * (lane & 31);
-    float cn[FTN], bn[FTN];
+        advance_load();
+        sA = sA1; sB = sB1;
+    };
+    stage(std::true_type{});
+    for (int c_kb = 1; c_kb < nks; ++c_kb) stage(std::false_type{});
+        {
+            // ---- end of a tile: LayerNorm statistics, constants of the layer, fp16, head split.
+            // The slot that held the weights of block g (now sB's predecessor) is free until the next
+            // block's activation loads are issued: it holds the row table meanwhile.
+            int tm, tn;
+            tile_coords<GROUP_M>((int)blockIdx.x + c_j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
+            const int64_t m0 = (int64_t)tm * FBM;
+            const int n0 = tn * FBN;
+            const int s_tab = sB >= 2 ? sB - 2 : sB + kSlots - 2;        // slot of the weights of block g
+            RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
+            fill_row_table<FBM, FNT>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
+            const int nb = n0 + wn * FWN + FTN * (lane & 31);
+            float cn[FTN], bn[FTN];
 #pragma unroll
-    for (int j = 0; j < FTN; ++j) {
-        cn[j] = nb < N ? cvec[nb + j] : 0.f;
-        bn[j] = nb < N ? bvec[nb + j] : 0.f;
+            for (int j = 0; j < FTN; ++j) {
+                cn[j] = nb < N ? cvec[nb + j] : 0.f;
+                bn[j] = nb < N ? bvec[nb + j] : 0.f;
+            }
+            __syncthreads();
+            store_tile<FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
+            __syncthreads();                                   // the table's slot is about to be refilled
+        }
     }
-    __syncthreads();
-    store_head_split<FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // loads issued past the end land before LDS is released
 }
 
 // One wavefront per output feature n: W'[n,:] = fp16(gamma * W[n,:]), c[n] = sum_k W'[n,k],
@@ -252,14 +339,20 @@ hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s)
 {
     const int64_t tiles_m64 = (a.M + FBM - 1) / FBM;
     const int tiles_n = (2 * a.d + FBN - 1) / FBN;
-    if (tiles_m64 * tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (tiles_m64 * tiles_n > 0x7fffffffLL || a.d % FBK != 0 || a.d < 2 * FBK) return hipErrorInvalidValue;
     const int tiles_m = (int)tiles_m64;
+    const int n_tiles = tiles_m * tiles_n;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if (cus <= 0) return hipErrorInvalidValue;
+    const int grid = n_tiles < cus ? n_tiles : cus;            // one resident workgroup per compute unit
     auto kern = kv_gemm_fold_kernel<4>;
     static_assert(kRingBytes == 160 * 1024, "the ring uses the whole 160 KiB LDS of a CU");
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(FNT), kRingBytes, s,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FNT), kRingBytes, s,
                        static_cast<const _Float16 *>(a.act), a.stats,
                        static_cast<const _Float16 *>(a.Wp), a.cvec, a.bvec,
                        static_cast<_Float16 *>(a.K_out), static_cast<_Float16 *>(a.V_out),

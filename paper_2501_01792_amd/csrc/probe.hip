@@ -60,18 +60,18 @@ extern "C" int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return HK_ERR_LAUNCH;
-    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return HK_ERR_LAUNCH; }
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return HK_ERR_LAUNCH; }
     hipLaunchKernelGGL(mfma_rate_kernel, dim3(cus), dim3(256), 0, s, sink, iters / 8 + 1, random_operands);   // warm up
-    hipEventRecord(e0, s);
+    (void)hipEventRecord(e0, s);
     hipLaunchKernelGGL(mfma_rate_kernel, dim3(cus), dim3(256), 0, s, sink, iters, random_operands);
-    hipEventRecord(e1, s);
+    (void)hipEventRecord(e1, s);
     int rc = HK_OK;
     float ms = 0.f;
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f)
         rc = HK_ERR_LAUNCH;
     else
         *tflops_out = (float)((double)cus * 4 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12);
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     return rc;
 }
