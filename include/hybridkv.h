@@ -67,8 +67,10 @@ typedef struct hk_shape {
     int32_t dtype;         /* HK_DTYPE_F16 */
     float ln_eps;          /* LayerNorm epsilon (inside the square root); OPT uses 1e-5 */
     float softmax_scale;   /* multiplies q.k before the softmax; <= 0 selects head_dim^-1/2 */
-    int32_t attn_splits;   /* token-axis splits per (sequence, head) in the attention kernel;
-                              0 lets the library choose, otherwise 1..HK_MAX_SPLITS */
+    int32_t attn_splits;   /* attention work split: 0 lets the library choose (the tokens of all
+                              (sequence, head) pairs are shared equally among the wavefronts that are
+                              resident at once); 1..HK_MAX_SPLITS asks for that many equal token ranges
+                              per pair */
     int32_t gemm_tile;     /* output tile edge of the projection kernel: 0 lets the library
                               choose, otherwise 128 or 256 */
 } hk_shape;
@@ -171,8 +173,8 @@ int hk_hybrid_decode_attn(const hk_shape *shape,
  *   events[0] before the first kernel,      events[1] after the LayerNorm statistics,
  *   events[2] after the K/V projection,     events[3] after the attention streaming kernel,
  *   events[4] after the merge of the attention partials (end of the step).
- * Stages that do not run (L_act == 0, a single attention chunk) leave their
- * event recorded back to back with the previous one.
+ * Stages that do not run (L_act == 0) leave their event recorded back to back
+ * with the previous one.
  */
 int hk_hybrid_decode_attn_marked(const hk_shape *shape,
                                  const void *q,

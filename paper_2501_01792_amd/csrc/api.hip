@@ -17,8 +17,7 @@ struct Plan {
     // sizes
     int64_t M;            // B * L_act
     int64_t BH;           // B * n_heads
-    int chunk;            // attention tokens per chunk
-    int total_chunks;
+    int n_waves;          // wavefronts of the attention kernel
     float scale;
     // workspace offsets (bytes)
     size_t off_k, off_v, off_stats, off_partial, total;
@@ -36,24 +35,6 @@ int check_shape(const hk_shape *s)
     if (s->attn_splits < 0 || s->attn_splits > HK_MAX_SPLITS) return HK_ERR_SHAPE;
     if (!(s->ln_eps >= 0.f) || !std::isfinite(s->ln_eps) || !std::isfinite(s->softmax_scale)) return HK_ERR_SHAPE;
     return HK_OK;
-}
-
-// Tokens per attention chunk.  One workgroup streams one chunk; a chunk is a multiple of the
-// 256 tokens that the 4 wavefronts of a workgroup consume per step.  Without a request the
-// chunk is chosen so that the launch has at least ~8 workgroups per compute unit.
-int choose_chunk(const hk_shape *s, int64_t BH, int64_t L)
-{
-    int64_t splits = s->attn_splits;
-    if (splits <= 0) {
-        const int64_t want = 8 * 256;
-        splits = (want + BH - 1) / BH;
-        if (splits < 1) splits = 1;
-        if (splits > HK_MAX_SPLITS) splits = HK_MAX_SPLITS;
-    }
-    int64_t chunk = (L + splits - 1) / splits;
-    chunk = (chunk + 255) / 256 * 256;
-    if (chunk < 256) chunk = 256;
-    return (int)chunk;
 }
 
 // Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
@@ -75,14 +56,10 @@ int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool re
     p->off_stats = 2 * kv_bytes;
     size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
     p->off_partial = end;
-    p->chunk = 256;
-    p->total_chunks = 0;
+    p->n_waves = 0;
     if (!regen_only && L_kv + L_act > 0 && p->BH > 0) {
-        p->chunk = choose_chunk(s, p->BH, L_kv + L_act);
-        p->total_chunks = hk::attn_total_chunks((int)L_kv, (int)L_act, p->chunk);
-        if (p->BH * (int64_t)p->total_chunks > 0x7fffffffLL) return HK_ERR_SHAPE;
-        if (p->total_chunks > 1)
-            end += align_up((size_t)p->BH * p->total_chunks * (s->head_dim + 2) * sizeof(float));
+        p->n_waves = hk::attn_wavefronts(p->BH, L_kv + L_act, s->attn_splits);
+        end += align_up(((size_t)p->n_waves + (size_t)p->BH) * (s->head_dim + 2) * sizeof(float));
     }
     p->total = end;
     return HK_OK;
@@ -262,7 +239,7 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     a.K0 = K_cache; a.V0 = V_cache; a.L0 = L_kv;
     a.K1 = K_regen; a.V1 = V_regen; a.L1 = L_act;
     a.BH = (int)p.BH; a.head_dim = shape->head_dim; a.scale = p.scale;
-    a.n_split = p.total_chunks; a.chunk = p.chunk;
+    a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
     a.after_main = (mk.ev && mk.n > 3) ? mk.ev[3] : nullptr;

@@ -45,14 +45,19 @@ struct AttnArgs {
     int BH;                // B * H
     int head_dim;          // 64 or 128
     float scale;           // multiplies q.k
-    int n_split;           // >= 1; token chunks per (b, h)
-    int chunk;             // tokens per chunk, multiple of 64; n_split * chunk >= L0 and L1 handled per segment
-    float *partial;        // [BH, n_split_total, dh + 2] fp32 (unused when n_split_total == 1)
+    int n_waves;           // wavefronts that share the BH * (L0 + L1) token positions equally (attn_wavefronts)
+    float *partial;        // [n_waves + BH, dh + 2] fp32
     void *out;             // [BH, dh] fp16
     hipEvent_t after_main; // optional: recorded after the streaming kernel, before the merge
 };
-// Number of token chunks the attention kernel uses for segments of length L0, L1.
-int attn_total_chunks(int L0, int L1, int chunk);
+// Wavefronts of the attention kernel that stay resident together on an MI355X: 256 compute units x
+// 4 SIMDs x 4 wavefronts (the kernel's register footprint, <= 128 VGPRs, allows 4 per SIMD).
+constexpr int kAttnResidentWaves = 256 * 4 * 4;
+constexpr int kAttnMaxWaves = 1 << 20;
+// Number of wavefronts the attention kernel uses for BH pairs of L tokens; splits > 0 asks for
+// that many token ranges per pair.  A function of the shape only, so that workspace sizes can be
+// computed without a device.
+int attn_wavefronts(int64_t BH, int64_t L, int splits);
 // Single-query attention over the two token segments taken as one context.
 hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s);
 

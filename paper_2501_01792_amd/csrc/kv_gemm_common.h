@@ -107,6 +107,9 @@ __device__ __forceinline__ void fill_row_table(RowDst *tab, int tid, int64_t m0,
     }
 }
 
+// The stores are non-temporal: the regenerated rows are read once, by the attention kernel, and must
+// not linger as dirty lines in the last-level cache, where their write-back would compete with that
+// kernel's reads.
 // Epilogue of one wavefront: out = rstd * acc + (nmr * cn + bn) in fp32, round to fp16, head-split
 // store into [B, H, L_cap, dh].  With the row table's (rstd, nmr) = (1, 0) this is acc + bn, the plain
 // bias add; with the row statistics it is the folded LayerNorm (cn = c[n], bn = b'[n]).
@@ -136,13 +139,13 @@ __device__ __forceinline__ void store_head_split(const float16_t (&acc)[TM][TN],
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
-                    *reinterpret_cast<half4_t *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<half4_t *>(dst));
                 } else if constexpr (TN == 2) {
                     half2_t v;
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
                         v[j] = (_Float16)__builtin_fmaf(acc[i][j][r], row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
-                    *reinterpret_cast<half2_t *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<half2_t *>(dst));
                 } else {
                     *dst = (_Float16)__builtin_fmaf(acc[i][0][r], row.rstd, __builtin_fmaf(row.nmr, cn[0], bn[0]));
                 }

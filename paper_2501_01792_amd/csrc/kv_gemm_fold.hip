@@ -94,7 +94,7 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[TM][TN], int l
                 asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));
                 v[j] = (_Float16)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
             }
-            if (row.base >= 0) *reinterpret_cast<half4_t *>(dst_base + row.base) = v;
+            if (row.base >= 0) __builtin_nontemporal_store(v, reinterpret_cast<half4_t *>(dst_base + row.base));
         }
         __builtin_amdgcn_sched_barrier(0);
     }
