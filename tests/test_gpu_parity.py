@@ -193,7 +193,9 @@ def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99, prepar
     oracle, which computes exactly those outputs from the same inputs (all K/V rows of the
     sampled head, via Eq. 7 restricted to that head's weight rows)."""
     batch = synth.make_batch(cfg, threads=16)
+    print("  inputs drawn", flush=True)
     out, K, V = _run_hybrid(hk, cfg, batch, prepared=prepared)
+    print("  GPU step done", flush=True)
     H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
     rng = np.random.default_rng(seed)
     if cfg.L_act:
@@ -227,3 +229,21 @@ def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99, prepar
 def test_full_size_opt6p7b_sampled(hk, oracle, prepared):
     """The configuration the benchmark times (OPT-6.7B-shaped layer, B=32, L=1024, ratio 0.5)."""
     _sampled_oracle_check(hk, oracle, synth.CONFIGS["opt6.7b"], prepared=prepared)
+
+
+# The other workloads of the benchmark contract at their full sizes (OPT-13B at ratio 0.25, OPT-30B
+# and OPT-66B with every token regenerated: the largest regeneration GEMMs, M = 131072 and 262144),
+# then the OPT-66B ratio sweep, also at full size.
+FULL = [
+    synth.CONFIGS["opt13b"],
+    synth.CONFIGS["opt30b"],
+    synth.CONFIGS["opt66b"],
+] + [synth.CONFIGS["opt66b"].with_ratio(r) for r in (0.25, 0.5, 0.75, 1.0)]
+
+
+@pytest.mark.parametrize("cfg", FULL, ids=lambda c: "%s-B%d" % (c.name, c.B))
+def test_full_size_configs_sampled(hk, oracle, cfg):
+    print("case", cfg, flush=True)
+    torch.cuda.empty_cache()
+    _sampled_oracle_check(hk, oracle, cfg, n_rows=24, n_pairs=2, prepared=True)
+    torch.cuda.empty_cache()
