@@ -7,6 +7,7 @@ OPT-6.7B-shaped workload (d=4096, 32 heads x 128, B=32, context 1024 at ratio 0.
 C ABI.  Inputs are resident in HBM before the timed region.  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config opt6.7b] [--no-cpu-baseline]
+    python bench.py --sweep [--config opt66b]      ratio sweep (KV fraction 0 .. 1) with the balance point
 """
 import argparse
 import json
@@ -79,18 +80,97 @@ def cpu_baseline(cfg, budget_s=15.0):
     }, n, out
 
 
+def sweep(args):
+    """Ratio sweep of one workload (Sec. 4.3): per KV fraction r the time of regeneration
+    (LayerNorm statistics + projection: the paper's T_kv_gen of the (1-r) B L checkpointed tokens)
+    and of attention, the least-squares line T_kv_gen(n) = a n + b over the sweep (the paper fits
+    the same line, Sec. 4.3 "Sampling-based linear regression"), and the ratio r* at which
+    T_kv_gen((1-r) n) = T_load_w + T_load_kv(r n) (Eq. 8-10) for stated host-link bandwidths.
+    The link is modelled (bytes / bandwidth), not measured: there is no host offload on this path.
+    Inputs are drawn on the GPU with the distributions of the benchmark recipe (timing only)."""
+    import numpy as np
+    import torch
+    from paper_2501_01792_amd import binding as hk, synth
+    from paper_2501_01792_amd.hipevents import EventSet
+    torch.cuda.set_device(0)
+    base = synth.CONFIGS[args.config]
+    d, H, dh, B, L = base.d, base.n_heads, base.head_dim, base.B, base.L
+    gen = torch.Generator(device="cuda").manual_seed(base.seed)
+    rn = lambda *shape, std=1.0, mean=0.0: (torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32) * std + mean).half()
+    kv_std = 0.02 * d ** 0.5
+    Wkv, bkv = rn(2 * d, d, std=0.02), rn(2 * d, std=0.01)
+    ln_w, ln_b = rn(d, std=0.02, mean=1.0), rn(d, std=0.02)
+    lp = (ln_w, ln_b, Wkv, bkv)
+    lp = lp + (hk.prepare_layer(*lp, H),)
+    q = rn(B, H, dh, std=kv_std)
+    act_full = torch.empty((B, L, d), dtype=torch.float16, device="cuda")
+    for b in range(B):
+        act_full[b] = rn(L, d)
+    K_full = torch.empty((B, H, L, dh), dtype=torch.float16, device="cuda")
+    V_full = torch.empty_like(K_full)
+    for b in range(B):
+        K_full[b] = rn(H, L, dh, std=kv_std)
+        V_full[b] = rn(H, L, dh, std=kv_std)
+    out = torch.empty((B, H, dh), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream()
+    rows = []
+    for r in synth.SWEEP_RATIOS:
+        cfg = base.with_ratio(r)
+        Kc = K_full[:, :, :cfg.L_kv].contiguous() if cfg.L_kv else None
+        Vc = V_full[:, :, :cfg.L_kv].contiguous() if cfg.L_kv else None
+        act = act_full[:, cfg.L_kv:].contiguous() if cfg.L_act else None
+        shape = hk.make_shape(d, H)
+        ws = hk.new_workspace(hk.hk_workspace_bytes(shape, B, cfg.L_kv, cfg.L_act))
+        for _ in range(args.warmup):
+            hk.hybrid_decode_attn(q, Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream)
+        events = [EventSet(5) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for e in events:
+            hk.hybrid_decode_attn(q, Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream, events=e)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        dur = [float(np.mean([e.elapsed_ms(i, i + 1) for e in events])) for i in range(4)]
+        for e in events:
+            e.destroy()
+        rows.append({"ratio": r, "L_kv": cfg.L_kv, "L_act": cfg.L_act, "regen_tokens": cfg.M, "ms_per_step": ms,
+                     "t_kv_gen_ms": dur[0] + dur[1], "t_attn_ms": dur[2] + dur[3],
+                     "gemm_tflops": (4.0 * cfg.M * d * d / (dur[1] * 1e-3) / 1e12) if cfg.M else None,
+                     "attn_gbps": float(B) * L * 4 * d / (dur[2] * 1e-3) / 1e9})
+        del Kc, Vc, act, ws
+        torch.cuda.empty_cache()
+    n = np.array([x["regen_tokens"] for x in rows if x["regen_tokens"]], dtype=np.float64)
+    t = np.array([x["t_kv_gen_ms"] for x in rows if x["regen_tokens"]], dtype=np.float64)
+    a, b0 = np.polyfit(n, t, 1)
+    r2 = 1.0 - float(((t - (a * n + b0)) ** 2).sum() / ((t - t.mean()) ** 2).sum())
+    n_tot = float(B) * L
+    balance = {}
+    for name, gbps in (("pcie4_x16_32GBps (the paper's link)", 32.0), ("pcie5_x16_64GBps", 64.0)):
+        per_tok_ms = 4.0 * d / (gbps * 1e9) * 1e3                  # T_load_kv per token of one layer (4d bytes, fp16)
+        t_w_ms = 24.0 * d * d / (gbps * 1e9) * 1e3                 # T_load_w: 12 d^2 fp16 parameters of one decoder layer
+        # a (1 - r) n + b = t_w + r n per_tok   ->   r = (a n + b - t_w) / (n (a + per_tok))
+        r_star = (a * n_tot + b0 - t_w_ms) / (n_tot * (a + per_tok_ms))
+        balance[name] = {"t_load_kv_ms_per_token": per_tok_ms, "t_load_w_ms": t_w_ms,
+                         "kv_fraction_at_balance": float(min(1.0, max(0.0, r_star)))}
+    print(json.dumps({"workload": "%s: d=%d H=%d B=%d L=%d" % (base.name, d, H, B, L), "steps": args.steps,
+                      "sweep": rows, "t_kv_gen_fit": {"ms_per_token": float(a), "ms_offset": float(b0), "r2": r2},
+                      "balance_model": balance}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="opt6.7b")
+    ap.add_argument("--config", default=None)
     ap.add_argument("--ratio", type=float, default=None, help="override the KV fraction of the context")
     ap.add_argument("--gemm-tile", type=int, default=0)
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unprepared", action="store_true",
                     help="do not call hk_prepare_layer: LayerNorm runs as the GEMM prologue instead of folded")
+    ap.add_argument("--sweep", action="store_true", help="ratio sweep of --config (default opt66b) instead of the bench line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of 1 GiB (3 launches) so that profiler byte counters "
                          "can be scaled against a kernel of known traffic")
@@ -109,6 +189,12 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     hk.lib()
+    if args.sweep:
+        args.config = args.config or "opt66b"
+        if args.steps == 50:
+            args.steps, args.warmup = 5, 2
+        return sweep(args)
+    args.config = args.config or "opt6.7b"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     if args.ratio is not None:
