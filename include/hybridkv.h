@@ -186,6 +186,36 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape,
                                  void **events, int32_t n_events);
 
 /*
+ * QKV generation for the current input token of every sequence, and its write-back (Sec. 4.2.2: the
+ * decode step generates Q, K, V of the input token, Eq. 2, and afterwards keeps the token either as
+ * a KV entry or as an activation checkpoint):
+ *     xhat = LayerNorm(x_cur; ln_w, ln_b, ln_eps)
+ *     q    = xhat x W_Q + b_Q                       -> q_out
+ *     k, v = xhat x [W_K W_V] + [b_K b_V]           -> row tok_pos of K_dst, V_dst   (when given)
+ *     x_cur                                         -> row act_pos of act_dst        (when given)
+ * A caller that keeps the token as a KV entry passes K_dst/V_dst = its cache and tok_pos = L_kv; one
+ * that keeps it as a checkpoint passes act_dst = its checkpoint store and act_pos = L_act (the
+ * token's K/V are then regenerated with the other checkpoints by hk_hybrid_decode_attn).  Either
+ * way the token is in a store afterwards and the step attends over it like over any other.
+ *
+ *   x_cur     [B, d] fp16, read only
+ *   params    ln_w, ln_b, Wkv [2d, d], bkv [2d] as everywhere (prepared is not used)
+ *   Wq, bq    [d, d] (output feature x input) and [d], fp16
+ *   q_out     [B, H, dh] fp16
+ *   K_dst, V_dst [B, H, L_cap, dh] fp16, both NULL or both given; only row tok_pos is written
+ *   act_dst   [B, act_cap, d] fp16 or NULL; only row act_pos is written
+ *   workspace needs hk_qkv_workspace_bytes(shape, B)
+ * B == 0 is a successful no-op.
+ */
+size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B);
+int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
+                   const hk_layer_params *params, const void *Wq, const void *bq,
+                   void *q_out,
+                   void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
+                   void *act_dst, int32_t act_cap, int32_t act_pos,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid (no operation of the paper): runs a loop of back-to-back
  * v_mfma_f32_32x32x16_f16 on every compute unit (4 wavefronts each, `iters`
  * x 16 instructions per wavefront) with all-zero (random_operands == 0) or

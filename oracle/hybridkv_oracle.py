@@ -165,3 +165,17 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, gamma, beta, Wkv, bkv, n_heads,
        _i64(B), _i64(d), _i64(n_heads), c_t(eps), c_t(scale),
        _ptr(out), _ptr(K_full), _ptr(V_full), _ptr(s_x), _ptr(s_kv))
     return out, K_full, V_full
+
+
+def qkv_current(x_cur, gamma, beta, Wq, bq, Wkv, bkv, n_heads, eps=1e-5, precision="f64"):
+    """QKV generation of the current input token of every sequence (Sec. 4.2.2; Eq. 2 with the
+    layer's pre-attention LayerNorm in front, biases added): ``x_cur[B, d]`` ->
+    ``(q, k, v)``, each ``[B, H, dh]``.  LayerNorm and projection are the routines above: the
+    query weight is one more set of output features of the same affine map."""
+    x_cur = np.asarray(x_cur)
+    B, d = x_cur.shape
+    dh = d // n_heads
+    xhat = layernorm(x_cur, gamma, beta, eps, precision)
+    q = kv_projection(xhat, Wq, bq, precision)
+    kv = kv_projection(xhat, Wkv, bkv, precision)
+    return (q.reshape(B, n_heads, dh), kv[:, :d].reshape(B, n_heads, dh), kv[:, d:].reshape(B, n_heads, dh))

@@ -64,6 +64,11 @@ def lib():
                                             vp, vp, sz, vp]
         L.hk_hybrid_decode_attn_marked.restype = ctypes.c_int
         L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
+        L.hk_qkv_workspace_bytes.restype = ctypes.c_size_t
+        L.hk_qkv_workspace_bytes.argtypes = [ctypes.POINTER(hk_shape), i32]
+        L.hk_qkv_current.restype = ctypes.c_int
+        L.hk_qkv_current.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp,
+                                     vp, vp, vp, i32, i32, vp, i32, i32, vp, sz, vp]
         L.hk_probe_mfma_rate.restype = ctypes.c_int
         L.hk_probe_mfma_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         L.hk_status_string.restype = ctypes.c_char_p
@@ -215,3 +220,33 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
         V = workspace[v_off:v_off + 2 * n].view(f16).view(B, H, L_act, dh)
         return out, K, V
     return out
+
+
+def hk_qkv_workspace_bytes(shape: hk_shape, B: int) -> int:
+    return int(lib().hk_qkv_workspace_bytes(ctypes.byref(shape), B))
+
+
+def qkv_current(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, q_out=None, K_dst=None, V_dst=None, tok_pos=0,
+                act_dst=None, act_pos=0, ln_eps=1e-5, workspace=None, stream=None):
+    """hk_qkv_current: ``x_cur[B, d]`` fp16 -> ``q[B, H, dh]``; writes the token's K/V row ``tok_pos`` into
+    ``K_dst, V_dst[B, H, L_cap, dh]`` and/or its input row ``act_pos`` into ``act_dst[B, act_cap, d]`` when given."""
+    import torch
+    f16 = torch.float16
+    B, d = x_cur.shape
+    shape = make_shape(d, n_heads, ln_eps)
+    dh = d // n_heads
+    if q_out is None:
+        q_out = torch.empty((B, n_heads, dh), dtype=f16, device=x_cur.device)
+    if workspace is None:
+        workspace = new_workspace(hk_qkv_workspace_bytes(shape, B), x_cur.device)
+    lp = _params(ln_w, ln_b, Wkv, bkv)
+    L_cap = 0 if K_dst is None else K_dst.shape[2]
+    act_cap = 0 if act_dst is None else act_dst.shape[1]
+    st = lib().hk_qkv_current(ctypes.byref(shape), _dev_ptr(x_cur, "x_cur", f16), B, ctypes.byref(lp),
+                              _dev_ptr(Wq, "Wq", f16), _dev_ptr(bq, "bq", f16), _dev_ptr(q_out, "q_out", f16),
+                              _dev_ptr(K_dst, "K_dst", f16), _dev_ptr(V_dst, "V_dst", f16), L_cap, tok_pos,
+                              _dev_ptr(act_dst, "act_dst", f16), act_cap, act_pos,
+                              _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_qkv_current")
+    return q_out

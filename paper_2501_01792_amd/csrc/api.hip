@@ -248,6 +248,61 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     return HK_OK;
 }
 
+size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
+{
+    if (check_shape(shape) != HK_OK || B < 0 || B > (1 << 24)) return 0;
+    const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
+    const size_t bytes = align_up(rows * (size_t)shape->d * 2);
+    return bytes > 0 ? bytes : kAlign;
+}
+
+int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
+                   const hk_layer_params *params, const void *Wq, const void *bq,
+                   void *q_out,
+                   void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
+                   void *act_dst, int32_t act_cap, int32_t act_pos,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    int st = check_shape(shape);
+    if (st != HK_OK) return st;
+    if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
+    if ((K_dst == nullptr) != (V_dst == nullptr)) return HK_ERR_NULL;
+    if (K_dst && (L_cap <= 0 || tok_pos < 0 || tok_pos >= L_cap)) return HK_ERR_SHAPE;
+    if (act_dst && (act_cap <= 0 || act_pos < 0 || act_pos >= act_cap)) return HK_ERR_SHAPE;
+    if ((long double)B * (K_dst ? L_cap : 1) * shape->d > 4.0e12L) return HK_ERR_SHAPE;
+    if ((long double)B * (act_dst ? act_cap : 1) * shape->d > 4.0e12L) return HK_ERR_SHAPE;
+    if (B == 0) return HK_OK;
+    st = check_params(params);
+    if (st != HK_OK) return st;
+    if (!x_cur || !Wq || !bq || !q_out || !workspace) return HK_ERR_NULL;
+    if (!aligned(x_cur, 16) || !aligned(Wq, 16) || !aligned(bq, 16) || !aligned(q_out, 16) ||
+        !aligned(workspace, kAlign))
+        return HK_ERR_ALIGN;
+    if (K_dst && (!aligned(K_dst, 16) || !aligned(V_dst, 16))) return HK_ERR_ALIGN;
+    if (act_dst && !aligned(act_dst, 16)) return HK_ERR_ALIGN;
+    if (workspace_bytes < hk_qkv_workspace_bytes(shape, B)) return HK_ERR_WORKSPACE;
+
+    const int d = shape->d;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    // rows are taken kQkvMaxRows at a time; the scratch row block is reused (same stream: ordered)
+    for (int32_t b0 = 0; b0 < B; b0 += hk::kQkvMaxRows) {
+        hk::QkvArgs a;
+        const int rows = B - b0 < hk::kQkvMaxRows ? B - b0 : hk::kQkvMaxRows;
+        a.x = static_cast<const char *>(x_cur) + (size_t)b0 * d * 2;
+        a.ln_w = params->ln_w; a.ln_b = params->ln_b; a.Wq = Wq; a.bq = bq; a.Wkv = params->Wkv; a.bkv = params->bkv;
+        a.xhat = workspace;
+        a.q_out = static_cast<char *>(q_out) + (size_t)b0 * d * 2;
+        a.K_dst = K_dst ? static_cast<char *>(K_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;
+        a.V_dst = V_dst ? static_cast<char *>(V_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;
+        a.act_dst = act_dst ? static_cast<char *>(act_dst) + ((size_t)b0 * act_cap + act_pos) * d * 2 : nullptr;
+        a.act_row_stride = (int64_t)act_cap * d;
+        a.B = rows; a.d = d; a.n_heads = shape->n_heads; a.head_dim = shape->head_dim;
+        a.L_cap = L_cap; a.tok_pos = tok_pos; a.eps = shape->ln_eps;
+        if (hk::launch_qkv_current(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    }
+    return HK_OK;
+}
+
 const char *hk_status_string(int status)
 {
     switch (status) {

@@ -61,4 +61,21 @@ int attn_wavefronts(int64_t BH, int64_t L, int splits);
 // Single-query attention over the two token segments taken as one context.
 hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s);
 
+struct QkvArgs {
+    const void *x;         // [B, d] fp16: layer input of the current token of every sequence
+    const void *ln_w, *ln_b;
+    const void *Wq, *bq;   // [d, d], [d]
+    const void *Wkv, *bkv; // [2d, d], [2d]
+    void *xhat;            // [B, d] fp16 scratch
+    void *q_out;           // [B, H, dh]
+    void *K_dst, *V_dst;   // [B, H, L_cap, dh] or both null: no K/V row is produced
+    void *act_dst;         // null, or where row b of x is copied: act_dst + b * act_row_stride (elements)
+    int64_t act_row_stride;
+    int B, d, n_heads, head_dim, L_cap, tok_pos;
+    float eps;
+};
+constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel takes
+// LayerNorm + Q (and K/V) projection of B <= kQkvMaxRows current-token rows, with write-back.
+hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s);
+
 }  // namespace hk

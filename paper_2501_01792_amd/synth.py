@@ -99,6 +99,15 @@ def make_params(cfg: LayerConfig) -> dict:
     return {"ln_w": ln_w, "ln_b": ln_b, "Wkv": Wkv, "bkv": bkv}
 
 
+def make_current_token(cfg: LayerConfig) -> dict:
+    """Inputs of the current-token QKV generation: ``x_cur [B, d] ~ N(0, 1)`` (a layer input, like the
+    checkpoints), ``Wq [d, d] ~ N(0, 0.02)``, ``bq [d] ~ N(0, 0.01)``; their own stream keyed (seed, 9)."""
+    rng = _rng(cfg.seed, 9)
+    d = cfg.d
+    return {"x_cur": _normal_f16(rng, (cfg.B, d)), "Wq": _normal_f16(rng, (d, d), std=0.02),
+            "bq": _normal_f16(rng, (d,), std=0.01)}
+
+
 def make_sequence(cfg: LayerConfig, b: int) -> dict:
     """Per-sequence tensors of sequence ``b``: ``act [L_act, d]``, ``q [H, dh]``,
     ``K_cache, V_cache [H, L_kv, dh]`` (fp16)."""

@@ -133,6 +133,33 @@ def test_prepare_layer_rejects_bad_arguments():
     assert _regen(ok, lp=hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, FAKE + 16)) == hk.HK_ERR_ALIGN
 
 
+def test_qkv_current_rejects_bad_arguments():
+    """Every check of hk_qkv_current runs on the host before a launch: no GPU is touched here."""
+    ok = hk.make_shape(768, 12)
+    need = hk.hk_qkv_workspace_bytes(ok, 4)
+    assert need >= 4 * 768 * 2
+    assert hk.hk_qkv_workspace_bytes(hk.make_shape(768, 11), 4) == 0
+    assert hk.hk_qkv_workspace_bytes(ok, 1000) == hk.hk_qkv_workspace_bytes(ok, 128)      # rows go 128 at a time
+    lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+
+    def call(shape=ok, x=FAKE, B=4, lp=lp, Wq=FAKE, bq=FAKE, q=FAKE, K=FAKE, V=FAKE, L_cap=8, pos=3,
+             A=FAKE, acap=8, apos=2, ws=FAKE, n=need):
+        return hk.lib().hk_qkv_current(ctypes.byref(shape), x, B, ctypes.byref(lp), Wq, bq, q, K, V, L_cap, pos,
+                                       A, acap, apos, ws, n, None)
+
+    assert call(shape=hk.make_shape(768, 11)) == hk.HK_ERR_SHAPE
+    assert call(B=-1) == hk.HK_ERR_SHAPE
+    assert call(B=0, x=None) == hk.HK_OK                              # nothing to do
+    assert call(V=None) == hk.HK_ERR_NULL                             # K and V go together
+    assert call(pos=8) == hk.HK_ERR_SHAPE and call(pos=-1) == hk.HK_ERR_SHAPE
+    assert call(apos=8) == hk.HK_ERR_SHAPE
+    assert call(x=None) == hk.HK_ERR_NULL and call(Wq=None) == hk.HK_ERR_NULL and call(q=None) == hk.HK_ERR_NULL
+    assert call(lp=hk.hk_layer_params(FAKE, None, FAKE, FAKE, None)) == hk.HK_ERR_NULL
+    assert call(x=FAKE + 8) == hk.HK_ERR_ALIGN and call(K=FAKE + 8) == hk.HK_ERR_ALIGN
+    assert call(A=FAKE + 2) == hk.HK_ERR_ALIGN and call(ws=FAKE + 16) == hk.HK_ERR_ALIGN
+    assert call(n=need - 1) == hk.HK_ERR_WORKSPACE
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 4, 768, dtype=torch.float16)

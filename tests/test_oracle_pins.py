@@ -286,3 +286,51 @@ def test_pins_detect_planted_mistakes(oracle):
     q, K, V = _rand((1, 1, 4), 64), _rand((1, 1, 6, 4), 65), _rand((1, 1, 6, 4), 66)
     unscaled = oracle.decode_attention(q, K, V, scale=1.0)
     assert np.abs(unscaled - oracle.decode_attention(q, K, V)).max() > 1e-3   # the dh^-1/2 scale matters
+
+
+# ---------------------------------------------------------------- current-token QKV generation
+def test_qkv_current_brute_force_and_library(oracle):
+    """q, k, v of the current token against Python loops written from Eq. 2 (+ LayerNorm, biases)
+    and against torch's CPU layer_norm / linear; head split checked index by index."""
+    rng = np.random.default_rng(31)
+    B, d, H = 3, 12, 3
+    dh = d // H
+    x = rng.standard_normal((B, d)) * 2 + 0.5
+    g, be = 1 + 0.1 * rng.standard_normal(d), 0.1 * rng.standard_normal(d)
+    Wq, bq = rng.standard_normal((d, d)), rng.standard_normal(d)
+    Wkv, bkv = rng.standard_normal((2 * d, d)), rng.standard_normal(2 * d)
+    q, k, v = oracle.qkv_current(x, g, be, Wq, bq, Wkv, bkv, H, eps=1e-5)
+    for b in range(B):
+        mu = sum(x[b]) / d
+        var = sum((x[b, j] - mu) ** 2 for j in range(d)) / d
+        xh = [(x[b, j] - mu) / math.sqrt(var + 1e-5) * g[j] + be[j] for j in range(d)]
+        for n in range(d):
+            h, i = divmod(n, dh)
+            assert abs(q[b, h, i] - (sum(xh[j] * Wq[n, j] for j in range(d)) + bq[n])) < 1e-12
+            assert abs(k[b, h, i] - (sum(xh[j] * Wkv[n, j] for j in range(d)) + bkv[n])) < 1e-12
+            assert abs(v[b, h, i] - (sum(xh[j] * Wkv[d + n, j] for j in range(d)) + bkv[d + n])) < 1e-12
+    xt = torch.nn.functional.layer_norm(torch.from_numpy(x), (d,), torch.from_numpy(g), torch.from_numpy(be), 1e-5)
+    qt = torch.nn.functional.linear(xt, torch.from_numpy(Wq), torch.from_numpy(bq)).numpy().reshape(B, H, dh)
+    np.testing.assert_allclose(q, qt, atol=1e-12)
+
+
+def test_current_token_joins_either_store_with_the_same_result(oracle):
+    """Sec. 4.2.2: the input token's K/V take part in its own attention and the token is then kept as
+    a KV entry or as a checkpoint.  Both routes must give the step the same output: appending its
+    (k, v) to the cache, or appending its layer input to the checkpoints (Sec. 3.3's exactness)."""
+    rng = np.random.default_rng(32)
+    B, d, H, L_kv, L_act = 2, 16, 4, 3, 5
+    dh = d // H
+    g, be = 1 + 0.1 * rng.standard_normal(d), 0.1 * rng.standard_normal(d)
+    Wq, bq = rng.standard_normal((d, d)) * 0.3, rng.standard_normal(d) * 0.1
+    Wkv, bkv = rng.standard_normal((2 * d, d)) * 0.3, rng.standard_normal(2 * d) * 0.1
+    x = rng.standard_normal((B, d))
+    act = rng.standard_normal((B, L_act, d))
+    Kc, Vc = rng.standard_normal((B, H, L_kv, dh)), rng.standard_normal((B, H, L_kv, dh))
+    q, k, v = oracle.qkv_current(x, g, be, Wq, bq, Wkv, bkv, H)
+    out_kv, _, _ = oracle.hybrid_decode_attn(q, np.concatenate([Kc, k[:, :, None]], axis=2),
+                                             np.concatenate([Vc, v[:, :, None]], axis=2), act, g, be, Wkv, bkv, H)
+    out_act, K_full, _ = oracle.hybrid_decode_attn(q, Kc, Vc, np.concatenate([act, x[:, None]], axis=1),
+                                                   g, be, Wkv, bkv, H)
+    np.testing.assert_allclose(out_kv, out_act, atol=1e-12)
+    np.testing.assert_allclose(K_full[:, :, -1], k, atol=1e-12)      # the regenerated row of the token is its k
