@@ -13,8 +13,8 @@
 //              row in fp16 to scratch (and the raw row to the checkpoint store when asked).
 //   qkv_rows:  one workgroup per slab of 32 output features.  Its 4 wavefronts each take a quarter of
 //              the reduction axis, stream their part of the 32 weight rows straight from HBM into
-//              registers (each lane 64 contiguous bytes per step, two lanes per 128-byte line, next
-//              step's loads in flight during the MFMAs) and multiply them with the matching part of
+//              registers (each lane 64 contiguous bytes per step, two lanes per 128-byte line, several
+//              steps' loads in flight during the MFMAs) and multiply them with the matching part of
 //              xhat (read through L2) on the matrix cores (v_mfma_f32_32x32x16_f16; the k order inside
 //              a step is permuted identically for both operands so that loads stay contiguous).
 //              The four partial sums meet in LDS; bias, fp16 and the scatter to q / K / V follow.
@@ -129,30 +129,47 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 
-    half8_t wv[2][4];
-    if (s_begin < s_end) {
+    // Weight pieces are fetched kDepth - 1 steps ahead, the xhat pieces of a step one step ahead.  Vector
+    // memory loads complete in issue order as far as s_waitcnt can tell, so inside a step the xhat loads
+    // (L2, wanted next step) are issued BEFORE the weight loads (HBM, wanted kDepth - 1 steps later):
+    // the wait for the former then leaves the latter in flight.
+    constexpr int kDepth = RB <= 2 ? 6 : 4;
+    constexpr int kXDepth = RB <= 2 ? 3 : 2;               // xhat pieces are fetched kXDepth - 1 steps ahead; divides kDepth
+    half8_t wv[kDepth][4];
+    half8_t xv[kXDepth][RB][4];
+    auto load_w = [&](int slot, int sc) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            wv[0][j] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(wp + (int64_t)s_begin * kStepK) + j);
-    }
-    for (int s = s_begin; s < s_end; s += 2) {
+            wv[slot][j] = *(reinterpret_cast<const half8_t *>(wp + (int64_t)sc * kStepK) + j);
+    };
+    auto load_x = [&](int slot, int sc) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int sc = s + u;
-            if (sc < s_end) {
-                if (sc + 1 < s_end) {
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        wv[u ^ 1][j] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(wp + (int64_t)(sc + 1) * kStepK) + j);
-                }
+            for (int j = 0; j < 4; ++j)
+                xv[slot][rb][j] = *(reinterpret_cast<const half8_t *>(xp[rb] + (int64_t)sc * kStepK) + j);
+    };
+    // Every load of the loop is unconditional (steps past the end re-read the last step, an L2 hit), so
+    // that the number of loads in flight at each wait is a compile-time fact; only the MFMAs are guarded.
+    const int last = s_end - 1;
+    auto clamp = [&](int sc) { return sc < last ? sc : last; };
+    if (s_begin < s_end) {
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    half8_t xv[4];
+        for (int u = 0; u < kXDepth - 1; ++u) load_x(u, clamp(s_begin + u));
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) xv[j] = *(reinterpret_cast<const half8_t *>(xp[rb] + (int64_t)sc * kStepK) + j);
+        for (int u = 0; u < kDepth - 1; ++u) load_w(u, clamp(s_begin + u));
+        for (int s = s_begin; s < s_end; s += kDepth) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xv[j], wv[u][j], acc[rb], 0, 0, 0);
+            for (int u = 0; u < kDepth; ++u) {             // unrolled so that every register slot index is static
+                const int sc = s + u;
+                load_x((u + kXDepth - 1) % kXDepth, clamp(sc + kXDepth - 1));
+                load_w((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
+                if (sc < s_end) {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xv[u % kXDepth][rb][j], wv[u][j], acc[rb], 0, 0, 0);
                 }
             }
         }
