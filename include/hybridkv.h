@@ -215,6 +215,66 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
                    void *act_dst, int32_t act_cap, int32_t act_pos,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Cache-management policy arithmetic (Sec. 4.3).  Host-only: every pointer below is a HOST pointer,
+ * nothing touches a device.  Times are in any one unit, sizes in any one unit; block counts are real
+ * numbers inside the models and whole blocks (rounded down) in the results.
+ */
+
+/* A linear time model T(n) = slope * n + offset over a block (or token) count n: the form the paper
+ * fits to its samples of T_kv_gen and T_load_kv ("Sampling-based linear regression"). */
+typedef struct hk_line {
+    double slope, offset;
+} hk_line;
+
+/* Least-squares line through `count` >= 2 samples (n[i], t[i]); *r2 (may be NULL) receives the
+ * coefficient of determination.  HK_ERR_SHAPE when all n[i] are equal. */
+int hk_fit_line(const double *n, const double *t, int32_t count, hk_line *line, double *r2);
+
+/* Parameters of Algorithm 1 ("Hybrid Cache Allocation Policy"). */
+typedef struct hk_alloc_params {
+    double T_load_w;       /* weight load latency of one decoder block */
+    hk_line T_kv_gen;      /* KV generation (recompute) latency of n checkpoint blocks; slope > 0 */
+    hk_line T_load_kv;     /* load latency of n KV blocks from the host; slope > 0 */
+    double n_act_gpu;      /* #ACT_GPU: checkpoint blocks resident in GPU memory */
+    double M_host;         /* total capacity of host memory */
+    double S_weight;       /* total size of the weight parameters */
+    double S_kv;           /* size of a KV block; a checkpoint block is half of it */
+} hk_alloc_params;
+
+typedef struct hk_alloc_result {
+    int64_t act_init, kv_init;       /* step 1 */
+    int64_t act_remain, kv_remain;   /* step 2 */
+    int64_t act_host, kv_host;       /* #ACT_Host = act_init + act_remain, #KV_Host = kv_init + kv_remain */
+} hk_alloc_result;
+
+/*
+ * Algorithm 1.  Step 1: T_budget = T_load_w - T_kv_gen(#ACT_GPU); if it is not negative, ACT_init is the
+ * block count whose regeneration takes T_budget, otherwise KV_init is the block count whose load takes
+ * -T_budget.  Step 2: the host memory left after the weights and step 1 is split into checkpoint and KV
+ * blocks that fill it exactly and take equal time (T_kv_gen(#ACT) = T_load_kv(#KV)); a negative
+ * solution of that 2 x 2 system is replaced by zero and the memory goes to the other kind.
+ */
+int hk_host_block_allocation(const hk_alloc_params *params, hk_alloc_result *result);
+
+enum { HK_BLOCK_KV = 0, HK_BLOCK_ACT = 1 };
+
+/*
+ * Eq. 11: a request keeps #ACT_req : #KV_req = #ACT_Host : #KV_Host.  Returns the type (HK_BLOCK_ACT or
+ * HK_BLOCK_KV) of the next block of a request that holds n_act checkpoint and n_kv KV blocks: the
+ * one that leaves its checkpoint share nearest the host share (ties: the checkpoint block).  With the
+ * paper's example, host ratio 3:1 and five checkpoint plus two KV blocks, the answer is a checkpoint
+ * block.  Negative counts or an all-zero host ratio return HK_ERR_SHAPE.
+ */
+int hk_next_block_type(int64_t n_act, int64_t n_kv, int64_t act_host, int64_t kv_host);
+
+/*
+ * Eq. 12 and 13 for one mini-batch: *balance = T_kv_gen(#ACT_mb) / T_load_kv(#KV_mb) and
+ * *cost = F_b = max(balance, 1 / balance).  Both times must be positive.
+ */
+int hk_minibatch_balance(const hk_line *T_kv_gen, const hk_line *T_load_kv, double n_act_mb, double n_kv_mb,
+                         double *balance, double *cost);
+
 /*
  * Measurement aid (no operation of the paper): runs a loop of back-to-back
  * v_mfma_f32_32x32x16_f16 on every compute unit (4 wavefronts each, `iters`

@@ -25,6 +25,23 @@ class hk_shape(ctypes.Structure):
                 ("attn_splits", ctypes.c_int32), ("gemm_tile", ctypes.c_int32)]
 
 
+class hk_line(ctypes.Structure):
+    _fields_ = [("slope", ctypes.c_double), ("offset", ctypes.c_double)]
+
+
+class hk_alloc_params(ctypes.Structure):
+    _fields_ = [("T_load_w", ctypes.c_double), ("T_kv_gen", hk_line), ("T_load_kv", hk_line),
+                ("n_act_gpu", ctypes.c_double), ("M_host", ctypes.c_double), ("S_weight", ctypes.c_double),
+                ("S_kv", ctypes.c_double)]
+
+
+class hk_alloc_result(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int64) for k in ("act_init", "kv_init", "act_remain", "kv_remain", "act_host", "kv_host")]
+
+
+HK_BLOCK_KV, HK_BLOCK_ACT = 0, 1
+
+
 class hk_layer_params(ctypes.Structure):
     _fields_ = [("ln_w", ctypes.c_void_p), ("ln_b", ctypes.c_void_p),
                 ("Wkv", ctypes.c_void_p), ("bkv", ctypes.c_void_p), ("prepared", ctypes.c_void_p)]
@@ -69,6 +86,16 @@ def lib():
         L.hk_qkv_current.restype = ctypes.c_int
         L.hk_qkv_current.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp,
                                      vp, vp, vp, i32, i32, vp, i32, i32, vp, sz, vp]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.hk_fit_line.restype = ctypes.c_int
+        L.hk_fit_line.argtypes = [dp, dp, i32, ctypes.POINTER(hk_line), dp]
+        L.hk_host_block_allocation.restype = ctypes.c_int
+        L.hk_host_block_allocation.argtypes = [ctypes.POINTER(hk_alloc_params), ctypes.POINTER(hk_alloc_result)]
+        L.hk_next_block_type.restype = ctypes.c_int
+        L.hk_next_block_type.argtypes = [ctypes.c_int64] * 4
+        L.hk_minibatch_balance.restype = ctypes.c_int
+        L.hk_minibatch_balance.argtypes = [ctypes.POINTER(hk_line), ctypes.POINTER(hk_line), ctypes.c_double,
+                                           ctypes.c_double, dp, dp]
         L.hk_probe_mfma_rate.restype = ctypes.c_int
         L.hk_probe_mfma_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         L.hk_status_string.restype = ctypes.c_char_p
@@ -250,3 +277,45 @@ def qkv_current(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, q_out=None, K_dst=
     if st != HK_OK:
         raise HybridKVError(st, "hk_qkv_current")
     return q_out
+
+
+# ----------------------------------------------------------------------------- host-only policy arithmetic (Sec. 4.3)
+def fit_line(n, t):
+    """hk_fit_line: least-squares (slope, offset, r2) of samples t[i] over n[i]."""
+    import numpy as np
+    n = np.ascontiguousarray(n, dtype=np.float64)
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    line, r2 = hk_line(), ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    st = lib().hk_fit_line(n.ctypes.data_as(dp), t.ctypes.data_as(dp), len(n), ctypes.byref(line), ctypes.byref(r2))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_fit_line")
+    return line.slope, line.offset, r2.value
+
+
+def host_block_allocation(T_load_w, T_kv_gen, T_load_kv, n_act_gpu, M_host, S_weight, S_kv):
+    """hk_host_block_allocation (Algorithm 1); lines are (slope, offset) pairs.  Returns a dict of the six counts."""
+    p = hk_alloc_params(T_load_w, hk_line(*T_kv_gen), hk_line(*T_load_kv), n_act_gpu, M_host, S_weight, S_kv)
+    r = hk_alloc_result()
+    st = lib().hk_host_block_allocation(ctypes.byref(p), ctypes.byref(r))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_host_block_allocation")
+    return {k: int(getattr(r, k)) for k, _ in hk_alloc_result._fields_}
+
+
+def next_block_type(n_act, n_kv, act_host, kv_host):
+    """hk_next_block_type (Eq. 11): "ACT" or "KV"."""
+    st = lib().hk_next_block_type(n_act, n_kv, act_host, kv_host)
+    if st < 0:
+        raise HybridKVError(st, "hk_next_block_type")
+    return "ACT" if st == HK_BLOCK_ACT else "KV"
+
+
+def minibatch_balance(T_kv_gen, T_load_kv, n_act_mb, n_kv_mb):
+    """hk_minibatch_balance (Eq. 12, 13): (balance, F_b)."""
+    b, c = ctypes.c_double(), ctypes.c_double()
+    st = lib().hk_minibatch_balance(ctypes.byref(hk_line(*T_kv_gen)), ctypes.byref(hk_line(*T_load_kv)),
+                                    n_act_mb, n_kv_mb, ctypes.byref(b), ctypes.byref(c))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_minibatch_balance")
+    return b.value, c.value
