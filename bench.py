@@ -141,8 +141,7 @@ def sweep(args):
         torch.cuda.empty_cache()
     n = np.array([x["regen_tokens"] for x in rows if x["regen_tokens"]], dtype=np.float64)
     t = np.array([x["t_kv_gen_ms"] for x in rows if x["regen_tokens"]], dtype=np.float64)
-    a, b0 = np.polyfit(n, t, 1)
-    r2 = 1.0 - float(((t - (a * n + b0)) ** 2).sum() / ((t - t.mean()) ** 2).sum())
+    a, b0, r2 = hk.fit_line(n, t)                                 # the library's least-squares line (Sec. 4.3)
     n_tot = float(B) * L
     balance = {}
     for name, gbps in (("pcie4_x16_32GBps (the paper's link)", 32.0), ("pcie5_x16_64GBps", 64.0)):

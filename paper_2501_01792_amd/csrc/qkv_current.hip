@@ -13,11 +13,11 @@
 //              row in fp16 to scratch (and the raw row to the checkpoint store when asked).
 //   qkv_rows:  one workgroup per slab of 32 output features.  Its 4 wavefronts each take a quarter of
 //              the reduction axis, stream their part of the 32 weight rows straight from HBM into
-//              registers (each lane 64 contiguous bytes per step, two lanes per 128-byte line, several
-//              steps' loads in flight during the MFMAs) and multiply them with the matching part of
-//              xhat (read through L2) on the matrix cores (v_mfma_f32_32x32x16_f16; the k order inside
-//              a step is permuted identically for both operands so that loads stay contiguous).
-//              The four partial sums meet in LDS; bias, fp16 and the scatter to q / K / V follow.
+//              registers with whole-line loads (8 lanes per 128-byte line, several steps in flight),
+//              turn them into MFMA operand layout through a private 4 KiB LDS block and multiply them
+//              with the matching part of xhat (read through L2 the same way) on the matrix cores
+//              (v_mfma_f32_32x32x16_f16).  The four partial sums meet in LDS; bias, fp16 and the
+//              scatter to q / K / V follow.
 #include "hk_internal.h"
 
 namespace hk {
@@ -90,6 +90,15 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
 
 constexpr int kSlab = 32;                // output features per workgroup
 constexpr int kStepK = 64;               // reduction elements per step of one wavefront
+constexpr int kBlockBytes = 32 * kStepK * 2;               // 4 KiB: 32 rows x 128 bytes of one operand, one step
+
+// Bytes of LDS of one workgroup: per wavefront one 4 KiB block for the weights and RB for xhat while the
+// loop runs; afterwards the same memory holds the four partial sums (4 x 32 RB x 32 floats).
+template <int RB>
+constexpr int qkv_rows_lds_bytes()
+{
+    return 4 * (1 + RB) * kBlockBytes > 4 * RB * 32 * kSlab * 4 ? 4 * (1 + RB) * kBlockBytes : 4 * RB * 32 * kSlab * 4;
+}
 
 // RB = row blocks of 32 (B <= 32 RB)
 template <int RB>
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
     _Float16 *__restrict__ q_out, _Float16 *__restrict__ K_dst, _Float16 *__restrict__ V_dst,
     int B, int d, int n_heads, int head_dim, int L_cap, int tok_pos)
 {
-    __shared__ float red[4][RB * 32][kSlab];          // 16 KiB per row block
+    extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,21 +116,40 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
     // the slab lies inside one of the three weight blocks (d % 32 == 0)
     const _Float16 *W = n0 < d ? Wq + (int64_t)n0 * d : Wkv + (int64_t)(n0 - d) * d;
 
-    const int ln = lane & 31, lh = lane >> 5;              // weight row / token row inside a block, k half
     // this wavefront's quarter of the reduction axis, in steps of 64 (the last quarter takes the remainder)
     const int steps_total = d / kStepK;
     const int per = (steps_total + 3) / 4;
     const int s_begin = wave * per < steps_total ? wave * per : steps_total;
     const int s_end = s_begin + per < steps_total ? s_begin + per : steps_total;
 
-    const _Float16 *wp = W + (int64_t)ln * d + 32 * lh;    // + 64 s: 64 contiguous bytes per step
-    const _Float16 *xp[RB];
+    // Global side: one load instruction covers 8 rows x 128 bytes, 8 lanes per row (whole lines; two lanes
+    // per row, which is what the MFMA operand layout would ask for, leaves the L2 with four 16-byte
+    // requests per line and runs at a quarter of the rate).  Lane l of load j: row 8 j + l / 8, chunk l % 8.
+    const int g_row = lane >> 3, g_chunk = lane & 7;
+    const _Float16 *wp = W + (int64_t)g_row * d + 8 * g_chunk;             // + 8 j rows, + 64 s
+    const _Float16 *xp[RB][4];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        int m = rb * 32 + ln;
-        if (m >= B) m = B - 1;                             // clamp: rows past the end are computed, never stored
-        xp[rb] = xhat + (int64_t)m * d + 32 * lh;
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int m = rb * 32 + 8 * j + g_row;
+            if (m >= B) m = B - 1;                         // clamp: rows past the end are computed, never stored
+            xp[rb][j] = xhat + (int64_t)m * d + 8 * g_chunk;
+        }
+    // LDS side (private to the wavefront, so no barrier): a block is 32 rows of 128 bytes, the 16-byte chunk
+    // index XOR-ed with (row / 2) % 8, which makes both the row-wise writes and the MFMA-operand reads
+    // (32 rows x one chunk per half wavefront) conflict-free.
+    unsigned char *my = smem + wave * (1 + RB) * kBlockBytes;
+    int wr_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + g_row;
+        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
     }
+    const int ln = lane & 31, lh = lane >> 5;              // operand row inside a block, k half of an MFMA
+    int rd_off[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) rd_off[jj] = ln * 128 + (((2 * jj + lh) ^ ((ln >> 1) & 7)) << 4);
 
     float16_t acc[RB];
 #pragma unroll
@@ -129,25 +157,24 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 
-    // Weight pieces are fetched kDepth - 1 steps ahead, the xhat pieces of a step one step ahead.  Vector
-    // memory loads complete in issue order as far as s_waitcnt can tell, so inside a step the xhat loads
-    // (L2, wanted next step) are issued BEFORE the weight loads (HBM, wanted kDepth - 1 steps later):
-    // the wait for the former then leaves the latter in flight.
+    // Weight pieces are fetched kDepth - 1 steps ahead, xhat pieces kXDepth - 1 steps ahead.  Vector memory
+    // loads complete in issue order as far as s_waitcnt can tell, so inside a step the xhat loads (L2) are
+    // issued BEFORE the weight loads (HBM): the wait for the former then leaves the latter in flight.
     constexpr int kDepth = RB <= 2 ? 6 : 4;
-    constexpr int kXDepth = RB <= 2 ? 3 : 2;               // xhat pieces are fetched kXDepth - 1 steps ahead; divides kDepth
+    constexpr int kXDepth = RB <= 2 ? 3 : 2;               // divides kDepth
     half8_t wv[kDepth][4];
     half8_t xv[kXDepth][RB][4];
     auto load_w = [&](int slot, int sc) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            wv[slot][j] = *(reinterpret_cast<const half8_t *>(wp + (int64_t)sc * kStepK) + j);
+            wv[slot][j] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(wp + (int64_t)(8 * j) * d + (int64_t)sc * kStepK));
     };
     auto load_x = [&](int slot, int sc) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                xv[slot][rb][j] = *(reinterpret_cast<const half8_t *>(xp[rb] + (int64_t)sc * kStepK) + j);
+                xv[slot][rb][j] = *reinterpret_cast<const half8_t *>(xp[rb][j] + (int64_t)sc * kStepK);
     };
     // Every load of the loop is unconditional (steps past the end re-read the last step, an L2 hit), so
     // that the number of loads in flight at each wait is a compile-time fact; only the MFMAs are guarded.
@@ -165,17 +192,33 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
                 load_x((u + kXDepth - 1) % kXDepth, clamp(sc + kXDepth - 1));
                 load_w((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
                 if (sc < s_end) {
+                    // registers (row-wise) -> LDS -> registers (MFMA operand layout)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) *reinterpret_cast<half8_t *>(my + wr_off[j]) = wv[u][j];
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xv[u % kXDepth][rb][j], wv[u][j], acc[rb], 0, 0, 0);
+                            *reinterpret_cast<half8_t *>(my + (1 + rb) * kBlockBytes + wr_off[j]) = xv[u % kXDepth][rb][j];
+                    half8_t wf[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) wf[jj] = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const half8_t xf = *reinterpret_cast<const half8_t *>(my + (1 + rb) * kBlockBytes + rd_off[jj]);
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf[jj], acc[rb], 0, 0, 0);
+                        }
                 }
             }
         }
     }
 
-    // ---- the four k quarters meet in LDS.  acc[rb][r]: token row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature lane%32
+    // ---- the four k quarters meet in LDS (the staging blocks are dead once every wavefront is here).
+    // acc[rb][r]: token row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature lane%32
+    __syncthreads();
+    float (*red)[RB * 32][kSlab] = reinterpret_cast<float (*)[RB * 32][kSlab]>(smem);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -216,7 +259,11 @@ template <int RB>
 hipError_t launch_rows(const QkvArgs &a, hipStream_t s)
 {
     const int slabs = (a.K_dst ? 3 : 1) * (a.d / kSlab);
-    hipLaunchKernelGGL(qkv_rows_kernel<RB>, dim3((unsigned)slabs), dim3(256), 0, s,
+    auto kern = qkv_rows_kernel<RB>;
+    constexpr int lds = qkv_rows_lds_bytes<RB>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)slabs), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.xhat), static_cast<const _Float16 *>(a.Wq),
                        static_cast<const _Float16 *>(a.bq), static_cast<const _Float16 *>(a.Wkv),
                        static_cast<const _Float16 *>(a.bkv), static_cast<_Float16 *>(a.q_out),
