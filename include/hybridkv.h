@@ -215,6 +215,52 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
                    void *act_dst, int32_t act_cap, int32_t act_pos,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Paged hybrid cache (Sec. 4.1, 4.2.1): the context of every request is a list of logical blocks of
+ * `block_tokens` tokens; a block is a KV block (K and V rows in the KV pool) or an ACT block (the
+ * tokens' checkpoints in the activation pool, half the bytes).  The block table maps each logical block
+ * to its kind and physical block number.  Everything lives in device memory (there is no host offload
+ * on this path, so the table carries no location).
+ *
+ *   K_pool, V_pool [P_kv, H, block_tokens, dh] fp16     a KV block holds its tokens head-major
+ *   act_pool       [P_act, block_tokens, d]    fp16     an ACT block holds its tokens' layer inputs
+ *   block_table    [B, max_blocks] int32, device: entry >= 0 is KV block `entry`; entry < 0 is ACT
+ *                  block ~entry (bitwise not).  Only the first ceil(seq_len[r] / block_tokens) entries of
+ *                  row r are read.  ACT entries must be < n_act_used, KV entries < P_kv.
+ *   seq_len        [B] int32, device: tokens of request r; the last block may be partly filled
+ *   cu_tokens      [B + 1] int64, device: exclusive prefix sums of seq_len
+ *   total_tokens   HOST copy of cu_tokens[B] (the library sizes its launch from it)
+ *   n_act_used     ACT blocks 0 .. n_act_used - 1 of the pool are in use: they are the ones regenerated
+ */
+typedef struct hk_paged_cache {
+    const void *K_pool, *V_pool;
+    const void *act_pool;
+    const int32_t *block_table;
+    const int32_t *seq_len;
+    const int64_t *cu_tokens;
+    int64_t total_tokens;
+    int32_t P_kv, P_act, n_act_used;
+    int32_t block_tokens;          /* a power of two, 16 .. 1024 */
+    int32_t max_blocks;
+} hk_paged_cache;
+
+/*
+ * The hybrid-cache decode step on a paged cache: regenerate the K/V rows of the ACT blocks in use
+ * (Sec. 3.3, Eq. 7, over the whole activation pool prefix as one GEMM), then for the decode query of
+ * every (request, head) attend over all of the request's tokens through the block table (Eq. 3, 4).
+ * Requests may have different lengths; a request of length 0 gets an all-zero output.
+ *
+ *   q, out     [B, H, dh] fp16
+ *   params     as for hk_hybrid_decode_attn (may be NULL when n_act_used == 0)
+ *   workspace  needs hk_paged_workspace_bytes(shape, B, cache)
+ * The table, lengths and prefix sums are device data and cannot be checked on the host; the kernels
+ * clamp block numbers to the pools, so inconsistent tables give wrong numbers, not stray accesses.
+ */
+size_t hk_paged_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache);
+int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const hk_paged_cache *cache,
+                         const hk_layer_params *params, void *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Cache-management policy arithmetic (Sec. 4.3).  Host-only: every pointer below is a HOST pointer,
  * nothing touches a device.  Times are in any one unit, sizes in any one unit; block counts are real

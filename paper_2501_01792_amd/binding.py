@@ -42,6 +42,13 @@ class hk_alloc_result(ctypes.Structure):
 HK_BLOCK_KV, HK_BLOCK_ACT = 0, 1
 
 
+class hk_paged_cache(ctypes.Structure):
+    _fields_ = [("K_pool", ctypes.c_void_p), ("V_pool", ctypes.c_void_p), ("act_pool", ctypes.c_void_p),
+                ("block_table", ctypes.c_void_p), ("seq_len", ctypes.c_void_p), ("cu_tokens", ctypes.c_void_p),
+                ("total_tokens", ctypes.c_int64), ("P_kv", ctypes.c_int32), ("P_act", ctypes.c_int32),
+                ("n_act_used", ctypes.c_int32), ("block_tokens", ctypes.c_int32), ("max_blocks", ctypes.c_int32)]
+
+
 class hk_layer_params(ctypes.Structure):
     _fields_ = [("ln_w", ctypes.c_void_p), ("ln_b", ctypes.c_void_p),
                 ("Wkv", ctypes.c_void_p), ("bkv", ctypes.c_void_p), ("prepared", ctypes.c_void_p)]
@@ -86,6 +93,11 @@ def lib():
         L.hk_qkv_current.restype = ctypes.c_int
         L.hk_qkv_current.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp,
                                      vp, vp, vp, i32, i32, vp, i32, i32, vp, sz, vp]
+        L.hk_paged_workspace_bytes.restype = ctypes.c_size_t
+        L.hk_paged_workspace_bytes.argtypes = [ctypes.POINTER(hk_shape), i32, ctypes.POINTER(hk_paged_cache)]
+        L.hk_paged_decode_attn.restype = ctypes.c_int
+        L.hk_paged_decode_attn.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_paged_cache),
+                                           ctypes.POINTER(hk_layer_params), vp, vp, sz, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.hk_fit_line.restype = ctypes.c_int
         L.hk_fit_line.argtypes = [dp, dp, i32, ctypes.POINTER(hk_line), dp]
@@ -319,3 +331,43 @@ def minibatch_balance(T_kv_gen, T_load_kv, n_act_mb, n_kv_mb):
     if st != HK_OK:
         raise HybridKVError(st, "hk_minibatch_balance")
     return b.value, c.value
+
+
+# ----------------------------------------------------------------------------- paged hybrid cache
+def make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu_tokens, total_tokens, block_tokens,
+                     n_act_used=None) -> hk_paged_cache:
+    """Fills an hk_paged_cache from GPU tensors (pools may be None when empty)."""
+    import torch
+    f16 = torch.float16
+    P_kv = 0 if K_pool is None else K_pool.shape[0]
+    P_act = 0 if act_pool is None else act_pool.shape[0]
+    ptr = lambda t, name, dt: (_dev_ptr(t, name, dt).value if t is not None else None)
+    return hk_paged_cache(ptr(K_pool, "K_pool", f16), ptr(V_pool, "V_pool", f16), ptr(act_pool, "act_pool", f16),
+                          ptr(block_table, "block_table", torch.int32), ptr(seq_len, "seq_len", torch.int32),
+                          ptr(cu_tokens, "cu_tokens", torch.int64), int(total_tokens), P_kv, P_act,
+                          P_act if n_act_used is None else int(n_act_used), int(block_tokens),
+                          0 if block_table is None else block_table.shape[1])
+
+
+def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_tokens, layer_params,
+                      n_act_used=None, out=None, ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None):
+    """hk_paged_decode_attn: ``q[B,H,dh]``, pools, ``block_table[B,max_blocks]`` int32, ``seq_len[B]`` int32 (GPU
+    tensors) -> ``out[B,H,dh]``.  The prefix sums and the host-side total are derived here from ``seq_len``."""
+    import torch
+    B, H, dh = q.shape
+    shape = make_shape(H * dh, H, ln_eps, softmax_scale)
+    cu = torch.zeros(B + 1, dtype=torch.int64, device=q.device)
+    cu[1:] = torch.cumsum(seq_len.to(torch.int64), 0)
+    total = int(cu[-1].item())
+    cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used)
+    if out is None:
+        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+    if workspace is None:
+        workspace = new_workspace(int(lib().hk_paged_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))), q.device)
+    lp = _params(*layer_params) if layer_params is not None else None
+    st = lib().hk_paged_decode_attn(ctypes.byref(shape), _dev_ptr(q, "q", torch.float16), B, ctypes.byref(cache),
+                                    ctypes.byref(lp) if lp is not None else None, _dev_ptr(out, "out", torch.float16),
+                                    _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_paged_decode_attn")
+    return out

@@ -303,6 +303,99 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
     return HK_OK;
 }
 
+namespace {
+
+struct PagedPlan {
+    int64_t M;                 // rows of the regeneration GEMM: n_act_used * block_tokens
+    int n_waves;
+    float scale;
+    size_t off_k, off_v, off_stats, off_partial, total;
+};
+
+int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p)
+{
+    int st = check_shape(s);
+    if (st != HK_OK) return st;
+    if (!c) return HK_ERR_NULL;
+    if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
+    const int bt = c->block_tokens;
+    if (bt < 16 || bt > 1024 || (bt & (bt - 1)) != 0) return HK_ERR_SHAPE;
+    if (c->P_kv < 0 || c->P_act < 0 || c->n_act_used < 0 || c->n_act_used > c->P_act || c->max_blocks < 0) return HK_ERR_SHAPE;
+    if (c->total_tokens < 0 || c->total_tokens > (int64_t)B * c->max_blocks * bt) return HK_ERR_SHAPE;
+    if (c->total_tokens > 0 && c->P_kv == 0 && c->n_act_used == 0) return HK_ERR_SHAPE;      // tokens but no block to hold them
+    p->M = (int64_t)c->n_act_used * bt;
+    const long double elems = ((long double)c->P_kv + c->P_act) * bt * (long double)s->d;
+    if (elems > 4.0e12L || p->M > 0x7fffffffLL || B * s->n_heads > 0x7fffffffLL) return HK_ERR_SHAPE;
+    p->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)s->head_dim);
+    const size_t kv_bytes = align_up((size_t)p->M * s->d * 2);
+    p->off_k = 0;
+    p->off_v = kv_bytes;
+    p->off_stats = 2 * kv_bytes;
+    size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
+    p->off_partial = end;
+    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0);
+    end += align_up(((size_t)p->n_waves + (size_t)B * s->n_heads) * (s->head_dim + 2) * sizeof(float));
+    p->total = end;
+    return HK_OK;
+}
+
+}  // namespace
+
+size_t hk_paged_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache)
+{
+    PagedPlan p;
+    if (make_paged_plan(shape, B, cache, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const hk_paged_cache *cache,
+                         const hk_layer_params *params, void *out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    PagedPlan p;
+    int st = make_paged_plan(shape, B, cache, &p);
+    if (st != HK_OK) return st;
+    if (B == 0) return HK_OK;
+    if (!q || !out || !workspace || !cache->block_table || !cache->seq_len || !cache->cu_tokens) return HK_ERR_NULL;
+    if (cache->P_kv > 0 && (!cache->K_pool || !cache->V_pool)) return HK_ERR_NULL;
+    if (cache->n_act_used > 0) {
+        st = check_params(params);
+        if (st != HK_OK) return st;
+        if (!cache->act_pool) return HK_ERR_NULL;
+        if (!aligned(cache->act_pool, 16)) return HK_ERR_ALIGN;
+    }
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign)) return HK_ERR_ALIGN;
+    if (cache->P_kv > 0 && (!aligned(cache->K_pool, 16) || !aligned(cache->V_pool, 16))) return HK_ERR_ALIGN;
+    if (!aligned(cache->block_table, 4) || !aligned(cache->seq_len, 4) || !aligned(cache->cu_tokens, 8)) return HK_ERR_ALIGN;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    void *K_regen = ws + p.off_k, *V_regen = ws + p.off_v;
+    if (cache->n_act_used > 0) {
+        // "KV Gen" over the ACT pool: block b of the pool is a sequence of block_tokens checkpoints whose
+        // K/V rows land in block b of the regenerated pools, which have the KV pool's layout
+        Plan rp;
+        rp.M = p.M;
+        st = regen_impl(shape, cache->act_pool, cache->n_act_used, cache->block_tokens, params, K_regen, V_regen,
+                        cache->block_tokens, 0, reinterpret_cast<float2 *>(ws + p.off_stats), rp, hs,
+                        Marks{nullptr, 0, nullptr});
+        if (st != HK_OK) return st;
+    }
+    hk::PagedAttnArgs a;
+    a.q = q;
+    a.K_pool = cache->K_pool; a.V_pool = cache->V_pool;
+    a.K_regen = cache->n_act_used > 0 ? K_regen : nullptr; a.V_regen = cache->n_act_used > 0 ? V_regen : nullptr;
+    a.block_table = cache->block_table; a.seq_len = cache->seq_len; a.cu_tokens = cache->cu_tokens;
+    a.total_tokens = cache->total_tokens; a.max_blocks = cache->max_blocks;
+    a.P_kv = cache->P_kv; a.P_act = cache->n_act_used; a.block_tokens = cache->block_tokens;
+    a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
+    a.partial = reinterpret_cast<float *>(ws + p.off_partial);
+    a.out = out;
+    if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    return HK_OK;
+}
+
 const char *hk_status_string(int status)
 {
     switch (status) {

@@ -78,4 +78,22 @@ constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel t
 // LayerNorm + Q (and K/V) projection of B <= kQkvMaxRows current-token rows, with write-back.
 hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s);
 
+struct PagedAttnArgs {
+    const void *q;                     // [B, H, dh] fp16
+    const void *K_pool, *V_pool;       // [P_kv, H, block_tokens, dh] fp16 (may be null when P_kv == 0)
+    const void *K_regen, *V_regen;     // [P_act, H, block_tokens, dh] fp16: regenerated ACT blocks (null when P_act == 0)
+    const int32_t *block_table;        // [B, max_blocks]: >= 0 KV block number, < 0 ACT block ~entry
+    const int32_t *seq_len;            // [B] tokens per request
+    const int64_t *cu_tokens;          // [B + 1] exclusive prefix sums of seq_len
+    int64_t total_tokens;              // cu_tokens[B]
+    int max_blocks, P_kv, P_act, block_tokens;
+    int B, H, head_dim;
+    float scale;
+    int n_waves;                       // attn_wavefronts(H, total_tokens, 0) -- pairs' tokens counted as one line
+    float *partial;                    // [n_waves + B H, dh + 2] fp32
+    void *out;                         // [B, H, dh] fp16
+};
+// Single-query attention of B requests of different lengths over a block-table-addressed hybrid cache.
+hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);
+
 }  // namespace hk

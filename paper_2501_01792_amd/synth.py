@@ -148,3 +148,40 @@ def make_batch(cfg: LayerConfig, sequences=None, threads: int = 8) -> dict:
             fill(i)
     out.update(make_params(cfg))
     return out
+
+
+def scatter_into_blocks(cfg: LayerConfig, batch: dict, seq_len, block_tokens: int, act_fraction: float, seed: int) -> dict:
+    """Lays a contiguous hybrid context out as a paged cache: request b keeps ``seq_len[b]`` tokens; each of
+    its logical blocks becomes an ACT block with probability ``act_fraction`` and a KV block otherwise;
+    physical block numbers are a random permutation of each pool (with spare, never referenced blocks).
+    ``batch`` needs ``act_full [B, L, d]`` (the layer inputs of every token) and ``K_full, V_full [B, H, L, dh]``
+    (their K/V rows).  Data movement only: no arithmetic of the method."""
+    rng = _rng(cfg.seed, 77, seed)
+    B, H, dh, d, bt = cfg.B, cfg.n_heads, cfg.head_dim, cfg.d, block_tokens
+    n_blocks = [(int(n) + bt - 1) // bt for n in seq_len]
+    max_blocks = max(max(n_blocks), 1)
+    kinds = [rng.random(nb) < act_fraction for nb in n_blocks]
+    n_act = int(sum(int(k.sum()) for k in kinds))
+    n_kv = int(sum(n_blocks)) - n_act
+    P_act, P_kv = n_act + 2, n_kv + 3
+    act_ids = rng.permutation(n_act)                     # ACT blocks in use are 0 .. n_act - 1
+    kv_ids = rng.permutation(P_kv)[:n_kv]
+    K_pool = _normal_f16(rng, (P_kv, H, bt, dh), std=3.0)   # spare blocks and unused rows hold unrelated numbers
+    V_pool = _normal_f16(rng, (P_kv, H, bt, dh), std=3.0)
+    act_pool = _normal_f16(rng, (P_act, bt, d), std=1.0)
+    table = np.full((B, max_blocks), 0x7fffffff, dtype=np.int32)   # never read beyond a request's blocks
+    ia = ik = 0
+    for b in range(B):
+        for i in range(n_blocks[b]):
+            t0, t1 = i * bt, min((i + 1) * bt, int(seq_len[b]))
+            if kinds[b][i]:
+                pb = int(act_ids[ia]); ia += 1
+                act_pool[pb, :t1 - t0] = batch["act_full"][b, t0:t1]
+                table[b, i] = ~pb
+            else:
+                pb = int(kv_ids[ik]); ik += 1
+                K_pool[pb, :, :t1 - t0] = batch["K_full"][b, :, t0:t1]
+                V_pool[pb, :, :t1 - t0] = batch["V_full"][b, :, t0:t1]
+                table[b, i] = pb
+    return {"K_pool": K_pool, "V_pool": V_pool, "act_pool": act_pool, "block_table": table,
+            "seq_len": np.asarray(seq_len, dtype=np.int32), "n_act_used": n_act, "kinds": kinds}

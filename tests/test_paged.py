@@ -1,0 +1,156 @@
+"""Paged hybrid cache (Sec. 4.1, 4.2.1): pins of the paged oracle (CPU), host-side argument checks of
+hk_paged_decode_attn (CPU), and GPU parity against the oracle through the C ABI."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hybridkv_oracle as ho
+from oracle import paged_oracle as pgo
+from paper_2501_01792_amd import binding as hk
+from paper_2501_01792_amd import synth
+
+MAX_ABS = 2e-2
+REL_L2 = 5e-3
+
+
+def _context(cfg, rng_seed):
+    """Contiguous context of cfg.B requests of cfg.L tokens: layer inputs of every token and K/V rows (any
+    numbers: a cache may hold anything) in fp16, plus layer parameters and queries."""
+    rng = np.random.default_rng(rng_seed)
+    B, H, dh, d, L = cfg.B, cfg.n_heads, cfg.head_dim, cfg.d, cfg.L
+    p = synth.make_params(cfg)
+    batch = {"act_full": rng.standard_normal((B, L, d)).astype(np.float16),
+             "K_full": (rng.standard_normal((B, H, L, dh)) * 0.02 * np.sqrt(d)).astype(np.float16),
+             "V_full": (rng.standard_normal((B, H, L, dh)) * 0.02 * np.sqrt(d)).astype(np.float16),
+             "q": (rng.standard_normal((B, H, dh)) * 0.02 * np.sqrt(d)).astype(np.float16)}
+    return p, batch
+
+
+def _reference_by_regrouping(cfg, p, batch, paged, bt):
+    """What the pinned contiguous oracle gives when each request's KV-block tokens are handed over as its
+    cache and its ACT-block tokens as its checkpoints (attention does not depend on token order)."""
+    out = np.zeros((cfg.B, cfg.n_heads, cfg.head_dim))
+    for b in range(cfg.B):
+        n = int(paged["seq_len"][b])
+        if n == 0:
+            continue
+        tok_kv = [t for t in range(n) if not paged["kinds"][b][t // bt]]
+        tok_act = [t for t in range(n) if paged["kinds"][b][t // bt]]
+        Kc = batch["K_full"][b:b + 1][:, :, tok_kv] if tok_kv else None
+        Vc = batch["V_full"][b:b + 1][:, :, tok_kv] if tok_kv else None
+        act = batch["act_full"][b:b + 1][:, tok_act] if tok_act else None
+        o, _, _ = ho.hybrid_decode_attn(batch["q"][b:b + 1], Kc, Vc, act, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
+        out[b] = o[0]
+    return out
+
+
+# ------------------------------------------------------------------ oracle pins (CPU)
+@pytest.mark.parametrize("bt,frac", [(16, 0.5), (32, 0.3), (16, 0.0), (16, 1.0), (64, 0.7)])
+def test_paged_oracle_equals_contiguous_oracle(bt, frac):
+    cfg = synth.LayerConfig("pg", 64, 4, 5, 150, 0.5, 51)
+    p, batch = _context(cfg, 1)
+    seq_len = [150, 1, 16, 0, 97]                     # full, single token, exactly one block, empty, ragged
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, frac, seed=2)
+    got = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
+                                paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
+    ref = _reference_by_regrouping(cfg, p, batch, paged, bt)
+    np.testing.assert_allclose(got, ref, atol=1e-12)
+    assert (got[3] == 0).all()                        # the empty request
+
+
+def test_paged_oracle_single_block_by_hand():
+    """One request, one KV block holding two tokens with k = v = (1,-1), (-1,1), q chosen so that the weights
+    are 3/4 and 1/4 (the hand-worked case of the contiguous oracle): out = (1/2, -1/2); rows of the block
+    beyond the request's length must not matter."""
+    bt = 16
+    K = np.full((1, 1, bt, 2), 99.0); K[0, 0, 0] = (1, -1); K[0, 0, 1] = (-1, 1)
+    q = np.array([[[np.log(3.0) / np.sqrt(2.0), 0.0]]])
+    out = pgo.paged_decode_attn(q, K, K.copy(), np.zeros((0, bt, 2)), np.array([[0]], dtype=np.int32), [2], bt,
+                                np.ones(2), np.zeros(2), np.zeros((4, 2)), np.zeros(4), 1, eps=0.0)
+    np.testing.assert_allclose(out[0, 0], (0.5, -0.5), atol=1e-14)
+
+
+# ------------------------------------------------------------------ host-side checks (CPU)
+def test_paged_rejects_bad_arguments():
+    FAKE = 0x10000
+    ok = hk.make_shape(768, 12)
+    lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+
+    def cache(**kw):
+        f = dict(K_pool=FAKE, V_pool=FAKE, act_pool=FAKE, block_table=FAKE, seq_len=FAKE, cu_tokens=FAKE,
+                 total_tokens=100, P_kv=8, P_act=8, n_act_used=4, block_tokens=16, max_blocks=8)
+        f.update(kw)
+        return hk.hk_paged_cache(**f)
+
+    def call(shape=ok, q=FAKE, B=2, c=None, lp=lp, out=FAKE, ws=FAKE, n=None):
+        c = c or cache()
+        need = hk.lib().hk_paged_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(c))
+        return hk.lib().hk_paged_decode_attn(ctypes.byref(shape), q, B, ctypes.byref(c), ctypes.byref(lp) if lp else None,
+                                             out, ws, need if n is None else n, None)
+
+    need = hk.lib().hk_paged_workspace_bytes(ctypes.byref(ok), 2, ctypes.byref(cache()))
+    assert need >= 2 * 4 * 16 * 768 * 2                                  # the regenerated K and V of the ACT blocks in use
+    assert call(c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE            # not a power of two
+    assert call(c=cache(block_tokens=8)) == hk.HK_ERR_SHAPE
+    assert call(c=cache(n_act_used=9)) == hk.HK_ERR_SHAPE                # more than the pool holds
+    assert call(c=cache(total_tokens=2 * 8 * 16 + 1)) == hk.HK_ERR_SHAPE  # more tokens than the tables can map
+    assert call(c=cache(P_kv=0, n_act_used=0, K_pool=None, V_pool=None)) == hk.HK_ERR_SHAPE   # tokens but no blocks
+    assert call(B=0, q=None, c=cache(total_tokens=0)) == hk.HK_OK
+    assert call(q=None) == hk.HK_ERR_NULL and call(c=cache(block_table=None)) == hk.HK_ERR_NULL
+    assert call(c=cache(K_pool=None)) == hk.HK_ERR_NULL and call(c=cache(act_pool=None)) == hk.HK_ERR_NULL
+    assert call(lp=None) == hk.HK_ERR_NULL                               # ACT blocks in use need the layer
+    assert call(c=cache(cu_tokens=FAKE + 4)) == hk.HK_ERR_ALIGN and call(q=FAKE + 2) == hk.HK_ERR_ALIGN
+    assert call(n=need - 1) == hk.HK_ERR_WORKSPACE
+
+
+# ------------------------------------------------------------------ GPU parity
+def _check(name, got, ref):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert np.isfinite(got).all(), name
+    max_abs = np.abs(got - ref).max()
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    print("%s: max_abs=%.3e rel_l2=%.3e" % (name, max_abs, rel), flush=True)
+    assert max_abs <= MAX_ABS and rel <= REL_L2, (name, max_abs, rel)
+
+
+GPU_CASES = [
+    # name, d, H, B, L, block_tokens, ACT share of the blocks, request lengths (None: random ragged)
+    ("dh64_bt16", 768, 12, 6, 300, 16, 0.5, [300, 1, 16, 0, 97, 255]),
+    ("dh128_bt32", 1024, 8, 5, 700, 32, 0.4, None),
+    ("all_kv", 512, 4, 4, 200, 16, 0.0, None),
+    ("all_act", 512, 4, 3, 130, 64, 1.0, None),
+    ("opt6.7b_shape", 4096, 32, 32, 1024, 16, 0.5, None),     # the benchmark layer with ragged requests
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", GPU_CASES, ids=lambda c: c[0])
+def test_paged_decode_matches_oracle(case):
+    name, d, H, B, L, bt, frac, lens = case
+    print("case", case[:7], flush=True)
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig(name, d, H, B, L, 0.5, 52)
+    p, batch = _context(cfg, 3)
+    rng = np.random.default_rng(4)
+    seq_len = lens if lens is not None else [int(v) for v in rng.integers(1, L + 1, B)]
+    if lens is None:
+        seq_len[0] = L
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, frac, seed=5)
+    g = lambda x: None if x is None or x.shape[0] == 0 else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    out = hk.paged_decode_attn(g(batch["q"]), g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"]),
+                               g(paged["block_table"]), g(paged["seq_len"]), bt, lp, n_act_used=paged["n_act_used"])
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    # the oracle walks the same tables; on the big case only a sample of the requests
+    sample = list(range(B)) if B <= 8 else [0, 1, B // 2, B - 1]
+    ref = pgo.paged_decode_attn(batch["q"][sample], paged["K_pool"], paged["V_pool"], paged["act_pool"],
+                                paged["block_table"][sample], paged["seq_len"][sample], bt,
+                                p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
+    _check("out", out[sample], ref)
+    for b in range(B):
+        if seq_len[b] == 0:
+            assert (out[b] == 0).all()
