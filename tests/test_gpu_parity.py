@@ -76,6 +76,7 @@ SMALL = [
     _cfg("all_cached", 512, 8, 3, 333, 1.0, 14),           # ratio 1: no regeneration
     _cfg("one_token_each", 256, 2, 2, 2, 0.5, 15),         # 1 cached + 1 checkpoint
     _cfg("single_act", 256, 4, 1, 1, 0.0, 16),             # a single context token
+    _cfg("ragged_n", 320, 5, 3, 70, 0.3, 17),              # 2d = 640 output features: 2.5 tiles of 256, 5 of 128
 ]
 
 
@@ -92,17 +93,19 @@ def test_hybrid_step_matches_oracle(hk, oracle, cfg, tile, prepared):
     _check("out", out, ref_out)
 
 
+@pytest.mark.parametrize("prepared", [False, True])
 @pytest.mark.parametrize("cfg", SMALL[:4], ids=lambda c: c.name)
-def test_regen_kv_into_cache_slot(hk, oracle, cfg):
+def test_regen_kv_into_cache_slot(hk, oracle, cfg, prepared):
     """hk_regen_kv writes rows [tok_off, tok_off + L_act) of a larger cache and nothing else."""
-    print("case", cfg, flush=True)
+    print("case", cfg, "prepared", prepared, flush=True)
     batch = synth.make_batch(cfg)
     B, H, dh, L_act = cfg.B, cfg.n_heads, cfg.head_dim, cfg.L_act
     L_cap, off = L_act + 9, 5
     K = torch.full((B, H, L_cap, dh), 7.0, dtype=torch.float16, device="cuda")
     V = torch.full((B, H, L_cap, dh), -7.0, dtype=torch.float16, device="cuda")
-    hk.regen_kv(_gpu(batch["act"]), *(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv")), H,
-                K_out=K, V_out=V, tok_off=off)
+    lp = tuple(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    prep = hk.prepare_layer(*lp, H) if prepared else None
+    hk.regen_kv(_gpu(batch["act"]), *lp, H, K_out=K, V_out=V, tok_off=off, prepared=prep, gemm_tile=256 if prepared else 0)
     torch.cuda.synchronize()
     K, V = K.cpu().numpy(), V.cpu().numpy()
     ref_K, ref_V = oracle.regen_kv(batch["act"], batch["ln_w"], batch["ln_b"], batch["Wkv"], batch["bkv"], H)
