@@ -42,7 +42,7 @@ def profiled_traffic(cfg_name):
             for line in f:
                 if line.startswith("TRAFFIC "):
                     parts = line.split()
-                    kv = dict(p.split("=") for p in parts[2:])
+                    kv = dict(p.split("=") for p in parts[1:] if "=" in p)
                     out[parts[1]] = (float(kv["fetch_kib"]) + float(kv["write_kib"])) * 1024.0
     except OSError:
         pass
@@ -168,7 +168,7 @@ def main():
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unprepared", action="store_true",
-                    help="do not call hk_prepare_layer: LayerNorm runs as the GEMM prologue instead of folded")
+                    help="do not call hk_prepare_layer: the library prepares the layer inside every step")
     ap.add_argument("--sweep", action="store_true", help="ratio sweep of --config (default opt66b) instead of the bench line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of 1 GiB (3 launches) so that profiler byte counters "
@@ -252,7 +252,7 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     gemm_flops, attn_bytes = algorithmic_counts(cfg)
     traffic = profiled_traffic(cfg.name) if args.ratio is None else {}
-    gemm_kernel = "kv_gemm_pipe_kernel" if args.unprepared else "kv_gemm_fold_kernel"
+    gemm_kernel = "kv_gemm_fold_kernel"
     roofline = None
     if cfg.M > 0 and dur["kv_gemm"] > 0:
         ach = gemm_flops / (dur["kv_gemm"] * 1e-3) / 1e12

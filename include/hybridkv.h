@@ -89,14 +89,16 @@ typedef struct hk_layer_params {
 /*
  * Bytes of device workspace that hk_hybrid_decode_attn needs for a batch of B
  * sequences with L_kv cached and L_act checkpointed tokens each (the
- * regenerated K/V, per-row LayerNorm statistics, and the attention partials
- * for shape->attn_splits).  Returns 0 when the shape is invalid.
+ * regenerated K/V, per-row LayerNorm statistics, room for a per-call prepared
+ * layer when the regeneration is large, and the attention partials for
+ * shape->attn_splits).  Returns 0 when the shape is invalid.
  */
 size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);
 
 /*
  * Bytes of device workspace that hk_regen_kv needs (per-row LayerNorm
- * statistics only).  Returns 0 when the shape is invalid.
+ * statistics, and room for a per-call prepared layer when the regeneration is
+ * large).  Returns 0 when the shape is invalid.
  */
 size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act);
 
@@ -109,8 +111,11 @@ size_t hk_regen_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_act)
  * statistics are applied to the accumulators.  hk_prepare_layer computes W'
  * (fp16), c and b' (fp32) into `prepared` (device, 256-byte aligned, at least
  * hk_prepared_bytes(shape) bytes, owned by the caller, valid as long as it is
- * referenced from hk_layer_params.prepared).  Calls given a prepared layer use
- * it for large batches; results agree with the unprepared path to rounding.
+ * referenced from hk_layer_params.prepared).  Large regenerations run on this
+ * form.  A call that is not given a prepared layer prepares one itself, in its
+ * workspace, every time (one extra pass over the weights); a caller that keeps
+ * the layer prepared saves that pass.  Small regenerations apply the LayerNorm
+ * on the fly instead and ignore `prepared`.
  */
 size_t hk_prepared_bytes(const hk_shape *shape);
 int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params,

@@ -20,7 +20,7 @@ struct Plan {
     int n_waves;          // wavefronts of the attention kernel
     float scale;
     // workspace offsets (bytes)
-    size_t off_k, off_v, off_stats, off_partial, total;
+    size_t off_k, off_v, off_stats, off_prep, off_partial, total;   // off_prep: per-call prepared layer (0 bytes when unused)
 };
 
 int check_shape(const hk_shape *s)
@@ -36,6 +36,11 @@ int check_shape(const hk_shape *s)
     if (!(s->ln_eps >= 0.f) || !std::isfinite(s->ln_eps) || !std::isfinite(s->softmax_scale)) return HK_ERR_SHAPE;
     return HK_OK;
 }
+
+struct PreparedLayout {
+    size_t off_w, off_c, off_b, total;
+};
+PreparedLayout prepared_layout(int d);
 
 // Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
 int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p)
@@ -55,6 +60,10 @@ int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool re
     p->off_v = kv_bytes;
     p->off_stats = 2 * kv_bytes;
     size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
+    // The large-problem projection kernel works on a prepared layer; room to prepare one per call, for
+    // callers that do not bring their own.
+    p->off_prep = end;
+    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile)) end += prepared_layout(s->d).total;
     p->off_partial = end;
     p->n_waves = 0;
     if (!regen_only && L_kv + L_act > 0 && p->BH > 0) {
@@ -76,9 +85,6 @@ int check_params(const hk_layer_params *lp)
 }
 
 // Layout of a prepared layer: W' [2d, d] fp16, then c [2d] fp32, then b' [2d] fp32, each 256-byte aligned.
-struct PreparedLayout {
-    size_t off_w, off_c, off_b, total;
-};
 PreparedLayout prepared_layout(int d)
 {
     PreparedLayout L;
@@ -98,22 +104,33 @@ struct Marks {
 };
 
 int regen_impl(const hk_shape *s, const void *act, int64_t B, int64_t L_act, const hk_layer_params *lp,
-               void *K_out, void *V_out, int L_cap, int tok_off, float2 *stats, const Plan &p, hipStream_t stream,
-               const Marks &mk)
+               void *K_out, void *V_out, int L_cap, int tok_off, float2 *stats, void *prep_scratch, int64_t M,
+               hipStream_t stream, const Marks &mk)
 {
-    if (hk::launch_ln_stats(act, stats, p.M, s->d, s->ln_eps, stream) != hipSuccess) return HK_ERR_LAUNCH;
+    const void *prepared = lp->prepared;
+    if (!prepared && hk::kv_gemm_uses_prepared(M, s->d, s->gemm_tile)) {
+        // no prepared layer given: prepare one into the workspace (one pass over the weights)
+        const PreparedLayout L = prepared_layout(s->d);
+        char *pp = static_cast<char *>(prep_scratch);
+        if (hk::launch_prepare_layer(lp->Wkv, lp->bkv, lp->ln_w, lp->ln_b, pp + L.off_w,
+                                     reinterpret_cast<float *>(pp + L.off_c), reinterpret_cast<float *>(pp + L.off_b),
+                                     s->d, stream) != hipSuccess)
+            return HK_ERR_LAUNCH;
+        prepared = prep_scratch;
+    }
+    if (hk::launch_ln_stats(act, stats, M, s->d, s->ln_eps, stream) != hipSuccess) return HK_ERR_LAUNCH;
     if (!mk.put(1)) return HK_ERR_LAUNCH;
     hk::KvGemmArgs g;
     g.act = act; g.stats = stats; g.ln_w = lp->ln_w; g.ln_b = lp->ln_b; g.Wkv = lp->Wkv; g.bkv = lp->bkv;
     g.Wp = nullptr; g.cvec = nullptr; g.bvec = nullptr;
-    if (lp->prepared) {
+    if (prepared) {
         const PreparedLayout L = prepared_layout(s->d);
-        const char *pp = static_cast<const char *>(lp->prepared);
+        const char *pp = static_cast<const char *>(prepared);
         g.Wp = pp + L.off_w;
         g.cvec = reinterpret_cast<const float *>(pp + L.off_c);
         g.bvec = reinterpret_cast<const float *>(pp + L.off_b);
     }
-    g.K_out = K_out; g.V_out = V_out; g.M = p.M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
+    g.K_out = K_out; g.V_out = V_out; g.M = M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
     g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile;
     if (hk::launch_kv_gemm(g, stream) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
@@ -180,7 +197,7 @@ int hk_regen_kv(const hk_shape *shape, const void *act, int32_t B, int32_t L_act
     if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace);
     return regen_impl(shape, act, B, L_act, params, K_out, V_out, L_cap, tok_off,
-                      reinterpret_cast<float2 *>(ws + p.off_stats), p, static_cast<hipStream_t>(stream),
+                      reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, static_cast<hipStream_t>(stream),
                       Marks{nullptr, 0, nullptr});
 }
 
@@ -228,7 +245,7 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     if (!mk.put(0)) return HK_ERR_LAUNCH;
     if (L_act > 0) {
         st = regen_impl(shape, act, B, L_act, params, K_regen, V_regen, L_act, 0,
-                        reinterpret_cast<float2 *>(ws + p.off_stats), p, hs, mk);
+                        reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, hs, mk);
         if (st != HK_OK) return st;
     } else if (!mk.put(1)) {
         return HK_ERR_LAUNCH;
@@ -309,7 +326,7 @@ struct PagedPlan {
     int64_t M;                 // rows of the regeneration GEMM: n_act_used * block_tokens
     int n_waves;
     float scale;
-    size_t off_k, off_v, off_stats, off_partial, total;
+    size_t off_k, off_v, off_stats, off_prep, off_partial, total;
 };
 
 int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p)
@@ -332,6 +349,8 @@ int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, Paged
     p->off_v = kv_bytes;
     p->off_stats = 2 * kv_bytes;
     size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
+    p->off_prep = end;
+    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile)) end += prepared_layout(s->d).total;
     p->off_partial = end;
     p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0);
     end += align_up(((size_t)p->n_waves + (size_t)B * s->n_heads) * (s->head_dim + 2) * sizeof(float));
@@ -375,10 +394,8 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     if (cache->n_act_used > 0) {
         // "KV Gen" over the ACT pool: block b of the pool is a sequence of block_tokens checkpoints whose
         // K/V rows land in block b of the regenerated pools, which have the KV pool's layout
-        Plan rp;
-        rp.M = p.M;
         st = regen_impl(shape, cache->act_pool, cache->n_act_used, cache->block_tokens, params, K_regen, V_regen,
-                        cache->block_tokens, 0, reinterpret_cast<float2 *>(ws + p.off_stats), rp, hs,
+                        cache->block_tokens, 0, reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, hs,
                         Marks{nullptr, 0, nullptr});
         if (st != HK_OK) return st;
     }

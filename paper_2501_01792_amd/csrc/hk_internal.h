@@ -29,13 +29,14 @@ struct KvGemmArgs {
 };
 // LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
+// Whether launch_kv_gemm takes the 256 x 256 streaming kernel for this problem (tile: 0 = choose, 128, 256).
+// That kernel works on a prepared layer (Wp, cvec, bvec), so the caller must supply one.
+bool kv_gemm_uses_prepared(int64_t M, int d, int tile);
 // The 256 x 256 kernel for prepared layers (LayerNorm folded around the product; needs Wp, cvec, bvec).
 hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s);
 // Fills Wp, cvec, bvec from the layer's parameters.
 hipError_t launch_prepare_layer(const void *Wkv, const void *bkv, const void *ln_w, const void *ln_b,
                                 void *Wp, float *cvec, float *bvec, int d, hipStream_t s);
-// The 256 x 256 software-pipelined kernel behind launch_kv_gemm for large problems.
-hipError_t launch_kv_gemm_pipe(const KvGemmArgs &a, hipStream_t s);
 
 struct AttnArgs {
     const void *q;         // [B, H, dh] fp16

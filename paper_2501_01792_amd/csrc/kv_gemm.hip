@@ -8,6 +8,7 @@
 //   * One workgroup = 4 wavefronts (one per SIMD) computes a BM x BN output tile; the
 //     wavefronts form a 2 x 2 grid, each owning a (BM/2) x (BN/2) sub-tile held in
 //     accumulator registers.
+//   (This is the kernel for small problems; large ones take the streaming kernel of kv_gemm_fold.hip.)
 //   * The k loop advances 64 at a time through a double-buffered LDS stage.  Global loads
 //     of step k+1 are in flight while the MFMAs of step k run; one barrier per step.
 //   * LayerNorm is the prologue of the A operand: raw fp16 activations are normalised in
@@ -184,18 +185,22 @@ hipError_t launch_tile(const KvGemmArgs &a, hipStream_t s)
 
 }  // namespace
 
+bool kv_gemm_uses_prepared(int64_t M, int d, int tile)
+{
+    // Large problems: 256x256 tiles (highest reuse per LDS byte).  Problems with too few such
+    // tiles to occupy the 256 compute units take 128x128 tiles.
+    const int64_t big_tiles = ((M + 255) / 256) * ((2 * (int64_t)d + 255) / 256);
+    return (tile ? tile : (big_tiles >= 512 ? 256 : 128)) == 256;
+}
+
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    // Large problems: 256x256 tiles (highest reuse per LDS byte).  Problems with too few such
-    // tiles to occupy the 256 compute units fall back to 128x128 tiles.
-    const int64_t big_tiles = ((a.M + 255) / 256) * ((2 * (int64_t)a.d + 255) / 256);
-    const int tile = a.tile ? a.tile : (big_tiles >= 512 ? 256 : 128);
-    if (tile == 256) {
-        // prepared layer: LayerNorm folded around the product; otherwise LayerNorm as the GEMM prologue
-        return a.Wp ? launch_kv_gemm_fold(a, s) : launch_kv_gemm_pipe(a, s);
+    if (kv_gemm_uses_prepared(a.M, a.d, a.tile)) {
+        if (!a.Wp || !a.cvec || !a.bvec) return hipErrorInvalidValue;
+        return launch_kv_gemm_fold(a, s);                  // LayerNorm folded around the product
     }
-    return launch_tile<128, 128, 2, 2, 8>(a, s);
+    return launch_tile<128, 128, 2, 2, 8>(a, s);           // LayerNorm as the GEMM prologue
 }
 
 }  // namespace hk

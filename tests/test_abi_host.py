@@ -44,7 +44,10 @@ def test_workspace_bytes():
     B, L_kv, L_act = 32, 512, 512
     w = hk.hk_workspace_bytes(s, B, L_kv, L_act)
     regen = 2 * B * L_act * 4096 * 2
-    assert regen + B * L_act * 8 <= w < regen + (64 << 20)
+    prep = hk.hk_prepared_bytes(s)                                  # room for a per-call prepared layer (large problems)
+    assert regen + B * L_act * 8 + prep <= w < regen + prep + (64 << 20)
+    small = hk.hk_workspace_bytes(s, 1, 0, 64)                      # a small problem takes the 128-tile kernel: no such room
+    assert small < prep
     assert hk.hk_regen_workspace_bytes(s, B, L_act) >= B * L_act * 8
     assert hk.hk_workspace_bytes(hk.make_shape(4096, 31), B, L_kv, L_act) == 0     # invalid shape
     assert hk.hk_workspace_bytes(s, 4, 100, 0) > 0
