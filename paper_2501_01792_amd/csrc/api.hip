@@ -352,7 +352,7 @@ int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, Paged
     p->off_prep = end;
     if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile)) end += prepared_layout(s->d).total;
     p->off_partial = end;
-    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0);
+    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, hk::kPagedResidentWaves);
     end += align_up(((size_t)p->n_waves + (size_t)B * s->n_heads) * (s->head_dim + 2) * sizeof(float));
     p->total = end;
     return HK_OK;

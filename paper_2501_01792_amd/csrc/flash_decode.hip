@@ -222,7 +222,7 @@ hipError_t launch_dh(const AttnArgs &a, hipStream_t s)
 
 }  // namespace
 
-int attn_wavefronts(int64_t BH, int64_t L, int splits)
+int attn_wavefronts(int64_t BH, int64_t L, int splits, int resident)
 {
     const int64_t total = BH * L;
     if (total <= 0) return 0;
@@ -230,7 +230,7 @@ int attn_wavefronts(int64_t BH, int64_t L, int splits)
     if (splits > 0) {
         W = BH * splits;                                       // `splits` equal token ranges per pair
     } else {
-        W = kAttnResidentWaves;                                // every wavefront resident: one round
+        W = resident;                                          // every wavefront resident: one round
         const int64_t by_work = (total + 2 * kTile - 1) / (2 * kTile);   // at least ~128 tokens each
         if (W > by_work) W = by_work;
     }

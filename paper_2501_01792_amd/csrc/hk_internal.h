@@ -54,11 +54,13 @@ struct AttnArgs {
 // Wavefronts of the attention kernel that stay resident together on an MI355X: 256 compute units x
 // 4 SIMDs x 4 wavefronts (the kernel's register footprint, <= 128 VGPRs, allows 4 per SIMD).
 constexpr int kAttnResidentWaves = 256 * 4 * 4;
+// The paged kernel carries block addressing on top and fits 3 wavefronts per SIMD.
+constexpr int kPagedResidentWaves = 256 * 4 * 3;
 constexpr int kAttnMaxWaves = 1 << 20;
 // Number of wavefronts the attention kernel uses for BH pairs of L tokens; splits > 0 asks for
 // that many token ranges per pair.  A function of the shape only, so that workspace sizes can be
 // computed without a device.
-int attn_wavefronts(int64_t BH, int64_t L, int splits);
+int attn_wavefronts(int64_t BH, int64_t L, int splits, int resident = kAttnResidentWaves);
 // Single-query attention over the two token segments taken as one context.
 hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s);
 

@@ -93,35 +93,43 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
 
         for (int tb = t_first & ~(kTile - 1); tb < t_last; tb += kTile) {
             half8_t kr[NL], vr[NL];
-            int64_t off[NL];
+            // Address of the rows of load group i: a wavefront-uniform block base (scalar registers) plus a
+            // 32-bit lane offset.  A 64-token tile meets at most four blocks (block_tokens >= 16); rows
+            // tb + i RPL .. + RPL - 1 lie in one of them (block_tokens is a multiple of RPL).  Groups past the
+            // last token are redirected to the last token's block and row, and masked below.
+            int64_t kv_base[4];          // element offset of (block, head h, token 0 of the pair) in its pool
+            bool kv_act[4];
 #pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                // rows tb + i RPL .. + RPL - 1 lie in one block (block_tokens is a multiple of RPL); groups
-                // past the last token are redirected to the last token's block and row, and masked below
-                int bi = (tb + i * RPL) >> blk_log2;
+            for (int j = 0; j < 4; ++j) {
+                int bi = (tb >> blk_log2) + j;
                 bi = bi < last_block ? bi : last_block;
-                int t = tb + i * RPL + g;
-                t = t < t_last ? t : t_last - 1;
-                int row = t - (bi << blk_log2);
-                row = row < 0 ? 0 : row;
                 const int32_t e = __builtin_amdgcn_readfirstlane(tab[bi]);
                 bool is_act = e < 0;
                 int pb = is_act ? ~e : e;
                 if ((is_act ? P_act : P_kv) <= 0) { is_act = !is_act; pb = 0; }   // a corrupt table cannot leave
                 const int P = is_act ? P_act : P_kv;                              // the pools (one is not empty)
                 pb = pb < P ? pb : P - 1;
-                const int64_t o = (int64_t)pb * blk_elems + ((int64_t)h * blk + row) * DH + c * 8;
-                off[i] = is_act ? -o - 1 : o;                      // sign selects the pool
+                kv_act[j] = is_act;
+                kv_base[j] = (int64_t)pb * blk_elems + (int64_t)h * (blk * DH) - (int64_t)(bi << blk_log2) * DH;   // + t * DH
+            }
+            auto lane_off = [&](int i) {
+                int t = tb + i * RPL + g;
+                t = t < t_last ? t : t_last - 1;
+                return (uint32_t)(t * DH + c * 8);
+            };
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int j = (i * RPL) >> blk_log2;               // 0..3, wavefront-uniform
+                const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
+                const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
+                kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? K_regen : K_pool) + b + lane_off(i)));
             }
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
-                const _Float16 *kp = off[i] < 0 ? K_regen + (-off[i] - 1) : K_pool + off[i];
-                kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(kp));
-            }
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                const _Float16 *vp = off[i] < 0 ? V_regen + (-off[i] - 1) : V_pool + off[i];
-                vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(vp));
+                const int j = (i * RPL) >> blk_log2;
+                const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
+                const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
+                vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? V_regen : V_pool) + b + lane_off(i)));
             }
 
             float pd[NL];
