@@ -250,3 +250,41 @@ def test_full_size_configs_sampled(hk, oracle, cfg):
     torch.cuda.empty_cache()
     _sampled_oracle_check(hk, oracle, cfg, n_rows=24, n_pairs=2, prepared=True)
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("tile", [0, 256])
+def test_step_replays_from_a_hip_graph(hk, tile):
+    """The step allocates nothing and never synchronises, so a caller may capture it into a HIP graph.
+    The graph is replayed several times, with eager work and synchronisations of the program's own in
+    between, on changing inputs; every replay must reproduce the eager result bit for bit."""
+    cfg = _cfg("graph", 1024, 8, 4, 320, 0.25, 26)
+    batch = synth.make_batch(cfg)
+    g = {k: _gpu(v) for k, v in batch.items()}
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    shape = hk.make_shape(cfg.d, cfg.n_heads, gemm_tile=tile)     # 256: the streaming kernel, layer prepared in the call
+    ws = hk.new_workspace(hk.hk_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
+    ws_eager = hk.new_workspace(hk.hk_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
+    out = torch.empty((cfg.B, cfg.n_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    q, act = g["q"].clone(), g["act"].clone()
+    # warm up on a side stream (kernel attributes are set on first use), then capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        hk.hybrid_decode_attn(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, out=out, workspace=ws, stream=side,
+                              gemm_tile=tile)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        hk.hybrid_decode_attn(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, out=out, workspace=ws,
+                              stream=torch.cuda.current_stream(), gemm_tile=tile)
+    rng = np.random.default_rng(6)
+    for it in range(4):
+        q.copy_(_gpu((rng.standard_normal(q.shape) * 2).astype(np.float16)))
+        act.copy_(_gpu(rng.standard_normal(act.shape).astype(np.float16)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        ref = hk.hybrid_decode_attn(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, workspace=ws_eager, gemm_tile=tile)
+        torch.cuda.synchronize()
+        assert torch.equal(got, ref), "replay %d differs from the eager step" % it
