@@ -19,6 +19,7 @@
 //              (v_mfma_f32_32x32x16_f16).  The four partial sums meet in LDS; bias, fp16 and the
 //              scatter to q / K / V follow.
 #include "hk_internal.h"
+#include "skinny_mma.h"
 
 namespace hk {
 namespace {
@@ -88,17 +89,7 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
     }
 }
 
-constexpr int kSlab = 32;                // output features per workgroup
-constexpr int kStepK = 64;               // reduction elements per step of one wavefront
-constexpr int kBlockBytes = 32 * kStepK * 2;               // 4 KiB: 32 rows x 128 bytes of one operand, one step
-
-// Bytes of LDS of one workgroup: per wavefront one 4 KiB block for the weights and RB for xhat while the
-// loop runs; afterwards the same memory holds the four partial sums (4 x 32 RB x 32 floats).
-template <int RB>
-constexpr int qkv_rows_lds_bytes()
-{
-    return 4 * (1 + RB) * kBlockBytes > 4 * RB * 32 * kSlab * 4 ? 4 * (1 + RB) * kBlockBytes : 4 * RB * 32 * kSlab * 4;
-}
+using skinny::kSlab;
 
 // RB = row blocks of 32 (B <= 32 RB)
 template <int RB>
@@ -109,122 +100,11 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(
     int B, int d, int n_heads, int head_dim, int L_cap, int tok_pos)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = threadIdx.x;
     const int n0 = blockIdx.x * kSlab;                     // first output feature of the slab, in [0, 3d)
     // the slab lies inside one of the three weight blocks (d % 32 == 0)
     const _Float16 *W = n0 < d ? Wq + (int64_t)n0 * d : Wkv + (int64_t)(n0 - d) * d;
-
-    // this wavefront's quarter of the reduction axis, in steps of 64 (the last quarter takes the remainder)
-    const int steps_total = d / kStepK;
-    const int per = (steps_total + 3) / 4;
-    const int s_begin = wave * per < steps_total ? wave * per : steps_total;
-    const int s_end = s_begin + per < steps_total ? s_begin + per : steps_total;
-
-    // Global side: one load instruction covers 8 rows x 128 bytes, 8 lanes per row (whole lines; two lanes
-    // per row, which is what the MFMA operand layout would ask for, leaves the L2 with four 16-byte
-    // requests per line and runs at a quarter of the rate).  Lane l of load j: row 8 j + l / 8, chunk l % 8.
-    const int g_row = lane >> 3, g_chunk = lane & 7;
-    const _Float16 *wp = W + (int64_t)g_row * d + 8 * g_chunk;             // + 8 j rows, + 64 s
-    const _Float16 *xp[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int m = rb * 32 + 8 * j + g_row;
-            if (m >= B) m = B - 1;                         // clamp: rows past the end are computed, never stored
-            xp[rb][j] = xhat + (int64_t)m * d + 8 * g_chunk;
-        }
-    // LDS side (private to the wavefront, so no barrier): a block is 32 rows of 128 bytes, the 16-byte chunk
-    // index XOR-ed with (row / 2) % 8, which makes both the row-wise writes and the MFMA-operand reads
-    // (32 rows x one chunk per half wavefront) conflict-free.
-    unsigned char *my = smem + wave * (1 + RB) * kBlockBytes;
-    int wr_off[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = 8 * j + g_row;
-        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
-    }
-    const int ln = lane & 31, lh = lane >> 5;              // operand row inside a block, k half of an MFMA
-    int rd_off[4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) rd_off[jj] = ln * 128 + (((2 * jj + lh) ^ ((ln >> 1) & 7)) << 4);
-
-    float16_t acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
-
-    // Weight pieces are fetched kDepth - 1 steps ahead, xhat pieces kXDepth - 1 steps ahead.  Vector memory
-    // loads complete in issue order as far as s_waitcnt can tell, so inside a step the xhat loads (L2) are
-    // issued BEFORE the weight loads (HBM): the wait for the former then leaves the latter in flight.
-    constexpr int kDepth = RB <= 2 ? 6 : 4;
-    constexpr int kXDepth = RB <= 2 ? 3 : 2;               // divides kDepth
-    half8_t wv[kDepth][4];
-    half8_t xv[kXDepth][RB][4];
-    auto load_w = [&](int slot, int sc) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            wv[slot][j] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>(wp + (int64_t)(8 * j) * d + (int64_t)sc * kStepK));
-    };
-    auto load_x = [&](int slot, int sc) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                xv[slot][rb][j] = *reinterpret_cast<const half8_t *>(xp[rb][j] + (int64_t)sc * kStepK);
-    };
-    // Every load of the loop is unconditional (steps past the end re-read the last step, an L2 hit), so
-    // that the number of loads in flight at each wait is a compile-time fact; only the MFMAs are guarded.
-    const int last = s_end - 1;
-    auto clamp = [&](int sc) { return sc < last ? sc : last; };
-    if (s_begin < s_end) {
-#pragma unroll
-        for (int u = 0; u < kXDepth - 1; ++u) load_x(u, clamp(s_begin + u));
-#pragma unroll
-        for (int u = 0; u < kDepth - 1; ++u) load_w(u, clamp(s_begin + u));
-        for (int s = s_begin; s < s_end; s += kDepth) {
-#pragma unroll
-            for (int u = 0; u < kDepth; ++u) {             // unrolled so that every register slot index is static
-                const int sc = s + u;
-                load_x((u + kXDepth - 1) % kXDepth, clamp(sc + kXDepth - 1));
-                load_w((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
-                if (sc < s_end) {
-                    // registers (row-wise) -> LDS -> registers (MFMA operand layout)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) *reinterpret_cast<half8_t *>(my + wr_off[j]) = wv[u][j];
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            *reinterpret_cast<half8_t *>(my + (1 + rb) * kBlockBytes + wr_off[j]) = xv[u % kXDepth][rb][j];
-                    half8_t wf[4];
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) wf[jj] = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) {
-                            const half8_t xf = *reinterpret_cast<const half8_t *>(my + (1 + rb) * kBlockBytes + rd_off[jj]);
-                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf[jj], acc[rb], 0, 0, 0);
-                        }
-                }
-            }
-        }
-    }
-
-    // ---- the four k quarters meet in LDS (the staging blocks are dead once every wavefront is here).
-    // acc[rb][r]: token row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature lane%32
-    __syncthreads();
-    float (*red)[RB * 32][kSlab] = reinterpret_cast<float (*)[RB * 32][kSlab]>(smem);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            red[wave][rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)][ln] = acc[rb][r];
-    __syncthreads();
+    float (*red)[RB * 32][kSlab] = skinny::slab_product<RB, true>(W, kSlab, d, xhat, B, d, d, smem);
 
     // bias, fp16, scatter: thread -> (row, feature) pairs of the B x 32 slab
     const int which = n0 / d;                              // 0: q, 1: k, 2: v
@@ -260,7 +140,7 @@ hipError_t launch_rows(const QkvArgs &a, hipStream_t s)
 {
     const int slabs = (a.K_dst ? 3 : 1) * (a.d / kSlab);
     auto kern = qkv_rows_kernel<RB>;
-    constexpr int lds = qkv_rows_lds_bytes<RB>();
+    constexpr int lds = skinny::lds_bytes<RB>();
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)slabs), dim3(256), lds, s,

@@ -1,0 +1,166 @@
+// Product of one slab of 32 rows streamed from HBM with a small set of rows kept hot in L2, on the matrix
+// cores: D[m][c] = sum_k A[m][k] * S[c][k], m < 32 RB small rows, c < 32 streamed rows, k < d.
+// Shared by the kernels whose cost is one pass over a large row-major operand and whose other operand
+// has few rows (current-token QKV generation; the weight-absorbed decode).
+//
+// One workgroup of 4 wavefronts per slab.  Each wavefront takes a quarter of the reduction axis, streams
+// its part of the slab straight into registers with whole-line loads (8 lanes per 128-byte line, several
+// steps in flight), turns it into MFMA operand layout through a private 4 KiB LDS block and multiplies
+// it with the matching part of the small operand (fetched the same way, through L2).  The four partial
+// sums are left in LDS for the caller's epilogue.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hk {
+namespace skinny {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kSlab = 32;                // streamed rows per workgroup
+constexpr int kStepK = 64;               // reduction elements per step of one wavefront
+constexpr int kBlockBytes = 32 * kStepK * 2;               // 4 KiB: 32 rows x 128 bytes of one operand, one step
+
+// Bytes of dynamic LDS of one workgroup: per wavefront one 4 KiB block for the streamed operand and RB for
+// the small one while the loop runs; afterwards the same memory holds the four partial sums.
+template <int RB>
+constexpr int lds_bytes()
+{
+    return 4 * (1 + RB) * kBlockBytes > 4 * RB * 32 * kSlab * 4 ? 4 * (1 + RB) * kBlockBytes : 4 * RB * 32 * kSlab * 4;
+}
+
+// S: first row of the slab (row stride ld_s elements; rows >= s_rows are not read: the last valid row stands
+// in for them).  A: first small row (row stride ld_a; rows >= a_rows likewise).  d % 64 == 0.
+// Returns red with red[w][m][c], w = 0..3, the partial sum of k quarter w; a barrier has been passed.
+template <int RB, bool NT>
+__device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, int s_rows, int64_t ld_s,
+                                                const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
+                                                int d, unsigned char *smem))[RB * 32][kSlab]
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // this wavefront's quarter of the reduction axis, in steps of 64 (the last quarter takes the remainder)
+    const int steps_total = d / kStepK;
+    const int per = (steps_total + 3) / 4;
+    const int s_begin = wave * per < steps_total ? wave * per : steps_total;
+    const int s_end = s_begin + per < steps_total ? s_begin + per : steps_total;
+
+    // Global side: one load instruction covers 8 rows x 128 bytes, 8 lanes per row (whole lines; two lanes
+    // per row, which is what the MFMA operand layout would ask for, leaves the L2 with four 16-byte
+    // requests per line and runs at a quarter of the rate).  Lane l of load j: row 8 j + l / 8, chunk l % 8.
+    const int g_row = lane >> 3, g_chunk = lane & 7;
+    const _Float16 *wp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int c = 8 * j + g_row;
+        if (c >= s_rows) c = s_rows - 1;                   // clamp: rows past the end are computed, never used
+        wp[j] = S + (int64_t)c * ld_s + 8 * g_chunk;
+    }
+    const _Float16 *xp[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int m = rb * 32 + 8 * j + g_row;
+            if (m >= a_rows) m = a_rows - 1;               // clamp: rows past the end are computed, never used
+            xp[rb][j] = A + (int64_t)m * ld_a + 8 * g_chunk;
+        }
+    // LDS side (private to the wavefront, so no barrier): a block is 32 rows of 128 bytes, the 16-byte chunk
+    // index XOR-ed with (row / 2) % 8, which makes both the row-wise writes and the MFMA-operand reads
+    // (32 rows x one chunk per half wavefront) conflict-free.
+    unsigned char *my = smem + wave * (1 + RB) * kBlockBytes;
+    int wr_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + g_row;
+        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
+    }
+    const int ln = lane & 31, lh = lane >> 5;              // operand row inside a block, k half of an MFMA
+    int rd_off[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) rd_off[jj] = ln * 128 + (((2 * jj + lh) ^ ((ln >> 1) & 7)) << 4);
+
+    float16_t acc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+
+    // Streamed pieces are fetched kDepth - 1 steps ahead, small-operand pieces kXDepth - 1 steps ahead.  Vector memory
+    // loads complete in issue order as far as s_waitcnt can tell, so inside a step the small-operand loads (L2) are
+    // issued BEFORE the streamed loads (HBM): the wait for the former then leaves the latter in flight.
+    constexpr int kDepth = RB <= 2 ? 6 : 4;
+    constexpr int kXDepth = RB <= 2 ? 3 : 2;               // divides kDepth
+    half8_t wv[kDepth][4];
+    half8_t xv[kXDepth][RB][4];
+    auto load_w = [&](int slot, int sc) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+        {
+            const half8_t *src = reinterpret_cast<const half8_t *>(wp[j] + (int64_t)sc * kStepK);
+            wv[slot][j] = NT ? __builtin_nontemporal_load(src) : *src;
+        }
+    };
+    auto load_x = [&](int slot, int sc) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xv[slot][rb][j] = *reinterpret_cast<const half8_t *>(xp[rb][j] + (int64_t)sc * kStepK);
+    };
+    // Every load of the loop is unconditional (steps past the end re-read the last step, an L2 hit), so
+    // that the number of loads in flight at each wait is a compile-time fact; only the MFMAs are guarded.
+    const int last = s_end - 1;
+    auto clamp = [&](int sc) { return sc < last ? sc : last; };
+    if (s_begin < s_end) {
+#pragma unroll
+        for (int u = 0; u < kXDepth - 1; ++u) load_x(u, clamp(s_begin + u));
+#pragma unroll
+        for (int u = 0; u < kDepth - 1; ++u) load_w(u, clamp(s_begin + u));
+        for (int s = s_begin; s < s_end; s += kDepth) {
+#pragma unroll
+            for (int u = 0; u < kDepth; ++u) {             // unrolled so that every register slot index is static
+                const int sc = s + u;
+                load_x((u + kXDepth - 1) % kXDepth, clamp(sc + kXDepth - 1));
+                load_w((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
+                if (sc < s_end) {
+                    // registers (row-wise) -> LDS -> registers (MFMA operand layout)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) *reinterpret_cast<half8_t *>(my + wr_off[j]) = wv[u][j];
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            *reinterpret_cast<half8_t *>(my + (1 + rb) * kBlockBytes + wr_off[j]) = xv[u % kXDepth][rb][j];
+                    half8_t wf[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) wf[jj] = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const half8_t xf = *reinterpret_cast<const half8_t *>(my + (1 + rb) * kBlockBytes + rd_off[jj]);
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf[jj], acc[rb], 0, 0, 0);
+                        }
+                }
+            }
+        }
+    }
+
+    // ---- the four k quarters meet in LDS (the staging blocks are dead once every wavefront is here).
+    // acc[rb][r]: small row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, streamed row lane%32
+    __syncthreads();
+    float (*red)[RB * 32][kSlab] = reinterpret_cast<float (*)[RB * 32][kSlab]>(smem);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            red[wave][rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)][ln] = acc[rb][r];
+    __syncthreads();
+
+    return red;
+}
+
+}  // namespace skinny
+}  // namespace hk
