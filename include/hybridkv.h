@@ -266,6 +266,31 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
                          const hk_layer_params *params, void *out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same step as hk_hybrid_decode_attn (Sec. 4.2.2; Eq. 7, 3, 4) with the same arguments and the same
+ * result up to rounding, computed WITHOUT regenerating K/V: a comparison variant beyond the paper.
+ * For one query per head the K projection of Eq. 7 is applied to the query instead of to the
+ * checkpoint rows (score_t = x^_t . (W_K,h^T q_h) + q_h . b_K,h) and the V projection to the weighted
+ * sum of the rows instead of to every row (o_h = W_V,h (sum_t p_t x^_t) + b_V,h), LayerNorm folded in as
+ * in the prepared layer; the checkpoints are read twice, the weights once, and about head_dim times
+ * fewer FLOP are spent.  The cached segment takes the ordinary attention kernel; the two segments are
+ * joined through their softmax maxima and denominators.  Intermediate values that the regenerating path
+ * rounds to fp16 (the K and V rows) are not rounded here and others are (the carried query, the
+ * weighted row sum), so the two entry points agree to the tolerance of the step, not bit for bit.
+ *
+ *   n_heads <= 128, B <= 65535; otherwise HK_ERR_SHAPE.
+ *   workspace    needs hk_absorbed_workspace_bytes(shape, B, L_kv, L_act); scratch only.
+ * A layer without `prepared` is prepared inside the call (one pass over the weights).
+ */
+size_t hk_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);
+int hk_hybrid_decode_attn_absorbed(const hk_shape *shape,
+                                   const void *q,
+                                   const void *K_cache, const void *V_cache, int32_t L_kv,
+                                   const void *act, int32_t L_act, int32_t B,
+                                   const hk_layer_params *params, float ratio,
+                                   void *out,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Cache-management policy arithmetic (Sec. 4.3).  Host-only: every pointer below is a HOST pointer,
  * nothing touches a device.  Times are in any one unit, sizes in any one unit; block counts are real

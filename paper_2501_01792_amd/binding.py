@@ -88,6 +88,10 @@ def lib():
                                             vp, vp, sz, vp]
         L.hk_hybrid_decode_attn_marked.restype = ctypes.c_int
         L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
+        L.hk_absorbed_workspace_bytes.restype = sz
+        L.hk_absorbed_workspace_bytes.argtypes = [shp, i32, i32, i32]
+        L.hk_hybrid_decode_attn_absorbed.restype = ctypes.c_int
+        L.hk_hybrid_decode_attn_absorbed.argtypes = L.hk_hybrid_decode_attn.argtypes
         L.hk_qkv_workspace_bytes.restype = ctypes.c_size_t
         L.hk_qkv_workspace_bytes.argtypes = [ctypes.POINTER(hk_shape), i32]
         L.hk_qkv_current.restype = ctypes.c_int
@@ -258,6 +262,36 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
         K = workspace[:2 * n].view(f16).view(B, H, L_act, dh)
         V = workspace[v_off:v_off + 2 * n].view(f16).view(B, H, L_act, dh)
         return out, K, V
+    return out
+
+
+def hk_absorbed_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int) -> int:
+    return int(lib().hk_absorbed_workspace_bytes(ctypes.byref(shape), B, L_kv, L_act))
+
+
+def hybrid_decode_attn_absorbed(q, K_cache, V_cache, act, layer_params, ratio, out=None, ln_eps=1e-5,
+                                softmax_scale=0.0, attn_splits=0, workspace=None, stream=None):
+    """hk_hybrid_decode_attn_absorbed: the arguments and the result of ``hybrid_decode_attn``, computed
+    without regenerating K/V."""
+    import torch
+    B, H, dh = q.shape
+    d = H * dh
+    L_kv = 0 if K_cache is None else K_cache.shape[2]
+    L_act = 0 if act is None else act.shape[1]
+    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, 0)
+    if out is None:
+        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+    if workspace is None:
+        workspace = new_workspace(hk_absorbed_workspace_bytes(shape, B, L_kv, L_act), q.device)
+    lp = _params(*layer_params)
+    f16 = torch.float16
+    st = lib().hk_hybrid_decode_attn_absorbed(
+        ctypes.byref(shape), _dev_ptr(q, "q", f16),
+        _dev_ptr(K_cache, "K_cache", f16), _dev_ptr(V_cache, "V_cache", f16), L_kv,
+        _dev_ptr(act, "act", f16), L_act, B, ctypes.byref(lp), float(ratio),
+        _dev_ptr(out, "out", f16), _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_hybrid_decode_attn_absorbed")
     return out
 
 

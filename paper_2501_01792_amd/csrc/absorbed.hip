@@ -1,0 +1,403 @@
+// Decode attention over the activation checkpoints WITHOUT regenerating their K/V rows.
+//
+// The hybrid step (Sec. 4.2.2) turns every checkpoint row x_t into a K row and a V row (Eq. 7) and then runs
+// the single-query attention (Eq. 4) over them.  For one query per head the two linear maps can be moved to
+// the other side of the sums, which gives the same result (up to rounding) for ~head_dim times fewer FLOP:
+// with the folded LayerNorm  K_t = rstd_t (x_t W'_K^T) + nmr_t c_K + b'_K  (likewise V),
+//
+//   score_t(h) = scale [ rstd_t (x_t . u_h) + nmr_t (q_h . c_K,h) + (q_h . b'_K,h) ],   u_h = q_h W'_K,h   [d]
+//   o_h        = W'_V,h y_h + (sum_t p_t nmr_t / l) c_V,h + b'_V,h,                     y_h = sum_t (p_t rstd_t / l) x_t
+//
+// so the checkpoints are streamed twice (scores, weighted row sum) and the weights once; nothing of size
+// [tokens, 2 d] is ever written.  The cached K/V segment goes through the ordinary decode kernel and the two
+// segments are joined by their softmax maxima and denominators.  This is a comparison variant beyond the
+// paper's design (which regenerates K/V with a GEMM); the paper's Eq. 3/4/7 define the result.
+//
+// Kernels (B sequences, H heads, L_act checkpoint rows per sequence):
+//   carry   U[b,h,:]  = q[b,h,:] W'_K,h          rows of W' reduced       column_product (MFMA)
+//   scores  raw[b,h,t] = x[b,t,:] . U[b,h,:]     rows of x streamed       skinny::slab_product (MFMA)
+//   softmax w[b,h,t]  = p_t rstd_t / l           one wavefront per (b,h)
+//   gather  Y[b,h,:]  = sum_t w[b,h,t] x[b,t,:]  rows of x reduced        column_product (MFMA)
+//   project o[b,h,:]  = W'_V,h Y[b,h,:] + ...    rows of W' streamed      skinny::slab_product (MFMA), joins the cached part
+#include "hk_internal.h"
+#include "skinny_mma.h"
+
+namespace hk {
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr float kNegBig = -1.0e30f;
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// column_product: Out[z][m][c] = sum_r A[z][m][r] * S[z][r][c]   (m < a_rows <= 32 RB, r < R, c < n_cols)
+//
+// The streamed operand S is row-major and the reduction runs over its ROWS, so it reaches the matrix cores
+// transposed.  One workgroup per block of 32 NB columns (and batch index z); its 4 wavefronts each take a
+// quarter of the rows in steps of 16: whole 16-byte pieces of 16 rows go from HBM to registers (several steps
+// in flight) and row-wise into a private LDS block, from which every lane picks the 8 values of its column
+// (rows padded by 16 bytes: the two half-wavefronts then use disjoint banks).  A (few rows, reduction axis
+// contiguous, zero beyond R up to the next multiple of 16) is read in operand layout through L2.
+// The four partial sums are added in turn through LDS and written as fp16.
+struct ColArgs {
+    const _Float16 *S; int64_t s_batch, ld_s; int R, n_cols;
+    const _Float16 *A; int64_t a_batch, ld_a; int a_rows;
+    _Float16 *Out; int64_t o_batch, ld_out;
+};
+
+template <int RB, int NB>
+constexpr int col_lds_bytes()
+{
+    constexpr int stage = 4 * 16 * (64 * NB + 16);
+    constexpr int red = 32 * RB * (32 * NB + 8) * 4;
+    return stage > red ? stage : red;
+}
+
+template <int RB, int NB>
+__global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int WC = 32 * NB;                            // columns of the workgroup
+    constexpr int LPR = 4 * NB;                            // lanes per row of a load (16 bytes each)
+    constexpr int RPI = 64 / LPR;                          // rows per load instruction; NB instructions per step
+    constexpr int XS = 2 * WC + 16;                        // bytes between rows of the staging block
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c0 = blockIdx.x * WC;
+    const int64_t z = blockIdx.y;
+    const int valid_cols = p.n_cols - c0 < WC ? p.n_cols - c0 : WC;   // multiple of 8, > 0
+    const _Float16 *S = p.S + z * p.s_batch + c0;
+    const _Float16 *A = p.A + z * p.a_batch;
+
+    const int steps_total = (p.R + 15) / 16;
+    const int per = (steps_total + 3) / 4;
+    const int s_begin = wave * per < steps_total ? wave * per : steps_total;
+    const int s_end = s_begin + per < steps_total ? s_begin + per : steps_total;
+
+    const int g_row = lane / LPR;
+    int g_chunk = lane % LPR;
+    const int wr_off = g_row * XS + g_chunk * 16;          // the LDS side keeps the lane's own chunk
+    if (8 * g_chunk >= valid_cols) g_chunk = valid_cols / 8 - 1;       // clamp: columns past the end are computed, never stored
+    const int ln = lane & 31, lh = lane >> 5;
+    int a_row[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int m = rb * 32 + ln;
+        a_row[rb] = m < p.a_rows ? m : p.a_rows - 1;       // clamp: rows past the end are computed, never stored
+    }
+    unsigned char *my = smem + wave * 16 * XS;
+
+    float16_t acc[RB][NB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
+
+    constexpr int kDepth = 4, kADepth = 2;                 // kADepth divides kDepth
+    half8_t sv[kDepth][NB];
+    half8_t av[kADepth][RB];
+    const int last = s_end - 1;
+    auto clamp = [&](int sc) { return sc < last ? sc : last; };
+    auto load_s = [&](int slot, int sc) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            int r = 16 * sc + RPI * j + g_row;
+            if (r >= p.R) r = p.R - 1;                     // rows past the end meet zeros of A
+            sv[slot][j] = *reinterpret_cast<const half8_t *>(S + (int64_t)r * p.ld_s + 8 * g_chunk);
+        }
+    };
+    auto load_a = [&](int slot, int sc) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            av[slot][rb] = *reinterpret_cast<const half8_t *>(A + (int64_t)a_row[rb] * p.ld_a + 16 * sc + 8 * lh);
+    };
+    // Every load of the loop is unconditional (steps past the end re-read the last step), so that the number
+    // of loads in flight at each wait is a compile-time fact; the small operand (L2) is asked for before the
+    // streamed one (HBM) because vector memory loads retire in issue order.
+    if (s_begin < s_end) {
+#pragma unroll
+        for (int u = 0; u < kADepth - 1; ++u) load_a(u, clamp(s_begin + u));
+#pragma unroll
+        for (int u = 0; u < kDepth - 1; ++u) load_s(u, clamp(s_begin + u));
+        for (int s = s_begin; s < s_end; s += kDepth) {
+#pragma unroll
+            for (int u = 0; u < kDepth; ++u) {
+                const int sc = s + u;
+                load_a((u + kADepth - 1) % kADepth, clamp(sc + kADepth - 1));
+                load_s((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
+                if (sc < s_end) {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        *reinterpret_cast<half8_t *>(my + RPI * j * XS + wr_off) = sv[u][j];
+                    half8_t bf[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[u % kADepth][rb], bf[nb], acc[rb][nb], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- the four row quarters are added in turn (wavefront 3 first) in one fp32 block, which replaces the
+    // staging blocks.  acc[rb][nb][r]: row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, column 32 nb + lane%32.
+    constexpr int RS = WC + 8;                             // floats between rows: half-wavefronts on disjoint banks
+    float *red = reinterpret_cast<float *>(smem);
+    __syncthreads();
+#pragma unroll 1
+    for (int turn = 3; turn >= 0; --turn) {
+        if (wave == turn) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float *dst = red + (rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)) * RS + 32 * nb + ln;
+                        *dst = turn == 3 ? acc[rb][nb][r] : *dst + acc[rb][nb][r];
+                    }
+        }
+        __syncthreads();
+    }
+    _Float16 *Out = p.Out + z * p.o_batch + c0;
+    for (int idx = tid; idx < p.a_rows * (WC / 8); idx += 256) {
+        const int m = idx / (WC / 8), ch = idx % (WC / 8);
+        if (8 * ch >= valid_cols) continue;
+        const float4_t lo = *reinterpret_cast<const float4_t *>(red + m * RS + 8 * ch);
+        const float4_t hi = *reinterpret_cast<const float4_t *>(red + m * RS + 8 * ch + 4);
+        half8_t o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[i] = (_Float16)lo[i];
+            o[4 + i] = (_Float16)hi[i];
+        }
+        *reinterpret_cast<half8_t *>(Out + (int64_t)m * p.ld_out + 8 * ch) = o;
+    }
+}
+
+template <int RB, int NB>
+hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
+{
+    auto kern = column_product_kernel<RB, NB>;
+    constexpr int lds = col_lds_bytes<RB, NB>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((p.n_cols + 32 * NB - 1) / (32 * NB)), (unsigned)batches), dim3(256), lds, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_column_product(const ColArgs &p, int batches, hipStream_t s)
+{
+    if (p.a_rows <= 0 || p.a_rows > 128 || p.R <= 0 || p.n_cols % 64 != 0 || batches <= 0 || batches > 65535)
+        return hipErrorInvalidValue;
+    switch ((p.a_rows + 31) / 32) {
+    case 1: return launch_col<1, 4>(p, batches, s);
+    case 2: return launch_col<2, 4>(p, batches, s);
+    case 3: return launch_col<3, 2>(p, batches, s);
+    default: return launch_col<4, 2>(p, batches, s);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// scores: raw[b][h][t] = x[b,t,:] . U[b,h,:] for a slab of 32 checkpoint rows of one sequence.
+template <int RB>
+__global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
+                                                              float *__restrict__ raw, int L_act, int Lp, int H, int d)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int t0 = blockIdx.x * skinny::kSlab;
+    const int64_t b = blockIdx.y;
+    const int rows = L_act - t0 < skinny::kSlab ? L_act - t0 : skinny::kSlab;
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false>(
+        act + (b * L_act + t0) * d, rows, d, U + b * H * d, H, d, d, smem);
+    for (int idx = tid; idx < H * skinny::kSlab; idx += 256) {
+        const int h = idx / skinny::kSlab, c = idx % skinny::kSlab;
+        if (c < rows)
+            raw[(b * H + h) * Lp + t0 + c] = (red[0][h][c] + red[1][h][c]) + (red[2][h][c] + red[3][h][c]);
+    }
+}
+
+// softmax over the checkpoint rows of one (sequence, head), one wavefront each.  In the log2 domain:
+//   s_t = sl (rstd_t raw_t + nmr_t c1 + c2),  c1 = q . c_K,h,  c2 = q . b'_K,h,  sl = scale log2(e)
+//   w_t = 2^(s_t - m) rstd_t / l  (fp16; zero from L_act to the padded row end),  sums = (m, l, sum_t p_t nmr_t / l)
+__global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q, const float *__restrict__ raw,
+                                                               const float2 *__restrict__ stats,
+                                                               const float *__restrict__ cvec, const float *__restrict__ bvec,
+                                                               _Float16 *__restrict__ w, float4 *__restrict__ sums,
+                                                               int BH, int H, int head_dim, int L_act, int Lp, float sl)
+{
+    const int lane = threadIdx.x & 63;
+    const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bh >= BH) return;                                  // whole wavefront leaves together; no barrier in this kernel
+    const int b = bh / H, h = bh % H;
+    float c1 = 0.f, c2 = 0.f;
+    for (int e = lane; e < head_dim; e += 64) {
+        const float qe = (float)q[(int64_t)bh * head_dim + e];
+        c1 = __builtin_fmaf(qe, cvec[h * head_dim + e], c1);
+        c2 = __builtin_fmaf(qe, bvec[h * head_dim + e], c2);
+    }
+    c1 = wave_sum(c1);
+    c2 = wave_sum(c2);
+    const float *r = raw + (int64_t)bh * Lp;
+    const float2 *st = stats + (int64_t)b * L_act;
+    auto score = [&](int t) {
+        const float2 s2 = st[t];
+        return sl * (__builtin_fmaf(s2.x, r[t], __builtin_fmaf(s2.y, c1, c2)));
+    };
+    float mx = kNegBig;
+    for (int t = lane; t < L_act; t += 64) mx = fmaxf(mx, score(t));
+    mx = wave_max(mx);
+    float l = 0.f, sn = 0.f;
+    for (int t = lane; t < L_act; t += 64) {
+        const float pt = __builtin_amdgcn_exp2f(score(t) - mx);
+        l += pt;
+        sn = __builtin_fmaf(pt, st[t].y, sn);
+    }
+    l = wave_sum(l);
+    sn = wave_sum(sn);
+    const float inv = 1.0f / l;
+    _Float16 *wr = w + (int64_t)bh * Lp;
+    for (int t = lane; t < Lp; t += 64)
+        wr[t] = t < L_act ? (_Float16)(__builtin_amdgcn_exp2f(score(t) - mx) * st[t].x * inv) : (_Float16)0.f;
+    if (lane == 0) sums[bh] = make_float4(mx, l, sn * inv, 0.f);
+}
+
+// project: o_a[b,h,e] = W'_V[h dh + e, :] . Y[b,h,:] + sn c_V + b'_V for a slab of 32 output features of one
+// head, then the join with the cached segment's (maximum, denominator, output).
+template <int RB>
+__global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *__restrict__ Wv, const _Float16 *__restrict__ Y,
+                                                               const float *__restrict__ cv, const float *__restrict__ bv,
+                                                               const float4 *__restrict__ sums,
+                                                               const _Float16 *__restrict__ out_c, const float2 *__restrict__ lse_c,
+                                                               _Float16 *__restrict__ out, int Bc, int H, int head_dim, int d)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int h = blockIdx.y;
+    const int n0 = h * head_dim + blockIdx.x * skinny::kSlab;          // first V feature of the slab
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, true>(
+        Wv + (int64_t)n0 * d, skinny::kSlab, d, Y + (int64_t)h * d, Bc, (int64_t)H * d, d, smem);
+    for (int idx = tid; idx < Bc * skinny::kSlab; idx += 256) {
+        const int b = idx / skinny::kSlab, c = idx % skinny::kSlab;
+        const int n = n0 + c;
+        const int64_t bh = (int64_t)b * H + h;
+        const float4 sa = sums[bh];
+        float o = (red[0][b][c] + red[1][b][c]) + (red[2][b][c] + red[3][b][c]);
+        o += __builtin_fmaf(sa.z, cv[n], bv[n]);
+        if (lse_c) {
+            const float2 sc = lse_c[bh];
+            const float m = fmaxf(sc.x, sa.x);
+            const float wc = sc.y * __builtin_amdgcn_exp2f(sc.x - m), wa = sa.y * __builtin_amdgcn_exp2f(sa.x - m);
+            o = (wc * (float)out_c[bh * head_dim + (n - h * head_dim)] + wa * o) / (wc + wa);
+        }
+        out[bh * head_dim + (n - h * head_dim)] = (_Float16)o;
+    }
+}
+
+template <int RB>
+hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
+{
+    auto kern = absorbed_scores_kernel<RB>;
+    constexpr int lds = skinny::lds_bytes<RB>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((a.L_act + skinny::kSlab - 1) / skinny::kSlab), (unsigned)a.B), dim3(256), lds, s,
+                       static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.L_act, Lp, a.H, a.d);
+    return hipGetLastError();
+}
+
+template <int RB>
+hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+{
+    auto kern = absorbed_project_kernel<RB>;
+    constexpr int lds = skinny::lds_bytes<RB>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    const int64_t bh0 = (int64_t)b0 * a.H;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.head_dim / skinny::kSlab), (unsigned)a.H), dim3(256), lds, s,
+                       static_cast<const _Float16 *>(a.Wp) + (int64_t)a.d * a.d, static_cast<const _Float16 *>(a.Y) + bh0 * a.d,
+                       a.cvec + a.d, a.bvec + a.d, a.sums + bh0,
+                       a.L_kv > 0 ? static_cast<const _Float16 *>(a.out_c) + bh0 * a.head_dim : nullptr,
+                       a.L_kv > 0 ? a.lse_c + bh0 : nullptr,
+                       static_cast<_Float16 *>(a.out) + bh0 * a.head_dim, Bc, a.H, a.head_dim, a.d);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int absorbed_row_pitch(int L_act) { return (L_act + 15) / 16 * 16; }
+
+hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
+{
+    if (a.B <= 0 || a.L_act <= 0) return hipSuccess;
+    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
+    const int Lp = absorbed_row_pitch(a.L_act);
+    const int64_t d = a.d;
+    hipError_t e;
+    // carry the queries through the key weights, at most kAbsorbMaxBatch sequences per launch
+    for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {
+        const int Bc = a.B - b0 < kAbsorbMaxBatch ? a.B - b0 : kAbsorbMaxBatch;
+        ColArgs c;
+        c.S = static_cast<const _Float16 *>(a.Wp); c.s_batch = (int64_t)a.head_dim * d; c.ld_s = d; c.R = a.head_dim; c.n_cols = a.d;
+        c.A = static_cast<const _Float16 *>(a.q) + b0 * d; c.a_batch = a.head_dim; c.ld_a = d; c.a_rows = Bc;
+        c.Out = static_cast<_Float16 *>(a.U) + b0 * a.H * d; c.o_batch = d; c.ld_out = a.H * d;
+        if ((e = launch_column_product(c, a.H, s)) != hipSuccess) return e;
+    }
+    switch ((a.H + 31) / 32) {
+    case 1: e = launch_scores<1>(a, Lp, s); break;
+    case 2: e = launch_scores<2>(a, Lp, s); break;
+    case 3: e = launch_scores<3>(a, Lp, s); break;
+    default: e = launch_scores<4>(a, Lp, s); break;
+    }
+    if (e != hipSuccess) return e;
+    const int64_t BH = (int64_t)a.B * a.H;
+    hipLaunchKernelGGL(absorbed_softmax_kernel, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
+                       static_cast<const _Float16 *>(a.q), a.w_raw, a.stats, a.cvec, a.bvec,
+                       static_cast<_Float16 *>(a.w), a.sums, (int)BH, a.H, a.head_dim, a.L_act, Lp,
+                       a.scale * 1.4426950408889634f);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    {
+        ColArgs c;
+        c.S = static_cast<const _Float16 *>(a.act); c.s_batch = (int64_t)a.L_act * d; c.ld_s = d; c.R = a.L_act; c.n_cols = a.d;
+        c.A = static_cast<const _Float16 *>(a.w); c.a_batch = (int64_t)a.H * Lp; c.ld_a = Lp; c.a_rows = a.H;
+        c.Out = static_cast<_Float16 *>(a.Y); c.o_batch = a.H * d; c.ld_out = d;
+        if ((e = launch_column_product(c, a.B, s)) != hipSuccess) return e;
+    }
+    for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {
+        const int Bc = a.B - b0 < kAbsorbMaxBatch ? a.B - b0 : kAbsorbMaxBatch;
+        switch ((Bc + 31) / 32) {
+        case 1: e = launch_project<1>(a, b0, Bc, s); break;
+        case 2: e = launch_project<2>(a, b0, Bc, s); break;
+        case 3: e = launch_project<3>(a, b0, Bc, s); break;
+        default: e = launch_project<4>(a, b0, Bc, s); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace hk

@@ -259,9 +259,135 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
+    a.lse = nullptr;
     a.after_main = (mk.ev && mk.n > 3) ? mk.ev[3] : nullptr;
     if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     if (!mk.put(4)) return HK_ERR_LAUNCH;
+    return HK_OK;
+}
+
+namespace {
+
+struct AbsorbedPlan {
+    int64_t M, BH;
+    int n_waves;               // wavefronts of the attention kernel over the cached segment
+    int Lp;
+    float scale;
+    size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_partial, total;
+};
+
+int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, AbsorbedPlan *p)
+{
+    Plan base;
+    int st = make_plan(s, B, L_kv, L_act, false, &base);
+    if (st != HK_OK) return st;
+    if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
+    p->M = base.M; p->BH = base.BH; p->scale = base.scale;
+    p->Lp = hk::absorbed_row_pitch((int)L_act);
+    size_t end = 0;
+    auto take = [&](size_t bytes) { const size_t at = end; end += align_up(bytes); return at; };
+    p->off_stats = take((size_t)p->M * sizeof(float2));
+    p->off_prep = take(L_act > 0 ? prepared_layout(s->d).total : 0);
+    const size_t bh = (size_t)p->BH;
+    const bool act = L_act > 0;
+    p->off_u = take(act ? bh * s->d * 2 : 0);
+    p->off_raw = take(act ? bh * p->Lp * 4 : 0);
+    p->off_w = take(act ? bh * p->Lp * 2 : 0);
+    p->off_sums = take(act ? bh * sizeof(float4) : 0);
+    p->off_y = take(act ? bh * s->d * 2 : 0);
+    p->off_outc = take(act ? bh * s->head_dim * 2 : 0);
+    p->off_lse = take(act ? bh * sizeof(float2) : 0);
+    p->n_waves = 0;
+    p->off_partial = end;
+    if (L_kv > 0 && p->BH > 0) {
+        p->n_waves = hk::attn_wavefronts(p->BH, L_kv, s->attn_splits);
+        take(((size_t)p->n_waves + bh) * (s->head_dim + 2) * sizeof(float));
+    }
+    p->total = end;
+    return HK_OK;
+}
+
+}  // namespace
+
+size_t hk_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act)
+{
+    AbsorbedPlan p;
+    if (make_absorbed_plan(shape, B, L_kv, L_act, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
+                                   const void *K_cache, const void *V_cache, int32_t L_kv,
+                                   const void *act, int32_t L_act, int32_t B,
+                                   const hk_layer_params *params, float ratio,
+                                   void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    AbsorbedPlan p;
+    int st = make_absorbed_plan(shape, B, L_kv, L_act, &p);
+    if (st != HK_OK) return st;
+    const int64_t L = (int64_t)L_kv + L_act;
+    if (L == 0) return HK_ERR_SHAPE;
+    if (!(ratio >= 0.f && ratio <= 1.f)) return HK_ERR_RATIO;
+    if (std::fabs((double)ratio * (double)L - (double)L_kv) > 0.5 + 1e-6 * (double)L) return HK_ERR_RATIO;
+    if (B == 0) return HK_OK;
+    if (!q || !out || !workspace) return HK_ERR_NULL;
+    if (L_kv > 0 && (!K_cache || !V_cache)) return HK_ERR_NULL;
+    if (L_act > 0) {
+        st = check_params(params);
+        if (st != HK_OK) return st;
+        if (!act) return HK_ERR_NULL;
+        if (!aligned(act, 16)) return HK_ERR_ALIGN;
+    }
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign)) return HK_ERR_ALIGN;
+    if (L_kv > 0 && (!aligned(K_cache, 16) || !aligned(V_cache, 16))) return HK_ERR_ALIGN;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (L_kv > 0) {
+        // the cached segment alone: straight to `out` when there are no checkpoints
+        hk::AttnArgs a;
+        a.q = q;
+        a.K0 = K_cache; a.V0 = V_cache; a.L0 = L_kv;
+        a.K1 = nullptr; a.V1 = nullptr; a.L1 = 0;
+        a.BH = (int)p.BH; a.head_dim = shape->head_dim; a.scale = p.scale;
+        a.n_waves = p.n_waves;
+        a.partial = reinterpret_cast<float *>(ws + p.off_partial);
+        a.out = L_act > 0 ? static_cast<void *>(ws + p.off_outc) : out;
+        a.lse = L_act > 0 ? reinterpret_cast<float2 *>(ws + p.off_lse) : nullptr;
+        a.after_main = nullptr;
+        if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    }
+    if (L_act == 0) return HK_OK;
+
+    const PreparedLayout PL = prepared_layout(shape->d);
+    const char *pp = static_cast<const char *>(params->prepared);
+    if (!pp) {
+        char *dst = ws + p.off_prep;
+        if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, dst + PL.off_w,
+                                     reinterpret_cast<float *>(dst + PL.off_c), reinterpret_cast<float *>(dst + PL.off_b),
+                                     shape->d, hs) != hipSuccess)
+            return HK_ERR_LAUNCH;
+        pp = dst;
+    }
+    float2 *stats = reinterpret_cast<float2 *>(ws + p.off_stats);
+    if (hk::launch_ln_stats(act, stats, p.M, shape->d, shape->ln_eps, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    hk::AbsorbedArgs a;
+    a.q = q; a.act = act; a.stats = stats;
+    a.Wp = pp + PL.off_w;
+    a.cvec = reinterpret_cast<const float *>(pp + PL.off_c);
+    a.bvec = reinterpret_cast<const float *>(pp + PL.off_b);
+    a.U = ws + p.off_u;
+    a.w_raw = reinterpret_cast<float *>(ws + p.off_raw);
+    a.w = ws + p.off_w;
+    a.sums = reinterpret_cast<float4 *>(ws + p.off_sums);
+    a.Y = ws + p.off_y;
+    a.out_c = ws + p.off_outc;
+    a.lse_c = reinterpret_cast<const float2 *>(ws + p.off_lse);
+    a.out = out;
+    a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d; a.L_act = L_act; a.L_kv = L_kv;
+    a.scale = p.scale;
+    if (hk::launch_absorbed(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
 

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
 // meets the pair's positions [bh L, (bh+1) L), at indices (wavefront + bh).
 template <int DH>
 __global__ __launch_bounds__(DH) void merge_partials_kernel(const float *__restrict__ partial, int L, int64_t total,
-                                                            int W, _Float16 *__restrict__ out)
+                                                            int W, _Float16 *__restrict__ out, float2 *__restrict__ lse)
 {
     const int bh = blockIdx.x, e = threadIdx.x;
     const int64_t lo = (int64_t)bh * L, hi = lo + L - 1;       // first and last position of the pair
@@ -198,6 +198,7 @@ __global__ __launch_bounds__(DH) void merge_partials_kernel(const float *__restr
         l = __builtin_fmaf(wgt, src[i * (DH + 2) + 1], l);
     }
     out[(int64_t)bh * DH + e] = (_Float16)(o / l);
+    if (lse && e == 0) lse[bh] = make_float2(mx, l);
 }
 
 template <int DH>
@@ -216,7 +217,7 @@ hipError_t launch_dh(const AttnArgs &a, hipStream_t s)
     if (e == hipSuccess && a.after_main) e = hipEventRecord(a.after_main, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(merge_partials_kernel<DH>, dim3((unsigned)a.BH), dim3(DH), 0, s,
-                       a.partial, L, total, a.n_waves, static_cast<_Float16 *>(a.out));
+                       a.partial, L, total, a.n_waves, static_cast<_Float16 *>(a.out), a.lse);
     return hipGetLastError();
 }
 

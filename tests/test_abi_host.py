@@ -97,6 +97,35 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
     assert _attn(ok, B=0, ratio=0.9) == hk.HK_ERR_RATIO
 
 
+def test_absorbed_rejects_bad_arguments():
+    """The variant that does not regenerate K/V validates like the step it mirrors, plus its own limits."""
+    def call(shape, q=FAKE, Kc=FAKE, Vc=FAKE, L_kv=128, act=FAKE, L_act=128, B=4, lp=None, ratio=0.5,
+             out=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        if lp is None:
+            lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+        return hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(shape), q, Kc, Vc, L_kv, act, L_act, B,
+                                                       ctypes.byref(lp), ratio, out, ws, ws_bytes, None)
+    ok = hk.make_shape(768, 12)
+    assert call(hk.make_shape(768, 11)) == hk.HK_ERR_SHAPE
+    assert call(hk.make_shape(129 * 64, 129)) == hk.HK_ERR_SHAPE           # more than 128 heads
+    assert call(ok, B=65536) == hk.HK_ERR_SHAPE
+    assert call(ok, ratio=0.25) == hk.HK_ERR_RATIO
+    assert call(ok, L_kv=0, L_act=0, ratio=0.0) == hk.HK_ERR_SHAPE
+    assert call(ok, q=None) == hk.HK_ERR_NULL
+    assert call(ok, act=None) == hk.HK_ERR_NULL
+    assert call(ok, Kc=None) == hk.HK_ERR_NULL
+    assert call(ok, lp=hk.hk_layer_params(FAKE, FAKE, None, FAKE, None)) == hk.HK_ERR_NULL
+    assert call(ok, out=FAKE + 4) == hk.HK_ERR_ALIGN
+    assert call(ok, act=FAKE + 8) == hk.HK_ERR_ALIGN
+    need = hk.hk_absorbed_workspace_bytes(ok, 4, 128, 128)
+    assert need > 0 and call(ok, ws_bytes=need - 1) == hk.HK_ERR_WORKSPACE
+    assert call(ok, B=0) == hk.HK_OK
+    # the workspace holds no regenerated K/V: far below the regenerating step's for a long checkpoint segment
+    big = hk.make_shape(4096, 32)
+    assert hk.hk_absorbed_workspace_bytes(big, 32, 0, 4096) < hk.hk_workspace_bytes(big, 32, 0, 4096) // 4
+    assert hk.hk_absorbed_workspace_bytes(hk.make_shape(129 * 64, 129), 1, 0, 16) == 0
+
+
 def _regen(shape, act=FAKE, B=4, L_act=128, lp=None, K=FAKE, V=FAKE, L_cap=128, tok_off=0, ws=FAKE, ws_bytes=1 << 40):
     if lp is None:
         lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)

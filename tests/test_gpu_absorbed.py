@@ -1,0 +1,118 @@
+"""GPU parity of the decode step that never regenerates K/V (hk_hybrid_decode_attn_absorbed): its output
+against the CPU oracle of the step (Eq. 7, 3, 4 written out), on the same seeded fp16 inputs and to the
+same tolerance as the regenerating entry point, which it must also agree with.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_01792_amd import synth
+from test_gpu_parity import MAX_ABS, REL_L2, SMALL, _cfg, _check, _gpu, _oracle_hybrid, _run_hybrid, hk  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_absorbed(hk, cfg, batch, prepared=False, **kw):
+    lp = tuple(_gpu(batch[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    if prepared:
+        lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    Kc = _gpu(batch["K_cache"]) if cfg.L_kv else None
+    Vc = _gpu(batch["V_cache"]) if cfg.L_kv else None
+    act = _gpu(batch["act"]) if cfg.L_act else None
+    out = hk.hybrid_decode_attn_absorbed(_gpu(batch["q"]), Kc, Vc, act, lp, cfg.ratio, **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+# Beyond the shared small cases: more than 32 / 64 heads (2 and 3 row blocks of the score product), more
+# than 32 sequences (row blocks of the two weight products), more than 128 sequences (two launches of
+# them), checkpoint counts that are not multiples of 16 or 32, a column count that is 64 mod 128.
+SHAPES = SMALL + [
+    _cfg("heads40", 2560, 40, 3, 150, 0.2, 21),
+    _cfg("heads72", 4608, 72, 2, 90, 0.1, 22),
+    _cfg("batch45", 512, 4, 45, 61, 0.5, 23),
+    _cfg("batch130", 256, 4, 130, 40, 0.25, 24),
+    _cfg("long_act", 512, 8, 2, 1500, 0.01, 25),
+]
+
+
+@pytest.mark.parametrize("prepared", [False, True])
+@pytest.mark.parametrize("cfg", SHAPES, ids=lambda c: c.name)
+def test_absorbed_step_matches_oracle(hk, oracle, cfg, prepared):
+    print("case", cfg, "prepared", prepared, flush=True)
+    batch = synth.make_batch(cfg)
+    out = _run_absorbed(hk, cfg, batch, prepared=prepared)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+    _check("out", out, ref_out)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[2], SHAPES[-5]], ids=lambda c: c.name)
+def test_absorbed_agrees_with_regenerating_path(hk, cfg):
+    print("case", cfg, flush=True)
+    batch = synth.make_batch(cfg)
+    a = _run_absorbed(hk, cfg, batch)
+    b, _, _ = _run_hybrid(hk, cfg, batch)
+    _check("absorbed vs regenerated", a, b)
+
+
+def test_absorbed_peaked_scores(hk, oracle):
+    """One checkpoint row that dominates the softmax and one cached row that does: the join of the two
+    segments has to carry maxima that differ by hundreds of units of the exponent."""
+    cfg = _cfg("peaked", 512, 4, 2, 96, 0.5, 31)
+    batch = synth.make_batch(cfg)
+    batch["q"] = (batch["q"].astype(np.float32) * 6).astype(np.float16)
+    batch["K_cache"][0, :, 5, :] = (batch["q"][0].astype(np.float32) * 0.5).astype(np.float16)
+    batch["act"][1, 7] = (batch["act"][1, 7].astype(np.float32) * 4).astype(np.float16)
+    out = _run_absorbed(hk, cfg, batch)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+    _check("out", out, ref_out)
+
+
+def test_absorbed_repeatable_and_workspace_reuse(hk, oracle):
+    """Two different problems through one workspace, larger first: the second result must not depend on
+    what the first left behind (the padded tail of the weight rows is rewritten every call)."""
+    big, small = SHAPES[2], SHAPES[1]
+    from paper_2501_01792_amd import binding
+    sh = binding.make_shape(big.d, big.n_heads, 1e-5, 0.0, 0, 0)
+    n = max(binding.hk_absorbed_workspace_bytes(sh, big.B, big.L_kv, big.L_act),
+            binding.hk_absorbed_workspace_bytes(binding.make_shape(small.d, small.n_heads, 1e-5, 0.0, 0, 0),
+                                                small.B, small.L_kv, small.L_act))
+    ws = binding.new_workspace(n, "cuda")
+    ws.fill_(0x7f)
+    for cfg in (big, small, small):
+        batch = synth.make_batch(cfg)
+        out = _run_absorbed(hk, cfg, batch, workspace=ws)
+        ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+        _check(cfg.name, out, ref_out)
+
+
+def _sampled_pairs_check(hk, oracle, cfg, n_pairs=3, seed=5):
+    batch = synth.make_batch(cfg, threads=16)
+    print("  inputs drawn", flush=True)
+    out = _run_absorbed(hk, cfg, batch, prepared=True)
+    print("  GPU step done", flush=True)
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
+    rng = np.random.default_rng(seed)
+    pairs = [(int(rng.integers(cfg.B)), int(rng.integers(H))) for _ in range(n_pairs)] + [(0, 0), (cfg.B - 1, H - 1)]
+    got, ref = [], []
+    for b, h in pairs:
+        Kb = batch["K_cache"][b, h].astype(np.float64)
+        Vb = batch["V_cache"][b, h].astype(np.float64)
+        if cfg.L_act:
+            xh = oracle.layernorm(batch["act"][b], batch["ln_w"], batch["ln_b"])
+            sel = np.r_[h * dh:(h + 1) * dh, d + h * dh:d + (h + 1) * dh]
+            kv = oracle.kv_projection(xh, batch["Wkv"][sel], batch["bkv"][sel])
+            Kb = np.concatenate([Kb, kv[:, :dh]], axis=0)
+            Vb = np.concatenate([Vb, kv[:, dh:]], axis=0)
+        ref.append(oracle.decode_attention(batch["q"][b:b + 1, h:h + 1], Kb[None, None], Vb[None, None])[0, 0])
+        got.append(out[b, h])
+    _check("out[sampled (b,h)]", np.stack(got), np.stack(ref))
+
+
+@pytest.mark.parametrize("name", ["opt6.7b", "opt13b", "opt30b"])
+def test_absorbed_full_size_sampled(hk, oracle, name):
+    cfg = synth.CONFIGS[name]
+    print("case", cfg, flush=True)
+    torch.cuda.empty_cache()
+    _sampled_pairs_check(hk, oracle, cfg)
+    torch.cuda.empty_cache()
