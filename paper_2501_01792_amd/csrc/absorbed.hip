@@ -5,21 +5,26 @@
 // the other side of the sums, which gives the same result (up to rounding) for ~head_dim times fewer FLOP:
 // with the folded LayerNorm  K_t = rstd_t (x_t W'_K^T) + nmr_t c_K + b'_K  (likewise V),
 //
-//   score_t(h) = scale [ rstd_t (x_t . u_h) + nmr_t (q_h . c_K,h) + (q_h . b'_K,h) ],   u_h = q_h W'_K,h   [d]
-//   o_h        = W'_V,h y_h + (sum_t p_t nmr_t / l) c_V,h + b'_V,h,                     y_h = sum_t (p_t rstd_t / l) x_t
+//   score_t(h) = scale [ rstd_t (x_t . u_h - mean_t sum_k u_h[k]) + q_h . b'_K,h ],     u_h = q_h W'_K,h   [d]
+//   o_h        = W'_V,h y_h + b'_V,h,            y_h = sum_t w_t (x_t - mean_t),         w_t = p_t rstd_t / l
 //
 // so the checkpoints are streamed twice (scores, weighted row sum) and the weights once; nothing of size
-// [tokens, 2 d] is ever written.  The cached K/V segment goes through the ordinary decode kernel and the two
+// [tokens, 2 d] is ever written.  u_h, w_t and y_h are kept in fp16; the two mean terms are formed from the
+// ROUNDED values (sum_k of the stored u_h, sum_t of the stored w_t) and subtracted in fp32 before anything is
+// rounded again, so that a row mean that is large against the row's spread cancels exactly as it does in
+// the LayerNorm, instead of leaving the rounding error of u_h or w_t multiplied by it.  The cached K/V segment goes through the ordinary decode kernel and the two
 // segments are joined by their softmax maxima and denominators.  This is a comparison variant beyond the
 // paper's design (which regenerates K/V with a GEMM); the paper's Eq. 3/4/7 define the result.
 //
 // Kernels (B sequences, H heads, L_act checkpoint rows per sequence):
-//   carry   U[b,h,:]  = q[b,h,:] W'_K,h          rows of W' reduced       column_product (MFMA)
-//   scores  raw[b,h,t] = x[b,t,:] . U[b,h,:]     rows of x streamed       skinny::slab_product (MFMA)
+//   carry   U[h,b,:]  = q[b,h,:] W'_K,h          rows of W' reduced       column_product (MFMA)
+//   scores  raw[b,h,t] = x[b,t,:] . U[h,b,:]     rows of x streamed       skinny::slab_product (MFMA); also the
+//                                                                         LayerNorm statistics of the rows
 //   softmax w[b,h,t]  = p_t rstd_t / l           one wavefront per (b,h)
-//   gather  Y[b,h,:]  = sum_t w[b,h,t] x[b,t,:]  rows of x reduced        column_product (MFMA)
-//   project o[b,h,:]  = W'_V,h Y[b,h,:] + ...    rows of W' streamed      skinny::slab_product (MFMA), joins the cached part
+//   gather  Y[b,h,:]  = sum_t w[b,h,t] x[b,t,:] - sum_t w[b,h,t] mean_t   rows of x reduced   column_product (MFMA)
+//   project o[b,h,:]  = W'_V,h Y[b,h,:] + b'_V   rows of W' streamed      skinny::slab_product (MFMA), joins the cached part
 #include "hk_internal.h"
+#include "kv_gemm_common.h"
 #include "skinny_mma.h"
 
 namespace hk {
@@ -48,51 +53,40 @@ __device__ __forceinline__ float wave_max(float v)
 // column_product: Out[z][m][c] = sum_r A[z][m][r] * S[z][r][c]   (m < a_rows <= 32 RB, r < R, c < n_cols)
 //
 // The streamed operand S is row-major and the reduction runs over its ROWS, so it reaches the matrix cores
-// transposed.  One workgroup per block of 32 NB columns (and batch index z); its 4 wavefronts each take a
-// quarter of the rows in steps of 16: whole 16-byte pieces of 16 rows go from HBM to registers (several steps
-// in flight) and row-wise into a private LDS block, from which every lane picks the 8 values of its column
-// (rows padded by 16 bytes: the two half-wavefronts then use disjoint banks).  A (few rows, reduction axis
-// contiguous, zero beyond R up to the next multiple of 16) is read in operand layout through L2.
-// The four partial sums are added in turn through LDS and written as fp16.
+// transposed.  Every wavefront owns a block of 64 columns (and a batch index z) and walks all R rows in steps
+// of 16: whole 128-byte pieces of 16 rows go from HBM to registers (kDepth - 1 steps in flight) and row-wise
+// into the wavefront's private LDS block, from which every lane picks the 8 values of its column (rows padded
+// by 16 bytes: the two half-wavefronts then use disjoint banks).  A (few rows, reduction axis contiguous,
+// zero beyond R up to the next multiple of 16) is read in MFMA operand layout through L2.  Wavefronts never
+// talk to each other: no barrier.  The result (minus an optional per-row constant, in fp32) leaves through the
+// same LDS block so that it is stored as whole 128-byte rows.
 struct ColArgs {
     const _Float16 *S; int64_t s_batch, ld_s; int R, n_cols;
     const _Float16 *A; int64_t a_batch, ld_a; int a_rows;
     _Float16 *Out; int64_t o_batch, ld_out;
+    const float *shift; int64_t shift_batch; int shift_stride;   // optional: Out[z][m][:] -= shift[z shift_batch + m shift_stride]
 };
 
-template <int RB, int NB>
-constexpr int col_lds_bytes()
-{
-    constexpr int stage = 4 * 16 * (64 * NB + 16);
-    constexpr int red = 32 * RB * (32 * NB + 8) * 4;
-    return stage > red ? stage : red;
-}
+constexpr int kColBlock = 64;                              // columns of one wavefront
+constexpr int kColStage = 32 * (2 * kColBlock + 16);       // bytes of LDS per wavefront: 32 rows of 128 + 16 bytes
 
-template <int RB, int NB>
+template <int RB>
 __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int WC = 32 * NB;                            // columns of the workgroup
-    constexpr int LPR = 4 * NB;                            // lanes per row of a load (16 bytes each)
-    constexpr int RPI = 64 / LPR;                          // rows per load instruction; NB instructions per step
-    constexpr int XS = 2 * WC + 16;                        // bytes between rows of the staging block
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c0 = blockIdx.x * WC;
+    __shared__ __align__(16) unsigned char smem[4 * kColStage];
+    constexpr int NB = kColBlock / 32;
+    constexpr int XS = 2 * kColBlock + 16;                 // bytes between rows of the LDS block
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c0 = (blockIdx.x * 4 + wave) * kColBlock;
+    if (c0 >= p.n_cols) return;                            // whole wavefront leaves; the kernel has no barrier
     const int64_t z = blockIdx.y;
-    const int valid_cols = p.n_cols - c0 < WC ? p.n_cols - c0 : WC;   // multiple of 8, > 0
     const _Float16 *S = p.S + z * p.s_batch + c0;
     const _Float16 *A = p.A + z * p.a_batch;
+    const int steps = (p.R + 15) / 16;
 
-    const int steps_total = (p.R + 15) / 16;
-    const int per = (steps_total + 3) / 4;
-    const int s_begin = wave * per < steps_total ? wave * per : steps_total;
-    const int s_end = s_begin + per < steps_total ? s_begin + per : steps_total;
-
-    const int g_row = lane / LPR;
-    int g_chunk = lane % LPR;
-    const int wr_off = g_row * XS + g_chunk * 16;          // the LDS side keeps the lane's own chunk
-    if (8 * g_chunk >= valid_cols) g_chunk = valid_cols / 8 - 1;       // clamp: columns past the end are computed, never stored
+    // one load instruction: 8 rows x 128 bytes, 8 lanes per row
+    const int g_row = lane >> 3, g_chunk = lane & 7;
     const int ln = lane & 31, lh = lane >> 5;
     int a_row[RB];
 #pragma unroll
@@ -100,7 +94,7 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
         const int m = rb * 32 + ln;
         a_row[rb] = m < p.a_rows ? m : p.a_rows - 1;       // clamp: rows past the end are computed, never stored
     }
-    unsigned char *my = smem + wave * 16 * XS;
+    unsigned char *my = smem + wave * kColStage;
 
     float16_t acc[RB][NB];
 #pragma unroll
@@ -110,15 +104,15 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
 
-    constexpr int kDepth = 4, kADepth = 2;                 // kADepth divides kDepth
-    half8_t sv[kDepth][NB];
+    constexpr int kDepth = 8, kADepth = 2;                 // kADepth divides kDepth
+    half8_t sv[kDepth][2];
     half8_t av[kADepth][RB];
-    const int last = s_end - 1;
+    const int last = steps - 1;
     auto clamp = [&](int sc) { return sc < last ? sc : last; };
     auto load_s = [&](int slot, int sc) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            int r = 16 * sc + RPI * j + g_row;
+        for (int j = 0; j < 2; ++j) {
+            int r = 16 * sc + 8 * j + g_row;
             if (r >= p.R) r = p.R - 1;                     // rows past the end meet zeros of A
             sv[slot][j] = *reinterpret_cast<const half8_t *>(S + (int64_t)r * p.ld_s + 8 * g_chunk);
         }
@@ -131,135 +125,140 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     // Every load of the loop is unconditional (steps past the end re-read the last step), so that the number
     // of loads in flight at each wait is a compile-time fact; the small operand (L2) is asked for before the
     // streamed one (HBM) because vector memory loads retire in issue order.
-    if (s_begin < s_end) {
 #pragma unroll
-        for (int u = 0; u < kADepth - 1; ++u) load_a(u, clamp(s_begin + u));
+    for (int u = 0; u < kADepth - 1; ++u) load_a(u, clamp(u));
 #pragma unroll
-        for (int u = 0; u < kDepth - 1; ++u) load_s(u, clamp(s_begin + u));
-        for (int s = s_begin; s < s_end; s += kDepth) {
+    for (int u = 0; u < kDepth - 1; ++u) load_s(u, clamp(u));
+    for (int s = 0; s < steps; s += kDepth) {
 #pragma unroll
-            for (int u = 0; u < kDepth; ++u) {
-                const int sc = s + u;
-                load_a((u + kADepth - 1) % kADepth, clamp(sc + kADepth - 1));
-                load_s((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
-                if (sc < s_end) {
+        for (int u = 0; u < kDepth; ++u) {
+            const int sc = s + u;
+            load_a((u + kADepth - 1) % kADepth, clamp(sc + kADepth - 1));
+            load_s((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
+            if (sc < steps) {
 #pragma unroll
-                    for (int j = 0; j < NB; ++j)
-                        *reinterpret_cast<half8_t *>(my + RPI * j * XS + wr_off) = sv[u][j];
-                    half8_t bf[NB];
+                for (int j = 0; j < 2; ++j)
+                    *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = sv[u][j];
+                half8_t bf[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[u % kADepth][rb], bf[nb], acc[rb][nb], 0, 0, 0);
-                }
+                        acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[u % kADepth][rb], bf[nb], acc[rb][nb], 0, 0, 0);
             }
         }
     }
 
-    // ---- the four row quarters are added in turn (wavefront 3 first) in one fp32 block, which replaces the
-    // staging blocks.  acc[rb][nb][r]: row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, column 32 nb + lane%32.
-    constexpr int RS = WC + 8;                             // floats between rows: half-wavefronts on disjoint banks
-    float *red = reinterpret_cast<float *>(smem);
-    __syncthreads();
-#pragma unroll 1
-    for (int turn = 3; turn >= 0; --turn) {
-        if (wave == turn) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float *dst = red + (rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)) * RS + 32 * nb + ln;
-                        *dst = turn == 3 ? acc[rb][nb][r] : *dst + acc[rb][nb][r];
-                    }
-        }
-        __syncthreads();
-    }
+    // ---- fp16, through the LDS block, out as whole rows.
+    // acc[rb][nb][r]: row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, column 32 nb + lane%32.
     _Float16 *Out = p.Out + z * p.o_batch + c0;
-    for (int idx = tid; idx < p.a_rows * (WC / 8); idx += 256) {
-        const int m = idx / (WC / 8), ch = idx % (WC / 8);
-        if (8 * ch >= valid_cols) continue;
-        const float4_t lo = *reinterpret_cast<const float4_t *>(red + m * RS + 8 * ch);
-        const float4_t hi = *reinterpret_cast<const float4_t *>(red + m * RS + 8 * ch + 4);
-        half8_t o;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            o[i] = (_Float16)lo[i];
-            o[4 + i] = (_Float16)hi[i];
+    for (int rb = 0; rb < RB; ++rb) {
+        float sub[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int m = 32 * rb + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (m >= p.a_rows) m = p.a_rows - 1;
+            sub[r] = p.shift ? p.shift[z * p.shift_batch + (int64_t)m * p.shift_stride] : 0.f;
         }
-        *reinterpret_cast<half8_t *>(Out + (int64_t)m * p.ld_out + 8 * ch) = o;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                *reinterpret_cast<_Float16 *>(my + (8 * (r >> 2) + 4 * lh + (r & 3)) * XS + 2 * (32 * nb + ln)) =
+                    (_Float16)(acc[rb][nb][r] - sub[r]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = 32 * rb + 8 * j + g_row;
+            const half8_t o = *reinterpret_cast<const half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk);
+            if (m < p.a_rows) *reinterpret_cast<half8_t *>(Out + (int64_t)m * p.ld_out + 8 * g_chunk) = o;
+        }
     }
 }
 
-template <int RB, int NB>
+template <int RB>
 hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
 {
-    auto kern = column_product_kernel<RB, NB>;
-    constexpr int lds = col_lds_bytes<RB, NB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((p.n_cols + 32 * NB - 1) / (32 * NB)), (unsigned)batches), dim3(256), lds, s, p);
+    const int blocks_x = (p.n_cols / kColBlock + 3) / 4;
+    hipLaunchKernelGGL(column_product_kernel<RB>, dim3((unsigned)blocks_x, (unsigned)batches), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
 hipError_t launch_column_product(const ColArgs &p, int batches, hipStream_t s)
 {
-    if (p.a_rows <= 0 || p.a_rows > 128 || p.R <= 0 || p.n_cols % 64 != 0 || batches <= 0 || batches > 65535)
+    if (p.a_rows <= 0 || p.a_rows > 128 || p.R <= 0 || p.n_cols % kColBlock != 0 || batches <= 0 || batches > 65535)
         return hipErrorInvalidValue;
     switch ((p.a_rows + 31) / 32) {
-    case 1: return launch_col<1, 4>(p, batches, s);
-    case 2: return launch_col<2, 4>(p, batches, s);
-    case 3: return launch_col<3, 2>(p, batches, s);
-    default: return launch_col<4, 2>(p, batches, s);
+    case 1: return launch_col<1>(p, batches, s);
+    case 2: return launch_col<2>(p, batches, s);
+    case 3: return launch_col<3>(p, batches, s);
+    default: return launch_col<4>(p, batches, s);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// scores: raw[b][h][t] = x[b,t,:] . U[b,h,:] for a slab of 32 checkpoint rows of one sequence.
+// scores: raw[b][h][t] = x[b,t,:] . U[h,b,:] for a slab of 32 checkpoint rows of one sequence, and the
+// LayerNorm statistics (rstd, -mean rstd) of those rows from the same pass.  Workgroup ids are regrouped so
+// that the slabs of one sequence, which share that sequence's U rows, run on one XCD and find them in its L2.
 template <int RB>
 __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
-                                                              float *__restrict__ raw, int L_act, int Lp, int H, int d)
+                                                              float *__restrict__ raw, float2 *__restrict__ stats,
+                                                              int B, int L_act, int Lp, int H, int d, float eps)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
-    const int t0 = blockIdx.x * skinny::kSlab;
-    const int64_t b = blockIdx.y;
+    const int slabs = (L_act + skinny::kSlab - 1) / skinny::kSlab;
+    const int item = gemm::xcd_regroup(blockIdx.x, slabs * B);
+    const int64_t b = item / slabs;
+    const int t0 = (item % slabs) * skinny::kSlab;
     const int rows = L_act - t0 < skinny::kSlab ? L_act - t0 : skinny::kSlab;
-    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false>(
-        act + (b * L_act + t0) * d, rows, d, U + b * H * d, H, d, d, smem);
+    const _Float16 *S = act + (b * L_act + t0) * d;
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false, true>(S, rows, d, U + b * d, H, (int64_t)B * d, d, smem);
     for (int idx = tid; idx < H * skinny::kSlab; idx += 256) {
         const int h = idx / skinny::kSlab, c = idx % skinny::kSlab;
         if (c < rows)
             raw[(b * H + h) * Lp + t0 + c] = (red[0][h][c] + red[1][h][c]) + (red[2][h][c] + red[3][h][c]);
     }
+    if (tid < rows) {
+        float (*mom)[skinny::kSlab][2] = skinny::moments<RB>(smem);
+        const float s1 = (mom[0][tid][0] + mom[1][tid][0]) + (mom[2][tid][0] + mom[3][tid][0]);
+        const float s2 = (mom[0][tid][1] + mom[1][tid][1]) + (mom[2][tid][1] + mom[3][tid][1]);
+        const float inv_d = 1.0f / (float)d;
+        const float dm = s1 * inv_d;                       // mean - first element
+        const float var = fmaxf(__builtin_fmaf(-dm, dm, s2 * inv_d), 0.f);
+        const float mean = (float)S[(int64_t)tid * d] + dm;
+        const float rstd = 1.0f / __builtin_sqrtf(var + eps);
+        stats[b * L_act + t0 + tid] = make_float2(rstd, -mean * rstd);
+    }
 }
 
 // softmax over the checkpoint rows of one (sequence, head), one wavefront each.  In the log2 domain:
-//   s_t = sl (rstd_t raw_t + nmr_t c1 + c2),  c1 = q . c_K,h,  c2 = q . b'_K,h,  sl = scale log2(e)
-//   w_t = 2^(s_t - m) rstd_t / l  (fp16; zero from L_act to the padded row end),  sums = (m, l, sum_t p_t nmr_t / l)
-__global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q, const float *__restrict__ raw,
-                                                               const float2 *__restrict__ stats,
-                                                               const float *__restrict__ cvec, const float *__restrict__ bvec,
+//   s_t = sl (rstd_t raw_t + nmr_t c1 + c2),  c1 = sum_k U[h,b,k] (the stored fp16 values),  c2 = q . b'_K,h,
+//   sl = scale log2(e);   w_t = fp16(2^(s_t - m) rstd_t / l), zero from L_act to the padded row end;
+//   sums = (m, l, sum_t w_t mean_t with the stored w_t, -)
+__global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q, const _Float16 *__restrict__ U,
+                                                               const float *__restrict__ raw, const float2 *__restrict__ stats,
+                                                               const float *__restrict__ bvec,
                                                                _Float16 *__restrict__ w, float4 *__restrict__ sums,
-                                                               int BH, int H, int head_dim, int L_act, int Lp, float sl)
+                                                               int B, int H, int head_dim, int d, int L_act, int Lp, float sl)
 {
     const int lane = threadIdx.x & 63;
     const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (bh >= BH) return;                                  // whole wavefront leaves together; no barrier in this kernel
+    if (bh >= B * H) return;                               // whole wavefront leaves together; no barrier in this kernel
     const int b = bh / H, h = bh % H;
     float c1 = 0.f, c2 = 0.f;
-    for (int e = lane; e < head_dim; e += 64) {
-        const float qe = (float)q[(int64_t)bh * head_dim + e];
-        c1 = __builtin_fmaf(qe, cvec[h * head_dim + e], c1);
-        c2 = __builtin_fmaf(qe, bvec[h * head_dim + e], c2);
+    const half8_t *u = reinterpret_cast<const half8_t *>(U + ((int64_t)h * B + b) * d);
+    for (int i = lane; i < d / 8; i += 64) {
+        const half8_t v = u[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) c1 += (float)v[j];
     }
+    for (int e = lane; e < head_dim; e += 64) c2 = __builtin_fmaf((float)q[(int64_t)bh * head_dim + e], bvec[h * head_dim + e], c2);
     c1 = wave_sum(c1);
     c2 = wave_sum(c2);
     const float *r = raw + (int64_t)bh * Lp;
@@ -271,34 +270,41 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     float mx = kNegBig;
     for (int t = lane; t < L_act; t += 64) mx = fmaxf(mx, score(t));
     mx = wave_max(mx);
-    float l = 0.f, sn = 0.f;
-    for (int t = lane; t < L_act; t += 64) {
-        const float pt = __builtin_amdgcn_exp2f(score(t) - mx);
-        l += pt;
-        sn = __builtin_fmaf(pt, st[t].y, sn);
-    }
+    float l = 0.f;
+    for (int t = lane; t < L_act; t += 64) l += __builtin_amdgcn_exp2f(score(t) - mx);
     l = wave_sum(l);
-    sn = wave_sum(sn);
     const float inv = 1.0f / l;
     _Float16 *wr = w + (int64_t)bh * Lp;
-    for (int t = lane; t < Lp; t += 64)
-        wr[t] = t < L_act ? (_Float16)(__builtin_amdgcn_exp2f(score(t) - mx) * st[t].x * inv) : (_Float16)0.f;
-    if (lane == 0) sums[bh] = make_float4(mx, l, sn * inv, 0.f);
+    float mu = 0.f;
+    for (int t = lane; t < Lp; t += 64) {
+        _Float16 wt = (_Float16)0.f;
+        if (t < L_act) {
+            const float2 s2 = st[t];
+            wt = (_Float16)(__builtin_amdgcn_exp2f(score(t) - mx) * s2.x * inv);
+            mu = __builtin_fmaf((float)wt, -s2.y / s2.x, mu);          // mean_t = -nmr_t / rstd_t
+        }
+        wr[t] = wt;
+    }
+    mu = wave_sum(mu);
+    if (lane == 0) sums[bh] = make_float4(mx, l, mu, 0.f);
 }
 
-// project: o_a[b,h,e] = W'_V[h dh + e, :] . Y[b,h,:] + sn c_V + b'_V for a slab of 32 output features of one
-// head, then the join with the cached segment's (maximum, denominator, output).
+// project: o_a[b,h,e] = W'_V[h dh + e, :] . Y[b,h,:] + b'_V for a slab of 32 output features of one head, then
+// the join with the cached segment's (maximum, denominator, output).  Workgroup ids are regrouped so that the
+// slabs of one head, which share that head's Y rows, run on one XCD.
 template <int RB>
 __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *__restrict__ Wv, const _Float16 *__restrict__ Y,
-                                                               const float *__restrict__ cv, const float *__restrict__ bv,
+                                                               const float *__restrict__ bv,
                                                                const float4 *__restrict__ sums,
                                                                const _Float16 *__restrict__ out_c, const float2 *__restrict__ lse_c,
                                                                _Float16 *__restrict__ out, int Bc, int H, int head_dim, int d)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
-    const int h = blockIdx.y;
-    const int n0 = h * head_dim + blockIdx.x * skinny::kSlab;          // first V feature of the slab
+    const int per_head = head_dim / skinny::kSlab;
+    const int item = gemm::xcd_regroup(blockIdx.x, per_head * H);
+    const int h = item / per_head;
+    const int n0 = h * head_dim + (item % per_head) * skinny::kSlab;   // first V feature of the slab
     float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, true>(
         Wv + (int64_t)n0 * d, skinny::kSlab, d, Y + (int64_t)h * d, Bc, (int64_t)H * d, d, smem);
     for (int idx = tid; idx < Bc * skinny::kSlab; idx += 256) {
@@ -307,7 +313,7 @@ __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *_
         const int64_t bh = (int64_t)b * H + h;
         const float4 sa = sums[bh];
         float o = (red[0][b][c] + red[1][b][c]) + (red[2][b][c] + red[3][b][c]);
-        o += __builtin_fmaf(sa.z, cv[n], bv[n]);
+        o += bv[n];
         if (lse_c) {
             const float2 sc = lse_c[bh];
             const float m = fmaxf(sc.x, sa.x);
@@ -322,11 +328,14 @@ template <int RB>
 hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
 {
     auto kern = absorbed_scores_kernel<RB>;
-    constexpr int lds = skinny::lds_bytes<RB>();
+    constexpr int lds = skinny::lds_bytes<RB>() + skinny::kMomentBytes;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((a.L_act + skinny::kSlab - 1) / skinny::kSlab), (unsigned)a.B), dim3(256), lds, s,
-                       static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.L_act, Lp, a.H, a.d);
+    const int64_t items = (int64_t)((a.L_act + skinny::kSlab - 1) / skinny::kSlab) * a.B;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
+                       static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,
+                       a.B, a.L_act, Lp, a.H, a.d, a.eps);
     return hipGetLastError();
 }
 
@@ -338,9 +347,9 @@ hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     const int64_t bh0 = (int64_t)b0 * a.H;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.head_dim / skinny::kSlab), (unsigned)a.H), dim3(256), lds, s,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.head_dim / skinny::kSlab * a.H)), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.Wp) + (int64_t)a.d * a.d, static_cast<const _Float16 *>(a.Y) + bh0 * a.d,
-                       a.cvec + a.d, a.bvec + a.d, a.sums + bh0,
+                       a.bvec + a.d, a.sums + bh0,
                        a.L_kv > 0 ? static_cast<const _Float16 *>(a.out_c) + bh0 * a.head_dim : nullptr,
                        a.L_kv > 0 ? a.lse_c + bh0 : nullptr,
                        static_cast<_Float16 *>(a.out) + bh0 * a.head_dim, Bc, a.H, a.head_dim, a.d);
@@ -364,7 +373,8 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
         ColArgs c;
         c.S = static_cast<const _Float16 *>(a.Wp); c.s_batch = (int64_t)a.head_dim * d; c.ld_s = d; c.R = a.head_dim; c.n_cols = a.d;
         c.A = static_cast<const _Float16 *>(a.q) + b0 * d; c.a_batch = a.head_dim; c.ld_a = d; c.a_rows = Bc;
-        c.Out = static_cast<_Float16 *>(a.U) + b0 * a.H * d; c.o_batch = d; c.ld_out = a.H * d;
+        c.Out = static_cast<_Float16 *>(a.U) + b0 * d; c.o_batch = a.B * d; c.ld_out = d;
+        c.shift = nullptr; c.shift_batch = 0; c.shift_stride = 0;
         if ((e = launch_column_product(c, a.H, s)) != hipSuccess) return e;
     }
     switch ((a.H + 31) / 32) {
@@ -376,8 +386,8 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
     if (e != hipSuccess) return e;
     const int64_t BH = (int64_t)a.B * a.H;
     hipLaunchKernelGGL(absorbed_softmax_kernel, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
-                       static_cast<const _Float16 *>(a.q), a.w_raw, a.stats, a.cvec, a.bvec,
-                       static_cast<_Float16 *>(a.w), a.sums, (int)BH, a.H, a.head_dim, a.L_act, Lp,
+                       static_cast<const _Float16 *>(a.q), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats, a.bvec,
+                       static_cast<_Float16 *>(a.w), a.sums, a.B, a.H, a.head_dim, a.d, a.L_act, Lp,
                        a.scale * 1.4426950408889634f);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     {
@@ -385,6 +395,7 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
         c.S = static_cast<const _Float16 *>(a.act); c.s_batch = (int64_t)a.L_act * d; c.ld_s = d; c.R = a.L_act; c.n_cols = a.d;
         c.A = static_cast<const _Float16 *>(a.w); c.a_batch = (int64_t)a.H * Lp; c.ld_a = Lp; c.a_rows = a.H;
         c.Out = static_cast<_Float16 *>(a.Y); c.o_batch = a.H * d; c.ld_out = d;
+        c.shift = &a.sums[0].z; c.shift_batch = 4 * (int64_t)a.H; c.shift_stride = 4;
         if ((e = launch_column_product(c, a.B, s)) != hipSuccess) return e;
     }
     for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {

@@ -370,12 +370,9 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
             return HK_ERR_LAUNCH;
         pp = dst;
     }
-    float2 *stats = reinterpret_cast<float2 *>(ws + p.off_stats);
-    if (hk::launch_ln_stats(act, stats, p.M, shape->d, shape->ln_eps, hs) != hipSuccess) return HK_ERR_LAUNCH;
     hk::AbsorbedArgs a;
-    a.q = q; a.act = act; a.stats = stats;
+    a.q = q; a.act = act; a.stats = reinterpret_cast<float2 *>(ws + p.off_stats);
     a.Wp = pp + PL.off_w;
-    a.cvec = reinterpret_cast<const float *>(pp + PL.off_c);
     a.bvec = reinterpret_cast<const float *>(pp + PL.off_b);
     a.U = ws + p.off_u;
     a.w_raw = reinterpret_cast<float *>(ws + p.off_raw);
@@ -386,7 +383,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
     a.lse_c = reinterpret_cast<const float2 *>(ws + p.off_lse);
     a.out = out;
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d; a.L_act = L_act; a.L_kv = L_kv;
-    a.scale = p.scale;
+    a.scale = p.scale; a.eps = shape->ln_eps;
     if (hk::launch_absorbed(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }

@@ -103,19 +103,19 @@ hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);
 struct AbsorbedArgs {
     const void *q;             // [B, H, dh] fp16
     const void *act;           // [B, L_act, d] fp16
-    const float2 *stats;       // [B * L_act]: (rstd, -mean * rstd) of every checkpoint row
+    float2 *stats;             // [B * L_act] scratch: (rstd, -mean * rstd) of every checkpoint row
     const void *Wp;            // prepared layer: [2d, d] fp16 gamma-scaled weights,
-    const float *cvec, *bvec;  //   [2d] row sums of Wp, [2d] bias with the LayerNorm bias folded in
-    void *U;                   // [B, H, d] fp16 scratch: the query carried through the key weights
+    const float *bvec;         //   [2d] bias with the LayerNorm bias folded in
+    void *U;                   // [H, B, d] fp16 scratch: the query carried through the key weights
     float *w_raw;              // [B, H, Lp] fp32 scratch: x_t . U  (Lp = absorbed_row_pitch(L_act))
     void *w;                   // [B, H, Lp] fp16 scratch: softmax weight times rstd, normalised; zero past L_act
-    float4 *sums;              // [B, H] scratch: (maximum, sum p, sum p * nmr / sum p, -)
+    float4 *sums;              // [B, H] scratch: (maximum, sum p, sum w mean, -)
     void *Y;                   // [B, H, d] fp16 scratch: weighted sum of the raw checkpoint rows
     const void *out_c;         // [B, H, dh] fp16: attention over the cached segment alone (unused when L_kv == 0)
     const float2 *lse_c;       // [B, H]: its (maximum, denominator)
     void *out;                 // [B, H, dh] fp16
     int B, H, head_dim, d, L_act, L_kv;
-    float scale;
+    float scale, eps;
 };
 constexpr int kAbsorbMaxHeads = 128;   // heads (rows of the small operand of the score product) per sequence
 constexpr int kAbsorbMaxBatch = 128;   // sequences one launch of the output projection takes

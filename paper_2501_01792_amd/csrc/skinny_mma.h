@@ -7,7 +7,8 @@
 // its part of the slab straight into registers with whole-line loads (8 lanes per 128-byte line, several
 // steps in flight), turns it into MFMA operand layout through a private 4 KiB LDS block and multiplies
 // it with the matching part of the small operand (fetched the same way, through L2).  The four partial
-// sums are left in LDS for the caller's epilogue.
+// sums are left in LDS for the caller's epilogue.  On request the pass also leaves the first two moments of
+// every streamed row (shifted by the row's first element), which is what a LayerNorm of those rows needs.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -16,6 +17,7 @@ namespace hk {
 namespace skinny {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kSlab = 32;                // streamed rows per workgroup
@@ -30,10 +32,21 @@ constexpr int lds_bytes()
     return 4 * (1 + RB) * kBlockBytes > 4 * RB * 32 * kSlab * 4 ? 4 * (1 + RB) * kBlockBytes : 4 * RB * 32 * kSlab * 4;
 }
 
+// Row moments of the streamed slab (STATS): after the call, for wavefront w and slab row c,
+//   moments(smem)[w][c] = (sum_k (S[c][k] - S[c][0]), sum_k (S[c][k] - S[c][0])^2) over k quarter w
+// (differences taken in fp16, sums in fp32; the shift keeps the variance free of cancellation when the row
+// mean is large against its spread).  They live behind the partial sums: add kMomentBytes to the LDS size.
+constexpr int kMomentBytes = 4 * kSlab * 2 * 4;
+template <int RB>
+__device__ __forceinline__ float (*moments(unsigned char *smem))[kSlab][2]
+{
+    return reinterpret_cast<float (*)[kSlab][2]>(smem + lds_bytes<RB>());
+}
+
 // S: first row of the slab (row stride ld_s elements; rows >= s_rows are not read: the last valid row stands
 // in for them).  A: first small row (row stride ld_a; rows >= a_rows likewise).  d % 64 == 0.
 // Returns red with red[w][m][c], w = 0..3, the partial sum of k quarter w; a barrier has been passed.
-template <int RB, bool NT>
+template <int RB, bool NT, bool STATS = false>
 __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, int s_rows, int64_t ld_s,
                                                 const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                                 int d, unsigned char *smem))[RB * 32][kSlab]
@@ -87,6 +100,17 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 
+    // row moments: lane (g_row, g_chunk) sums its 8-element pieces of rows 8 j + g_row
+    float m1[4] = {0.f, 0.f, 0.f, 0.f}, m2[4] = {0.f, 0.f, 0.f, 0.f};
+    half8_t shift[4];
+    if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const _Float16 c = *(wp[j] - 8 * g_chunk);     // first element of the row
+            shift[j] = half8_t{c, c, c, c, c, c, c, c};
+        }
+    }
+
     // Streamed pieces are fetched kDepth - 1 steps ahead, small-operand pieces kXDepth - 1 steps ahead.  Vector memory
     // loads complete in issue order as far as s_waitcnt can tell, so inside a step the small-operand loads (L2) are
     // issued BEFORE the streamed loads (HBM): the wait for the former then leaves the latter in flight.
@@ -128,6 +152,18 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
                     // registers (row-wise) -> LDS -> registers (MFMA operand layout)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) *reinterpret_cast<half8_t *>(my + wr_off[j]) = wv[u][j];
+                    if constexpr (STATS) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const half8_t xs = wv[u][j] - shift[j];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const half2_t pr = {xs[2 * e], xs[2 * e + 1]};
+                                m1[j] = __builtin_amdgcn_fdot2(pr, half2_t{(_Float16)1.f, (_Float16)1.f}, m1[j], false);
+                                m2[j] = __builtin_amdgcn_fdot2(pr, pr, m2[j], false);
+                            }
+                        }
+                    }
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -144,6 +180,22 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
                             acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf, wf[jj], acc[rb], 0, 0, 0);
                         }
                 }
+            }
+        }
+    }
+
+    if constexpr (STATS) {
+        float (*mom)[kSlab][2] = moments<RB>(smem);        // behind everything else in LDS: no aliasing
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int off = 1; off < 8; off <<= 1) {
+                m1[j] += __shfl_xor(m1[j], off, 64);
+                m2[j] += __shfl_xor(m2[j], off, 64);
+            }
+            if (g_chunk == 0) {
+                mom[wave][8 * j + g_row][0] = m1[j];
+                mom[wave][8 * j + g_row][1] = m2[j];
             }
         }
     }

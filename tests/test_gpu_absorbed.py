@@ -68,6 +68,21 @@ def test_absorbed_peaked_scores(hk, oracle):
     _check("out", out, ref_out)
 
 
+@pytest.mark.parametrize("prepared", [False, True])
+def test_absorbed_rows_with_large_mean(hk, oracle, prepared):
+    """Checkpoint rows whose mean is up to 200 times their spread: the mean has to cancel exactly in the
+    carried query and in the weighted row sum (both kept in fp16), as it does in a LayerNorm; and the row
+    statistics come from a single pass."""
+    cfg = _cfg("shifted", 1024, 8, 2, 130, 0.0, 21)
+    batch = synth.make_batch(cfg)
+    rng = np.random.default_rng(5)
+    act = batch["act"].astype(np.float32) * rng.uniform(0.1, 6.0, size=(cfg.B, cfg.L, 1)) + rng.uniform(-20, 20, size=(cfg.B, cfg.L, 1))
+    batch["act"] = act.astype(np.float16)
+    out = _run_absorbed(hk, cfg, batch, prepared=prepared)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+    _check("out", out, ref_out)
+
+
 def test_absorbed_repeatable_and_workspace_reuse(hk, oracle):
     """Two different problems through one workspace, larger first: the second result must not depend on
     what the first left behind (the padded tail of the weight rows is rewritten every call)."""
