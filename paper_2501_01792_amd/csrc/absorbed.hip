@@ -53,13 +53,14 @@ __device__ __forceinline__ float wave_max(float v)
 // column_product: Out[z][m][c] = sum_r A[z][m][r] * S[z][r][c]   (m < a_rows <= 32 RB, r < R, c < n_cols)
 //
 // The streamed operand S is row-major and the reduction runs over its ROWS, so it reaches the matrix cores
-// transposed.  Every wavefront owns a block of 64 columns (and a batch index z) and walks all R rows in steps
-// of 16: whole 128-byte pieces of 16 rows go from HBM to registers (kDepth - 1 steps in flight) and row-wise
-// into the wavefront's private LDS block, from which every lane picks the 8 values of its column (rows padded
-// by 16 bytes: the two half-wavefronts then use disjoint banks).  A (few rows, reduction axis contiguous,
-// zero beyond R up to the next multiple of 16) is read in MFMA operand layout through L2.  Wavefronts never
-// talk to each other: no barrier.  The result (minus an optional per-row constant, in fp32) leaves through the
-// same LDS block so that it is stored as whole 128-byte rows.
+// transposed.  Every wavefront owns a block of 64 columns and walks all R rows in steps of 16: whole 128-byte
+// pieces of 16 rows go from HBM to registers (kDepth - 1 steps in flight) and row-wise into the wavefront's
+// private LDS block, from which every lane picks the 8 values of its column (rows padded by 16 bytes: the two
+// half-wavefronts then use disjoint banks).  The small operand A (few rows, reduction axis contiguous, zero
+// beyond R up to the next multiple of 64) is the same for the four wavefronts of a workgroup: it is fetched
+// once per 64 reduction elements with whole-line loads, two tiles ahead, and shared through a double-buffered
+// LDS tile (one barrier per 64 reduction elements).  The result (minus an optional per-row constant, in fp32)
+// leaves through the private LDS block so that it is stored as whole 128-byte rows.
 struct ColArgs {
     const _Float16 *S; int64_t s_batch, ld_s; int R, n_cols;
     const _Float16 *A; int64_t a_batch, ld_a; int a_rows;
@@ -68,33 +69,48 @@ struct ColArgs {
 };
 
 constexpr int kColBlock = 64;                              // columns of one wavefront
-constexpr int kColStage = 32 * (2 * kColBlock + 16);       // bytes of LDS per wavefront: 32 rows of 128 + 16 bytes
+constexpr int kColStage = 32 * (2 * kColBlock + 16);       // bytes of private LDS per wavefront: 32 rows of 128 + 16 bytes
+constexpr int kTileBytes = 32 * 128;                       // 32 operand rows x 64 reduction elements
+
+template <int RB>
+constexpr int col_lds_bytes() { return 4 * kColStage + 2 * RB * kTileBytes; }
 
 template <int RB>
 __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 {
-    __shared__ __align__(16) unsigned char smem[4 * kColStage];
+    extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NB = kColBlock / 32;
-    constexpr int XS = 2 * kColBlock + 16;                 // bytes between rows of the LDS block
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c0 = (blockIdx.x * 4 + wave) * kColBlock;
-    if (c0 >= p.n_cols) return;                            // whole wavefront leaves; the kernel has no barrier
+    constexpr int XS = 2 * kColBlock + 16;                 // bytes between rows of the private LDS block
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int c0 = (blockIdx.x * 4 + wave) * kColBlock;
+    const bool live = c0 < p.n_cols;                       // a wavefront past the last column block works on the
+    if (!live) c0 = p.n_cols - kColBlock;                  // last one (it shares the barriers) and stores nothing
     const int64_t z = blockIdx.y;
     const _Float16 *S = p.S + z * p.s_batch + c0;
     const _Float16 *A = p.A + z * p.a_batch;
     const int steps = (p.R + 15) / 16;
+    const int tiles = (steps + 3) / 4;
 
     // one load instruction: 8 rows x 128 bytes, 8 lanes per row
     const int g_row = lane >> 3, g_chunk = lane & 7;
     const int ln = lane & 31, lh = lane >> 5;
-    int a_row[RB];
+    // the A tile: thread -> (row tid / 8 of every 32-row block, 16-byte chunk tid % 8)
+    const int t_row = tid >> 3, t_chunk = tid & 7;
+    const _Float16 *ap[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int m = rb * 32 + ln;
-        a_row[rb] = m < p.a_rows ? m : p.a_rows - 1;       // clamp: rows past the end are computed, never stored
+        int m = rb * 32 + t_row;
+        if (m >= p.a_rows) m = p.a_rows - 1;               // clamp: rows past the end are computed, never stored
+        ap[rb] = A + (int64_t)m * p.ld_a + 8 * t_chunk;
     }
+    // tile layout: row-major 128-byte rows, chunk index XOR-ed with (row / 2) % 8 (conflict-free both ways)
+    const int t_wr = t_row * 128 + ((t_chunk ^ ((t_row >> 1) & 7)) << 4);
+    int t_rd[4];                                           // operand fragment of step s % 4: chunks 2 (s % 4) + lane / 32
+#pragma unroll
+    for (int q = 0; q < 4; ++q) t_rd[q] = ln * 128 + (((2 * q + lh) ^ ((ln >> 1) & 7)) << 4);
     unsigned char *my = smem + wave * kColStage;
+    unsigned char *tile = smem + 4 * kColStage;
 
     float16_t acc[RB][NB];
 #pragma unroll
@@ -104,10 +120,10 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
 
-    constexpr int kDepth = 8, kADepth = 2;                 // kADepth divides kDepth
+    constexpr int kDepth = 8;                              // streamed steps in registers; two tiles per pass of the loop
     half8_t sv[kDepth][2];
-    half8_t av[kADepth][RB];
-    const int last = steps - 1;
+    half8_t av[2][RB];
+    const int last = steps - 1, last_tile = tiles - 1;
     auto clamp = [&](int sc) { return sc < last ? sc : last; };
     auto load_s = [&](int slot, int sc) {
 #pragma unroll
@@ -117,44 +133,61 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
             sv[slot][j] = *reinterpret_cast<const half8_t *>(S + (int64_t)r * p.ld_s + 8 * g_chunk);
         }
     };
-    auto load_a = [&](int slot, int sc) {
+    auto load_a = [&](int slot, int g) {
+        if (g > last_tile) g = last_tile;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) av[slot][rb] = *reinterpret_cast<const half8_t *>(ap[rb] + 64 * g);
+    };
+    auto put_a = [&](int slot, int buf) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-            av[slot][rb] = *reinterpret_cast<const half8_t *>(A + (int64_t)a_row[rb] * p.ld_a + 16 * sc + 8 * lh);
+            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kTileBytes + t_wr) = av[slot][rb];
     };
-    // Every load of the loop is unconditional (steps past the end re-read the last step), so that the number
-    // of loads in flight at each wait is a compile-time fact; the small operand (L2) is asked for before the
-    // streamed one (HBM) because vector memory loads retire in issue order.
-#pragma unroll
-    for (int u = 0; u < kADepth - 1; ++u) load_a(u, clamp(u));
+    // Every load of the loop is unconditional (steps and tiles past the end re-read the last one), so that
+    // the number of loads in flight at each wait is a compile-time fact.
+    load_a(0, 0);
+    load_a(1, 1);
 #pragma unroll
     for (int u = 0; u < kDepth - 1; ++u) load_s(u, clamp(u));
-    for (int s = 0; s < steps; s += kDepth) {
+    put_a(0, 0);
+    __syncthreads();
+    for (int g0 = 0; g0 < tiles; g0 += 2) {
 #pragma unroll
-        for (int u = 0; u < kDepth; ++u) {
-            const int sc = s + u;
-            load_a((u + kADepth - 1) % kADepth, clamp(sc + kADepth - 1));
-            load_s((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
-            if (sc < steps) {
+        for (int gg = 0; gg < 2; ++gg) {
+            const int g = g0 + gg;
+            if (g < tiles) {                               // uniform over the workgroup
+                put_a((gg + 1) & 1, (gg + 1) & 1);         // tile g + 1 (fetched one pass ago) for the next pass
+                load_a(gg, g + 2);
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = sv[u][j];
-                half8_t bf[NB];
+                for (int q = 0; q < 4; ++q) {
+                    const int u = 4 * gg + q, sc = 4 * g + q;
+                    load_s((u + kDepth - 1) % kDepth, clamp(sc + kDepth - 1));
+                    if (sc < steps) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+                        for (int j = 0; j < 2; ++j)
+                            *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = sv[u][j];
+                        half8_t bf[NB];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
+                        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
+                            for (int i = 0; i < 8; ++i)
+                                bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[u % kADepth][rb], bf[nb], acc[rb][nb], 0, 0, 0);
+                        for (int rb = 0; rb < RB; ++rb) {
+                            const half8_t af = *reinterpret_cast<const half8_t *>(tile + (gg * RB + rb) * kTileBytes + t_rd[q]);
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+                                acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf[nb], acc[rb][nb], 0, 0, 0);
+                        }
+                    }
+                }
+                __syncthreads();                           // tile g + 1 is complete; tile g is free for g + 2
             }
         }
     }
+    if (!live) return;                                     // no barrier below
 
-    // ---- fp16, through the LDS block, out as whole rows.
+    // ---- fp16, through the private LDS block, out as whole rows.
     // acc[rb][nb][r]: row 32 rb + 8 (r/4) + 4 (lane/32) + r%4, column 32 nb + lane%32.
     _Float16 *Out = p.Out + z * p.o_batch + c0;
 #pragma unroll
@@ -184,11 +217,16 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 template <int RB>
 hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
 {
+    auto kern = column_product_kernel<RB>;
+    constexpr int lds = col_lds_bytes<RB>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
     const int blocks_x = (p.n_cols / kColBlock + 3) / 4;
-    hipLaunchKernelGGL(column_product_kernel<RB>, dim3((unsigned)blocks_x, (unsigned)batches), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks_x, (unsigned)batches), dim3(256), lds, s, p);
     return hipGetLastError();
 }
 
+// A must be readable (and zero beyond R) up to the next multiple of 64 reduction elements.
 hipError_t launch_column_product(const ColArgs &p, int batches, hipStream_t s)
 {
     if (p.a_rows <= 0 || p.a_rows > 128 || p.R <= 0 || p.n_cols % kColBlock != 0 || batches <= 0 || batches > 65535)
@@ -202,12 +240,26 @@ hipError_t launch_column_product(const ColArgs &p, int batches, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// scores: raw[b][h][t] = x[b,t,:] . U[h,b,:] for a slab of 32 checkpoint rows of one sequence, and the
-// LayerNorm statistics (rstd, -mean rstd) of those rows from the same pass.  Workgroup ids are regrouped so
-// that the slabs of one sequence, which share that sequence's U rows, run on one XCD and find them in its L2.
+// scores: raw[b][h][t] = (x[b,t,:] - x[b,t,0]) . U[h,b,:] for the checkpoint rows of one sequence, and the
+// LayerNorm statistics of those rows from the same pass:
+//   stats[b L_act + t] = (rstd, mean, -(mean - x[b,t,0]) rstd, -)
+// The rows enter the product minus their first element, so that a large row mean is neither multiplied with
+// the rounding error of U nor left to cancel later.  Workgroup ids are regrouped so that the workgroups of one
+// sequence, which share that sequence's U rows, run on one XCD and find them in its L2.
+__device__ __forceinline__ float4 row_stats(float s1, float s2, float first, int d, float eps)
+{
+    const float inv_d = 1.0f / (float)d;
+    const float dm = s1 * inv_d;                           // mean - first element
+    const float var = fmaxf(__builtin_fmaf(-dm, dm, s2 * inv_d), 0.f);
+    const float rstd = 1.0f / __builtin_sqrtf(var + eps);
+    return make_float4(rstd, first + dm, -dm * rstd, 0.f);
+}
+
+// Few checkpoint rows in all: a slab of 32 rows per workgroup, the reduction axis cut over its 4 wavefronts
+// (skinny::slab_product), so that even a small problem fills the chip.  Every workgroup reads all of U[:,b,:].
 template <int RB>
 __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
-                                                              float *__restrict__ raw, float2 *__restrict__ stats,
+                                                              float *__restrict__ raw, float4 *__restrict__ stats,
                                                               int B, int L_act, int Lp, int H, int d, float eps)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -228,44 +280,180 @@ __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__
         float (*mom)[skinny::kSlab][2] = skinny::moments<RB>(smem);
         const float s1 = (mom[0][tid][0] + mom[1][tid][0]) + (mom[2][tid][0] + mom[3][tid][0]);
         const float s2 = (mom[0][tid][1] + mom[1][tid][1]) + (mom[2][tid][1] + mom[3][tid][1]);
-        const float inv_d = 1.0f / (float)d;
-        const float dm = s1 * inv_d;                       // mean - first element
-        const float var = fmaxf(__builtin_fmaf(-dm, dm, s2 * inv_d), 0.f);
-        const float mean = (float)S[(int64_t)tid * d] + dm;
-        const float rstd = 1.0f / __builtin_sqrtf(var + eps);
-        stats[b * L_act + t0 + tid] = make_float2(rstd, -mean * rstd);
+        stats[b * L_act + t0 + tid] = row_stats(s1, s2, (float)S[(int64_t)tid * d], d, eps);
+    }
+}
+
+// Many checkpoint rows: 128 rows per workgroup, 32 per wavefront, each wavefront walking the whole reduction
+// axis in steps of 64.  The U tile of a step (32 RB rows x 128 bytes) is the same for the four wavefronts: it
+// is fetched once with whole-line loads (as far ahead as the streamed rows, because vector memory loads
+// retire in issue order) and shared through a double-buffered LDS tile, one barrier per step; U is read once
+// per 128 rows instead of once per 32.  The streamed rows go from HBM to registers to the wavefront's private
+// LDS block (row-wise in, MFMA operand layout out) as in skinny::slab_product.  No reduction across
+// wavefronts: scores and statistics are stored straight from registers.
+template <int RB>
+constexpr int scores_block_lds_bytes() { return 4 * skinny::kBlockBytes + 2 * RB * skinny::kBlockBytes; }
+
+template <int RB>
+__global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
+                                                                    float *__restrict__ raw, float4 *__restrict__ stats,
+                                                                    int B, int L_act, int Lp, int H, int d, float eps)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kBlk = skinny::kBlockBytes;
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int blocks = (L_act + 127) / 128;
+    const int item = gemm::xcd_regroup(blockIdx.x, blocks * B);
+    const int64_t b = item / blocks;
+    const int tw = (item % blocks) * 128 + 32 * wave;      // first row of this wavefront
+    const int rows = L_act - tw < 32 ? (L_act - tw > 0 ? L_act - tw : 0) : 32;
+    const int steps = d / 64;
+
+    const int g_row = lane >> 3, g_chunk = lane & 7;
+    const int ln = lane & 31, lh = lane >> 5;
+    const _Float16 *sp[4];
+    half2_t shift[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int t = tw + 8 * j + g_row;
+        if (t >= L_act) t = L_act - 1;                     // clamp: rows past the end are computed, never stored
+        const _Float16 *row = act + (b * L_act + t) * d;
+        const _Float16 c = row[0];
+        shift[j] = half2_t{c, c};
+        sp[j] = row + 8 * g_chunk;
+    }
+    const int t_row = tid >> 3, t_chunk = tid & 7;
+    const _Float16 *up[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        int h = rb * 32 + t_row;
+        if (h >= H) h = H - 1;                             // clamp: heads past the end are computed, never stored
+        up[rb] = U + ((int64_t)h * B + b) * d + 8 * t_chunk;
+    }
+    // LDS blocks: 32 rows of 128 bytes, chunk index XOR-ed with (row / 2) % 8
+    int wr_off[4], rd_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + g_row;
+        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
+        rd_off[j] = ln * 128 + (((2 * j + lh) ^ ((ln >> 1) & 7)) << 4);
+    }
+    const int t_wr = t_row * 128 + ((t_chunk ^ ((t_row >> 1) & 7)) << 4);
+    unsigned char *my = smem + wave * kBlk;
+    unsigned char *tile = smem + 4 * kBlk;
+
+    float16_t acc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+    float m1[4] = {0.f, 0.f, 0.f, 0.f}, m2[4] = {0.f, 0.f, 0.f, 0.f};
+
+    constexpr int kDepth = RB <= 1 ? 6 : 5;
+    half8_t sv[kDepth][4];
+    half8_t uv[kDepth][RB];
+    const int last = steps - 1;
+    auto fetch = [&](int slot, int sc) {                   // U (L2) before the streamed rows (HBM)
+        if (sc > last) sc = last;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) uv[slot][rb] = *reinterpret_cast<const half8_t *>(up[rb] + 64 * sc);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sv[slot][j] = *reinterpret_cast<const half8_t *>(sp[j] + 64 * sc);
+    };
+    auto put_u = [&](int slot, int buf) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kBlk + t_wr) = uv[slot][rb];
+    };
+#pragma unroll
+    for (int u = 0; u < kDepth - 1; ++u) fetch(u, u);
+    put_u(0, 0);
+    __syncthreads();
+    for (int s = 0; s < steps; s += kDepth) {
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int sc = s + u;
+            fetch((u + kDepth - 1) % kDepth, sc + kDepth - 1);
+            if (sc < steps) {                              // uniform over the workgroup
+                put_u((u + 1) % kDepth, (sc + 1) & 1);     // the tile of step sc + 1, for the next pass
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    half8_t piece;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const half2_t pr = half2_t{sv[u][j][2 * e], sv[u][j][2 * e + 1]} - shift[j];
+                        m1[j] = __builtin_amdgcn_fdot2(pr, half2_t{(_Float16)1.f, (_Float16)1.f}, m1[j], false);
+                        m2[j] = __builtin_amdgcn_fdot2(pr, pr, m2[j], false);
+                        piece[2 * e] = pr[0];
+                        piece[2 * e + 1] = pr[1];
+                    }
+                    *reinterpret_cast<half8_t *>(my + wr_off[j]) = piece;
+                }
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const half8_t wf = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        const half8_t uf = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlk + rd_off[jj]);
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(uf, wf, acc[rb], 0, 0, 0);
+                    }
+                }
+                __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
+            }
+        }
+    }
+
+    // acc[rb][r]: head 32 rb + 8 (r/4) + 4 (lane/32) + r%4, row lane%32
+    if (ln < rows) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int h = 32 * rb + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (h < H) raw[(b * H + h) * Lp + tw + ln] = acc[rb][r];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {
+            m1[j] += __shfl_xor(m1[j], off, 64);
+            m2[j] += __shfl_xor(m2[j], off, 64);
+        }
+        const int row = 8 * j + g_row;
+        if (g_chunk == 0 && row < rows) stats[b * L_act + tw + row] = row_stats(m1[j], m2[j], (float)shift[j][0], d, eps);
     }
 }
 
 // softmax over the checkpoint rows of one (sequence, head), one wavefront each.  In the log2 domain:
-//   s_t = sl (rstd_t raw_t + nmr_t c1 + c2),  c1 = sum_k U[h,b,k] (the stored fp16 values),  c2 = q . b'_K,h,
+//   s_t = sl (rstd_t raw_t + k_t c1 + c2),  k_t = -(mean_t - x_t[0]) rstd_t,  c1 = q . c_K,h,  c2 = q . b'_K,h,
 //   sl = scale log2(e);   w_t = fp16(2^(s_t - m) rstd_t / l), zero from L_act to the padded row end;
 //   sums = (m, l, sum_t w_t mean_t with the stored w_t, -)
-__global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q, const _Float16 *__restrict__ U,
-                                                               const float *__restrict__ raw, const float2 *__restrict__ stats,
-                                                               const float *__restrict__ bvec,
+__global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q,
+                                                               const float *__restrict__ raw, const float4 *__restrict__ stats,
+                                                               const float *__restrict__ cvec, const float *__restrict__ bvec,
                                                                _Float16 *__restrict__ w, float4 *__restrict__ sums,
-                                                               int B, int H, int head_dim, int d, int L_act, int Lp, float sl)
+                                                               int B, int H, int head_dim, int L_act, int Lp, float sl)
 {
     const int lane = threadIdx.x & 63;
     const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= B * H) return;                               // whole wavefront leaves together; no barrier in this kernel
     const int b = bh / H, h = bh % H;
     float c1 = 0.f, c2 = 0.f;
-    const half8_t *u = reinterpret_cast<const half8_t *>(U + ((int64_t)h * B + b) * d);
-    for (int i = lane; i < d / 8; i += 64) {
-        const half8_t v = u[i];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) c1 += (float)v[j];
+    for (int e = lane; e < head_dim; e += 64) {
+        const float qe = (float)q[(int64_t)bh * head_dim + e];
+        c1 = __builtin_fmaf(qe, cvec[h * head_dim + e], c1);
+        c2 = __builtin_fmaf(qe, bvec[h * head_dim + e], c2);
     }
-    for (int e = lane; e < head_dim; e += 64) c2 = __builtin_fmaf((float)q[(int64_t)bh * head_dim + e], bvec[h * head_dim + e], c2);
     c1 = wave_sum(c1);
     c2 = wave_sum(c2);
     const float *r = raw + (int64_t)bh * Lp;
-    const float2 *st = stats + (int64_t)b * L_act;
+    const float4 *st = stats + (int64_t)b * L_act;
     auto score = [&](int t) {
-        const float2 s2 = st[t];
-        return sl * (__builtin_fmaf(s2.x, r[t], __builtin_fmaf(s2.y, c1, c2)));
+        const float4 s4 = st[t];
+        return sl * (__builtin_fmaf(s4.x, r[t], __builtin_fmaf(s4.z, c1, c2)));
     };
     float mx = kNegBig;
     for (int t = lane; t < L_act; t += 64) mx = fmaxf(mx, score(t));
@@ -279,9 +467,9 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     for (int t = lane; t < Lp; t += 64) {
         _Float16 wt = (_Float16)0.f;
         if (t < L_act) {
-            const float2 s2 = st[t];
-            wt = (_Float16)(__builtin_amdgcn_exp2f(score(t) - mx) * s2.x * inv);
-            mu = __builtin_fmaf((float)wt, -s2.y / s2.x, mu);          // mean_t = -nmr_t / rstd_t
+            const float4 s4 = st[t];
+            wt = (_Float16)(__builtin_amdgcn_exp2f(score(t) - mx) * s4.x * inv);
+            mu = __builtin_fmaf((float)wt, s4.y, mu);
         }
         wr[t] = wt;
     }
@@ -324,15 +512,19 @@ __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *_
     }
 }
 
+constexpr int64_t kBlockModeMinRows = 128 * 512;           // from here on 128-row workgroups still fill the chip twice
+
 template <int RB>
 hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
 {
-    auto kern = absorbed_scores_kernel<RB>;
-    constexpr int lds = skinny::lds_bytes<RB>() + skinny::kMomentBytes;
+    const bool block_mode = (int64_t)a.B * a.L_act >= kBlockModeMinRows;
+    const int per = block_mode ? 128 : skinny::kSlab;
+    const int64_t items = (int64_t)((a.L_act + per - 1) / per) * a.B;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    auto kern = block_mode ? absorbed_scores_block_kernel<RB> : absorbed_scores_kernel<RB>;
+    const int lds = block_mode ? scores_block_lds_bytes<RB>() : skinny::lds_bytes<RB>() + skinny::kMomentBytes;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    const int64_t items = (int64_t)((a.L_act + skinny::kSlab - 1) / skinny::kSlab) * a.B;
-    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,
                        a.B, a.L_act, Lp, a.H, a.d, a.eps);
@@ -358,7 +550,7 @@ hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
 
 }  // namespace
 
-int absorbed_row_pitch(int L_act) { return (L_act + 15) / 16 * 16; }
+int absorbed_row_pitch(int L_act) { return (L_act + 63) / 64 * 64; }
 
 hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
 {
@@ -386,8 +578,8 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
     if (e != hipSuccess) return e;
     const int64_t BH = (int64_t)a.B * a.H;
     hipLaunchKernelGGL(absorbed_softmax_kernel, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
-                       static_cast<const _Float16 *>(a.q), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats, a.bvec,
-                       static_cast<_Float16 *>(a.w), a.sums, a.B, a.H, a.head_dim, a.d, a.L_act, Lp,
+                       static_cast<const _Float16 *>(a.q), a.w_raw, a.stats, a.cvec, a.bvec,
+                       static_cast<_Float16 *>(a.w), a.sums, a.B, a.H, a.head_dim, a.L_act, Lp,
                        a.scale * 1.4426950408889634f);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     {

@@ -286,7 +286,7 @@ int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act
     p->Lp = hk::absorbed_row_pitch((int)L_act);
     size_t end = 0;
     auto take = [&](size_t bytes) { const size_t at = end; end += align_up(bytes); return at; };
-    p->off_stats = take((size_t)p->M * sizeof(float2));
+    p->off_stats = take((size_t)p->M * sizeof(float4));
     p->off_prep = take(L_act > 0 ? prepared_layout(s->d).total : 0);
     const size_t bh = (size_t)p->BH;
     const bool act = L_act > 0;
@@ -371,8 +371,9 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
         pp = dst;
     }
     hk::AbsorbedArgs a;
-    a.q = q; a.act = act; a.stats = reinterpret_cast<float2 *>(ws + p.off_stats);
+    a.q = q; a.act = act; a.stats = reinterpret_cast<float4 *>(ws + p.off_stats);
     a.Wp = pp + PL.off_w;
+    a.cvec = reinterpret_cast<const float *>(pp + PL.off_c);
     a.bvec = reinterpret_cast<const float *>(pp + PL.off_b);
     a.U = ws + p.off_u;
     a.w_raw = reinterpret_cast<float *>(ws + p.off_raw);

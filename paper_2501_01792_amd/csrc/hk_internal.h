@@ -103,9 +103,9 @@ hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);
 struct AbsorbedArgs {
     const void *q;             // [B, H, dh] fp16
     const void *act;           // [B, L_act, d] fp16
-    float2 *stats;             // [B * L_act] scratch: (rstd, -mean * rstd) of every checkpoint row
+    float4 *stats;             // [B * L_act] scratch: (rstd, mean, -(mean - first element) rstd, -) of every checkpoint row
     const void *Wp;            // prepared layer: [2d, d] fp16 gamma-scaled weights,
-    const float *bvec;         //   [2d] bias with the LayerNorm bias folded in
+    const float *cvec, *bvec;  //   [2d] row sums of Wp, [2d] bias with the LayerNorm bias folded in
     void *U;                   // [H, B, d] fp16 scratch: the query carried through the key weights
     float *w_raw;              // [B, H, Lp] fp32 scratch: x_t . U  (Lp = absorbed_row_pitch(L_act))
     void *w;                   // [B, H, Lp] fp16 scratch: softmax weight times rstd, normalised; zero past L_act

@@ -32,10 +32,12 @@ constexpr int lds_bytes()
     return 4 * (1 + RB) * kBlockBytes > 4 * RB * 32 * kSlab * 4 ? 4 * (1 + RB) * kBlockBytes : 4 * RB * 32 * kSlab * 4;
 }
 
-// Row moments of the streamed slab (STATS): after the call, for wavefront w and slab row c,
+// Shifted rows and their moments (STATS): every streamed row enters the product minus its first element,
+// D[m][c] = sum_k A[m][k] (S[c][k] - S[c][0]), and after the call, for wavefront w and slab row c,
 //   moments(smem)[w][c] = (sum_k (S[c][k] - S[c][0]), sum_k (S[c][k] - S[c][0])^2) over k quarter w
-// (differences taken in fp16, sums in fp32; the shift keeps the variance free of cancellation when the row
-// mean is large against its spread).  They live behind the partial sums: add kMomentBytes to the LDS size.
+// (differences taken in fp16, |difference| < 65504 assumed; sums in fp32).  The shift keeps a row mean that
+// is large against the row's spread out of the variance and out of the product.  The moments live behind the
+// partial sums: add kMomentBytes to the LDS size.
 constexpr int kMomentBytes = 4 * kSlab * 2 * 4;
 template <int RB>
 __device__ __forceinline__ float (*moments(unsigned char *smem))[kSlab][2]
@@ -151,18 +153,18 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
                 if (sc < s_end) {
                     // registers (row-wise) -> LDS -> registers (MFMA operand layout)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) *reinterpret_cast<half8_t *>(my + wr_off[j]) = wv[u][j];
-                    if constexpr (STATS) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const half8_t xs = wv[u][j] - shift[j];
+                    for (int j = 0; j < 4; ++j) {
+                        half8_t piece = wv[u][j];
+                        if constexpr (STATS) {
+                            piece -= shift[j];             // the product is taken with the shifted rows
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
-                                const half2_t pr = {xs[2 * e], xs[2 * e + 1]};
+                                const half2_t pr = {piece[2 * e], piece[2 * e + 1]};
                                 m1[j] = __builtin_amdgcn_fdot2(pr, half2_t{(_Float16)1.f, (_Float16)1.f}, m1[j], false);
                                 m2[j] = __builtin_amdgcn_fdot2(pr, pr, m2[j], false);
                             }
                         }
+                        *reinterpret_cast<half8_t *>(my + wr_off[j]) = piece;
                     }
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb)

@@ -33,6 +33,9 @@ SHAPES = SMALL + [
     _cfg("batch45", 512, 4, 45, 61, 0.5, 23),
     _cfg("batch130", 256, 4, 130, 40, 0.25, 24),
     _cfg("long_act", 512, 8, 2, 1500, 0.01, 25),
+    # 65536 checkpoint rows or more select the score kernel with 128-row workgroups; 1030 rows per sequence
+    # leave a last workgroup with 6 rows (three of its wavefronts own none)
+    _cfg("block_rows", 256, 4, 64, 1030, 0.0, 26),
 ]
 
 
@@ -124,9 +127,17 @@ def _sampled_pairs_check(hk, oracle, cfg, n_pairs=3, seed=5):
     _check("out[sampled (b,h)]", np.stack(got), np.stack(ref))
 
 
-@pytest.mark.parametrize("name", ["opt6.7b", "opt13b", "opt30b"])
+BIG = {
+    "opt6.7b": synth.CONFIGS["opt6.7b"],
+    "opt13b": synth.CONFIGS["opt13b"],
+    "opt30b": synth.CONFIGS["opt30b"],                     # 131072 checkpoint rows: 128-row workgroups, 56 heads
+    "block_heads72": _cfg("block_heads72", 4608, 72, 17, 4000, 0.02, 27),   # the same kernel with 3 head blocks, ragged
+}
+
+
+@pytest.mark.parametrize("name", list(BIG))
 def test_absorbed_full_size_sampled(hk, oracle, name):
-    cfg = synth.CONFIGS[name]
+    cfg = BIG[name]
     print("case", cfg, flush=True)
     torch.cuda.empty_cache()
     _sampled_pairs_check(hk, oracle, cfg)
