@@ -133,7 +133,18 @@ def sweep(args):
         dur = [float(np.mean([e.elapsed_ms(i, i + 1) for e in events])) for i in range(4)]
         for e in events:
             e.destroy()
+        del ws
+        ws = hk.new_workspace(hk.hk_absorbed_workspace_bytes(shape, B, cfg.L_kv, cfg.L_act))
+        for _ in range(2):
+            hk.hybrid_decode_attn_absorbed(q, Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            hk.hybrid_decode_attn_absorbed(q, Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream)
+        torch.cuda.synchronize()
+        ms_absorbed = (time.perf_counter() - t0) / args.steps * 1e3
         rows.append({"ratio": r, "L_kv": cfg.L_kv, "L_act": cfg.L_act, "regen_tokens": cfg.M, "ms_per_step": ms,
+                     "absorbed_ms_per_step": ms_absorbed,
                      "t_kv_gen_ms": dur[0] + dur[1], "t_attn_ms": dur[2] + dur[3],
                      "gemm_tflops": (4.0 * cfg.M * d * d / (dur[1] * 1e-3) / 1e12) if cfg.M else None,
                      "attn_gbps": float(B) * L * 4 * d / (dur[2] * 1e-3) / 1e9})
@@ -167,6 +178,10 @@ def main():
     ap.add_argument("--gemm-tile", type=int, default=0)
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true", help="skip the comparison variants timed after the bench line's region")
+    ap.add_argument("--absorbed", action="store_true",
+                    help="time the comparison variant that does not regenerate K/V (hk_hybrid_decode_attn_absorbed) as the step; "
+                         "prints its own line, not the benchmark's")
     ap.add_argument("--unprepared", action="store_true",
                     help="do not call hk_prepare_layer: the library prepares the layer inside every step")
     ap.add_argument("--sweep", action="store_true", help="ratio sweep of --config (default opt66b) instead of the bench line")
@@ -225,6 +240,14 @@ def main():
         hk.hybrid_decode_attn(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream,
                               attn_splits=args.attn_splits, gemm_tile=args.gemm_tile, events=events)
 
+    if args.absorbed:
+        del ws
+        ws = hk.new_workspace(hk.hk_absorbed_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
+
+        def step(events=None):
+            hk.hybrid_decode_attn_absorbed(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=stream,
+                                           attn_splits=args.attn_splits)
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -242,6 +265,29 @@ def main():
         step(events[s])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+
+    if args.absorbed:
+        for e in events:
+            e.destroy()
+        ms = elapsed / args.steps * 1e3
+        # bytes the variant has to move: the checkpoints twice, the cached K/V once, the prepared weights once
+        nbytes = 2.0 * cfg.M * cfg.d * 2 + float(cfg.B) * cfg.L_kv * 4 * cfg.d + (4.0 * cfg.d * cfg.d if cfg.M else 0.0)
+        line = {"metric": "absorbed_decode_context_tokens_per_s", "value": cfg.B * cfg.L / (ms * 1e-3), "unit": "tokens/s",
+                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+                "config": {"workload": "%s: d=%d H=%d B=%d L=%d ratio=%g, decode step of one layer without regenerating K/V "
+                                       "(comparison variant)" % (cfg.name, cfg.d, cfg.n_heads, cfg.B, cfg.L, cfg.ratio)},
+                "roofline": {"kernel": "whole step (all kernels)", "bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9,
+                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                             "traffic": None}}
+        if not args.no_cpu_baseline:
+            base, n, ref = cpu_baseline(cfg)
+            line["cpu_baseline"] = base
+            got = out[:n].float().cpu().numpy()
+            line["parity_vs_cpu_sample"] = {"max_abs": float(np.abs(got - ref).max()),
+                                            "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+        print(json.dumps(line))
+        return 0
 
     # per-kernel durations from the events recorded on the launch stream inside the timed region
     names = ["ln_stats", "kv_gemm", "flash_decode", "merge_partials"]
@@ -293,6 +339,28 @@ def main():
     result["mfma_rate_probe_tflops"] = {"zero_operands": hk.probe_mfma_rate(False), "random_operands": hk.probe_mfma_rate(True)}
     if roofline.get("bound") == "mfma":
         roofline["frac_of_probe_random"] = roofline["achieved"] / result["mfma_rate_probe_tflops"]["random_operands"]
+
+    if not args.no_variants:
+        # Comparison point beyond the paper (not part of `value`): the same step without regenerating K/V,
+        # the projections moved to the query and to the weighted row sum (hk_hybrid_decode_attn_absorbed).
+        ref_out = out.clone()
+        ws2 = hk.new_workspace(hk.hk_absorbed_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
+        out2 = torch.empty_like(out)
+        run2 = lambda: hk.hybrid_decode_attn_absorbed(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out2, workspace=ws2,
+                                                      stream=stream, attn_splits=args.attn_splits)
+        for _ in range(3):
+            run2()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run2()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) / args.steps * 1e3
+        diff = (out2.float() - ref_out.float())
+        result["absorbed_variant"] = {"ms_per_step": ms2, "speedup_vs_regenerating": ms_per_step / ms2,
+                                      "max_abs_vs_regenerating": float(diff.abs().max()),
+                                      "rel_l2_vs_regenerating": float(diff.norm() / ref_out.float().norm())}
+        del ws2
 
     if not args.no_cpu_baseline:
         base, n, ref = cpu_baseline(cfg)
