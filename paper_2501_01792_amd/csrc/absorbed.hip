@@ -284,128 +284,28 @@ __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__
     }
 }
 
-// Many checkpoint rows: 128 rows per workgroup, 32 per wavefront, each wavefront walking the whole reduction
-// axis in steps of 64.  The U tile of a step (32 RB rows x 128 bytes) is the same for the four wavefronts: it
-// is fetched once with whole-line loads (as far ahead as the streamed rows, because vector memory loads
-// retire in issue order) and shared through a double-buffered LDS tile, one barrier per step; U is read once
-// per 128 rows instead of once per 32.  The streamed rows go from HBM to registers to the wavefront's private
-// LDS block (row-wise in, MFMA operand layout out) as in skinny::slab_product.  No reduction across
-// wavefronts: scores and statistics are stored straight from registers.
-template <int RB>
-constexpr int scores_block_lds_bytes() { return 4 * skinny::kBlockBytes + 2 * RB * skinny::kBlockBytes; }
-
+// Many checkpoint rows: 128 rows per workgroup (skinny::block_product): U is read once per 128 rows instead of
+// once per 32, and scores and statistics are stored straight from registers.
 template <int RB>
 __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
                                                                     float *__restrict__ raw, float4 *__restrict__ stats,
                                                                     int B, int L_act, int Lp, int H, int d, float eps)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int kBlk = skinny::kBlockBytes;
-    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blocks = (L_act + 127) / 128;
     const int item = gemm::xcd_regroup(blockIdx.x, blocks * B);
     const int64_t b = item / blocks;
-    const int tw = (item % blocks) * 128 + 32 * wave;      // first row of this wavefront
+    const int t0 = (item % blocks) * 128;
+    const int tw = t0 + 32 * wave;                         // first row of this wavefront
     const int rows = L_act - tw < 32 ? (L_act - tw > 0 ? L_act - tw : 0) : 32;
-    const int steps = d / 64;
-
-    const int g_row = lane >> 3, g_chunk = lane & 7;
-    const int ln = lane & 31, lh = lane >> 5;
-    const _Float16 *sp[4];
-    half2_t shift[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int t = tw + 8 * j + g_row;
-        if (t >= L_act) t = L_act - 1;                     // clamp: rows past the end are computed, never stored
-        const _Float16 *row = act + (b * L_act + t) * d;
-        const _Float16 c = row[0];
-        shift[j] = half2_t{c, c};
-        sp[j] = row + 8 * g_chunk;
-    }
-    const int t_row = tid >> 3, t_chunk = tid & 7;
-    const _Float16 *up[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        int h = rb * 32 + t_row;
-        if (h >= H) h = H - 1;                             // clamp: heads past the end are computed, never stored
-        up[rb] = U + ((int64_t)h * B + b) * d + 8 * t_chunk;
-    }
-    // LDS blocks: 32 rows of 128 bytes, chunk index XOR-ed with (row / 2) % 8
-    int wr_off[4], rd_off[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = 8 * j + g_row;
-        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
-        rd_off[j] = ln * 128 + (((2 * j + lh) ^ ((ln >> 1) & 7)) << 4);
-    }
-    const int t_wr = t_row * 128 + ((t_chunk ^ ((t_row >> 1) & 7)) << 4);
-    unsigned char *my = smem + wave * kBlk;
-    unsigned char *tile = smem + 4 * kBlk;
-
     float16_t acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
-    float m1[4] = {0.f, 0.f, 0.f, 0.f}, m2[4] = {0.f, 0.f, 0.f, 0.f};
-
-    constexpr int kDepth = RB <= 1 ? 6 : 5;
-    half8_t sv[kDepth][4];
-    half8_t uv[kDepth][RB];
-    const int last = steps - 1;
-    auto fetch = [&](int slot, int sc) {                   // U (L2) before the streamed rows (HBM)
-        if (sc > last) sc = last;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) uv[slot][rb] = *reinterpret_cast<const half8_t *>(up[rb] + 64 * sc);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) sv[slot][j] = *reinterpret_cast<const half8_t *>(sp[j] + 64 * sc);
-    };
-    auto put_u = [&](int slot, int buf) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kBlk + t_wr) = uv[slot][rb];
-    };
-#pragma unroll
-    for (int u = 0; u < kDepth - 1; ++u) fetch(u, u);
-    put_u(0, 0);
-    __syncthreads();
-    for (int s = 0; s < steps; s += kDepth) {
-#pragma unroll
-        for (int u = 0; u < kDepth; ++u) {
-            const int sc = s + u;
-            fetch((u + kDepth - 1) % kDepth, sc + kDepth - 1);
-            if (sc < steps) {                              // uniform over the workgroup
-                put_u((u + 1) % kDepth, (sc + 1) & 1);     // the tile of step sc + 1, for the next pass
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    half8_t piece;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const half2_t pr = half2_t{sv[u][j][2 * e], sv[u][j][2 * e + 1]} - shift[j];
-                        m1[j] = __builtin_amdgcn_fdot2(pr, half2_t{(_Float16)1.f, (_Float16)1.f}, m1[j], false);
-                        m2[j] = __builtin_amdgcn_fdot2(pr, pr, m2[j], false);
-                        piece[2 * e] = pr[0];
-                        piece[2 * e + 1] = pr[1];
-                    }
-                    *reinterpret_cast<half8_t *>(my + wr_off[j]) = piece;
-                }
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const half8_t wf = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb) {
-                        const half8_t uf = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlk + rd_off[jj]);
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(uf, wf, acc[rb], 0, 0, 0);
-                    }
-                }
-                __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
-            }
-        }
-    }
-
-    // acc[rb][r]: head 32 rb + 8 (r/4) + 4 (lane/32) + r%4, row lane%32
+    float m1[4], m2[4];
+    _Float16 first[4];
+    skinny::block_product<RB, false, true>(act + (b * L_act + t0) * d, L_act - t0 < 128 ? L_act - t0 : 128, d,
+                                           U + b * d, H, (int64_t)B * d, 0, d / 64, smem, acc, m1, m2, first);
+    const int ln = lane & 31, lh = lane >> 5;
     if (ln < rows) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -417,13 +317,8 @@ __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int off = 1; off < 8; off <<= 1) {
-            m1[j] += __shfl_xor(m1[j], off, 64);
-            m2[j] += __shfl_xor(m2[j], off, 64);
-        }
-        const int row = 8 * j + g_row;
-        if (g_chunk == 0 && row < rows) stats[b * L_act + tw + row] = row_stats(m1[j], m2[j], (float)shift[j][0], d, eps);
+        const int row = 8 * j + (lane >> 3);
+        if ((lane & 7) == 0 && row < rows) stats[b * L_act + tw + row] = row_stats(m1[j], m2[j], (float)first[j], d, eps);
     }
 }
 
@@ -522,7 +417,7 @@ hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
     const int64_t items = (int64_t)((a.L_act + per - 1) / per) * a.B;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = block_mode ? absorbed_scores_block_kernel<RB> : absorbed_scores_kernel<RB>;
-    const int lds = block_mode ? scores_block_lds_bytes<RB>() : skinny::lds_bytes<RB>() + skinny::kMomentBytes;
+    const int lds = block_mode ? skinny::block_lds_bytes<RB>() : skinny::lds_bytes<RB>() + skinny::kMomentBytes;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,

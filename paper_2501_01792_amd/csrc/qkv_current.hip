@@ -8,21 +8,23 @@
 //   k, v = xhat [Wk; Wv]^T + [bk; bv]            -> K_dst, V_dst [B, H, L_cap, dh] at token tok_pos
 //
 // With B rows only, this is a skinny GEMM whose cost is one pass over the weights (2 d^2 or 6 d^2
-// bytes): an HBM streaming kernel.  Two kernels:
-//   ln_rows:   one wavefront per row: statistics from a register copy of the row, then the normalised
-//              row in fp16 to scratch (and the raw row to the checkpoint store when asked).
-//   qkv_rows:  one workgroup per slab of 32 output features.  Its 4 wavefronts each take a quarter of
-//              the reduction axis, stream their part of the 32 weight rows straight from HBM into
-//              registers with whole-line loads (8 lanes per 128-byte line, several steps in flight),
-//              turn them into MFMA operand layout through a private 4 KiB LDS block and multiply them
-//              with the matching part of xhat (read through L2 the same way) on the matrix cores
-//              (v_mfma_f32_32x32x16_f16).  The four partial sums meet in LDS; bias, fp16 and the
-//              scatter to q / K / V follow.
+// bytes): an HBM streaming kernel.  Three kernels:
+//   ln_rows:    one wavefront per row: statistics from a register copy of the row, then the normalised
+//               row in fp16 to scratch (and the raw row to the checkpoint store when asked).
+//   qkv_block:  one workgroup per (block of 128 output features, part of the reduction axis): its 4
+//               wavefronts stream 32 weight rows each from HBM (whole-line loads, several steps in
+//               flight, through a private LDS block into MFMA operand layout) and share the matching
+//               tile of xhat through LDS, so that xhat is read from L2 once per 128 weight rows
+//               (skinny::block_product).  The reduction axis is cut over workgroups only as far as it
+//               takes to fill the chip; every part leaves an fp32 partial result in scratch.
+//   qkv_finish: sums the parts, adds the bias, rounds to fp16 and scatters to q / K / V.
 #include "hk_internal.h"
 #include "skinny_mma.h"
 
 namespace hk {
 namespace {
+
+using skinny::float16_t;
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -89,39 +91,71 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
     }
 }
 
-using skinny::kSlab;
-
-// RB = row blocks of 32 (B <= 32 RB)
+// Feature blocks: 128 rows of Wq (ceil(d / 128) blocks), then 128 rows of [Wk; Wv] (ceil(2d / 128) blocks),
+// so that a block never straddles the two weight arrays.  Partials: part[ks][m][n], n in [0, 3d) fp32.
 template <int RB>
-__global__ __launch_bounds__(256) void qkv_rows_kernel(
-    const _Float16 *__restrict__ xhat, const _Float16 *__restrict__ Wq, const _Float16 *__restrict__ bq,
-    const _Float16 *__restrict__ Wkv, const _Float16 *__restrict__ bkv,
-    _Float16 *__restrict__ q_out, _Float16 *__restrict__ K_dst, _Float16 *__restrict__ V_dst,
-    int B, int d, int n_heads, int head_dim, int L_cap, int tok_pos)
+__global__ __launch_bounds__(256) void qkv_block_kernel(
+    const _Float16 *__restrict__ xhat, const _Float16 *__restrict__ Wq, const _Float16 *__restrict__ Wkv,
+    float *__restrict__ part, int B, int d, int q_blocks, int steps_per_part)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int n0 = blockIdx.x * kSlab;                     // first output feature of the slab, in [0, 3d)
-    // the slab lies inside one of the three weight blocks (d % 32 == 0)
-    const _Float16 *W = n0 < d ? Wq + (int64_t)n0 * d : Wkv + (int64_t)(n0 - d) * d;
-    float (*red)[RB * 32][kSlab] = skinny::slab_product<RB, true>(W, kSlab, d, xhat, B, d, d, smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int blk = blockIdx.x, ks = blockIdx.y;
+    const bool is_q = blk < q_blocks;
+    const int n0 = is_q ? blk * 128 : (blk - q_blocks) * 128;              // first row inside its weight array
+    const int n_rows = (is_q ? d : 2 * d) - n0 < 128 ? (is_q ? d : 2 * d) - n0 : 128;
+    const _Float16 *W = (is_q ? Wq : Wkv) + (int64_t)n0 * d;
+    const int steps = d / 64;
+    const int k_begin = ks * steps_per_part;
+    const int k_steps = steps - k_begin < steps_per_part ? steps - k_begin : steps_per_part;
+    float16_t acc[RB];
+    float m1[4], m2[4];
+    _Float16 first[4];
+    skinny::block_product<RB, true, false>(W, n_rows, d, xhat, B, d, k_begin, k_steps, smem, acc, m1, m2, first);
+    // acc[rb][r]: row (sequence) 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature 32 wave + lane%32 of the block
+    const int ln = lane & 31, lh = lane >> 5;
+    const int c = 32 * wave + ln;
+    if (c < n_rows) {
+        const int n = (is_q ? 0 : d) + n0 + c;
+        float *dst = part + (int64_t)ks * B * 3 * d + n;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = 32 * rb + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (m < B) dst[(int64_t)m * 3 * d] = acc[rb][r];
+            }
+    }
+}
 
-    // bias, fp16, scatter: thread -> (row, feature) pairs of the B x 32 slab
-    const int which = n0 / d;                              // 0: q, 1: k, 2: v
-    const int nn0 = n0 - which * d;
-    for (int idx = tid; idx < B * kSlab; idx += 256) {
-        const int m = idx / kSlab, c = idx % kSlab;
-        const float sum = (red[0][m][c] + red[1][m][c]) + (red[2][m][c] + red[3][m][c]);
-        const int nn = nn0 + c;
-        const float bias = which == 0 ? (float)bq[nn] : (float)bkv[(which - 1) * d + nn];
-        const _Float16 o = (_Float16)(sum + bias);
-        if (which == 0) {
-            q_out[(int64_t)m * d + nn] = o;
-        } else {
-            const int h = nn / head_dim, e = nn % head_dim;
-            _Float16 *dst = which == 1 ? K_dst : V_dst;
-            dst[(((int64_t)m * n_heads + h) * L_cap + tok_pos) * head_dim + e] = o;
-        }
+// out[m][n] = fp16(sum_ks part[ks][m][n] + bias[n]), 4 features per thread, scattered to q / K / V.
+__global__ __launch_bounds__(256) void qkv_finish_kernel(
+    const float *__restrict__ part, int parts, const _Float16 *__restrict__ bq, const _Float16 *__restrict__ bkv,
+    _Float16 *__restrict__ q_out, _Float16 *__restrict__ K_dst, _Float16 *__restrict__ V_dst,
+    int B, int d, int n_out, int n_heads, int head_dim, int L_cap, int tok_pos)
+{
+    typedef float float4_t __attribute__((ext_vector_type(4)));
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    const int per_row = n_out / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)B * per_row) return;
+    const int m = (int)(idx / per_row), n = (int)(idx % per_row) * 4;
+    const int64_t stride = (int64_t)B * 3 * d;
+    const float *src = part + (int64_t)m * 3 * d + n;
+    float4_t sum = *reinterpret_cast<const float4_t *>(src);
+    for (int ks = 1; ks < parts; ++ks) sum += *reinterpret_cast<const float4_t *>(src + ks * stride);
+    const int which = n / d, nn = n - which * d;                           // 0: q, 1: k, 2: v
+    const _Float16 *bias = which == 0 ? bq + nn : bkv + (which - 1) * d + nn;
+    half4_t o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (_Float16)(sum[i] + (float)bias[i]);
+    if (which == 0) {
+        *reinterpret_cast<half4_t *>(q_out + (int64_t)m * d + nn) = o;
+    } else {
+        const int h = nn / head_dim, e = nn % head_dim;
+        _Float16 *dst = which == 1 ? K_dst : V_dst;
+        *reinterpret_cast<half4_t *>(dst + (((int64_t)m * n_heads + h) * L_cap + tok_pos) * head_dim + e) = o;
     }
 }
 
@@ -136,19 +170,16 @@ hipError_t launch_ln_rows(const QkvArgs &a, hipStream_t s)
 }
 
 template <int RB>
-hipError_t launch_rows(const QkvArgs &a, hipStream_t s)
+hipError_t launch_block(const QkvArgs &a, int parts, int steps_per_part, hipStream_t s)
 {
-    const int slabs = (a.K_dst ? 3 : 1) * (a.d / kSlab);
-    auto kern = qkv_rows_kernel<RB>;
-    constexpr int lds = skinny::lds_bytes<RB>();
+    const int q_blocks = (a.d + 127) / 128, kv_blocks = a.K_dst ? (2 * a.d + 127) / 128 : 0;
+    auto kern = qkv_block_kernel<RB>;
+    constexpr int lds = skinny::block_lds_bytes<RB>();
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)slabs), dim3(256), lds, s,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(q_blocks + kv_blocks), (unsigned)parts), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.xhat), static_cast<const _Float16 *>(a.Wq),
-                       static_cast<const _Float16 *>(a.bq), static_cast<const _Float16 *>(a.Wkv),
-                       static_cast<const _Float16 *>(a.bkv), static_cast<_Float16 *>(a.q_out),
-                       static_cast<_Float16 *>(a.K_dst), static_cast<_Float16 *>(a.V_dst),
-                       a.B, a.d, a.n_heads, a.head_dim, a.L_cap, a.tok_pos);
+                       static_cast<const _Float16 *>(a.Wkv), a.part, a.B, a.d, q_blocks, steps_per_part);
     return hipGetLastError();
 }
 
@@ -166,13 +197,38 @@ hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
     else if (nv <= 16) e = launch_ln_rows<16>(a, s);
     else e = launch_ln_rows<kMaxVec>(a, s);
     if (e != hipSuccess) return e;
-    const int rb = (a.B + 31) / 32;
-    switch (rb) {
-    case 1: return launch_rows<1>(a, s);
-    case 2: return launch_rows<2>(a, s);
-    case 3: return launch_rows<3>(a, s);
-    default: return launch_rows<4>(a, s);
+    int parts, steps_per_part;
+    qkv_parts(a.d, &parts, &steps_per_part);
+    switch ((a.B + 31) / 32) {
+    case 1: e = launch_block<1>(a, parts, steps_per_part, s); break;
+    case 2: e = launch_block<2>(a, parts, steps_per_part, s); break;
+    case 3: e = launch_block<3>(a, parts, steps_per_part, s); break;
+    default: e = launch_block<4>(a, parts, steps_per_part, s); break;
     }
+    if (e != hipSuccess) return e;
+    const int n_out = (a.K_dst ? 3 : 1) * a.d;
+    const int64_t threads = (int64_t)a.B * (n_out / 4);
+    hipLaunchKernelGGL(qkv_finish_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       a.part, parts, static_cast<const _Float16 *>(a.bq), static_cast<const _Float16 *>(a.bkv),
+                       static_cast<_Float16 *>(a.q_out), static_cast<_Float16 *>(a.K_dst), static_cast<_Float16 *>(a.V_dst),
+                       a.B, a.d, n_out, a.n_heads, a.head_dim, a.L_cap, a.tok_pos);
+    return hipGetLastError();
+}
+
+// Parts of the reduction axis (d / 64 steps): enough workgroups to fill the chip about three times when Q, K
+// and V are produced, at least 4 steps per part, no empty part.  The same cut is used when only Q is
+// produced, so that q does not depend on whether K/V are asked for (the order of the fp32 sums is the same),
+// and the scratch size is one function of d.
+void qkv_parts(int d, int *parts, int *steps_per_part)
+{
+    const int steps = d / 64;
+    const int blocks = (d + 127) / 128 + (2 * d + 127) / 128;
+    int want = (768 + blocks - 1) / blocks;
+    if (want > steps / 4) want = steps / 4;
+    if (want < 1) want = 1;
+    if (want > 16) want = 16;
+    *steps_per_part = (steps + want - 1) / want;
+    *parts = (steps + *steps_per_part - 1) / *steps_per_part;
 }
 
 }  // namespace hk

@@ -9,6 +9,9 @@
 // it with the matching part of the small operand (fetched the same way, through L2).  The four partial
 // sums are left in LDS for the caller's epilogue.  On request the pass also leaves the first two moments of
 // every streamed row (shifted by the row's first element), which is what a LayerNorm of those rows needs.
+//
+// block_product is the form for many streamed rows: 128 per workgroup, 32 per wavefront, every wavefront
+// walking the same range of the reduction axis, the small operand's tile shared through LDS.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -214,6 +217,145 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
     __syncthreads();
 
     return red;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// block_product: D[m][c] = sum_k A[m][k] * S[c][k] over k in [64 k_begin, 64 (k_begin + k_steps)), for the 32
+// streamed rows c = 32 wave + lane % 32 of a block of up to 128 rows that the 4 wavefronts of a workgroup share.
+//
+// The tile of the small operand of a step (32 RB rows x 128 bytes) is the same for the four wavefronts: it is
+// fetched once per workgroup with whole-line loads (as far ahead as the streamed rows, because vector memory
+// loads retire in issue order) and shared through a double-buffered LDS tile, one barrier per step; so the
+// small operand is read once per 128 streamed rows.  The streamed rows go from HBM to registers to the
+// wavefront's private LDS block (row-wise in, MFMA operand layout out) as in slab_product.  There is no
+// reduction across wavefronts: the result stays in registers,
+//   acc[rb][r] = D[32 rb + 8 (r/4) + 4 (lane/32) + r%4][32 wave + lane%32].
+// STATS: rows enter the product minus their first element; m1[j], m2[j] are the first two moments of row
+// 32 wave + 8 j + lane / 8 (complete in every lane of the row's 8), first[j] that row's first element.
+// All 256 threads must call it (barriers), with the same k range.  n_rows >= 1 rows of S are valid; rows
+// past them are computed from the last valid row and must not be stored.
+template <int RB>
+constexpr int block_lds_bytes() { return 4 * kBlockBytes + 2 * RB * kBlockBytes; }
+
+template <int RB, bool NT, bool STATS>
+__device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, int n_rows, int64_t ld_s,
+                                              const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
+                                              int k_begin, int k_steps, unsigned char *smem,
+                                              float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g_row = lane >> 3, g_chunk = lane & 7;
+    const int ln = lane & 31, lh = lane >> 5;
+    const _Float16 *sp[4];
+    half2_t shift[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int r = 32 * wave + 8 * j + g_row;
+        if (r >= n_rows) r = n_rows - 1;
+        const _Float16 *row = S + (int64_t)r * ld_s;
+        if constexpr (STATS) {
+            first[j] = row[0];
+            shift[j] = half2_t{first[j], first[j]};
+        } else {
+            first[j] = (_Float16)0.f;
+        }
+        sp[j] = row + 64 * (int64_t)k_begin + 8 * g_chunk;
+        m1[j] = 0.f;
+        m2[j] = 0.f;
+    }
+    const int t_row = tid >> 3, t_chunk = tid & 7;         // the shared tile: thread -> (row of every 32-row block, chunk)
+    const _Float16 *ap[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        int m = rb * 32 + t_row;
+        if (m >= a_rows) m = a_rows - 1;
+        ap[rb] = A + (int64_t)m * ld_a + 64 * (int64_t)k_begin + 8 * t_chunk;
+    }
+    // LDS blocks: 32 rows of 128 bytes, chunk index XOR-ed with (row / 2) % 8
+    int wr_off[4], rd_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + g_row;
+        wr_off[j] = row * 128 + ((g_chunk ^ ((row >> 1) & 7)) << 4);
+        rd_off[j] = ln * 128 + (((2 * j + lh) ^ ((ln >> 1) & 7)) << 4);
+    }
+    const int t_wr = t_row * 128 + ((t_chunk ^ ((t_row >> 1) & 7)) << 4);
+    unsigned char *my = smem + wave * kBlockBytes;
+    unsigned char *tile = smem + 4 * kBlockBytes;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+
+    constexpr int kDepth = RB <= 1 ? 6 : 5;
+    half8_t sv[kDepth][4];
+    half8_t av[kDepth][RB];
+    const int last = k_steps - 1;
+    auto fetch = [&](int slot, int sc) {                   // the small operand (L2) before the streamed rows (HBM)
+        if (sc > last) sc = last;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) av[slot][rb] = *reinterpret_cast<const half8_t *>(ap[rb] + 64 * sc);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half8_t *src = reinterpret_cast<const half8_t *>(sp[j] + 64 * sc);
+            sv[slot][j] = NT ? __builtin_nontemporal_load(src) : *src;
+        }
+    };
+    auto put_a = [&](int slot, int buf) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kBlockBytes + t_wr) = av[slot][rb];
+    };
+    if (k_steps <= 0) return;                              // uniform over the workgroup
+#pragma unroll
+    for (int u = 0; u < kDepth - 1; ++u) fetch(u, u);
+    put_a(0, 0);
+    __syncthreads();
+    for (int s = 0; s < k_steps; s += kDepth) {
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int sc = s + u;
+            fetch((u + kDepth - 1) % kDepth, sc + kDepth - 1);
+            if (sc < k_steps) {                            // uniform over the workgroup
+                put_a((u + 1) % kDepth, (sc + 1) & 1);     // the tile of step sc + 1, for the next pass
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    half8_t piece = sv[u][j];
+                    if constexpr (STATS) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const half2_t pr = half2_t{piece[2 * e], piece[2 * e + 1]} - shift[j];
+                            m1[j] = __builtin_amdgcn_fdot2(pr, half2_t{(_Float16)1.f, (_Float16)1.f}, m1[j], false);
+                            m2[j] = __builtin_amdgcn_fdot2(pr, pr, m2[j], false);
+                            piece[2 * e] = pr[0];
+                            piece[2 * e + 1] = pr[1];
+                        }
+                    }
+                    *reinterpret_cast<half8_t *>(my + wr_off[j]) = piece;
+                }
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const half8_t wf = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        const half8_t af = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlockBytes + rd_off[jj]);
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
+                    }
+                }
+                __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
+            }
+        }
+    }
+    if constexpr (STATS) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int off = 1; off < 8; off <<= 1) {
+                m1[j] += __shfl_xor(m1[j], off, 64);
+                m2[j] += __shfl_xor(m2[j], off, 64);
+            }
+    }
 }
 
 }  // namespace skinny
