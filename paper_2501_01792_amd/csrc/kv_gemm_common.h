@@ -88,23 +88,27 @@ struct __align__(16) RowDst {
     int64_t base;         // element offset of K[b, 0, tok_off + t, 0]; negative: row is past the end, store nothing
 };
 
+// Table entry of global row m: where its head-split output starts and its LayerNorm statistics.
+__device__ __forceinline__ RowDst row_dst(int64_t m, int64_t M, int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
+                                          const float2 *__restrict__ stats)
+{
+    RowDst e;
+    e.rstd = 1.f; e.nmr = 0.f; e.base = -1;
+    if (m < M) {
+        const uint32_t b = (uint32_t)m / (uint32_t)L_act, t = (uint32_t)m % (uint32_t)L_act;   // M < 2^31
+        e.base = (((int64_t)b * n_heads) * L_cap + tok_off + t) * head_dim;
+        if (stats) { const float2 st = stats[m]; e.rstd = st.x; e.nmr = st.y; }
+    }
+    return e;
+}
+
 // Fills tab[0 .. BM) for the tile whose first row is m0.  Call between two workgroup barriers.
 template <int BM, int NT>
 __device__ __forceinline__ void fill_row_table(RowDst *tab, int tid, int64_t m0, int64_t M,
                                                int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
                                                const float2 *__restrict__ stats)
 {
-    for (int row = tid; row < BM; row += NT) {
-        const int64_t m = m0 + row;
-        RowDst e;
-        e.rstd = 1.f; e.nmr = 0.f; e.base = -1;
-        if (m < M) {
-            const uint32_t b = (uint32_t)m / (uint32_t)L_act, t = (uint32_t)m % (uint32_t)L_act;   // M < 2^31
-            e.base = (((int64_t)b * n_heads) * L_cap + tok_off + t) * head_dim;
-            if (stats) { const float2 st = stats[m]; e.rstd = st.x; e.nmr = st.y; }
-        }
-        tab[row] = e;
-    }
+    for (int row = tid; row < BM; row += NT) tab[row] = row_dst(m0 + row, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
 }
 
 // The stores are non-temporal: the regenerated rows are read once, by the attention kernel, and must

@@ -256,18 +256,17 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         sA = sA1; sB = sB1;
     };
     stage(std::true_type{});
-    for (int c_kb = 1; c_kb < nks; ++c_kb) stage(std::false_type{});
-        {
+    for (int c_kb = 1; c_kb < nks - 1; ++c_kb) stage(std::false_type{});
             // ---- end of a tile: LayerNorm statistics, constants of the layer, fp16, head split.
-            // The slot that held the weights of block g (now sB's predecessor) is free until the next
-            // block's activation loads are issued: it holds the row table meanwhile.
+            // What the epilogue needs from memory (the row's statistics, the constants of this lane's output
+            // features) is asked for before the tile's last k block, whose MFMAs hide the latency; these
+            // loads are older than the last block's activation loads, so its vmcnt(8) covers them.
+            static_assert(FBM == FNT, "one table row per thread");
             int tm, tn;
             tile_coords<GROUP_M>((int)blockIdx.x + c_j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
             const int64_t m0 = (int64_t)tm * FBM;
             const int n0 = tn * FBN;
-            const int s_tab = sB >= 2 ? sB - 2 : sB + kSlots - 2;        // slot of the weights of block g
-            RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
-            fill_row_table<FBM, FNT>(tab, tid, m0, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
+            const RowDst my_row = row_dst(m0 + tid, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
             const int nb = n0 + wn * FWN + FTN * (lane & 31);
             float cn[FTN], bn[FTN];
 #pragma unroll
@@ -275,6 +274,13 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
                 cn[j] = nb < N ? cvec[nb + j] : 0.f;
                 bn[j] = nb < N ? bvec[nb + j] : 0.f;
             }
+    stage(std::false_type{});                                  // the last k block (nks >= 2)
+        {
+            // The slot that held the weights of block g (now sB's predecessor) is free until the next
+            // block's activation loads are issued: it holds the row table meanwhile.
+            const int s_tab = sB >= 2 ? sB - 2 : sB + kSlots - 2;        // slot of the weights of block g
+            RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
+            tab[tid] = my_row;
             __syncthreads();
             store_tile<FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
             __syncthreads();                                   // the table's slot is about to be refilled

@@ -1,0 +1,148 @@
+"""Timing of the entry points beside the benchmark's path (bench.py times the hybrid step itself):
+
+    python -m paper_2501_01792_amd.measure qkv   [--config opt6.7b] [--iters 20]
+    python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged]
+
+Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
+parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
+token) COLD: the weights of one layer fit in the 256 MB last-level cache, which a real decoder of dozens of
+layers would have evicted by the time a layer comes round again, so a 512 MiB buffer is read between calls.
+``paged`` measures hk_paged_decode_attn (Sec. 4.1, 5.1: block table, ragged requests) on the workload's
+B, H, L with blocks of ``--block-tokens`` tokens scattered over the pools in random order.
+"""
+import argparse
+import json
+import sys
+
+import numpy as np
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def measure_qkv(args):
+    import torch
+    from . import binding as hk, synth
+    cfg = synth.CONFIGS[args.config]
+    B, d, H, dh = cfg.B, cfg.d, cfg.n_heads, cfg.head_dim
+    f16 = torch.float16
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen, device="cuda") * std + mean).to(f16)
+    x = rn(B, d)
+    Wq, bq, Wkv, bkv = rn(d, d, std=0.02), rn(d, std=0.01), rn(2 * d, d, std=0.02), rn(2 * d, std=0.01)
+    ln_w, ln_b = rn(d, std=0.02, mean=1.0), rn(d, std=0.02)
+    K = torch.empty(B, H, 4, dh, device="cuda", dtype=f16)
+    V = torch.empty_like(K)
+    q = torch.empty(B, H, dh, device="cuda", dtype=f16)
+    ws = hk.new_workspace(hk.hk_qkv_workspace_bytes(hk.make_shape(d, H), B))
+    flush = torch.empty(1 << 29, dtype=torch.uint8, device="cuda").fill_(1)
+    out = {}
+    for name, with_kv in (("q_k_v", True), ("q_only", False)):
+        call = lambda: hk.qkv_current(x, ln_w, ln_b, Wkv, bkv, Wq, bq, H, q_out=q, K_dst=K if with_kv else None,
+                                      V_dst=V if with_kv else None, tok_pos=1, workspace=ws)
+        for _ in range(3):
+            call()
+        ts = []
+        for _ in range(args.iters):
+            flush.view(torch.int32).max()                      # evicts the weights from the last-level cache
+            e0, e1 = _events(torch)
+            e0.record(); call(); e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = float(np.mean(ts))
+        nbytes = (6 if with_kv else 2) * d * d                 # one pass over the fp16 weights
+        out[name] = {"ms": ms, "min_ms": float(np.min(ts)), "weight_bytes": nbytes, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / 8000.0}
+    print(json.dumps({"entry": "hk_qkv_current", "workload": "%s: B=%d d=%d H=%d, cold" % (cfg.name, B, d, H),
+                      "iters": args.iters, "result": out}))
+    return 0
+
+
+def measure_paged(args):
+    import torch
+    from . import binding as hk, synth
+    cfg = synth.CONFIGS[args.config]
+    B, d, H, dh, L, bt = cfg.B, cfg.d, cfg.n_heads, cfg.head_dim, cfg.L, args.block_tokens
+    f16 = torch.float16
+    rng = np.random.default_rng(cfg.seed)
+    lens = rng.integers(L // 2, L + 1, B) if args.ragged else np.full(B, L)
+    nb = (lens + bt - 1) // bt
+    total_blocks, max_blocks = int(nb.sum()), int(nb.max())
+    kinds = rng.random(total_blocks) < args.act_fraction
+    n_act = int(kinds.sum())
+    n_kv = total_blocks - n_act
+    table = np.zeros((B, max_blocks), np.int32)
+    pa, pk = rng.permutation(max(n_act, 1)), rng.permutation(max(n_kv, 1))
+    ia = ik = k = 0
+    for b in range(B):
+        for i in range(nb[b]):
+            if kinds[k]:
+                table[b, i] = ~int(pa[ia]); ia += 1
+            else:
+                table[b, i] = int(pk[ik]); ik += 1
+            k += 1
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen, device="cuda") * std + mean).to(f16)
+    kv_std = 0.02 * d ** 0.5
+    Kp = torch.empty(max(n_kv, 1), H, bt, dh, device="cuda", dtype=f16)
+    Vp = torch.empty_like(Kp)
+    step = max(1, (1 << 28) // (H * bt * dh))
+    for i in range(0, Kp.shape[0], step):                      # drawn in pieces: the fp32 temporaries stay small
+        Kp[i:i + step] = rn(*Kp[i:i + step].shape, std=kv_std)
+        Vp[i:i + step] = rn(*Vp[i:i + step].shape, std=kv_std)
+    Ap = rn(max(n_act, 1), bt, d)
+    q = rn(B, H, dh, std=kv_std)
+    Wkv, bkv = rn(2 * d, d, std=0.02), rn(2 * d, std=0.01)
+    ln_w, ln_b = rn(d, std=0.02, mean=1.0), rn(d, std=0.02)
+    lp = (ln_w, ln_b, Wkv, bkv)
+    lp = lp + (hk.prepare_layer(*lp, H),)
+    tb, sl = torch.from_numpy(table).cuda(), torch.from_numpy(lens.astype(np.int32)).cuda()
+    out = torch.empty(B, H, dh, device="cuda", dtype=f16)
+    call = lambda: hk.paged_decode_attn(q, Kp if n_kv else None, Vp if n_kv else None, Ap if n_act else None, tb, sl, bt, lp,
+                                        n_act_used=n_act, out=out)
+    for _ in range(2):
+        call()
+    ts = []
+    for _ in range(args.iters):
+        e0, e1 = _events(torch)
+        e0.record(); call(); e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = float(np.mean(ts))
+    tokens = int(lens.sum())
+    attn_bytes = float(tokens) * 4 * d                          # every token's K and V row once
+    regen_flop = 4.0 * n_act * bt * d * d
+    print(json.dumps({"entry": "hk_paged_decode_attn",
+                      "workload": "%s: B=%d H=%d dh=%d L%s%d, %d-token blocks, %.0f %% ACT blocks" %
+                                  (cfg.name, B, H, dh, "<=" if args.ragged else "=", L, bt, 100 * args.act_fraction),
+                      "iters": args.iters, "ms": ms, "min_ms": float(np.min(ts)), "tokens": tokens, "act_blocks": n_act,
+                      "kv_blocks": n_kv, "attention_bytes": attn_bytes, "regen_flop": regen_flop,
+                      "attention_GBps_if_all_time_were_attention": attn_bytes / (ms * 1e-3) / 1e9}))
+    return 0
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("what", choices=["qkv", "paged"])
+    ap.add_argument("--config", default=None)
+    ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--block-tokens", type=int, default=16)
+    ap.add_argument("--act-fraction", type=float, default=0.0)
+    ap.add_argument("--ragged", action="store_true")
+    args = ap.parse_args()
+    import torch
+    if not torch.cuda.is_available():
+        print("measure: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    from . import binding as hk
+    hk.lib()
+    if args.what == "qkv":
+        args.config = args.config or "opt6.7b"
+        return measure_qkv(args)
+    args.config = args.config or "opt66b"
+    return measure_paged(args)
+
+
+if __name__ == "__main__":
+    sys.exit(main())
