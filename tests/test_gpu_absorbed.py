@@ -142,3 +142,41 @@ def test_absorbed_full_size_sampled(hk, oracle, name):
     torch.cuda.empty_cache()
     _sampled_pairs_check(hk, oracle, cfg)
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("prepared", [False, True])
+def test_absorbed_step_replays_from_a_hip_graph(hk, prepared):
+    """The entry point allocates nothing and never synchronises: captured into a HIP graph and replayed on
+    changing inputs, with eager work and synchronisations in between, it reproduces the eager result bit
+    for bit (also when the layer is prepared inside the call)."""
+    cfg = _cfg("graph", 1024, 8, 4, 320, 0.25, 26)
+    batch = synth.make_batch(cfg)
+    g = {k: _gpu(v) for k, v in batch.items()}
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    if prepared:
+        lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    shape = hk.make_shape(cfg.d, cfg.n_heads)
+    n = hk.hk_absorbed_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act)
+    ws, ws_eager = hk.new_workspace(n), hk.new_workspace(n)
+    out = torch.empty((cfg.B, cfg.n_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    q, act = g["q"].clone(), g["act"].clone()
+    side = torch.cuda.Stream()                               # warm up first: kernel attributes are set on first use
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        hk.hybrid_decode_attn_absorbed(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, out=out, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        hk.hybrid_decode_attn_absorbed(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, out=out, workspace=ws,
+                                       stream=torch.cuda.current_stream())
+    rng = np.random.default_rng(6)
+    for it in range(4):
+        q.copy_(_gpu((rng.standard_normal(q.shape) * 2).astype(np.float16)))
+        act.copy_(_gpu(rng.standard_normal(act.shape).astype(np.float16)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        ref = hk.hybrid_decode_attn_absorbed(q, g["K_cache"], g["V_cache"], act, lp, cfg.ratio, workspace=ws_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(got, ref), "replay %d differs from the eager step" % it

@@ -334,3 +334,46 @@ def test_current_token_joins_either_store_with_the_same_result(oracle):
                                                    g, be, Wkv, bkv, H)
     np.testing.assert_allclose(out_kv, out_act, atol=1e-12)
     np.testing.assert_allclose(K_full[:, :, -1], k, atol=1e-12)      # the regenerated row of the token is its k
+
+
+def test_projections_moved_across_the_sums_give_the_same_step(oracle):
+    """The identity behind hk_hybrid_decode_attn_absorbed, in fp64 and with the oracle as the reference: for
+    one query per head the K projection of Eq. 7 can be applied to the query and the V projection to the
+    weighted sum of the checkpoint rows, LayerNorm folded in, the cached segment joined through its softmax
+    maximum and denominator.  Written with plain numpy from the formulas in include/hybridkv.h; any slip in
+    them (a missing mean term, a wrong head slice, the join) shows here without a GPU."""
+    rng = np.random.default_rng(3)
+    B, H, dh, L_kv, L_act, eps = 3, 2, 8, 13, 24, 1e-5
+    d = H * dh
+    q = rng.standard_normal((B, H, dh))
+    Kc, Vc = rng.standard_normal((B, H, L_kv, dh)), rng.standard_normal((B, H, L_kv, dh))
+    act = rng.standard_normal((B, L_act, d)) * rng.uniform(0.2, 3.0, size=(B, L_act, 1)) + rng.uniform(-5, 5, size=(B, L_act, 1))
+    g, be = 1 + 0.2 * rng.standard_normal(d), 0.2 * rng.standard_normal(d)
+    W, bias = rng.standard_normal((2 * d, d)) * 0.3, rng.standard_normal(2 * d) * 0.1
+    ref, _, _ = oracle.hybrid_decode_attn(q, Kc, Vc, act, g, be, W, bias, H)
+    Wp = W * g[None, :]                                    # gamma folded into the weights
+    bp = bias + W @ be                                     # beta folded into the bias
+    scale = dh ** -0.5
+    out = np.empty_like(ref)
+    for s in range(B):
+        x = act[s]
+        mean = x.mean(axis=1)
+        rstd = 1.0 / np.sqrt(x.var(axis=1) + eps)
+        for h in range(H):
+            ks, vs = slice(h * dh, (h + 1) * dh), slice(d + h * dh, d + (h + 1) * dh)
+            u = q[s, h] @ Wp[ks]                           # the query carried through the key weights  [d]
+            sc_a = scale * (rstd * (x @ u - mean * u.sum()) + q[s, h] @ bp[ks])
+            m_a = sc_a.max()
+            p = np.exp(sc_a - m_a)
+            l_a = p.sum()
+            y = ((p * rstd / l_a)[:, None] * (x - mean[:, None])).sum(axis=0)      # weighted, centred row sum  [d]
+            o_a = Wp[vs] @ y + bp[vs]
+            sc_c = scale * (Kc[s, h] @ q[s, h])
+            m_c = sc_c.max()
+            pc = np.exp(sc_c - m_c)
+            l_c = pc.sum()
+            o_c = pc @ Vc[s, h] / l_c
+            m = max(m_a, m_c)
+            wa, wc = l_a * np.exp(m_a - m), l_c * np.exp(m_c - m)
+            out[s, h] = (wa * o_a + wc * o_c) / (wa + wc)
+    assert np.abs(out - ref).max() <= 1e-10 * max(1.0, np.abs(ref).max())
