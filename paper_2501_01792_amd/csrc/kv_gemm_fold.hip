@@ -12,7 +12,9 @@
 //
 // Kernel shape (CDNA4).  One workgroup per compute unit, resident for the whole launch (grid =
 // number of compute units); it walks its share of the 256 x 256 output tiles.  4 wavefronts,
-// 128 x 128 accumulators each (AGPRs).  The reduction axis advances in k blocks of 64; a k block
+// 128 x 128 accumulators each (AGPRs), as 8 x 8 blocks of v_mfma_f32_16x16x32_f16: on fp16 operands with
+// full mantissas the launch runs against the power limit, and this shape does 15 % more flops inside it
+// than 32x32x16 (half the accumulator register traffic per flop).  The reduction axis advances in k blocks of 64; a k block
 // of one operand is a "unit" of 256 rows x 128 bytes = 32 KiB, and the 160 KiB of LDS are a ring of
 // 5 units through which the units of all the workgroup's tiles stream in consumption order
 // (activations of block g, weights of block g, activations of block g+1, ...): the loads run
@@ -20,16 +22,18 @@
 //   * Loads are buffer_load ... lds, 16 bytes per lane; the 8 lanes of an LDS row fetch one whole
 //     128-byte line of a global row (half-line requests halve the useful rate of the L2 channels).
 //     The XOR swizzle of the 16-byte chunk index, (row / 2) % 8, is applied on the global side; it
-//     makes the 32-row x 16-byte fragment reads (ds_read_b128) conflict-free.
-//   * While k block g is consumed (64 MFMAs per wavefront) the activations of block g+2 are issued
-//     during its first half and the weights of block g+2 right after the barrier in its last
-//     quarter, into the slot that barrier has just freed.  One barrier per k block.
-//   * Fragments are double-buffered in registers; every MFMA slot carries at most one LDS read
-//     and one direct load.
+//     makes the 16-row x 4-chunk fragment reads (ds_read_b128) conflict-free.
+//   * While k block g is consumed (2 sub-steps of k = 32, 64 MFMAs each per wavefront) the activations
+//     of block g+2 are issued during its first half and the weights of block g+2 right after the
+//     barrier early in its second half, into the slot that barrier has just freed.  One barrier per
+//     k block.
+//   * Fragments (8 + 8 per sub-step) are double-buffered in registers; every MFMA slot carries at most
+//     one LDS read and one direct load.
 //   * End of a tile: a row table (destination offset + statistics per row) is built in the one
 //     slot that is free at that moment; accumulators are read out of the AGPRs four rows at a
-//     time, combined with the statistics, rounded to fp16 and stored head-split.  The next
-//     tile's first MFMAs start from a zero C operand instead of cleared accumulators.
+//     time, combined with the statistics, rounded to fp16 and stored head-split, 8 consecutive
+//     features (16 bytes) per store.  The next tile's first MFMAs start from a zero C operand instead
+//     of cleared accumulators.
 #include "hk_internal.h"
 #include "kv_gemm_common.h"
 
@@ -42,7 +46,7 @@ using namespace gemm;
 
 constexpr int FBM = 256, FBN = 256, FBK = 64;
 constexpr int FNT = 256;                                    // 4 wavefronts, 2 x 2
-constexpr int FWM = 128, FWN = 128, FTM = 4, FTN = 4;
+constexpr int FWM = 128, FWN = 128, FTM = 8, FTN = 8;          // 8 x 8 MFMA blocks of 16 x 16 per wavefront
 constexpr int kSlots = 5;
 constexpr int kRowBytes = FBK * 2;                          // 128-byte LDS rows: 8 chunks of 16 bytes
 constexpr int kUnitBytes = 256 * kRowBytes;                 // 32 KiB: one operand of one k block
@@ -58,43 +62,45 @@ struct Frags {
 __device__ __forceinline__ int next2(int s) { s += 2; return s >= kSlots ? s - kSlots : s; }
 
 
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// acc[i][j][r] is MFMA block (i, j), register r: tile row wrow0 + 16 i + 4 (lane / 16) + r, output feature
+// nb + j with nb = n0 + wcol0 + TN * (lane % 16): a lane holds TN = 8 consecutive features of every row.
 template <int TM, int TN>
-__device__ __forceinline__ void store_tile(const float16_t (&acc)[TM][TN], int lane, const RowDst *tab,
+__device__ __forceinline__ void store_tile(const float4_t (&acc)[TM][TN], int lane, const RowDst *tab,
                                                   int wrow0, int nb, int d, int head_dim, int L_cap,
                                                   const float (&cn)[TN], const float (&bn)[TN],
                                                   _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
 {
+    static_assert(TN == 8, "one 16-byte store per row");
     if (nb >= 2 * d) return;
     const bool is_v = nb >= d;
     const int nn = is_v ? nb - d : nb;
     const int h = nn / head_dim, e = nn % head_dim;
     _Float16 *dst_base = (is_v ? V_out : K_out) + ((int64_t)h * L_cap * head_dim + e);
-    const RowDst *my = tab + wrow0 + 4 * (lane >> 5);
-    // groups of 4 consecutive rows (one r / 4 of one block row); the table rows of the next group are
-    // fetched while the current group is converted and stored
+    const RowDst *my = tab + wrow0 + 4 * (lane >> 4);
+    // groups of 4 consecutive rows (one block row); the table rows of the next group are fetched while the
+    // current group is converted and stored
     RowDst rows[2][4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) rows[0][k] = my[k];
 #pragma unroll
-    for (int gi = 0; gi < TM * 4; ++gi) {
-        const int i = gi >> 2, rg = gi & 3;
-        if (gi + 1 < TM * 4) {
-            const int i1 = (gi + 1) >> 2, rg1 = (gi + 1) & 3;
+    for (int i = 0; i < TM; ++i) {
+        if (i + 1 < TM) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) rows[(gi + 1) & 1][k] = my[i1 * 32 + 8 * rg1 + k];
+            for (int k = 0; k < 4; ++k) rows[(i + 1) & 1][k] = my[(i + 1) * 16 + k];
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const RowDst row = rows[gi & 1][k];
-            const int r = 4 * rg + k;
-            half4_t v;
+        for (int r = 0; r < 4; ++r) {
+            const RowDst row = rows[i & 1][r];
+            half8_t v;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < TN; ++j) {
                 float a;
                 asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));
                 v[j] = (_Float16)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
             }
-            if (row.base >= 0) __builtin_nontemporal_store(v, reinterpret_cast<half4_t *>(dst_base + row.base));
+            if (row.base >= 0) __builtin_nontemporal_store(v, reinterpret_cast<half8_t *>(dst_base + row.base));
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -128,7 +134,10 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     const int l_row = lane >> 3;
     const int l_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
     const int a_voff0 = ((8 * wave + l_row) * d + l_chunk * 8) * 2;          // activation row 8 w + l/8 (+ 32 i)
-    const int b_voff0 = ((32 * wave + 4 * l_row) * d + l_chunk * 8) * 2;     // weight row 32 w + 4 (l/8) (+ 128 (i/4) + i%4)
+    // LDS row rho = 8 (w + 4 i) + l/8 of the weight unit belongs to wavefront column rho / 128, MFMA block
+    // j = (rho % 128) / 16, block column c = rho % 16, and holds weight row 128 (rho / 128) + 8 c + j (so that a lane
+    // ends up with 8 consecutive features): 64 (w % 2) + w / 2 + 8 (l/8)  (+ 128 (i/4) + 2 (i%4))
+    const int b_voff0 = ((64 * (wave & 1) + (wave >> 1) + 8 * l_row) * d + l_chunk * 8) * 2;
     const int dma_wave = wave * 1024;                                        // + 4096 i, + slot
 
     // state of the load cursor: the k block whose units are issued next
@@ -163,25 +172,29 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
     };
     auto issue_b = [&](int slot, int i) {
-        int v = b_voff0 + ((i >> 2) * 128 + (i & 3)) * d * 2;
+        int v = b_voff0 + ((i >> 2) * 128 + 2 * (i & 3)) * d * 2;
         v = v < b_vmax ? v : b_vmax;
         unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
     };
 
-    // ---- fragment reads: row (lane % 32) + 32 i of the wavefront's sub-tile, logical chunk 2 ks + lane / 32
-    const int fr = lane & 31, fc = lane >> 5;
-    int frag_off[4];
+    // ---- fragment reads: row (lane % 16) + 16 i of the wavefront's sub-tile, logical chunk 4 ks + lane / 16
+    const int fr = lane & 15, fc = lane >> 4;
+    int frag_off[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) frag_off[ks] = fr * kRowBytes + (((2 * ks + fc) ^ ((fr >> 1) & 7)) << 4);
+    for (int ks = 0; ks < 2; ++ks) frag_off[ks] = fr * kRowBytes + (((4 * ks + fc) ^ ((fr >> 1) & 7)) << 4);
     const int a_rd_wave = wm * FWM * kRowBytes;
     const int b_rd_wave = wn * FWN * kRowBytes;
-    // which = 0..3: a[which] from the unit in slot sa, 4..7: b[which - 4] from the unit in slot sb
+    // The reads of a sub-step in the order its MFMAs need them: a[0], b[0..7], a[1..7].
+    // which = 0: a[0]; 1..8: b[which - 1]; 9..15: a[which - 8]
     auto read_frag = [&](Frags &f, int sa, int sb, int ks, int which) {
-        if (which < 4)
-            f.a[which] = *reinterpret_cast<const half8_t *>(smem + sa * kUnitBytes + a_rd_wave + frag_off[ks] + which * (32 * kRowBytes));
-        else
-            f.b[which - 4] = *reinterpret_cast<const half8_t *>(smem + sb * kUnitBytes + b_rd_wave + frag_off[ks] + (which - 4) * (32 * kRowBytes));
+        if (which == 0 || which > 8) {
+            const int i = which == 0 ? 0 : which - 8;
+            f.a[i] = *reinterpret_cast<const half8_t *>(smem + sa * kUnitBytes + a_rd_wave + frag_off[ks] + i * (16 * kRowBytes));
+        } else {
+            const int j = which - 1;
+            f.b[j] = *reinterpret_cast<const half8_t *>(smem + sb * kUnitBytes + b_rd_wave + frag_off[ks] + j * (16 * kRowBytes));
+        }
     };
 
     Frags f0, f1;
@@ -200,56 +213,38 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) read_frag(f0, 0, 1, 0, q);
+    for (int q = 0; q < 16; ++q) read_frag(f0, 0, 1, 0, q);
 
     int sA = 0, sB = 1;                                        // slots of the units of k block g
     for (int c_j = 0; c_j < my_tiles; ++c_j) {                 // tiles of this workgroup
-    float16_t acc[FTM][FTN];
+    float4_t acc[FTM][FTN];
     // one k block; `first`: the tile's first block, whose first MFMAs start from zero accumulators
     auto stage = [&](auto first) {
         constexpr bool FIRST = decltype(first)::value;
-        float16_t zero;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+        const float4_t zero = {0.f, 0.f, 0.f, 0.f};
         const int sA1 = next2(sA), sB1 = next2(sB);            // k block g + 1
         const int sA2 = next2(sA1), sB2 = sA;                  // k block g + 2: units 2g+4, 2g+5
-        // ---- sub-step 0 (f0): fragments of sub-step 1 -> f1; activations of block g+2, loads 0..3
+        // ---- sub-step 0 (f0, k 0..31): fragments of sub-step 1 -> f1; activations of block g+2
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f0.a[q >> 2], f0.b[q & 3], FIRST ? zero : acc[q >> 2][q & 3], 0, 0, 0);
-            if (q < 8) read_frag(f1, sA, sB, 1, q);
-            if ((q & 3) == 3) issue_a(sA2, q >> 2);
+        for (int q = 0; q < 64; ++q) {
+            acc[q >> 3][q & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7], 0, 0, 0);
+            if (q < 32 && (q & 1) == 0) read_frag(f1, sA, sB, 1, q >> 1);
+            if ((q & 7) == 7) issue_a(sA2, q >> 3);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // ---- sub-step 1 (f1): fragments of sub-step 2 -> f0; activations of block g+2, loads 4..7
+        // ---- sub-step 1 (f1, k 32..63): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; weights of block g+2
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f1.a[q >> 2], f1.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
-            if (q < 8) read_frag(f0, sA, sB, 2, q);
-            if ((q & 3) == 3) issue_a(sA2, 4 + (q >> 2));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // ---- sub-step 2 (f0): fragments of sub-step 3 -> f1
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f0.a[q >> 2], f0.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
-            if (q < 8) read_frag(f1, sA, sB, 3, q);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // ---- sub-step 3 (f1): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; weights of block g+2
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f1.a[q >> 2], f1.b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
-            if (q == 1) {
+        for (int q = 0; q < 64; ++q) {
+            acc[q >> 3][q & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7], 0, 0, 0);
+            if (q == 3) {
                 // Every LDS read of block g has been issued.  Wait for them and for this wavefront's loads
                 // of block g+1 (the 8 activation loads of block g+2 may fly), then meet the others: after
                 // the barrier block g+1 is complete in LDS and the slots of block g may be refilled.
                 asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
-            if (q >= 2 && q < 10) read_frag(f0, sA1, sB1, 0, q - 2);
-            if (q >= 2 && (q & 1) == 0) issue_b(sB2, (q - 2) >> 1);      // q = 2, 4, .., 14: loads 0..6
-            if (q == 15) issue_b(sB2, 7);
+            if (q >= 4 && q < 36 && (q & 1) == 0) read_frag(f0, sA1, sB1, 0, (q - 4) >> 1);
+            if (q >= 7 && (q & 7) == 7) issue_b(sB2, q >> 3);                // q = 7, 15, .., 63: loads 0..7
             __builtin_amdgcn_sched_barrier(0);
         }
         advance_load();
@@ -267,7 +262,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
             const int64_t m0 = (int64_t)tm * FBM;
             const int n0 = tn * FBN;
             const RowDst my_row = row_dst(m0 + tid, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
-            const int nb = n0 + wn * FWN + FTN * (lane & 31);
+            const int nb = n0 + wn * FWN + FTN * (lane & 15);
             float cn[FTN], bn[FTN];
 #pragma unroll
             for (int j = 0; j < FTN; ++j) {
