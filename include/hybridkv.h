@@ -353,13 +353,15 @@ int hk_minibatch_balance(const hk_line *T_kv_gen, const hk_line *T_load_kv, doub
 
 /*
  * Measurement aid (no operation of the paper): runs a loop of back-to-back
- * v_mfma_f32_32x32x16_f16 on every compute unit (4 wavefronts each, `iters`
- * x 16 instructions per wavefront) with all-zero (random_operands == 0) or
+ * v_mfma_f32_16x16x32_f16 (the projection kernel's instruction) on every
+ * compute unit (4 wavefronts each, `iters` x 64 instructions per wavefront,
+ * 1 Mflop per iteration and wavefront) with all-zero (random_operands == 0) or
  * random fp16 operands and returns the sustained rate in TFLOP/s through
  * `tflops_out` (HOST pointer).  `sink` is device scratch of at least
  * (number of compute units) * 1024 bytes.  Synchronises the stream.  The rate
- * with random operands is the practical ceiling of any fp16 MFMA kernel on the
- * GPU at hand; it is reported next to the projection kernel's roofline figure.
+ * with random operands is the practical ceiling of an fp16 kernel built on
+ * that instruction on the GPU at hand (the 32x32x16 form sustains ~15 % less);
+ * it is reported next to the projection kernel's roofline figure.
  */
 int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
                        float *tflops_out, void *stream);

@@ -136,7 +136,7 @@ def hk_regen_workspace_bytes(shape: hk_shape, B: int, L_act: int) -> int:
     return int(lib().hk_regen_workspace_bytes(ctypes.byref(shape), B, L_act))
 
 
-def probe_mfma_rate(random_operands: bool, iters: int = 20000, stream=None) -> float:
+def probe_mfma_rate(random_operands: bool, iters: int = 10000, stream=None) -> float:
     """hk_probe_mfma_rate: sustained TFLOP/s of a pure fp16 MFMA loop with zero / random operands."""
     sink = new_workspace(1 << 20)
     out = ctypes.c_float()

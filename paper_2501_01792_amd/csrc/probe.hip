@@ -1,28 +1,29 @@
 // Measurement aid: the matrix-core rate this GPU sustains on a loop of nothing but
-// v_mfma_f32_32x32x16_f16, with all-zero or with random operands.  On MI355X the two differ widely
-// (the shader clock drops under random fp16 operands), so the second number is the practical
-// ceiling against which the projection kernel's fraction of the published peak should be read.
+// v_mfma_f32_16x16x32_f16 (the instruction of the projection kernel, on its 8 x 8 grid of accumulator
+// blocks), with all-zero or with random operands.  On MI355X the two differ widely (the shader clock
+// drops under random fp16 operands), so the second number is the practical ceiling against which the
+// projection kernel's fraction of the published peak should be read.  The accumulators are pinned to
+// their registers by inline asm: left to the register allocator, a loop over 64 four-register
+// accumulators gets shuffled between register files and measures the shuffling.
 #include "../../include/hybridkv.h"
 #include <hip/hip_runtime.h>
 
 namespace {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters, int random_operands)
 {
-    float16_t acc[4][4];
+    float4_t acc[64];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int q = 0; q < 64; ++q)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    half8_t a[4], b[4];
+        for (int r = 0; r < 4; ++r) acc[q][r] = 0.f;
+    half8_t a[8], b[8];
     unsigned x = 12345u + threadIdx.x * 7919u + blockIdx.x * 104729u;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             x = x * 1664525u + 1013904223u;
@@ -32,16 +33,14 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters, 
         }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int q = 0; q < 16; ++q)
-            acc[q >> 2][q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[q >> 2], b[q & 3], acc[q >> 2][q & 3], 0, 0, 0);
+        for (int q = 0; q < 64; ++q)
+            asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[q]) : "v"(a[q >> 3]), "v"(b[q & 7]));
     }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int q = 0; q < 64; ++q)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+        for (int r = 0; r < 4; ++r) s += acc[q][r];
     sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
@@ -70,7 +69,7 @@ extern "C" int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float 
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f)
         rc = HK_ERR_LAUNCH;
     else
-        *tflops_out = (float)((double)cus * 4 * iters * 16 * 32768.0 / (ms * 1e-3) / 1e12);
+        *tflops_out = (float)((double)cus * 4 * iters * 64 * 16384.0 / (ms * 1e-3) / 1e12);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return rc;
