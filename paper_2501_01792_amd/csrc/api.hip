@@ -103,7 +103,7 @@ struct Marks {
     bool put(int i) const { return !(ev && i < n && ev[i]) || hipEventRecord(ev[i], stream) == hipSuccess; }
 };
 
-int regen_impl(const hk_shape *s, const void *act, int64_t B, int64_t L_act, const hk_layer_params *lp,
+int regen_impl(const hk_shape *s, const void *act, int64_t L_act, const hk_layer_params *lp,
                void *K_out, void *V_out, int L_cap, int tok_off, float2 *stats, void *prep_scratch, int64_t M,
                hipStream_t stream, const Marks &mk)
 {
@@ -196,7 +196,7 @@ int hk_regen_kv(const hk_shape *shape, const void *act, int32_t B, int32_t L_act
         return HK_ERR_ALIGN;
     if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace);
-    return regen_impl(shape, act, B, L_act, params, K_out, V_out, L_cap, tok_off,
+    return regen_impl(shape, act, L_act, params, K_out, V_out, L_cap, tok_off,
                       reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, static_cast<hipStream_t>(stream),
                       Marks{nullptr, 0, nullptr});
 }
@@ -244,7 +244,7 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     const Marks mk{reinterpret_cast<hipEvent_t *>(events), events ? n_events : 0, hs};
     if (!mk.put(0)) return HK_ERR_LAUNCH;
     if (L_act > 0) {
-        st = regen_impl(shape, act, B, L_act, params, K_regen, V_regen, L_act, 0,
+        st = regen_impl(shape, act, L_act, params, K_regen, V_regen, L_act, 0,
                         reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, hs, mk);
         if (st != HK_OK) return st;
     } else if (!mk.put(1)) {
@@ -521,7 +521,7 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     if (cache->n_act_used > 0) {
         // "KV Gen" over the ACT pool: block b of the pool is a sequence of block_tokens checkpoints whose
         // K/V rows land in block b of the regenerated pools, which have the KV pool's layout
-        st = regen_impl(shape, cache->act_pool, cache->n_act_used, cache->block_tokens, params, K_regen, V_regen,
+        st = regen_impl(shape, cache->act_pool, cache->block_tokens, params, K_regen, V_regen,
                         cache->block_tokens, 0, reinterpret_cast<float2 *>(ws + p.off_stats), ws + p.off_prep, p.M, hs,
                         Marks{nullptr, 0, nullptr});
         if (st != HK_OK) return st;
