@@ -177,6 +177,8 @@ def main():
     ap.add_argument("--ratio", type=float, default=None, help="override the KV fraction of the context")
     ap.add_argument("--gemm-tile", type=int, default=0)
     ap.add_argument("--attn-splits", type=int, default=0)
+    ap.add_argument("--dtype", choices=["f16", "bf16"], default="f16",
+                    help="bf16: the same step on bf16-rounded inputs (comparison; no CPU sample, no variants)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true", help="skip the comparison variants timed after the bench line's region")
     ap.add_argument("--absorbed", action="store_true",
@@ -216,6 +218,9 @@ def main():
 
     batch = synth.make_batch(cfg, threads=16)
     g = {k: torch.from_numpy(v).cuda() for k, v in batch.items()}
+    if args.dtype == "bf16":
+        g = {k: v.to(torch.bfloat16) for k, v in g.items()}
+        args.no_cpu_baseline = args.no_variants = True
     lp = (g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"])
     prepare_ms = None
     if not args.unprepared and cfg.L_act:
@@ -231,9 +236,10 @@ def main():
     Kc = g["K_cache"] if cfg.L_kv else None
     Vc = g["V_cache"] if cfg.L_kv else None
     act = g["act"] if cfg.L_act else None
-    shape = hk.make_shape(cfg.d, cfg.n_heads, attn_splits=args.attn_splits, gemm_tile=args.gemm_tile)
+    shape = hk.make_shape(cfg.d, cfg.n_heads, attn_splits=args.attn_splits, gemm_tile=args.gemm_tile,
+                          dtype=hk.HK_DTYPE_BF16 if args.dtype == "bf16" else hk.HK_DTYPE_F16)
     ws = hk.new_workspace(hk.hk_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act))
-    out = torch.empty((cfg.B, cfg.n_heads, cfg.head_dim), dtype=torch.float16, device="cuda")
+    out = torch.empty((cfg.B, cfg.n_heads, cfg.head_dim), dtype=g["q"].dtype, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step(events=None):
@@ -319,7 +325,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "%s: d=%d H=%d dh=%d B=%d L=%d ratio=%g (L_kv=%d, L_act=%d), hybrid-cache decode step "
                                "of one layer" % (cfg.name, cfg.d, cfg.n_heads, cfg.head_dim, cfg.B, cfg.L, cfg.ratio,
                                                  cfg.L_kv, cfg.L_act),

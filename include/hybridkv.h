@@ -12,7 +12,11 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller and must be
  *     16-byte aligned.  hk_shape / hk_layer_params themselves are HOST structs
  *     passed by pointer and read before the call returns.
- *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16); accumulation is fp32.
+ *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16), the precision of the paper's
+ *     models (Sec. 6.1); accumulation is fp32.  hk_prepare_layer, hk_regen_kv and
+ *     the hybrid step (hk_hybrid_decode_attn, _marked, and their size queries)
+ *     also take bfloat16 (HK_DTYPE_BF16: every fp16 tensor below is bf16
+ *     instead); the other entry points return HK_ERR_DTYPE for it.
  *   - The library allocates nothing.  Scratch memory is the caller's
  *     `workspace` (device, 256-byte aligned, at least hk_workspace_bytes()).
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
@@ -53,18 +57,18 @@ typedef enum hk_status {
     HK_ERR_RATIO = -3,     /* ratio outside [0,1] or inconsistent with L_kv, L_act */
     HK_ERR_ALIGN = -4,     /* a data pointer is not 16-byte aligned (workspace: 256) */
     HK_ERR_WORKSPACE = -5, /* workspace_bytes smaller than hk_workspace_bytes() */
-    HK_ERR_DTYPE = -6,     /* dtype other than HK_DTYPE_F16 */
+    HK_ERR_DTYPE = -6,     /* a dtype the entry point does not take */
     HK_ERR_LAUNCH = -7     /* the HIP runtime reported an error at launch */
 } hk_status;
 
-enum { HK_DTYPE_F16 = 0 };
+enum { HK_DTYPE_F16 = 0, HK_DTYPE_BF16 = 1 };
 
 /* Shape and numerics of one decoder layer.  Host struct. */
 typedef struct hk_shape {
     int32_t d;             /* hidden size */
     int32_t n_heads;       /* H */
     int32_t head_dim;      /* dh, 64 or 128; d == n_heads * head_dim */
-    int32_t dtype;         /* HK_DTYPE_F16 */
+    int32_t dtype;         /* HK_DTYPE_F16 or HK_DTYPE_BF16 */
     float ln_eps;          /* LayerNorm epsilon (inside the square root); OPT uses 1e-5 */
     float softmax_scale;   /* multiplies q.k before the softmax; <= 0 selects head_dim^-1/2 */
     int32_t attn_splits;   /* attention work split: 0 lets the library choose (the tokens of all

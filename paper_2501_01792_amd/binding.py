@@ -16,6 +16,7 @@ HK_OK = 0
 HK_ERR_NULL, HK_ERR_SHAPE, HK_ERR_RATIO, HK_ERR_ALIGN = -1, -2, -3, -4
 HK_ERR_WORKSPACE, HK_ERR_DTYPE, HK_ERR_LAUNCH = -5, -6, -7
 HK_DTYPE_F16 = 0
+HK_DTYPE_BF16 = 1
 HK_MAX_SPLITS = 64
 
 
@@ -124,8 +125,14 @@ def status_string(status: int) -> str:
     return lib().hk_status_string(int(status)).decode()
 
 
-def make_shape(d, n_heads, ln_eps=1e-5, softmax_scale=0.0, attn_splits=0, gemm_tile=0) -> hk_shape:
-    return hk_shape(d, n_heads, d // n_heads, HK_DTYPE_F16, ln_eps, softmax_scale, attn_splits, gemm_tile)
+def make_shape(d, n_heads, ln_eps=1e-5, softmax_scale=0.0, attn_splits=0, gemm_tile=0, dtype=HK_DTYPE_F16) -> hk_shape:
+    return hk_shape(d, n_heads, d // n_heads, dtype, ln_eps, softmax_scale, attn_splits, gemm_tile)
+
+
+def _dtype_code(t):
+    """The C ABI's dtype code of a tensor: fp16, or bf16 where the entry point takes it."""
+    import torch
+    return HK_DTYPE_BF16 if t.dtype == torch.bfloat16 else HK_DTYPE_F16
 
 
 def hk_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int) -> int:
@@ -167,9 +174,9 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _params(ln_w, ln_b, Wkv, bkv, prepared=None):
+def _params(ln_w, ln_b, Wkv, bkv, prepared=None, el=None):
     import torch
-    f16 = torch.float16
+    f16 = el or torch.float16
     pp = _dev_ptr(prepared, "prepared")
     return hk_layer_params(_dev_ptr(ln_w, "ln_w", f16).value, _dev_ptr(ln_b, "ln_b", f16).value,
                            _dev_ptr(Wkv, "Wkv", f16).value, _dev_ptr(bkv, "bkv", f16).value,
@@ -184,9 +191,9 @@ def prepare_layer(ln_w, ln_b, Wkv, bkv, n_heads, stream=None):
     """hk_prepare_layer: returns the prepared-layer buffer (a uint8 GPU tensor) to pass as the fifth
     element of ``layer_params`` / the ``prepared`` argument."""
     d = ln_w.shape[0]
-    shape = make_shape(d, n_heads)
+    shape = make_shape(d, n_heads, dtype=_dtype_code(Wkv))
     buf = new_workspace(hk_prepared_bytes(shape), ln_w.device)
-    lp = _params(ln_w, ln_b, Wkv, bkv)
+    lp = _params(ln_w, ln_b, Wkv, bkv, el=Wkv.dtype)
     st = lib().hk_prepare_layer(ctypes.byref(shape), ctypes.byref(lp), _dev_ptr(buf, "prepared"), buf.numel(),
                                 _stream_ptr(stream))
     if st != HK_OK:
@@ -207,18 +214,19 @@ def regen_kv(act, ln_w, ln_b, Wkv, bkv, n_heads, K_out=None, V_out=None, tok_off
     workspace when they are not given."""
     import torch
     B, L_act, d = act.shape
-    shape = make_shape(d, n_heads, ln_eps, gemm_tile=gemm_tile)
+    el = act.dtype                                           # fp16, or bf16 (every tensor then)
+    shape = make_shape(d, n_heads, ln_eps, gemm_tile=gemm_tile, dtype=_dtype_code(act))
     dh = d // n_heads
     if K_out is None:
-        K_out = torch.empty((B, n_heads, L_act, dh), dtype=torch.float16, device=act.device)
+        K_out = torch.empty((B, n_heads, L_act, dh), dtype=el, device=act.device)
         V_out = torch.empty_like(K_out)
     L_cap = K_out.shape[2]
     if workspace is None:
         workspace = new_workspace(hk_regen_workspace_bytes(shape, B, L_act), act.device)
-    lp = _params(ln_w, ln_b, Wkv, bkv, prepared)
-    st = lib().hk_regen_kv(ctypes.byref(shape), _dev_ptr(act, "act", torch.float16), B, L_act,
-                           ctypes.byref(lp), _dev_ptr(K_out, "K_out", torch.float16),
-                           _dev_ptr(V_out, "V_out", torch.float16), L_cap, tok_off,
+    lp = _params(ln_w, ln_b, Wkv, bkv, prepared, el=el)
+    st = lib().hk_regen_kv(ctypes.byref(shape), _dev_ptr(act, "act", el), B, L_act,
+                           ctypes.byref(lp), _dev_ptr(K_out, "K_out", el),
+                           _dev_ptr(V_out, "V_out", el), L_cap, tok_off,
                            _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_regen_kv")
@@ -238,13 +246,13 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
     d = H * dh
     L_kv = 0 if K_cache is None else K_cache.shape[2]
     L_act = 0 if act is None else act.shape[1]
-    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, gemm_tile)
+    f16 = q.dtype                                            # fp16, or bf16 (every tensor then)
+    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, gemm_tile, dtype=_dtype_code(q))
     if out is None:
-        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+        out = torch.empty((B, H, dh), dtype=f16, device=q.device)
     if workspace is None:
         workspace = new_workspace(hk_workspace_bytes(shape, B, L_kv, L_act), q.device)
-    lp = _params(*layer_params)
-    f16 = torch.float16
+    lp = _params(*layer_params[:4], prepared=layer_params[4] if len(layer_params) > 4 else None, el=f16)
     args = [ctypes.byref(shape), _dev_ptr(q, "q", f16),
             _dev_ptr(K_cache, "K_cache", f16), _dev_ptr(V_cache, "V_cache", f16), L_kv,
             _dev_ptr(act, "act", f16), L_act, B, ctypes.byref(lp), float(ratio),

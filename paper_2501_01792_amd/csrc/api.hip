@@ -23,10 +23,11 @@ struct Plan {
     size_t off_k, off_v, off_stats, off_prep, off_partial, total;   // off_prep: per-call prepared layer (0 bytes when unused)
 };
 
-int check_shape(const hk_shape *s)
+// bf16: only the entry points of the benchmark's path take it (prepare, regenerate, the hybrid step)
+int check_shape(const hk_shape *s, bool allow_bf16 = false)
 {
     if (!s) return HK_ERR_NULL;
-    if (s->dtype != HK_DTYPE_F16) return HK_ERR_DTYPE;
+    if (s->dtype != HK_DTYPE_F16 && !(allow_bf16 && s->dtype == HK_DTYPE_BF16)) return HK_ERR_DTYPE;
     if (s->d <= 0 || s->n_heads <= 0) return HK_ERR_SHAPE;
     if (s->gemm_tile != 0 && s->gemm_tile != 128 && s->gemm_tile != 256) return HK_ERR_SHAPE;
     if (s->head_dim != 64 && s->head_dim != 128) return HK_ERR_SHAPE;
@@ -43,9 +44,9 @@ struct PreparedLayout {
 PreparedLayout prepared_layout(int d);
 
 // Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
-int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p)
+int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p, bool allow_bf16 = true)
 {
-    int st = check_shape(s);
+    int st = check_shape(s, allow_bf16);
     if (st != HK_OK) return st;
     if (B < 0 || L_kv < 0 || L_act < 0) return HK_ERR_SHAPE;
     if (B > (1 << 24) || L_kv > (1 << 28) || L_act > (1 << 28)) return HK_ERR_SHAPE;
@@ -63,7 +64,7 @@ int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool re
     // The large-problem projection kernel works on a prepared layer; room to prepare one per call, for
     // callers that do not bring their own.
     p->off_prep = end;
-    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile)) end += prepared_layout(s->d).total;
+    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile, s->dtype)) end += prepared_layout(s->d).total;
     p->off_partial = end;
     p->n_waves = 0;
     if (!regen_only && L_kv + L_act > 0 && p->BH > 0) {
@@ -108,17 +109,17 @@ int regen_impl(const hk_shape *s, const void *act, int64_t L_act, const hk_layer
                hipStream_t stream, const Marks &mk)
 {
     const void *prepared = lp->prepared;
-    if (!prepared && hk::kv_gemm_uses_prepared(M, s->d, s->gemm_tile)) {
+    if (!prepared && hk::kv_gemm_uses_prepared(M, s->d, s->gemm_tile, s->dtype)) {
         // no prepared layer given: prepare one into the workspace (one pass over the weights)
         const PreparedLayout L = prepared_layout(s->d);
         char *pp = static_cast<char *>(prep_scratch);
         if (hk::launch_prepare_layer(lp->Wkv, lp->bkv, lp->ln_w, lp->ln_b, pp + L.off_w,
                                      reinterpret_cast<float *>(pp + L.off_c), reinterpret_cast<float *>(pp + L.off_b),
-                                     s->d, stream) != hipSuccess)
+                                     s->d, stream, s->dtype) != hipSuccess)
             return HK_ERR_LAUNCH;
         prepared = prep_scratch;
     }
-    if (hk::launch_ln_stats(act, stats, M, s->d, s->ln_eps, stream) != hipSuccess) return HK_ERR_LAUNCH;
+    if (hk::launch_ln_stats(act, stats, M, s->d, s->ln_eps, stream, s->dtype) != hipSuccess) return HK_ERR_LAUNCH;
     if (!mk.put(1)) return HK_ERR_LAUNCH;
     hk::KvGemmArgs g;
     g.act = act; g.stats = stats; g.ln_w = lp->ln_w; g.ln_b = lp->ln_b; g.Wkv = lp->Wkv; g.bkv = lp->bkv;
@@ -131,7 +132,7 @@ int regen_impl(const hk_shape *s, const void *act, int64_t L_act, const hk_layer
         g.bvec = reinterpret_cast<const float *>(pp + L.off_b);
     }
     g.K_out = K_out; g.V_out = V_out; g.M = M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
-    g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile;
+    g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile; g.dtype = s->dtype;
     if (hk::launch_kv_gemm(g, stream) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -142,14 +143,14 @@ extern "C" {
 
 size_t hk_prepared_bytes(const hk_shape *shape)
 {
-    if (check_shape(shape) != HK_OK) return 0;
+    if (check_shape(shape, true) != HK_OK) return 0;
     return prepared_layout(shape->d).total;
 }
 
 int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params, void *prepared, size_t prepared_bytes,
                      void *stream)
 {
-    int st = check_shape(shape);
+    int st = check_shape(shape, true);
     if (st != HK_OK) return st;
     st = check_params(params);
     if (st != HK_OK) return st;
@@ -160,7 +161,7 @@ int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params, void 
     char *pp = static_cast<char *>(prepared);
     if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, pp + L.off_w,
                                  reinterpret_cast<float *>(pp + L.off_c), reinterpret_cast<float *>(pp + L.off_b),
-                                 shape->d, static_cast<hipStream_t>(stream)) != hipSuccess)
+                                 shape->d, static_cast<hipStream_t>(stream), shape->dtype) != hipSuccess)
         return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -260,6 +261,7 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
     a.lse = nullptr;
+    a.dtype = shape->dtype;
     a.after_main = (mk.ev && mk.n > 3) ? mk.ev[3] : nullptr;
     if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     if (!mk.put(4)) return HK_ERR_LAUNCH;
@@ -279,7 +281,7 @@ struct AbsorbedPlan {
 int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, AbsorbedPlan *p)
 {
     Plan base;
-    int st = make_plan(s, B, L_kv, L_act, false, &base);
+    int st = make_plan(s, B, L_kv, L_act, false, &base, false);
     if (st != HK_OK) return st;
     if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
     p->M = base.M; p->BH = base.BH; p->scale = base.scale;
@@ -355,6 +357,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
         a.partial = reinterpret_cast<float *>(ws + p.off_partial);
         a.out = L_act > 0 ? static_cast<void *>(ws + p.off_outc) : out;
         a.lse = L_act > 0 ? reinterpret_cast<float2 *>(ws + p.off_lse) : nullptr;
+        a.dtype = 0;
         a.after_main = nullptr;
         if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     }

@@ -24,26 +24,27 @@
 //   * Online softmax state is kept per lane group (the lanes sharing a row) in the log2 domain
 //     with a finite "-infinity" so that fully masked tiles need no special case.
 #include "hk_internal.h"
+#include "elem.h"
 
 namespace hk {
 namespace {
 
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = 4;
 constexpr int kTile = 64;               // tokens per wavefront step
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf in running maxima
 
-__device__ __forceinline__ float dot8(half8_t a, half8_t b)
+template <int DT>
+__device__ __forceinline__ float dot8(typename Elem<DT>::V8 a, typename Elem<DT>::V8 b)
 {
+    typedef typename Elem<DT>::V2 half2_t;
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         half2_t x = {a[2 * j], a[2 * j + 1]};
         half2_t y = {b[2 * j], b[2 * j + 1]};
-        s = __builtin_amdgcn_fdot2(x, y, s, false);
+        s = Elem<DT>::dot2(x, y, s);
     }
     return s;
 }
@@ -51,14 +52,16 @@ __device__ __forceinline__ float dot8(half8_t a, half8_t b)
 // First position of the range of wavefront w when `total` positions are cut into W ranges.
 __host__ __device__ inline int64_t range_begin(int64_t w, int64_t total, int64_t W) { return (w * total) / W; }
 
-template <int DH>
+template <int DH, int DT>
 __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
-    const _Float16 *__restrict__ q,
-    const _Float16 *__restrict__ K0, const _Float16 *__restrict__ V0,
-    const _Float16 *__restrict__ K1, const _Float16 *__restrict__ V1,
+    const typename Elem<DT>::T *__restrict__ q,
+    const typename Elem<DT>::T *__restrict__ K0, const typename Elem<DT>::T *__restrict__ V0,
+    const typename Elem<DT>::T *__restrict__ K1, const typename Elem<DT>::T *__restrict__ V1,
     int L0, int L1, int64_t total, int W, float scale_log2e,
     float *__restrict__ partial)
 {
+    typedef typename Elem<DT>::T elem_t;
+    typedef typename Elem<DT>::V8 half8_t;
     constexpr int LPR = DH / 8;          // lanes per row
     constexpr int RPL = 64 / LPR;        // rows per load instruction == lane groups per wavefront
     constexpr int NL = LPR;              // loads per lane per 64-token tile
@@ -90,8 +93,8 @@ __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
             const int a = t_first > s_lo ? t_first : s_lo, b = t_last < s_hi ? t_last : s_hi;
             if (a >= b) continue;
             const int Ls = seg ? L1 : L0;
-            const _Float16 *Kp = (seg ? K1 : K0) + (int64_t)bh * Ls * DH;
-            const _Float16 *Vp = (seg ? V1 : V0) + (int64_t)bh * Ls * DH;
+            const elem_t *Kp = (seg ? K1 : K0) + (int64_t)bh * Ls * DH;
+            const elem_t *Vp = (seg ? V1 : V0) + (int64_t)bh * Ls * DH;
             const int t_begin = a - s_lo, t_end = b - s_lo;        // token range inside the segment
 
             for (int tb = t_begin; tb < t_end; tb += kTile) {
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
                 // partial dot products, then reduce-scatter over the LPR lanes of a group
                 float pd[NL];
 #pragma unroll
-                for (int i = 0; i < NL; ++i) pd[i] = dot8(qv, kr[i]);
+                for (int i = 0; i < NL; ++i) pd[i] = dot8<DT>(qv, kr[i]);
 #pragma unroll
                 for (int h = NL / 2; h >= 1; h >>= 1) {
                     const bool up = (c & h) != 0;
@@ -173,9 +176,9 @@ __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
 
 // Log-sum-exp merge of the partials of one (sequence, head): those of the wavefronts whose range
 // meets the pair's positions [bh L, (bh+1) L), at indices (wavefront + bh).
-template <int DH>
+template <int DH, int DT>
 __global__ __launch_bounds__(DH) void merge_partials_kernel(const float *__restrict__ partial, int L, int64_t total,
-                                                            int W, _Float16 *__restrict__ out, float2 *__restrict__ lse)
+                                                            int W, typename Elem<DT>::T *__restrict__ out, float2 *__restrict__ lse)
 {
     const int bh = blockIdx.x, e = threadIdx.x;
     const int64_t lo = (int64_t)bh * L, hi = lo + L - 1;       // first and last position of the pair
@@ -197,27 +200,28 @@ __global__ __launch_bounds__(DH) void merge_partials_kernel(const float *__restr
         o = __builtin_fmaf(wgt, src[i * (DH + 2) + 2 + e], o);
         l = __builtin_fmaf(wgt, src[i * (DH + 2) + 1], l);
     }
-    out[(int64_t)bh * DH + e] = (_Float16)(o / l);
+    out[(int64_t)bh * DH + e] = (typename Elem<DT>::T)(o / l);
     if (lse && e == 0) lse[bh] = make_float2(mx, l);
 }
 
-template <int DH>
+template <int DH, int DT>
 hipError_t launch_dh(const AttnArgs &a, hipStream_t s)
 {
+    typedef typename Elem<DT>::T elem_t;
     const int L = a.L0 + a.L1;
     const int64_t total = (int64_t)a.BH * L;
     const float scale_log2e = a.scale * 1.4426950408889634f;
     const unsigned blocks = (unsigned)((a.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
-    hipLaunchKernelGGL(flash_decode_kernel<DH>, dim3(blocks), dim3(kThreads), 0, s,
-                       static_cast<const _Float16 *>(a.q),
-                       static_cast<const _Float16 *>(a.K0), static_cast<const _Float16 *>(a.V0),
-                       static_cast<const _Float16 *>(a.K1), static_cast<const _Float16 *>(a.V1),
+    hipLaunchKernelGGL((flash_decode_kernel<DH, DT>), dim3(blocks), dim3(kThreads), 0, s,
+                       static_cast<const elem_t *>(a.q),
+                       static_cast<const elem_t *>(a.K0), static_cast<const elem_t *>(a.V0),
+                       static_cast<const elem_t *>(a.K1), static_cast<const elem_t *>(a.V1),
                        a.L0, a.L1, total, a.n_waves, scale_log2e, a.partial);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.after_main) e = hipEventRecord(a.after_main, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(merge_partials_kernel<DH>, dim3((unsigned)a.BH), dim3(DH), 0, s,
-                       a.partial, L, total, a.n_waves, static_cast<_Float16 *>(a.out), a.lse);
+    hipLaunchKernelGGL((merge_partials_kernel<DH, DT>), dim3((unsigned)a.BH), dim3(DH), 0, s,
+                       a.partial, L, total, a.n_waves, static_cast<elem_t *>(a.out), a.lse);
     return hipGetLastError();
 }
 
@@ -245,8 +249,8 @@ hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s)
     if (a.BH <= 0) return hipSuccess;
     if (a.n_waves <= 0 || a.n_waves > kAttnMaxWaves || (int64_t)a.n_waves > (int64_t)a.BH * (a.L0 + a.L1))
         return hipErrorInvalidValue;
-    if (a.head_dim == 128) return launch_dh<128>(a, s);
-    if (a.head_dim == 64) return launch_dh<64>(a, s);
+    if (a.head_dim == 128) return a.dtype == 1 ? launch_dh<128, 1>(a, s) : launch_dh<128, 0>(a, s);
+    if (a.head_dim == 64) return a.dtype == 1 ? launch_dh<64, 1>(a, s) : launch_dh<64, 0>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -6,9 +6,9 @@
 
 namespace hk {
 
-// Per-row LayerNorm statistics of act[M, d] (fp16) in fp32.
+// Per-row LayerNorm statistics of act[M, d] (fp16, or bf16 with dtype 1) in fp32.
 // stats[r] = (rstd_r, -mean_r * rstd_r), so that (x - mean) * rstd == fma(x, stats.x, stats.y).
-hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s);
+hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s, int dtype = 0);
 
 struct KvGemmArgs {
     const void *act;       // [M, d] fp16
@@ -26,17 +26,18 @@ struct KvGemmArgs {
     int d, n_heads, head_dim;
     int L_act, L_cap, tok_off;
     int tile;              // 0 = choose, else 128 or 256
+    int dtype;             // 0: fp16, 1: bf16 (bf16 always takes the 256 x 256 kernel)
 };
 // LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
 // Whether launch_kv_gemm takes the 256 x 256 streaming kernel for this problem (tile: 0 = choose, 128, 256).
 // That kernel works on a prepared layer (Wp, cvec, bvec), so the caller must supply one.
-bool kv_gemm_uses_prepared(int64_t M, int d, int tile);
+bool kv_gemm_uses_prepared(int64_t M, int d, int tile, int dtype = 0);
 // The 256 x 256 kernel for prepared layers (LayerNorm folded around the product; needs Wp, cvec, bvec).
 hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s);
 // Fills Wp, cvec, bvec from the layer's parameters.
 hipError_t launch_prepare_layer(const void *Wkv, const void *bkv, const void *ln_w, const void *ln_b,
-                                void *Wp, float *cvec, float *bvec, int d, hipStream_t s);
+                                void *Wp, float *cvec, float *bvec, int d, hipStream_t s, int dtype = 0);
 
 struct AttnArgs {
     const void *q;         // [B, H, dh] fp16
@@ -51,6 +52,7 @@ struct AttnArgs {
     void *out;             // [BH, dh] fp16
     float2 *lse;           // optional [BH]: (running maximum in the log2 domain, softmax denominator) of every pair
     hipEvent_t after_main; // optional: recorded after the streaming kernel, before the merge
+    int dtype;             // 0: fp16, 1: bf16
 };
 // Wavefronts of the attention kernel that stay resident together on an MI355X: 256 compute units x
 // 4 SIMDs x 4 wavefronts (the kernel's register footprint, <= 128 VGPRs, allows 4 per SIMD).

@@ -185,8 +185,9 @@ hipError_t launch_tile(const KvGemmArgs &a, hipStream_t s)
 
 }  // namespace
 
-bool kv_gemm_uses_prepared(int64_t M, int d, int tile)
+bool kv_gemm_uses_prepared(int64_t M, int d, int tile, int dtype)
 {
+    if (dtype == 1) return true;                           // bf16: one kernel for every problem size
     // Large problems: 256x256 tiles (highest reuse per LDS byte).  Problems with too few such
     // tiles to occupy the 256 compute units take 128x128 tiles.
     const int64_t big_tiles = ((M + 255) / 256) * ((2 * (int64_t)d + 255) / 256);
@@ -196,7 +197,7 @@ bool kv_gemm_uses_prepared(int64_t M, int d, int tile)
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    if (kv_gemm_uses_prepared(a.M, a.d, a.tile)) {
+    if (kv_gemm_uses_prepared(a.M, a.d, a.tile, a.dtype)) {
         if (!a.Wp || !a.cvec || !a.bvec) return hipErrorInvalidValue;
         return launch_kv_gemm_fold(a, s);                  // LayerNorm folded around the product
     }

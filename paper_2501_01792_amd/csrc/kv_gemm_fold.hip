@@ -35,6 +35,7 @@
 //     features (16 bytes) per store.  The next tile's first MFMAs start from a zero C operand instead
 //     of cleared accumulators.
 #include "hk_internal.h"
+#include "elem.h"
 #include "kv_gemm_common.h"
 
 #include <type_traits>
@@ -55,29 +56,30 @@ constexpr int kLoadsPerUnit = 8;                            // direct loads one 
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
+template <int DT>
 struct Frags {
-    half8_t a[FTM], b[FTN];
+    typename Elem<DT>::V8 a[FTM], b[FTN];
 };
 
 __device__ __forceinline__ int next2(int s) { s += 2; return s >= kSlots ? s - kSlots : s; }
 
 
-typedef float float4_t __attribute__((ext_vector_type(4)));
-
 // acc[i][j][r] is MFMA block (i, j), register r: tile row wrow0 + 16 i + 4 (lane / 16) + r, output feature
 // nb + j with nb = n0 + wcol0 + TN * (lane % 16): a lane holds TN = 8 consecutive features of every row.
-template <int TM, int TN>
+template <int DT, int TM, int TN>
 __device__ __forceinline__ void store_tile(const float4_t (&acc)[TM][TN], int lane, const RowDst *tab,
                                                   int wrow0, int nb, int d, int head_dim, int L_cap,
                                                   const float (&cn)[TN], const float (&bn)[TN],
-                                                  _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out)
+                                                  typename Elem<DT>::T *__restrict__ K_out, typename Elem<DT>::T *__restrict__ V_out)
 {
+    typedef typename Elem<DT>::T elem_t;
+    typedef typename Elem<DT>::V8 half8_t;
     static_assert(TN == 8, "one 16-byte store per row");
     if (nb >= 2 * d) return;
     const bool is_v = nb >= d;
     const int nn = is_v ? nb - d : nb;
     const int h = nn / head_dim, e = nn % head_dim;
-    _Float16 *dst_base = (is_v ? V_out : K_out) + ((int64_t)h * L_cap * head_dim + e);
+    elem_t *dst_base = (is_v ? V_out : K_out) + ((int64_t)h * L_cap * head_dim + e);
     const RowDst *my = tab + wrow0 + 4 * (lane >> 4);
     // groups of 4 consecutive rows (one block row); the table rows of the next group are fetched while the
     // current group is converted and stored
@@ -98,7 +100,7 @@ __device__ __forceinline__ void store_tile(const float4_t (&acc)[TM][TN], int la
             for (int j = 0; j < TN; ++j) {
                 float a;
                 asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));
-                v[j] = (_Float16)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
+                v[j] = (elem_t)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
             }
             if (row.base >= 0) __builtin_nontemporal_store(v, reinterpret_cast<half8_t *>(dst_base + row.base));
         }
@@ -106,15 +108,17 @@ __device__ __forceinline__ void store_tile(const float4_t (&acc)[TM][TN], int la
     }
 }
 
-template <int GROUP_M>
+template <int GROUP_M, int DT>
 __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
-    const _Float16 *__restrict__ act, const float2 *__restrict__ stats,
-    const _Float16 *__restrict__ Wp, const float *__restrict__ cvec, const float *__restrict__ bvec,
-    _Float16 *__restrict__ K_out, _Float16 *__restrict__ V_out,
+    const typename Elem<DT>::T *__restrict__ act, const float2 *__restrict__ stats,
+    const typename Elem<DT>::T *__restrict__ Wp, const float *__restrict__ cvec, const float *__restrict__ bvec,
+    typename Elem<DT>::T *__restrict__ K_out, typename Elem<DT>::T *__restrict__ V_out,
     int64_t M, int d, int n_heads, int head_dim, int L_act, int L_cap, int tok_off,
     int tiles_m, int tiles_n)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    typedef typename Elem<DT>::T elem_t;
+    typedef typename Elem<DT>::V8 half8_t;
 
     const int N = 2 * d;
     const int tid = threadIdx.x;
@@ -152,8 +156,8 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         int64_t a_bytes = (M - m0) * (int64_t)d * 2, b_bytes = ((int64_t)N - n0) * d * 2;
         if (a_bytes > 0x7fffffff) a_bytes = 0x7fffffff;        // a tile spans < 2^30 bytes
         if (b_bytes > 0x7fffffff) b_bytes = 0x7fffffff;
-        a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(act + m0 * (int64_t)d), 0, (int)a_bytes, 0x00020000);
-        b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(Wp + (int64_t)n0 * d), 0, (int)b_bytes, 0x00020000);
+        a_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<elem_t *>(act + m0 * (int64_t)d), 0, (int)a_bytes, 0x00020000);
+        b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<elem_t *>(Wp + (int64_t)n0 * d), 0, (int)b_bytes, 0x00020000);
         const int ra = (M - m0 < FBM) ? (int)(M - m0) - 1 : FBM - 1;
         const int rb = (N - n0 < FBN) ? (N - n0) - 1 : FBN - 1;
         a_vmax = (ra * d + l_chunk * 8) * 2;
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     const int b_rd_wave = wn * FWN * kRowBytes;
     // The reads of a sub-step in the order its MFMAs need them: a[0], b[0..7], a[1..7].
     // which = 0: a[0]; 1..8: b[which - 1]; 9..15: a[which - 8]
-    auto read_frag = [&](Frags &f, int sa, int sb, int ks, int which) {
+    auto read_frag = [&](Frags<DT> &f, int sa, int sb, int ks, int which) {
         if (which == 0 || which > 8) {
             const int i = which == 0 ? 0 : which - 8;
             f.a[i] = *reinterpret_cast<const half8_t *>(smem + sa * kUnitBytes + a_rd_wave + frag_off[ks] + i * (16 * kRowBytes));
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         }
     };
 
-    Frags f0, f1;
+    Frags<DT> f0, f1;
 
     // ---- prologue: k blocks 0 and 1 in flight (units 0..3 -> slots 0..3), block 0 landed, its first fragments read
     set_load_tile(0);
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         // ---- sub-step 0 (f0, k 0..31): fragments of sub-step 1 -> f1; activations of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
-            acc[q >> 3][q & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7], 0, 0, 0);
+            acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7]);
             if (q < 32 && (q & 1) == 0) read_frag(f1, sA, sB, 1, q >> 1);
             if ((q & 7) == 7) issue_a(sA2, q >> 3);
             __builtin_amdgcn_sched_barrier(0);
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         // ---- sub-step 1 (f1, k 32..63): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; weights of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
-            acc[q >> 3][q & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7], 0, 0, 0);
+            acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7]);
             if (q == 3) {
                 // Every LDS read of block g has been issued.  Wait for them and for this wavefront's loads
                 // of block g+1 (the 8 activation loads of block g+2 may fly), then meet the others: after
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
             RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
             tab[tid] = my_row;
             __syncthreads();
-            store_tile<FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
+            store_tile<DT, FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
             __syncthreads();                                   // the table's slot is about to be refilled
         }
     }
@@ -286,16 +290,18 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
 
 // One wavefront per output feature n: W'[n,:] = fp16(gamma * W[n,:]), c[n] = sum_k W'[n,k],
 // b'[n] = b[n] + sum_k beta_k W[n,k]  (sums in fp32).
-__global__ __launch_bounds__(256) void prepare_layer_kernel(const _Float16 *__restrict__ W,
-                                                            const _Float16 *__restrict__ bkv,
-                                                            const _Float16 *__restrict__ ln_w,
-                                                            const _Float16 *__restrict__ ln_b,
-                                                            _Float16 *__restrict__ Wp, float *__restrict__ cvec,
+template <int DT>
+__global__ __launch_bounds__(256) void prepare_layer_kernel(const typename Elem<DT>::T *__restrict__ W,
+                                                            const typename Elem<DT>::T *__restrict__ bkv,
+                                                            const typename Elem<DT>::T *__restrict__ ln_w,
+                                                            const typename Elem<DT>::T *__restrict__ ln_b,
+                                                            typename Elem<DT>::T *__restrict__ Wp, float *__restrict__ cvec,
                                                             float *__restrict__ bvec, int N, int d)
 {
     const int lane = threadIdx.x & 63;
     const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (n >= N) return;                                        // whole wavefront leaves together; no barrier here
+    typedef typename Elem<DT>::V8 half8_t;
     const half8_t *src = reinterpret_cast<const half8_t *>(W + (int64_t)n * d);
     half8_t *dst = reinterpret_cast<half8_t *>(Wp + (int64_t)n * d);
     const half8_t *g = reinterpret_cast<const half8_t *>(ln_w);
@@ -306,7 +312,7 @@ __global__ __launch_bounds__(256) void prepare_layer_kernel(const _Float16 *__re
         half8_t o;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            o[j] = (_Float16)((float)w[j] * (float)gv[j]);
+            o[j] = (typename Elem<DT>::T)((float)w[j] * (float)gv[j]);
             c += (float)o[j];
             bb = __builtin_fmaf((float)bv[j], (float)w[j], bb);
         }
@@ -323,17 +329,42 @@ __global__ __launch_bounds__(256) void prepare_layer_kernel(const _Float16 *__re
     }
 }
 
+template <int DT>
+hipError_t prepare_dt(const void *Wkv, const void *bkv, const void *ln_w, const void *ln_b,
+                      void *Wp, float *cvec, float *bvec, int d, hipStream_t s)
+{
+    typedef typename Elem<DT>::T elem_t;
+    const int N = 2 * d;
+    hipLaunchKernelGGL(prepare_layer_kernel<DT>, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s,
+                       static_cast<const elem_t *>(Wkv), static_cast<const elem_t *>(bkv),
+                       static_cast<const elem_t *>(ln_w), static_cast<const elem_t *>(ln_b),
+                       static_cast<elem_t *>(Wp), cvec, bvec, N, d);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t fold_dt(const KvGemmArgs &a, int grid, int tiles_m, int tiles_n, hipStream_t s)
+{
+    typedef typename Elem<DT>::T elem_t;
+    auto kern = kv_gemm_fold_kernel<4, DT>;
+    static_assert(kRingBytes == 160 * 1024, "the ring uses the whole 160 KiB LDS of a CU");
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FNT), kRingBytes, s,
+                       static_cast<const elem_t *>(a.act), a.stats,
+                       static_cast<const elem_t *>(a.Wp), a.cvec, a.bvec,
+                       static_cast<elem_t *>(a.K_out), static_cast<elem_t *>(a.V_out),
+                       a.M, a.d, a.n_heads, a.head_dim, a.L_act, a.L_cap, a.tok_off, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_prepare_layer(const void *Wkv, const void *bkv, const void *ln_w, const void *ln_b,
-                                void *Wp, float *cvec, float *bvec, int d, hipStream_t s)
+                                void *Wp, float *cvec, float *bvec, int d, hipStream_t s, int dtype)
 {
-    const int N = 2 * d;
-    hipLaunchKernelGGL(prepare_layer_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s,
-                       static_cast<const _Float16 *>(Wkv), static_cast<const _Float16 *>(bkv),
-                       static_cast<const _Float16 *>(ln_w), static_cast<const _Float16 *>(ln_b),
-                       static_cast<_Float16 *>(Wp), cvec, bvec, N, d);
-    return hipGetLastError();
+    return dtype == 1 ? prepare_dt<1>(Wkv, bkv, ln_w, ln_b, Wp, cvec, bvec, d, s)
+                      : prepare_dt<0>(Wkv, bkv, ln_w, ln_b, Wp, cvec, bvec, d, s);
 }
 
 hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s)
@@ -349,16 +380,7 @@ hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s)
     if (e != hipSuccess) return e;
     if (cus <= 0) return hipErrorInvalidValue;
     const int grid = n_tiles < cus ? n_tiles : cus;            // one resident workgroup per compute unit
-    auto kern = kv_gemm_fold_kernel<4>;
-    static_assert(kRingBytes == 160 * 1024, "the ring uses the whole 160 KiB LDS of a CU");
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FNT), kRingBytes, s,
-                       static_cast<const _Float16 *>(a.act), a.stats,
-                       static_cast<const _Float16 *>(a.Wp), a.cvec, a.bvec,
-                       static_cast<_Float16 *>(a.K_out), static_cast<_Float16 *>(a.V_out),
-                       a.M, a.d, a.n_heads, a.head_dim, a.L_act, a.L_cap, a.tok_off, tiles_m, tiles_n);
-    return hipGetLastError();
+    return a.dtype == 1 ? fold_dt<1>(a, grid, tiles_m, tiles_n, s) : fold_dt<0>(a, grid, tiles_m, tiles_n, s);
 }
 
 }  // namespace hk

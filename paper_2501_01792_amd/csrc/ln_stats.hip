@@ -7,12 +7,10 @@
 // Mean and variance are taken in two passes over the row (over a register copy of the row when it
 // fits, else over memory, where the second pass hits L2), both summed in fp32 with wavefront shuffles.
 #include "hk_internal.h"
-#include <hip/hip_fp16.h>
+#include "elem.h"
 
 namespace hk {
 namespace {
-
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -26,21 +24,24 @@ constexpr int kMaxVec = 20;        // rows of up to 64 * 8 * 20 = 10240 elements
 
 // Rows that fit in registers are read from memory once: 16-byte loads, all issued before the first
 // use, then mean and centred sum of squares from the register copy.
-template <int NV>
-__global__ __launch_bounds__(256) void ln_stats_reg_kernel(const _Float16 *__restrict__ act,
+template <int DT, int NV>
+__global__ __launch_bounds__(256) void ln_stats_reg_kernel(const typename Elem<DT>::T *__restrict__ act,
                                                            float2 *__restrict__ stats,
                                                            int64_t M, int d, float eps)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     if (row >= M) return;   // whole wavefront leaves together; no barrier in this kernel
+    typedef typename Elem<DT>::V8 half8_t;
     const half8_t *p = reinterpret_cast<const half8_t *>(act + row * (int64_t)d);
     const int nvec = d >> 3;   // host guarantees d % 8 == 0
     half8_t v[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int idx = lane + 64 * i;
-        half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+        half8_t z;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) z[j] = (typename Elem<DT>::T)0.f;
         v[i] = idx < nvec ? p[idx] : z;
     }
     float s = 0.f;
@@ -66,13 +67,15 @@ __global__ __launch_bounds__(256) void ln_stats_reg_kernel(const _Float16 *__res
 }
 
 // Any row length: two passes over memory (the second one hits L2).
-__global__ __launch_bounds__(256) void ln_stats_kernel(const _Float16 *__restrict__ act,
+template <int DT>
+__global__ __launch_bounds__(256) void ln_stats_kernel(const typename Elem<DT>::T *__restrict__ act,
                                                        float2 *__restrict__ stats,
                                                        int64_t M, int d, float eps)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
     if (row >= M) return;   // whole wavefront leaves together; no barrier in this kernel
+    typedef typename Elem<DT>::V8 half8_t;
     const half8_t *p = reinterpret_cast<const half8_t *>(act + row * (int64_t)d);
     const int nvec = d >> 3;
 
@@ -98,21 +101,27 @@ __global__ __launch_bounds__(256) void ln_stats_kernel(const _Float16 *__restric
     if (lane == 0) stats[row] = make_float2(rstd, -mean * rstd);
 }
 
-}  // namespace
-
-hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s)
+template <int DT>
+hipError_t launch_dt(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s)
 {
-    if (M <= 0) return hipSuccess;
     const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
-    const _Float16 *a = static_cast<const _Float16 *>(act);
+    const typename Elem<DT>::T *a = static_cast<const typename Elem<DT>::T *>(act);
     const int nv = (d / 8 + 63) / 64;          // 16-byte chunks per lane
     const dim3 grid((unsigned)blocks), block(256);
-    if (nv <= 4) hipLaunchKernelGGL(ln_stats_reg_kernel<4>, grid, block, 0, s, a, stats, M, d, eps);
-    else if (nv <= 8) hipLaunchKernelGGL(ln_stats_reg_kernel<8>, grid, block, 0, s, a, stats, M, d, eps);
-    else if (nv <= 12) hipLaunchKernelGGL(ln_stats_reg_kernel<12>, grid, block, 0, s, a, stats, M, d, eps);
-    else if (nv <= kMaxVec) hipLaunchKernelGGL(ln_stats_reg_kernel<kMaxVec>, grid, block, 0, s, a, stats, M, d, eps);
-    else hipLaunchKernelGGL(ln_stats_kernel, grid, block, 0, s, a, stats, M, d, eps);
+    if (nv <= 4) hipLaunchKernelGGL((ln_stats_reg_kernel<DT, 4>), grid, block, 0, s, a, stats, M, d, eps);
+    else if (nv <= 8) hipLaunchKernelGGL((ln_stats_reg_kernel<DT, 8>), grid, block, 0, s, a, stats, M, d, eps);
+    else if (nv <= 12) hipLaunchKernelGGL((ln_stats_reg_kernel<DT, 12>), grid, block, 0, s, a, stats, M, d, eps);
+    else if (nv <= kMaxVec) hipLaunchKernelGGL((ln_stats_reg_kernel<DT, kMaxVec>), grid, block, 0, s, a, stats, M, d, eps);
+    else hipLaunchKernelGGL(ln_stats_kernel<DT>, grid, block, 0, s, a, stats, M, d, eps);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ln_stats(const void *act, float2 *stats, int64_t M, int d, float eps, hipStream_t s, int dtype)
+{
+    if (M <= 0) return hipSuccess;
+    return dtype == 1 ? launch_dt<1>(act, stats, M, d, eps, s) : launch_dt<0>(act, stats, M, d, eps, s);
 }
 
 }  // namespace hk

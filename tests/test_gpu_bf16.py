@@ -1,0 +1,109 @@
+"""GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn with HK_DTYPE_BF16)
+against the CPU oracle fed with the same bf16-rounded inputs.
+
+The benchmark's tolerance is stated for fp16.  A bf16 value carries 8 significant bits, so the output
+rounding alone is up to 2^-8 of the value (fp16: 2^-11), and the prepared weights gamma * W are rounded
+to bf16 as well.  The bar here, derived from that: max abs error <= 2^-7 * max |reference| (twice the
+half-ulp of the largest value, for output rounding plus the rounding noise of the weights), relative L2
+error <= 5e-3 as for fp16 (expected ~3e-3: 2^-8 / sqrt 3 from each of the two roundings).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_01792_amd import synth
+from test_gpu_parity import SMALL, _oracle_hybrid, hk  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 5e-3
+
+
+def _bf16(x):
+    """numpy array -> (bf16 GPU tensor, the same values as float64 on the host)."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.cuda(), t.float().numpy().astype(np.float64)
+
+
+def _check(name, got, ref):
+    got = got.float().cpu().numpy().astype(np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.isfinite(got).all(), name + ": non-finite values"
+    max_abs = np.abs(got - ref).max() if got.size else 0.0
+    bound = 2.0 ** -7 * max(np.abs(ref).max(), 1e-30) if got.size else 0.0
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30) if got.size else 0.0
+    print("%s: max_abs=%.3e (bound %.3e) rel_l2=%.3e" % (name, max_abs, bound, rel), flush=True)
+    assert max_abs <= bound, "%s: max abs error %.3e > %.3e" % (name, max_abs, bound)
+    assert rel <= REL_L2, "%s: relative L2 error %.3e" % (name, rel)
+
+
+def _inputs(cfg):
+    batch = synth.make_batch(cfg)
+    g, h = {}, {}
+    for k, v in batch.items():
+        g[k], h[k] = _bf16(v)
+    return g, h
+
+
+@pytest.mark.parametrize("prepared", [False, True])
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_bf16_hybrid_step_matches_oracle(hk, oracle, cfg, prepared):
+    print("case", cfg, "prepared", prepared, flush=True)
+    g, h = _inputs(cfg)
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    if prepared:
+        lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    out, K, V = hk.hybrid_decode_attn(g["q"], g["K_cache"] if cfg.L_kv else None, g["V_cache"] if cfg.L_kv else None,
+                                      g["act"] if cfg.L_act else None, lp, cfg.ratio, return_regen=True)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16 and K.dtype == torch.bfloat16
+    ref_out, ref_K, ref_V = _oracle_hybrid(oracle, cfg, h)
+    if cfg.L_act:
+        _check("K_regen", K, ref_K[:, :, cfg.L_kv:])
+        _check("V_regen", V, ref_V[:, :, cfg.L_kv:])
+    _check("out", out, ref_out)
+
+
+def test_bf16_regen_into_cache_slot(hk, oracle):
+    """hk_regen_kv in bf16 writes rows tok_off .. tok_off + L_act of a larger cache and nothing else."""
+    cfg = SMALL[2]
+    g, h = _inputs(cfg)
+    B, H, dh, L_act = cfg.B, cfg.n_heads, cfg.head_dim, cfg.L_act
+    L_cap, off = L_act + 7, 3
+    K = torch.full((B, H, L_cap, dh), 5.0, dtype=torch.bfloat16, device="cuda")
+    V = torch.full((B, H, L_cap, dh), -5.0, dtype=torch.bfloat16, device="cuda")
+    hk.regen_kv(g["act"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], H, K_out=K, V_out=V, tok_off=off)
+    torch.cuda.synchronize()
+    xh = oracle.layernorm(h["act"].reshape(-1, cfg.d), h["ln_w"], h["ln_b"])
+    kv = oracle.kv_projection(xh, h["Wkv"], h["bkv"]).reshape(B, L_act, 2, H, dh)
+    _check("K rows", K[:, :, off:off + L_act], kv[:, :, 0].transpose(0, 2, 1, 3))
+    _check("V rows", V[:, :, off:off + L_act], kv[:, :, 1].transpose(0, 2, 1, 3))
+    keep = np.ones(L_cap, bool); keep[off:off + L_act] = False
+    assert (K[:, :, keep].float() == 5.0).all() and (V[:, :, keep].float() == -5.0).all()
+
+
+def test_bf16_full_size_opt6p7b_sampled(hk, oracle):
+    """The benchmark's workload in bf16: sampled K/V rows and sampled (sequence, head) outputs."""
+    cfg = synth.CONFIGS["opt6.7b"]
+    g, h = _inputs(cfg)
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    out, K, V = hk.hybrid_decode_attn(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio, return_regen=True)
+    torch.cuda.synchronize()
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
+    rng = np.random.default_rng(9)
+    rows = [(int(rng.integers(cfg.B)), int(rng.integers(cfg.L_act))) for _ in range(32)] + [(0, 0), (cfg.B - 1, cfg.L_act - 1)]
+    xh = oracle.layernorm(np.stack([h["act"][b, t] for b, t in rows]), h["ln_w"], h["ln_b"])
+    kv = oracle.kv_projection(xh, h["Wkv"], h["bkv"])
+    _check("K_regen[sampled rows]", torch.stack([K[b, :, t, :].reshape(d) for b, t in rows]), kv[:, :d])
+    _check("V_regen[sampled rows]", torch.stack([V[b, :, t, :].reshape(d) for b, t in rows]), kv[:, d:])
+    got, ref = [], []
+    for b, hd in [(int(rng.integers(cfg.B)), int(rng.integers(H))) for _ in range(3)] + [(cfg.B - 1, H - 1)]:
+        xh = oracle.layernorm(h["act"][b], h["ln_w"], h["ln_b"])
+        sel = np.r_[hd * dh:(hd + 1) * dh, d + hd * dh:d + (hd + 1) * dh]
+        kvh = oracle.kv_projection(xh, h["Wkv"][sel], h["bkv"][sel])
+        Kb = np.concatenate([h["K_cache"][b, hd], kvh[:, :dh]], axis=0)
+        Vb = np.concatenate([h["V_cache"][b, hd], kvh[:, dh:]], axis=0)
+        ref.append(oracle.decode_attention(h["q"][b:b + 1, hd:hd + 1], Kb[None, None], Vb[None, None])[0, 0])
+        got.append(out[b, hd])
+    _check("out[sampled (b,h)]", torch.stack(got), np.stack(ref))
