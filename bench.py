@@ -179,6 +179,9 @@ def main():
     ap.add_argument("--attn-splits", type=int, default=0)
     ap.add_argument("--dtype", choices=["f16", "bf16"], default="f16",
                     help="bf16: the same step on bf16-rounded inputs (comparison; no CPU sample, no variants)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (the library allocates nothing and never synchronises, "
+                         "so a caller can capture it); reported as graph_replay_ms_per_step, not as the benchmark's value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true", help="skip the comparison variants timed after the bench line's region")
     ap.add_argument("--absorbed", action="store_true",
@@ -345,6 +348,27 @@ def main():
     result["mfma_rate_probe_tflops"] = {"zero_operands": hk.probe_mfma_rate(False), "random_operands": hk.probe_mfma_rate(True)}
     if roofline.get("bound") == "mfma":
         roofline["frac_of_probe_random"] = roofline["achieved"] / result["mfma_rate_probe_tflops"]["random_operands"]
+
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):                           # kernel attributes are set on first use: warm up before capture
+            hk.hybrid_decode_attn(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=side,
+                                  attn_splits=args.attn_splits, gemm_tile=args.gemm_tile)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            hk.hybrid_decode_attn(g["q"], Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws, stream=torch.cuda.current_stream(),
+                                  attn_splits=args.attn_splits, gemm_tile=args.gemm_tile)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
 
     if not args.no_variants:
         # Comparison point beyond the paper (not part of `value`): the same step without regenerating K/V,
