@@ -241,7 +241,10 @@ FULL = [
     synth.CONFIGS["opt13b"],
     synth.CONFIGS["opt30b"],
     synth.CONFIGS["opt66b"],
-] + [synth.CONFIGS["opt66b"].with_ratio(r) for r in (0.25, 0.5, 0.75, 1.0)]
+] + [synth.CONFIGS["opt66b"].with_ratio(r) for r in (0.25, 0.5, 0.75, 1.0)] + [
+    _cfg("dh64_big", 2048, 32, 16, 2048, 0.5, 31),        # head_dim 64 through the 256-tile kernel and 4096 attention wavefronts
+    _cfg("one_long_sequence", 1024, 8, 1, 40000, 0.9, 32),  # 8 (sequence, head) pairs only: every pair is cut over ~500 wavefronts
+]
 
 
 @pytest.mark.parametrize("cfg", FULL, ids=lambda c: "%s-B%d" % (c.name, c.B))
