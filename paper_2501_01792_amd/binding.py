@@ -103,6 +103,10 @@ def lib():
         L.hk_paged_decode_attn.restype = ctypes.c_int
         L.hk_paged_decode_attn.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_paged_cache),
                                            ctypes.POINTER(hk_layer_params), vp, vp, sz, vp]
+        L.hk_paged_absorbed_workspace_bytes.restype = sz
+        L.hk_paged_absorbed_workspace_bytes.argtypes = L.hk_paged_workspace_bytes.argtypes
+        L.hk_paged_decode_attn_absorbed.restype = ctypes.c_int
+        L.hk_paged_decode_attn_absorbed.argtypes = L.hk_paged_decode_attn.argtypes
         dp = ctypes.POINTER(ctypes.c_double)
         L.hk_fit_line.restype = ctypes.c_int
         L.hk_fit_line.argtypes = [dp, dp, i32, ctypes.POINTER(hk_line), dp]
@@ -392,9 +396,11 @@ def make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu_tokens, 
 
 
 def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_tokens, layer_params,
-                      n_act_used=None, out=None, ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None):
+                      n_act_used=None, out=None, ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None,
+                      absorbed=False):
     """hk_paged_decode_attn: ``q[B,H,dh]``, pools, ``block_table[B,max_blocks]`` int32, ``seq_len[B]`` int32 (GPU
-    tensors) -> ``out[B,H,dh]``.  The prefix sums and the host-side total are derived here from ``seq_len``."""
+    tensors) -> ``out[B,H,dh]``.  The prefix sums and the host-side total are derived here from ``seq_len``.
+    ``absorbed`` selects hk_paged_decode_attn_absorbed (the same step without regenerating K/V)."""
     import torch
     B, H, dh = q.shape
     shape = make_shape(H * dh, H, ln_eps, softmax_scale)
@@ -404,12 +410,14 @@ def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_t
     cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used)
     if out is None:
         out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+    size_fn = lib().hk_paged_absorbed_workspace_bytes if absorbed else lib().hk_paged_workspace_bytes
+    entry = lib().hk_paged_decode_attn_absorbed if absorbed else lib().hk_paged_decode_attn
     if workspace is None:
-        workspace = new_workspace(int(lib().hk_paged_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))), q.device)
+        workspace = new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))), q.device)
     lp = _params(*layer_params) if layer_params is not None else None
-    st = lib().hk_paged_decode_attn(ctypes.byref(shape), _dev_ptr(q, "q", torch.float16), B, ctypes.byref(cache),
+    st = entry(ctypes.byref(shape), _dev_ptr(q, "q", torch.float16), B, ctypes.byref(cache),
                                     ctypes.byref(lp) if lp is not None else None, _dev_ptr(out, "out", torch.float16),
                                     _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
     if st != HK_OK:
-        raise HybridKVError(st, "hk_paged_decode_attn")
+        raise HybridKVError(st, "hk_paged_decode_attn_absorbed" if absorbed else "hk_paged_decode_attn")
     return out

@@ -66,6 +66,11 @@ struct ColArgs {
     const _Float16 *A; int64_t a_batch, ld_a; int a_rows;
     _Float16 *Out; int64_t o_batch, ld_out;
     const float *shift; int64_t shift_batch; int shift_stride;   // optional: Out[z][m][:] -= shift[z shift_batch + m shift_stride]
+    // optional, for rows that live in blocks of 2^blk_log2 (>= 16) rows scattered over a pool: row r of batch z is
+    // row r % block of pool block blk_list[z list_pitch + r / block] (S then points at the pool, s_batch = 0), and
+    // batch z has R_list[z] rows (0: the output rows of z are zero)
+    const int32_t *blk_list; int list_pitch, blk_log2;
+    const int32_t *R_list;
 };
 
 constexpr int kColBlock = 64;                              // columns of one wavefront
@@ -89,7 +94,8 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     const int64_t z = blockIdx.y;
     const _Float16 *S = p.S + z * p.s_batch + c0;
     const _Float16 *A = p.A + z * p.a_batch;
-    const int steps = (p.R + 15) / 16;
+    const int R = p.R_list ? p.R_list[z] : p.R;            // uniform over the workgroup
+    const int steps = (R + 15) / 16;
     const int tiles = (steps + 3) / 4;
 
     // one load instruction: 8 rows x 128 bytes, 8 lanes per row
@@ -126,11 +132,19 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     const int last = steps - 1, last_tile = tiles - 1;
     auto clamp = [&](int sc) { return sc < last ? sc : last; };
     auto load_s = [&](int slot, int sc) {
+        // the 16 rows of a step share a block; its number comes through a scalar load (sc and z are uniform), which
+        // does not wait for the vector loads in flight
+        const int r0 = 16 * sc;
+        int64_t first = r0;
+        if (p.blk_list) {
+            const int32_t bid = p.blk_list[z * p.list_pitch + (r0 >> p.blk_log2)];
+            first = ((int64_t)bid << p.blk_log2) + (r0 & ((1 << p.blk_log2) - 1));
+        }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            int r = 16 * sc + 8 * j + g_row;
-            if (r >= p.R) r = p.R - 1;                     // rows past the end meet zeros of A
-            sv[slot][j] = *reinterpret_cast<const half8_t *>(S + (int64_t)r * p.ld_s + 8 * g_chunk);
+            int rr = 8 * j + g_row;
+            if (r0 + rr >= R) rr = R - 1 - r0;             // rows past the end meet zeros of A; r0 < R for every step asked for
+            sv[slot][j] = *reinterpret_cast<const half8_t *>(S + (first + rr) * p.ld_s + 8 * g_chunk);
         }
     };
     auto load_a = [&](int slot, int g) {
@@ -143,6 +157,16 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
         for (int rb = 0; rb < RB; ++rb)
             *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kTileBytes + t_wr) = av[slot][rb];
     };
+    if (R <= 0) {                                          // nothing to sum (uniform over the workgroup: no barrier is missed)
+        if (live) {
+            _Float16 *Out0 = p.Out + z * p.o_batch + c0;
+            half8_t zero8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) zero8[i] = (_Float16)0.f;
+            for (int m = g_row; m < p.a_rows; m += 8) *reinterpret_cast<half8_t *>(Out0 + (int64_t)m * p.ld_out + 8 * g_chunk) = zero8;
+        }
+        return;
+    }
     // Every load of the loop is unconditional (steps and tiles past the end re-read the last one), so that
     // the number of loads in flight at each wait is a compile-time fact.
     load_a(0, 0);
@@ -330,12 +354,14 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
                                                                const float *__restrict__ raw, const float4 *__restrict__ stats,
                                                                const float *__restrict__ cvec, const float *__restrict__ bvec,
                                                                _Float16 *__restrict__ w, float4 *__restrict__ sums,
-                                                               int B, int H, int head_dim, int L_act, int Lp, float sl)
+                                                               int B, int H, int head_dim, int L_all, int Lp, float sl,
+                                                               const int32_t *__restrict__ n_rows, int stats_pitch)
 {
     const int lane = threadIdx.x & 63;
     const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= B * H) return;                               // whole wavefront leaves together; no barrier in this kernel
     const int b = bh / H, h = bh % H;
+    const int L_act = n_rows ? n_rows[b] : L_all;          // sequences may have their own numbers of rows (0: no weight at all)
     float c1 = 0.f, c2 = 0.f;
     for (int e = lane; e < head_dim; e += 64) {
         const float qe = (float)q[(int64_t)bh * head_dim + e];
@@ -345,7 +371,7 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     c1 = wave_sum(c1);
     c2 = wave_sum(c2);
     const float *r = raw + (int64_t)bh * Lp;
-    const float4 *st = stats + (int64_t)b * L_act;
+    const float4 *st = stats + (int64_t)b * stats_pitch;
     auto score = [&](int t) {
         const float4 s4 = st[t];
         return sl * (__builtin_fmaf(s4.x, r[t], __builtin_fmaf(s4.z, c1, c2)));
@@ -356,7 +382,7 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     float l = 0.f;
     for (int t = lane; t < L_act; t += 64) l += __builtin_amdgcn_exp2f(score(t) - mx);
     l = wave_sum(l);
-    const float inv = 1.0f / l;
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
     _Float16 *wr = w + (int64_t)bh * Lp;
     float mu = 0.f;
     for (int t = lane; t < Lp; t += 64) {
@@ -397,12 +423,16 @@ __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *_
         const float4 sa = sums[bh];
         float o = (red[0][b][c] + red[1][b][c]) + (red[2][b][c] + red[3][b][c]);
         o += bv[n];
+        // join of the two segments; a segment without tokens has denominator 0 and drops out, both empty: zero
+        float m = sa.x, wc = 0.f, oc = 0.f;
         if (lse_c) {
             const float2 sc = lse_c[bh];
-            const float m = fmaxf(sc.x, sa.x);
-            const float wc = sc.y * __builtin_amdgcn_exp2f(sc.x - m), wa = sa.y * __builtin_amdgcn_exp2f(sa.x - m);
-            o = (wc * (float)out_c[bh * head_dim + (n - h * head_dim)] + wa * o) / (wc + wa);
+            m = fmaxf(sc.x, sa.x);
+            wc = sc.y * __builtin_amdgcn_exp2f(sc.x - m);
+            oc = (float)out_c[bh * head_dim + (n - h * head_dim)];
         }
+        const float wa = sa.y * __builtin_amdgcn_exp2f(sa.x - m);
+        o = wc + wa > 0.f ? (wc * oc + wa * o) / (wc + wa) : 0.f;
         out[bh * head_dim + (n - h * head_dim)] = (_Float16)o;
     }
 }
@@ -447,14 +477,19 @@ hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
 
 int absorbed_row_pitch(int L_act) { return (L_act + 63) / 64 * 64; }
 
-hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
+namespace {
+
+// What the steps of the checkpoint part need beyond AbsorbedArgs when the rows live in pool blocks.
+struct PagedRows {
+    const int32_t *blk_list;   // [B, list_pitch]: the checkpoint blocks of every request, in logical order
+    const int32_t *n_rows;     // [B]: checkpoint rows of every request
+    int list_pitch, blk_log2;
+};
+
+hipError_t launch_carry(const AbsorbedArgs &a, hipStream_t s)
 {
-    if (a.B <= 0 || a.L_act <= 0) return hipSuccess;
-    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
-    const int Lp = absorbed_row_pitch(a.L_act);
     const int64_t d = a.d;
-    hipError_t e;
-    // carry the queries through the key weights, at most kAbsorbMaxBatch sequences per launch
+    // the queries through the key weights, at most kAbsorbMaxBatch sequences per launch
     for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {
         const int Bc = a.B - b0 < kAbsorbMaxBatch ? a.B - b0 : kAbsorbMaxBatch;
         ColArgs c;
@@ -462,27 +497,33 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
         c.A = static_cast<const _Float16 *>(a.q) + b0 * d; c.a_batch = a.head_dim; c.ld_a = d; c.a_rows = Bc;
         c.Out = static_cast<_Float16 *>(a.U) + b0 * d; c.o_batch = a.B * d; c.ld_out = d;
         c.shift = nullptr; c.shift_batch = 0; c.shift_stride = 0;
-        if ((e = launch_column_product(c, a.H, s)) != hipSuccess) return e;
+        c.blk_list = nullptr; c.list_pitch = 0; c.blk_log2 = 0; c.R_list = nullptr;
+        const hipError_t e = launch_column_product(c, a.H, s);
+        if (e != hipSuccess) return e;
     }
-    switch ((a.H + 31) / 32) {
-    case 1: e = launch_scores<1>(a, Lp, s); break;
-    case 2: e = launch_scores<2>(a, Lp, s); break;
-    case 3: e = launch_scores<3>(a, Lp, s); break;
-    default: e = launch_scores<4>(a, Lp, s); break;
-    }
-    if (e != hipSuccess) return e;
+    return hipSuccess;
+}
+
+// softmax, weighted row sum, output projection and join; pr == nullptr: a.L_act contiguous rows per sequence
+hipError_t launch_after_scores(const AbsorbedArgs &a, int Lp, const PagedRows *pr, hipStream_t s)
+{
+    const int64_t d = a.d;
+    hipError_t e;
     const int64_t BH = (int64_t)a.B * a.H;
     hipLaunchKernelGGL(absorbed_softmax_kernel, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
                        static_cast<const _Float16 *>(a.q), a.w_raw, a.stats, a.cvec, a.bvec,
                        static_cast<_Float16 *>(a.w), a.sums, a.B, a.H, a.head_dim, a.L_act, Lp,
-                       a.scale * 1.4426950408889634f);
+                       a.scale * 1.4426950408889634f, pr ? pr->n_rows : static_cast<const int32_t *>(nullptr),
+                       pr ? Lp : a.L_act);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     {
         ColArgs c;
-        c.S = static_cast<const _Float16 *>(a.act); c.s_batch = (int64_t)a.L_act * d; c.ld_s = d; c.R = a.L_act; c.n_cols = a.d;
+        c.S = static_cast<const _Float16 *>(a.act); c.s_batch = pr ? 0 : (int64_t)a.L_act * d; c.ld_s = d; c.R = a.L_act; c.n_cols = a.d;
         c.A = static_cast<const _Float16 *>(a.w); c.a_batch = (int64_t)a.H * Lp; c.ld_a = Lp; c.a_rows = a.H;
         c.Out = static_cast<_Float16 *>(a.Y); c.o_batch = a.H * d; c.ld_out = d;
         c.shift = &a.sums[0].z; c.shift_batch = 4 * (int64_t)a.H; c.shift_stride = 4;
+        c.blk_list = pr ? pr->blk_list : nullptr; c.list_pitch = pr ? pr->list_pitch : 0; c.blk_log2 = pr ? pr->blk_log2 : 0;
+        c.R_list = pr ? pr->n_rows : nullptr;
         if ((e = launch_column_product(c, a.B, s)) != hipSuccess) return e;
     }
     for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {
@@ -496,6 +537,149 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Paged cache (Sec. 4.1, 4.2.1): the checkpoint rows of a request sit in blocks of the activation pool named by
+// its row of the block table (entries < 0: checkpoint block ~entry).
+//
+// index: one wavefront per request walks its table row and leaves the request's checkpoint blocks in logical
+// order (list), their count, the rows of the last of them (only a request's final block can be partly filled)
+// and the request's number of checkpoint rows.  Blocks outside the pool prefix in use are left out.
+__global__ __launch_bounds__(256) void paged_act_index_kernel(const int32_t *__restrict__ table, int max_blocks,
+                                                              const int32_t *__restrict__ seq_len, int blk_log2, int n_act_used, int B,
+                                                              int32_t *__restrict__ list, int32_t *__restrict__ count,
+                                                              int32_t *__restrict__ last_rows, int32_t *__restrict__ n_rows)
+{
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= B) return;                                    // whole wavefront leaves together; no barrier in this kernel
+    const int bt = 1 << blk_log2;
+    const int len = seq_len[b];
+    int nb = len > 0 ? (len + bt - 1) >> blk_log2 : 0;
+    if (nb > max_blocks) nb = max_blocks;
+    int k0 = 0, last_i = -1;
+    for (int base = 0; base < nb; base += 64) {
+        const int i = base + lane;
+        const int32_t e = i < nb ? table[(int64_t)b * max_blocks + i] : 0;
+        const bool is = i < nb && e < 0 && ~e < n_act_used;
+        const unsigned long long mask = __ballot(is);
+        if (is) list[(int64_t)b * max_blocks + k0 + __popcll(mask & ((1ull << lane) - 1ull))] = ~e;
+        k0 += __popcll(mask);
+        if (mask) last_i = base + 63 - __builtin_clzll(mask);
+    }
+    if (lane == 0) {
+        int lr = bt;
+        if (last_i >= 0) { const int rest = len - (last_i << blk_log2); lr = rest < bt ? rest : bt; }
+        count[b] = k0;
+        last_rows[b] = lr;
+        n_rows[b] = k0 > 0 ? ((k0 - 1) << blk_log2) + lr : 0;
+    }
+}
+
+// scores of one slab (min(32, block) rows) of one checkpoint block of one request, as absorbed_scores_kernel;
+// rows are numbered inside the request in the order of its block list (raw, stats: pitch Lp per request).
+template <int RB>
+__global__ __launch_bounds__(256) void paged_scores_kernel(const _Float16 *__restrict__ act_pool, const _Float16 *__restrict__ U,
+                                                           float *__restrict__ raw, float4 *__restrict__ stats,
+                                                           const int32_t *__restrict__ list, const int32_t *__restrict__ count,
+                                                           const int32_t *__restrict__ last_rows,
+                                                           int B, int max_blocks, int blk_log2, int slab, int Lp, int H, int d, float eps)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int bt = 1 << blk_log2;
+    const int subs = bt / slab;
+    const int64_t per_b = (int64_t)max_blocks * subs;
+    const int item = gemm::xcd_regroup(blockIdx.x, (int)(per_b * B));
+    const int64_t b = item / per_b;
+    const int k = (int)((item % per_b) / subs), sub = (int)(item % subs);
+    const int cnt = count[b];
+    if (k >= cnt) return;                                  // uniform over the workgroup, before any barrier
+    const int valid = k == cnt - 1 ? last_rows[b] : bt;
+    const int rows = valid - slab * sub < slab ? valid - slab * sub : slab;
+    if (rows <= 0) return;
+    const int64_t blk = list[b * max_blocks + k];
+    const _Float16 *S = act_pool + ((blk << blk_log2) + slab * sub) * d;
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false, true>(S, rows, d, U + b * d, H, (int64_t)B * d, d, smem);
+    const int r0 = (k << blk_log2) + slab * sub;           // first row's number inside the request
+    for (int idx = tid; idx < H * skinny::kSlab; idx += 256) {
+        const int h = idx / skinny::kSlab, c = idx % skinny::kSlab;
+        if (c < rows)
+            raw[(b * H + h) * Lp + r0 + c] = (red[0][h][c] + red[1][h][c]) + (red[2][h][c] + red[3][h][c]);
+    }
+    if (tid < rows) {
+        float (*mom)[skinny::kSlab][2] = skinny::moments<RB>(smem);
+        const float s1 = (mom[0][tid][0] + mom[1][tid][0]) + (mom[2][tid][0] + mom[3][tid][0]);
+        const float s2 = (mom[0][tid][1] + mom[1][tid][1]) + (mom[2][tid][1] + mom[3][tid][1]);
+        stats[b * Lp + r0 + tid] = row_stats(s1, s2, (float)S[(int64_t)tid * d], d, eps);
+    }
+}
+
+template <int RB>
+hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2, hipStream_t s)
+{
+    const AbsorbedArgs &a = p.abs;
+    const int slab = p.block_tokens < skinny::kSlab ? p.block_tokens : skinny::kSlab;
+    const int64_t items = (int64_t)a.B * p.max_blocks * (p.block_tokens / slab);
+    if (items <= 0) return hipSuccess;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    auto kern = paged_scores_kernel<RB>;
+    constexpr int lds = skinny::lds_bytes<RB>() + skinny::kMomentBytes;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
+                       static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,
+                       p.list, p.count, p.last_rows, a.B, p.max_blocks, blk_log2, slab, Lp, a.H, a.d, a.eps);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
+{
+    if (a.B <= 0 || a.L_act <= 0) return hipSuccess;
+    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
+    const int Lp = absorbed_row_pitch(a.L_act);
+    hipError_t e = launch_carry(a, s);
+    if (e != hipSuccess) return e;
+    switch ((a.H + 31) / 32) {
+    case 1: e = launch_scores<1>(a, Lp, s); break;
+    case 2: e = launch_scores<2>(a, Lp, s); break;
+    case 3: e = launch_scores<3>(a, Lp, s); break;
+    default: e = launch_scores<4>(a, Lp, s); break;
+    }
+    if (e != hipSuccess) return e;
+    return launch_after_scores(a, Lp, nullptr, s);
+}
+
+// a.abs: act = the activation pool, L_act = max_blocks * block_tokens (the most rows a request can have), L_kv != 0
+// iff out_c / lse_c hold the attention over the KV blocks; stats and w_raw, w have pitch absorbed_row_pitch(L_act).
+hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &p, hipStream_t s)
+{
+    const AbsorbedArgs &a = p.abs;
+    if (a.B <= 0) return hipSuccess;
+    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
+    if (p.block_tokens < 16 || (p.block_tokens & (p.block_tokens - 1)) != 0 || p.max_blocks <= 0 || a.L_act != p.max_blocks * p.block_tokens)
+        return hipErrorInvalidValue;
+    int blk_log2 = 0;
+    while ((1 << blk_log2) < p.block_tokens) ++blk_log2;
+    const int Lp = absorbed_row_pitch(a.L_act);
+    hipLaunchKernelGGL(paged_act_index_kernel, dim3((unsigned)((a.B + 3) / 4)), dim3(256), 0, s,
+                       p.block_table, p.max_blocks, p.seq_len, blk_log2, p.n_act_used, a.B, p.list, p.count, p.last_rows, p.n_rows);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if ((e = launch_carry(a, s)) != hipSuccess) return e;
+    switch ((a.H + 31) / 32) {
+    case 1: e = launch_paged_scores<1>(p, Lp, blk_log2, s); break;
+    case 2: e = launch_paged_scores<2>(p, Lp, blk_log2, s); break;
+    case 3: e = launch_paged_scores<3>(p, Lp, blk_log2, s); break;
+    default: e = launch_paged_scores<4>(p, Lp, blk_log2, s); break;
+    }
+    if (e != hipSuccess) return e;
+    PagedRows pr;
+    pr.blk_list = p.list; pr.n_rows = p.n_rows; pr.list_pitch = p.max_blocks; pr.blk_log2 = blk_log2;
+    return launch_after_scores(a, Lp, &pr, s);
 }
 
 }  // namespace hk

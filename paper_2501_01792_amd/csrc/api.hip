@@ -539,7 +539,142 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
+    a.skip_act = false; a.lse = nullptr;
     if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    return HK_OK;
+}
+
+namespace {
+
+struct PagedAbsorbedPlan {
+    int n_waves, Lp;
+    float scale;
+    size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_list, off_count, off_last,
+        off_rows, off_partial, total;
+};
+
+int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedAbsorbedPlan *p)
+{
+    PagedPlan base;                                        // the checks of the paged step
+    int st = make_paged_plan(s, B, c, &base);
+    if (st != HK_OK) return st;
+    if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
+    const int64_t max_rows = (int64_t)c->max_blocks * c->block_tokens;     // the most checkpoint rows a request can have
+    if (max_rows > (1 << 28) || B * c->max_blocks > 0x7fffffffLL) return HK_ERR_SHAPE;
+    p->scale = base.scale;
+    p->Lp = hk::absorbed_row_pitch((int)max_rows);
+    const bool act = c->n_act_used > 0;
+    const size_t b = (size_t)B, bh = b * s->n_heads;
+    size_t end = 0;
+    auto take = [&](size_t bytes) { const size_t at = end; end += align_up(bytes); return at; };
+    p->off_stats = take(act ? b * p->Lp * sizeof(float4) : 0);
+    p->off_prep = take(act ? prepared_layout(s->d).total : 0);
+    p->off_u = take(act ? bh * s->d * 2 : 0);
+    p->off_raw = take(act ? bh * p->Lp * 4 : 0);
+    p->off_w = take(act ? bh * p->Lp * 2 : 0);
+    p->off_sums = take(act ? bh * sizeof(float4) : 0);
+    p->off_y = take(act ? bh * s->d * 2 : 0);
+    p->off_outc = take(act ? bh * s->head_dim * 2 : 0);
+    p->off_lse = take(act ? bh * sizeof(float2) : 0);
+    p->off_list = take(act ? b * c->max_blocks * sizeof(int32_t) : 0);
+    p->off_count = take(act ? b * sizeof(int32_t) : 0);
+    p->off_last = take(act ? b * sizeof(int32_t) : 0);
+    p->off_rows = take(act ? b * sizeof(int32_t) : 0);
+    p->off_partial = end;
+    // the attention over the KV blocks alone: its kernel form fits 2 wavefronts per SIMD
+    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, 256 * 4 * 2);
+    take(((size_t)p->n_waves + bh) * (s->head_dim + 2) * sizeof(float));
+    p->total = end;
+    return HK_OK;
+}
+
+}  // namespace
+
+size_t hk_paged_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache)
+{
+    PagedAbsorbedPlan p;
+    if (make_paged_absorbed_plan(shape, B, cache, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t B, const hk_paged_cache *cache,
+                                  const hk_layer_params *params, void *out,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    PagedAbsorbedPlan p;
+    int st = make_paged_absorbed_plan(shape, B, cache, &p);
+    if (st != HK_OK) return st;
+    if (B == 0) return HK_OK;
+    if (!q || !out || !workspace || !cache->block_table || !cache->seq_len || !cache->cu_tokens) return HK_ERR_NULL;
+    if (cache->P_kv > 0 && (!cache->K_pool || !cache->V_pool)) return HK_ERR_NULL;
+    if (cache->n_act_used > 0) {
+        st = check_params(params);
+        if (st != HK_OK) return st;
+        if (!cache->act_pool) return HK_ERR_NULL;
+        if (!aligned(cache->act_pool, 16)) return HK_ERR_ALIGN;
+    }
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign)) return HK_ERR_ALIGN;
+    if (cache->P_kv > 0 && (!aligned(cache->K_pool, 16) || !aligned(cache->V_pool, 16))) return HK_ERR_ALIGN;
+    if (!aligned(cache->block_table, 4) || !aligned(cache->seq_len, 4) || !aligned(cache->cu_tokens, 8)) return HK_ERR_ALIGN;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const bool act = cache->n_act_used > 0;
+    const bool kv = cache->P_kv > 0;
+    if (kv || !act) {
+        // attention over the KV blocks alone (checkpoint blocks skipped); with no checkpoint block in use it is the
+        // whole step and goes straight to `out`
+        hk::PagedAttnArgs a;
+        a.q = q;
+        a.K_pool = cache->K_pool; a.V_pool = cache->V_pool;
+        a.K_regen = nullptr; a.V_regen = nullptr;
+        a.block_table = cache->block_table; a.seq_len = cache->seq_len; a.cu_tokens = cache->cu_tokens;
+        a.total_tokens = cache->total_tokens; a.max_blocks = cache->max_blocks;
+        a.P_kv = cache->P_kv; a.P_act = 0; a.block_tokens = cache->block_tokens;
+        a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
+        a.partial = reinterpret_cast<float *>(ws + p.off_partial);
+        a.out = act ? static_cast<void *>(ws + p.off_outc) : out;
+        a.skip_act = kv;                                   // without a KV pool there is nothing to attend: lengths are 0
+        a.lse = act ? reinterpret_cast<float2 *>(ws + p.off_lse) : nullptr;
+        if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    }
+    if (!act) return HK_OK;
+
+    const PreparedLayout PL = prepared_layout(shape->d);
+    const char *pp = static_cast<const char *>(params->prepared);
+    if (!pp) {
+        char *dst = ws + p.off_prep;
+        if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, dst + PL.off_w,
+                                     reinterpret_cast<float *>(dst + PL.off_c), reinterpret_cast<float *>(dst + PL.off_b),
+                                     shape->d, hs) != hipSuccess)
+            return HK_ERR_LAUNCH;
+        pp = dst;
+    }
+    hk::PagedAbsorbedArgs pa;
+    hk::AbsorbedArgs &a = pa.abs;
+    a.q = q; a.act = cache->act_pool; a.stats = reinterpret_cast<float4 *>(ws + p.off_stats);
+    a.Wp = pp + PL.off_w;
+    a.cvec = reinterpret_cast<const float *>(pp + PL.off_c);
+    a.bvec = reinterpret_cast<const float *>(pp + PL.off_b);
+    a.U = ws + p.off_u;
+    a.w_raw = reinterpret_cast<float *>(ws + p.off_raw);
+    a.w = ws + p.off_w;
+    a.sums = reinterpret_cast<float4 *>(ws + p.off_sums);
+    a.Y = ws + p.off_y;
+    a.out_c = ws + p.off_outc;
+    a.lse_c = reinterpret_cast<const float2 *>(ws + p.off_lse);
+    a.out = out;
+    a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d;
+    a.L_act = cache->max_blocks * cache->block_tokens; a.L_kv = kv ? 1 : 0;
+    a.scale = p.scale; a.eps = shape->ln_eps;
+    pa.block_table = cache->block_table; pa.seq_len = cache->seq_len;
+    pa.max_blocks = cache->max_blocks; pa.block_tokens = cache->block_tokens; pa.n_act_used = cache->n_act_used;
+    pa.list = reinterpret_cast<int32_t *>(ws + p.off_list);
+    pa.count = reinterpret_cast<int32_t *>(ws + p.off_count);
+    pa.last_rows = reinterpret_cast<int32_t *>(ws + p.off_last);
+    pa.n_rows = reinterpret_cast<int32_t *>(ws + p.off_rows);
+    if (hk::launch_paged_absorbed(pa, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
 

@@ -101,6 +101,8 @@ struct PagedAttnArgs {
     int n_waves;                       // attn_wavefronts(H, total_tokens, 0) -- pairs' tokens counted as one line
     float *partial;                    // [n_waves + B H, dh + 2] fp32
     void *out;                         // [B, H, dh] fp16
+    bool skip_act;                     // attend over the KV blocks only (needs P_kv > 0); K_regen, V_regen are not read
+    float2 *lse;                       // optional [B H]: (maximum in the log2 domain, denominator) of every pair; (., 0) when empty
 };
 // Single-query attention of B requests of different lengths over a block-table-addressed hybrid cache.
 hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);
@@ -127,5 +129,16 @@ constexpr int kAbsorbMaxBatch = 128;   // sequences one launch of the output pro
 int absorbed_row_pitch(int L_act);     // elements between the rows of w_raw and w
 // The checkpoint part of the decode attention without regenerating K/V (see absorbed.hip).
 hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s);
+
+struct PagedAbsorbedArgs {
+    AbsorbedArgs abs;                  // act = the activation pool [P_act, block_tokens, d]; L_act = max_blocks * block_tokens
+    const int32_t *block_table;        // [B, max_blocks]: < 0: checkpoint block ~entry
+    const int32_t *seq_len;            // [B]
+    int max_blocks, block_tokens, n_act_used;
+    int32_t *list;                     // [B, max_blocks] scratch: the checkpoint blocks of every request in logical order
+    int32_t *count, *last_rows, *n_rows;   // [B] scratch each: their number, the rows of the last one, the request's checkpoint rows
+};
+// The same over a paged cache: the checkpoint rows of a request are found through its row of the block table.
+hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &a, hipStream_t s);
 
 }  // namespace hk

@@ -50,7 +50,7 @@ __device__ __forceinline__ int request_of(const int64_t *__restrict__ cu, int B,
     return lo;
 }
 
-template <int DH>
+template <int DH, bool SKIP>
 __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
     const _Float16 *__restrict__ q,
     const _Float16 *__restrict__ K_pool, const _Float16 *__restrict__ V_pool,      // KV blocks
@@ -99,6 +99,8 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
             // last token are redirected to the last token's block and row, and masked below.
             int64_t kv_base[4];          // element offset of (block, head h, token 0 of the pair) in its pool
             bool kv_act[4];
+            bool kv_skip[4];             // skip_act: the tokens of ACT blocks take no part (they are attended elsewhere);
+                                         // their loads go to KV block 0 and their scores are masked
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int bi = (tb >> blk_log2) + j;
@@ -106,6 +108,8 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
                 const int32_t e = __builtin_amdgcn_readfirstlane(tab[bi]);
                 bool is_act = e < 0;
                 int pb = is_act ? ~e : e;
+                kv_skip[j] = SKIP && is_act;
+                if (kv_skip[j]) { is_act = false; pb = 0; }                       // skip_act implies P_kv > 0
                 if ((is_act ? P_act : P_kv) <= 0) { is_act = !is_act; pb = 0; }   // a corrupt table cannot leave
                 const int P = is_act ? P_act : P_kv;                              // the pools (one is not empty)
                 pb = pb < P ? pb : P - 1;
@@ -147,7 +151,9 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
             }
             // lane (g, c) now owns the score of token tb + c*RPL + g
             const int my_t = tb + c * RPL + g;
-            const float s = (my_t >= t_first && my_t < t_last) ? pd[0] * scale_log2e : -INFINITY;
+            const int my_j = (c * RPL) >> blk_log2;              // the block (of the tile's four) of this lane's token
+            const bool skipped = SKIP && (my_j == 0 ? kv_skip[0] : my_j == 1 ? kv_skip[1] : my_j == 2 ? kv_skip[2] : kv_skip[3]);
+            const float s = (my_t >= t_first && my_t < t_last && !skipped) ? pd[0] * scale_log2e : -INFINITY;
 
             float m_tile = s;
 #pragma unroll
@@ -194,13 +200,15 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
 template <int DH>
 __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict__ partial,
                                                          const int32_t *__restrict__ seq_len, const int64_t *__restrict__ cu,
-                                                         int H, int64_t total, int W, _Float16 *__restrict__ out)
+                                                         int H, int64_t total, int W, _Float16 *__restrict__ out,
+                                                         float2 *__restrict__ lse)
 {
     const int pair = blockIdx.x, e = threadIdx.x;
     const int r = pair / H, h = pair % H;
     const int len = seq_len[r];
     if (len <= 0) {                      // no context: the softmax is over nothing; define the output as zero
         out[(int64_t)pair * DH + e] = (_Float16)0.f;
+        if (lse && e == 0) lse[pair] = make_float2(kNegBig, 0.f);
         return;
     }
     const int64_t lo = (int64_t)H * cu[r] + (int64_t)h * len, hi = lo + len - 1;
@@ -221,7 +229,8 @@ __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict
         o = __builtin_fmaf(wgt, src[i * (DH + 2) + 2 + e], o);
         l = __builtin_fmaf(wgt, src[i * (DH + 2) + 1], l);
     }
-    out[(int64_t)pair * DH + e] = (_Float16)(o / l);
+    out[(int64_t)pair * DH + e] = (_Float16)(l > 0.f ? o / l : 0.f);   // l == 0: every token of the pair was skipped
+    if (lse && e == 0) lse[pair] = make_float2(mx, l);
 }
 
 template <int DH>
@@ -233,7 +242,8 @@ hipError_t launch_dh(const PagedAttnArgs &a, hipStream_t s)
     while ((1 << blk_log2) < a.block_tokens) ++blk_log2;
     if (total > 0) {
         const unsigned blocks = (unsigned)((a.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
-        hipLaunchKernelGGL(paged_decode_kernel<DH>, dim3(blocks), dim3(kThreads), 0, s,
+        auto kern = a.skip_act ? paged_decode_kernel<DH, true> : paged_decode_kernel<DH, false>;
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), 0, s,
                            static_cast<const _Float16 *>(a.q),
                            static_cast<const _Float16 *>(a.K_pool), static_cast<const _Float16 *>(a.V_pool),
                            static_cast<const _Float16 *>(a.K_regen), static_cast<const _Float16 *>(a.V_regen),
@@ -244,7 +254,7 @@ hipError_t launch_dh(const PagedAttnArgs &a, hipStream_t s)
     }
     hipLaunchKernelGGL(paged_merge_kernel<DH>, dim3((unsigned)(a.B * a.H)), dim3(DH), 0, s,
                        a.partial, a.seq_len, a.cu_tokens, a.H, total > 0 ? total : 1, a.n_waves > 0 ? a.n_waves : 1,
-                       static_cast<_Float16 *>(a.out));
+                       static_cast<_Float16 *>(a.out), a.lse);
     return hipGetLastError();
 }
 
@@ -254,6 +264,7 @@ hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (a.block_tokens < 16 || (a.block_tokens & (a.block_tokens - 1)) != 0) return hipErrorInvalidValue;
+    if (a.skip_act && a.P_kv <= 0) return hipErrorInvalidValue;
     if (a.total_tokens > 0 && (a.n_waves <= 0 || (int64_t)a.n_waves > (int64_t)a.H * a.total_tokens)) return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_dh<128>(a, s);
     if (a.head_dim == 64) return launch_dh<64>(a, s);

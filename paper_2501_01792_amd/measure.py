@@ -1,7 +1,7 @@
 """Timing of the entry points beside the benchmark's path (bench.py times the hybrid step itself):
 
     python -m paper_2501_01792_amd.measure qkv   [--config opt6.7b] [--iters 20]
-    python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged]
+    python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged] [--absorbed]
 
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
@@ -100,7 +100,7 @@ def measure_paged(args):
     tb, sl = torch.from_numpy(table).cuda(), torch.from_numpy(lens.astype(np.int32)).cuda()
     out = torch.empty(B, H, dh, device="cuda", dtype=f16)
     call = lambda: hk.paged_decode_attn(q, Kp if n_kv else None, Vp if n_kv else None, Ap if n_act else None, tb, sl, bt, lp,
-                                        n_act_used=n_act, out=out)
+                                        n_act_used=n_act, out=out, absorbed=args.absorbed)
     for _ in range(2):
         call()
     ts = []
@@ -113,7 +113,7 @@ def measure_paged(args):
     tokens = int(lens.sum())
     attn_bytes = float(tokens) * 4 * d                          # every token's K and V row once
     regen_flop = 4.0 * n_act * bt * d * d
-    print(json.dumps({"entry": "hk_paged_decode_attn",
+    print(json.dumps({"entry": "hk_paged_decode_attn_absorbed" if args.absorbed else "hk_paged_decode_attn",
                       "workload": "%s: B=%d H=%d dh=%d L%s%d, %d-token blocks, %.0f %% ACT blocks" %
                                   (cfg.name, B, H, dh, "<=" if args.ragged else "=", L, bt, 100 * args.act_fraction),
                       "iters": args.iters, "ms": ms, "min_ms": float(np.min(ts)), "tokens": tokens, "act_blocks": n_act,
@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--block-tokens", type=int, default=16)
     ap.add_argument("--act-fraction", type=float, default=0.0)
     ap.add_argument("--ragged", action="store_true")
+    ap.add_argument("--absorbed", action="store_true", help="paged: the entry point that does not regenerate K/V")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():

@@ -104,6 +104,26 @@ def test_paged_rejects_bad_arguments():
     assert call(c=cache(cu_tokens=FAKE + 4)) == hk.HK_ERR_ALIGN and call(q=FAKE + 2) == hk.HK_ERR_ALIGN
     assert call(n=need - 1) == hk.HK_ERR_WORKSPACE
 
+    # the entry point that does not regenerate K/V: the same checks, its own limits and its own (smaller) workspace
+    def call2(shape=ok, q=FAKE, B=2, c=None, lp=lp, out=FAKE, ws=FAKE, n=None):
+        c = c or cache()
+        need2 = hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(c))
+        return hk.lib().hk_paged_decode_attn_absorbed(ctypes.byref(shape), q, B, ctypes.byref(c), ctypes.byref(lp) if lp else None,
+                                                      out, ws, need2 if n is None else n, None)
+
+    need2 = hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(ok), 2, ctypes.byref(cache()))
+    assert need2 > 0
+    assert call2(c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE and call2(c=cache(n_act_used=9)) == hk.HK_ERR_SHAPE
+    assert call2(shape=hk.make_shape(129 * 64, 129)) == hk.HK_ERR_SHAPE       # more than 128 heads
+    assert call2(q=None) == hk.HK_ERR_NULL and call2(c=cache(act_pool=None)) == hk.HK_ERR_NULL and call2(lp=None) == hk.HK_ERR_NULL
+    assert call2(out=FAKE + 2) == hk.HK_ERR_ALIGN and call2(n=need2 - 1) == hk.HK_ERR_WORKSPACE
+    assert call2(B=0, q=None, c=cache(total_tokens=0)) == hk.HK_OK
+    big = hk.hk_paged_cache(K_pool=FAKE, V_pool=FAKE, act_pool=FAKE, block_table=FAKE, seq_len=FAKE, cu_tokens=FAKE,
+                            total_tokens=32 * 4096, P_kv=8, P_act=32 * 256, n_act_used=32 * 256, block_tokens=16, max_blocks=256)
+    s67 = hk.make_shape(4096, 32)
+    assert hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(s67), 32, ctypes.byref(big)) < \
+        hk.lib().hk_paged_workspace_bytes(ctypes.byref(s67), 32, ctypes.byref(big)) // 4
+
 
 # ------------------------------------------------------------------ GPU parity
 def _check(name, got, ref):
@@ -126,10 +146,11 @@ GPU_CASES = [
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("absorbed", [False, True], ids=["regenerating", "absorbed"])
 @pytest.mark.parametrize("case", GPU_CASES, ids=lambda c: c[0])
-def test_paged_decode_matches_oracle(case):
+def test_paged_decode_matches_oracle(case, absorbed):
     name, d, H, B, L, bt, frac, lens = case
-    print("case", case[:7], flush=True)
+    print("case", case[:7], "absorbed", absorbed, flush=True)
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a GPU; there is no CPU path")
     cfg = synth.LayerConfig(name, d, H, B, L, 0.5, 52)
@@ -142,7 +163,8 @@ def test_paged_decode_matches_oracle(case):
     g = lambda x: None if x is None or x.shape[0] == 0 else torch.from_numpy(np.ascontiguousarray(x)).cuda()
     lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
     out = hk.paged_decode_attn(g(batch["q"]), g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"]),
-                               g(paged["block_table"]), g(paged["seq_len"]), bt, lp, n_act_used=paged["n_act_used"])
+                               g(paged["block_table"]), g(paged["seq_len"]), bt, lp, n_act_used=paged["n_act_used"],
+                               absorbed=absorbed)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
     # the oracle walks the same tables; on the big case only a sample of the requests
@@ -154,3 +176,24 @@ def test_paged_decode_matches_oracle(case):
     for b in range(B):
         if seq_len[b] == 0:
             assert (out[b] == 0).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("absorbed", [False, True], ids=["regenerating", "absorbed"])
+def test_paged_decode_without_a_kv_pool(absorbed):
+    """Every block a checkpoint block and no KV pool at all (P_kv == 0, NULL pools)."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("no_kv_pool", 512, 8, 4, 150, 0.5, 53)
+    p, batch = _context(cfg, 6)
+    seq_len = [150, 33, 64, 1]
+    bt = 32
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, 1.0, seed=8)
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    out = hk.paged_decode_attn(g(batch["q"]), None, None, g(paged["act_pool"]), g(paged["block_table"]), g(paged["seq_len"]), bt, lp,
+                               n_act_used=paged["n_act_used"], absorbed=absorbed)
+    torch.cuda.synchronize()
+    ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
+                                paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
+    _check("out", out.cpu().numpy(), ref)
