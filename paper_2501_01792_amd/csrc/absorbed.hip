@@ -577,42 +577,50 @@ __global__ __launch_bounds__(256) void paged_act_index_kernel(const int32_t *__r
     }
 }
 
-// scores of one slab (min(32, block) rows) of one checkpoint block of one request, as absorbed_scores_kernel;
-// rows are numbered inside the request in the order of its block list (raw, stats: pitch Lp per request).
+// scores of 128 checkpoint rows of one request, as absorbed_scores_block_kernel (U is read once per 128 rows);
+// rows are numbered inside the request in the order of its block list (raw, stats: pitch Lp per request) and
+// found through that list (a block holds at least 16 rows, so the 8 rows of a load share a block).
 template <int RB>
 __global__ __launch_bounds__(256) void paged_scores_kernel(const _Float16 *__restrict__ act_pool, const _Float16 *__restrict__ U,
                                                            float *__restrict__ raw, float4 *__restrict__ stats,
-                                                           const int32_t *__restrict__ list, const int32_t *__restrict__ count,
-                                                           const int32_t *__restrict__ last_rows,
-                                                           int B, int max_blocks, int blk_log2, int slab, int Lp, int H, int d, float eps)
+                                                           const int32_t *__restrict__ list, const int32_t *__restrict__ n_rows,
+                                                           int B, int max_blocks, int blk_log2, int groups, int Lp, int H, int d, float eps)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int bt = 1 << blk_log2;
-    const int subs = bt / slab;
-    const int64_t per_b = (int64_t)max_blocks * subs;
-    const int item = gemm::xcd_regroup(blockIdx.x, (int)(per_b * B));
-    const int64_t b = item / per_b;
-    const int k = (int)((item % per_b) / subs), sub = (int)(item % subs);
-    const int cnt = count[b];
-    if (k >= cnt) return;                                  // uniform over the workgroup, before any barrier
-    const int valid = k == cnt - 1 ? last_rows[b] : bt;
-    const int rows = valid - slab * sub < slab ? valid - slab * sub : slab;
-    if (rows <= 0) return;
-    const int64_t blk = list[b * max_blocks + k];
-    const _Float16 *S = act_pool + ((blk << blk_log2) + slab * sub) * d;
-    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false, true>(S, rows, d, U + b * d, H, (int64_t)B * d, d, smem);
-    const int r0 = (k << blk_log2) + slab * sub;           // first row's number inside the request
-    for (int idx = tid; idx < H * skinny::kSlab; idx += 256) {
-        const int h = idx / skinny::kSlab, c = idx % skinny::kSlab;
-        if (c < rows)
-            raw[(b * H + h) * Lp + r0 + c] = (red[0][h][c] + red[1][h][c]) + (red[2][h][c] + red[3][h][c]);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int item = gemm::xcd_regroup(blockIdx.x, groups * B);
+    const int64_t b = item / groups;
+    const int r0 = (item % groups) * 128;                  // first row of the workgroup inside the request
+    const int total = n_rows[b];
+    if (r0 >= total) return;                               // uniform over the workgroup, before any barrier
+    const int n = total - r0 < 128 ? total - r0 : 128;
+    const int32_t *blocks = list + b * max_blocks;
+    const int mask = (1 << blk_log2) - 1;
+    auto row_of = [=](int r) {
+        const int rr = r0 + r;
+        return act_pool + (((int64_t)blocks[rr >> blk_log2] << blk_log2) + (rr & mask)) * d;
+    };
+    float16_t acc[RB];
+    float m1[4], m2[4];
+    _Float16 first[4];
+    skinny::block_product_rows<RB, false, true>(row_of, n, U + b * d, H, (int64_t)B * d, 0, d / 64, smem, acc, m1, m2, first);
+    const int rw = r0 + 32 * wave;                         // first row of this wavefront
+    const int rows = total - rw < 32 ? (total - rw > 0 ? total - rw : 0) : 32;
+    const int ln = lane & 31, lh = lane >> 5;
+    if (ln < rows) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int h = 32 * rb + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (h < H) raw[(b * H + h) * Lp + rw + ln] = acc[rb][r];
+            }
     }
-    if (tid < rows) {
-        float (*mom)[skinny::kSlab][2] = skinny::moments<RB>(smem);
-        const float s1 = (mom[0][tid][0] + mom[1][tid][0]) + (mom[2][tid][0] + mom[3][tid][0]);
-        const float s2 = (mom[0][tid][1] + mom[1][tid][1]) + (mom[2][tid][1] + mom[3][tid][1]);
-        stats[b * Lp + r0 + tid] = row_stats(s1, s2, (float)S[(int64_t)tid * d], d, eps);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + (lane >> 3);
+        if ((lane & 7) == 0 && row < rows) stats[b * Lp + rw + row] = row_stats(m1[j], m2[j], (float)first[j], d, eps);
     }
 }
 
@@ -620,17 +628,17 @@ template <int RB>
 hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2, hipStream_t s)
 {
     const AbsorbedArgs &a = p.abs;
-    const int slab = p.block_tokens < skinny::kSlab ? p.block_tokens : skinny::kSlab;
-    const int64_t items = (int64_t)a.B * p.max_blocks * (p.block_tokens / slab);
+    const int groups = (a.L_act + 127) / 128;              // of the longest request possible; shorter ones leave early
+    const int64_t items = (int64_t)a.B * groups;
     if (items <= 0) return hipSuccess;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = paged_scores_kernel<RB>;
-    constexpr int lds = skinny::lds_bytes<RB>() + skinny::kMomentBytes;
+    constexpr int lds = skinny::block_lds_bytes<RB>();
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,
-                       p.list, p.count, p.last_rows, a.B, p.max_blocks, blk_log2, slab, Lp, a.H, a.d, a.eps);
+                       p.list, p.n_rows, a.B, p.max_blocks, blk_log2, groups, Lp, a.H, a.d, a.eps);
     return hipGetLastError();
 }
 

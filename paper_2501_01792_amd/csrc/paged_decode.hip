@@ -126,14 +126,26 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
                 const int j = (i * RPL) >> blk_log2;               // 0..3, wavefront-uniform
                 const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
                 const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
-                kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? K_regen : K_pool) + b + lane_off(i)));
+                const bool sk = SKIP && (j == 0 ? kv_skip[0] : j == 1 ? kv_skip[1] : j == 2 ? kv_skip[2] : kv_skip[3]);
+                if (sk) {                                          // wavefront-uniform: the rows of a skipped block are not fetched
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kr[i][e] = (_Float16)0.f;
+                } else {
+                    kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? K_regen : K_pool) + b + lane_off(i)));
+                }
             }
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
                 const int j = (i * RPL) >> blk_log2;
                 const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
                 const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
-                vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? V_regen : V_pool) + b + lane_off(i)));
+                const bool sk = SKIP && (j == 0 ? kv_skip[0] : j == 1 ? kv_skip[1] : j == 2 ? kv_skip[2] : kv_skip[3]);
+                if (sk) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vr[i][e] = (_Float16)0.f;
+                } else {
+                    vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? V_regen : V_pool) + b + lane_off(i)));
+                }
             }
 
             float pd[NL];

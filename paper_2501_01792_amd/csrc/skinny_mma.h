@@ -237,11 +237,13 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
 template <int RB>
 constexpr int block_lds_bytes() { return 4 * kBlockBytes + 2 * RB * kBlockBytes; }
 
-template <int RB, bool NT, bool STATS>
-__device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, int n_rows, int64_t ld_s,
-                                              const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
-                                              int k_begin, int k_steps, unsigned char *smem,
-                                              float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
+// row_of(r) is the address of streamed row r, r < n_rows (rows need not be evenly spaced: they may sit in
+// blocks scattered over a pool).
+template <int RB, bool NT, bool STATS, typename RowOf>
+__device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
+                                                   const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
+                                                   int k_begin, int k_steps, unsigned char *smem,
+                                                   float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -253,7 +255,7 @@ __device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, in
     for (int j = 0; j < 4; ++j) {
         int r = 32 * wave + 8 * j + g_row;
         if (r >= n_rows) r = n_rows - 1;
-        const _Float16 *row = S + (int64_t)r * ld_s;
+        const _Float16 *row = row_of(r);
         if constexpr (STATS) {
             first[j] = row[0];
             shift[j] = half2_t{first[j], first[j]};
@@ -356,6 +358,17 @@ __device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, in
                 m2[j] += __shfl_xor(m2[j], off, 64);
             }
     }
+}
+
+// Evenly spaced rows: S is the first row of the block, ld_s the distance between rows.
+template <int RB, bool NT, bool STATS>
+__device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, int n_rows, int64_t ld_s,
+                                              const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
+                                              int k_begin, int k_steps, unsigned char *smem,
+                                              float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
+{
+    block_product_rows<RB, NT, STATS>([=](int r) { return S + (int64_t)r * ld_s; }, n_rows, A, a_rows, ld_a, k_begin, k_steps,
+                                      smem, acc, m1, m2, first);
 }
 
 }  // namespace skinny
