@@ -543,13 +543,16 @@ hipError_t launch_after_scores(const AbsorbedArgs &a, int Lp, const PagedRows *p
 // Paged cache (Sec. 4.1, 4.2.1): the checkpoint rows of a request sit in blocks of the activation pool named by
 // its row of the block table (entries < 0: checkpoint block ~entry).
 //
-// index: one wavefront per request walks its table row and leaves the request's checkpoint blocks in logical
-// order (list), their count, the rows of the last of them (only a request's final block can be partly filled)
-// and the request's number of checkpoint rows.  Blocks outside the pool prefix in use are left out.
-__global__ __launch_bounds__(256) void paged_act_index_kernel(const int32_t *__restrict__ table, int max_blocks,
-                                                              const int32_t *__restrict__ seq_len, int blk_log2, int n_act_used, int B,
-                                                              int32_t *__restrict__ list, int32_t *__restrict__ count,
-                                                              int32_t *__restrict__ last_rows, int32_t *__restrict__ n_rows)
+// index: one wavefront per request walks its table row and leaves (a) the request's checkpoint blocks in logical
+// order (list), their count, the rows of the last of them (only a request's final block can be partly filled) and
+// the request's number of checkpoint rows; (b) the same view of its KV blocks: a table row that holds only them,
+// in order, and the request's number of cached tokens, i.e. what the block-table attention kernel needs to walk
+// the cached tokens alone.  Checkpoint blocks outside the pool prefix in use are left out.
+__global__ __launch_bounds__(256) void paged_index_kernel(const int32_t *__restrict__ table, int max_blocks,
+                                                          const int32_t *__restrict__ seq_len, int blk_log2, int n_act_used, int B,
+                                                          int32_t *__restrict__ list, int32_t *__restrict__ count,
+                                                          int32_t *__restrict__ last_rows, int32_t *__restrict__ n_rows,
+                                                          int32_t *__restrict__ kv_table, int32_t *__restrict__ kv_len)
 {
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -558,22 +561,50 @@ __global__ __launch_bounds__(256) void paged_act_index_kernel(const int32_t *__r
     const int len = seq_len[b];
     int nb = len > 0 ? (len + bt - 1) >> blk_log2 : 0;
     if (nb > max_blocks) nb = max_blocks;
-    int k0 = 0, last_i = -1;
+    int k0 = 0, last_i = -1, c0 = 0, last_c = -1;
     for (int base = 0; base < nb; base += 64) {
         const int i = base + lane;
         const int32_t e = i < nb ? table[(int64_t)b * max_blocks + i] : 0;
         const bool is = i < nb && e < 0 && ~e < n_act_used;
-        const unsigned long long mask = __ballot(is);
-        if (is) list[(int64_t)b * max_blocks + k0 + __popcll(mask & ((1ull << lane) - 1ull))] = ~e;
+        const bool kv = i < nb && e >= 0;
+        const unsigned long long below = (1ull << lane) - 1ull;
+        const unsigned long long mask = __ballot(is), cmask = __ballot(kv);
+        if (is) list[(int64_t)b * max_blocks + k0 + __popcll(mask & below)] = ~e;
+        if (kv) kv_table[(int64_t)b * max_blocks + c0 + __popcll(cmask & below)] = e;
         k0 += __popcll(mask);
+        c0 += __popcll(cmask);
         if (mask) last_i = base + 63 - __builtin_clzll(mask);
+        if (cmask) last_c = base + 63 - __builtin_clzll(cmask);
     }
     if (lane == 0) {
-        int lr = bt;
-        if (last_i >= 0) { const int rest = len - (last_i << blk_log2); lr = rest < bt ? rest : bt; }
+        auto rows_of = [&](int n_blocks, int last) {       // rows of n_blocks blocks whose last one is logical block `last`
+            if (n_blocks <= 0) return 0;
+            const int rest = len - (last << blk_log2);
+            return ((n_blocks - 1) << blk_log2) + (rest < bt ? rest : bt);
+        };
         count[b] = k0;
-        last_rows[b] = lr;
-        n_rows[b] = k0 > 0 ? ((k0 - 1) << blk_log2) + lr : 0;
+        n_rows[b] = rows_of(k0, last_i);
+        last_rows[b] = k0 > 0 ? n_rows[b] - ((k0 - 1) << blk_log2) : bt;
+        kv_len[b] = rows_of(c0, last_c);
+    }
+}
+
+// cu[0] = 0, cu[b + 1] = cu[b] + len[b]: one wavefront, 64 requests per step.
+__global__ __launch_bounds__(64) void paged_prefix_kernel(const int32_t *__restrict__ len, int B, int64_t *__restrict__ cu)
+{
+    const int lane = threadIdx.x;
+    int64_t carry = 0;
+    if (lane == 0) cu[0] = 0;
+    for (int base = 0; base < B; base += 64) {
+        const int i = base + lane;
+        int64_t v = i < B ? len[i] : 0;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int64_t up = __shfl_up(v, off, 64);
+            if (lane >= off) v += up;
+        }
+        if (i < B) cu[i + 1] = carry + v;
+        carry += __shfl(v, 63, 64);
     }
 }
 
@@ -661,8 +692,26 @@ hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
     return launch_after_scores(a, Lp, nullptr, s);
 }
 
-// a.abs: act = the activation pool, L_act = max_blocks * block_tokens (the most rows a request can have), L_kv != 0
-// iff out_c / lse_c hold the attention over the KV blocks; stats and w_raw, w have pitch absorbed_row_pitch(L_act).
+// The two views of the block table that the paged step without regeneration works on (see paged_index_kernel).
+hipError_t launch_paged_index(const PagedAbsorbedArgs &p, hipStream_t s)
+{
+    const AbsorbedArgs &a = p.abs;
+    if (a.B <= 0) return hipSuccess;
+    if (p.block_tokens < 16 || (p.block_tokens & (p.block_tokens - 1)) != 0 || p.max_blocks <= 0) return hipErrorInvalidValue;
+    int blk_log2 = 0;
+    while ((1 << blk_log2) < p.block_tokens) ++blk_log2;
+    hipLaunchKernelGGL(paged_index_kernel, dim3((unsigned)((a.B + 3) / 4)), dim3(256), 0, s,
+                       p.block_table, p.max_blocks, p.seq_len, blk_log2, p.n_act_used, a.B, p.list, p.count, p.last_rows, p.n_rows,
+                       p.kv_table, p.kv_len);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(paged_prefix_kernel, dim3(1), dim3(64), 0, s, p.kv_len, a.B, p.kv_cu);
+    return hipGetLastError();
+}
+
+// After launch_paged_index (and the attention over the KV view).  a.abs: act = the activation pool, L_act =
+// max_blocks * block_tokens (the most rows a request can have), L_kv != 0 iff out_c / lse_c hold the attention
+// over the KV blocks; stats and w_raw, w have pitch absorbed_row_pitch(L_act).
 hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &p, hipStream_t s)
 {
     const AbsorbedArgs &a = p.abs;
@@ -673,11 +722,8 @@ hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &p, hipStream_t s)
     int blk_log2 = 0;
     while ((1 << blk_log2) < p.block_tokens) ++blk_log2;
     const int Lp = absorbed_row_pitch(a.L_act);
-    hipLaunchKernelGGL(paged_act_index_kernel, dim3((unsigned)((a.B + 3) / 4)), dim3(256), 0, s,
-                       p.block_table, p.max_blocks, p.seq_len, blk_log2, p.n_act_used, a.B, p.list, p.count, p.last_rows, p.n_rows);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_carry(a, s);
     if (e != hipSuccess) return e;
-    if ((e = launch_carry(a, s)) != hipSuccess) return e;
     switch ((a.H + 31) / 32) {
     case 1: e = launch_paged_scores<1>(p, Lp, blk_log2, s); break;
     case 2: e = launch_paged_scores<2>(p, Lp, blk_log2, s); break;

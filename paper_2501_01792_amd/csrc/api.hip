@@ -539,7 +539,7 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
-    a.skip_act = false; a.lse = nullptr;
+    a.total_dev = nullptr; a.lse = nullptr;
     if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -550,7 +550,7 @@ struct PagedAbsorbedPlan {
     int n_waves, Lp;
     float scale;
     size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_list, off_count, off_last,
-        off_rows, off_partial, total;
+        off_rows, off_kvtab, off_kvlen, off_kvcu, off_partial, total;
 };
 
 int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedAbsorbedPlan *p)
@@ -580,9 +580,12 @@ int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache 
     p->off_count = take(act ? b * sizeof(int32_t) : 0);
     p->off_last = take(act ? b * sizeof(int32_t) : 0);
     p->off_rows = take(act ? b * sizeof(int32_t) : 0);
+    p->off_kvtab = take(act ? b * c->max_blocks * sizeof(int32_t) : 0);
+    p->off_kvlen = take(act ? b * sizeof(int32_t) : 0);
+    p->off_kvcu = take(act ? (b + 1) * sizeof(int64_t) : 0);
     p->off_partial = end;
-    // the attention over the KV blocks alone: its kernel form fits 2 wavefronts per SIMD
-    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, 256 * 4 * 2);
+    // the attention over the KV blocks alone: sized for every token being cached (the device knows the true number)
+    p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, hk::kPagedResidentWaves);
     take(((size_t)p->n_waves + bh) * (s->head_dim + 2) * sizeof(float));
     p->total = end;
     return HK_OK;
@@ -622,24 +625,20 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const bool act = cache->n_act_used > 0;
     const bool kv = cache->P_kv > 0;
-    if (kv || !act) {
-        // attention over the KV blocks alone (checkpoint blocks skipped); with no checkpoint block in use it is the
-        // whole step and goes straight to `out`
-        hk::PagedAttnArgs a;
-        a.q = q;
-        a.K_pool = cache->K_pool; a.V_pool = cache->V_pool;
-        a.K_regen = nullptr; a.V_regen = nullptr;
-        a.block_table = cache->block_table; a.seq_len = cache->seq_len; a.cu_tokens = cache->cu_tokens;
-        a.total_tokens = cache->total_tokens; a.max_blocks = cache->max_blocks;
-        a.P_kv = cache->P_kv; a.P_act = 0; a.block_tokens = cache->block_tokens;
-        a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
-        a.partial = reinterpret_cast<float *>(ws + p.off_partial);
-        a.out = act ? static_cast<void *>(ws + p.off_outc) : out;
-        a.skip_act = kv;                                   // without a KV pool there is nothing to attend: lengths are 0
-        a.lse = act ? reinterpret_cast<float2 *>(ws + p.off_lse) : nullptr;
-        if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    hk::PagedAttnArgs t;
+    t.q = q;
+    t.K_pool = cache->K_pool; t.V_pool = cache->V_pool;
+    t.K_regen = nullptr; t.V_regen = nullptr;
+    t.block_table = cache->block_table; t.seq_len = cache->seq_len; t.cu_tokens = cache->cu_tokens;
+    t.total_tokens = cache->total_tokens; t.max_blocks = cache->max_blocks;
+    t.P_kv = cache->P_kv; t.P_act = 0; t.block_tokens = cache->block_tokens;
+    t.B = B; t.H = shape->n_heads; t.head_dim = shape->head_dim; t.scale = p.scale; t.n_waves = p.n_waves;
+    t.partial = reinterpret_cast<float *>(ws + p.off_partial);
+    t.out = out; t.total_dev = nullptr; t.lse = nullptr;
+    if (!act) {                                            // no checkpoint block in use: the block-table attention is the whole step
+        if (hk::launch_paged_decode(t, hs) != hipSuccess) return HK_ERR_LAUNCH;
+        return HK_OK;
     }
-    if (!act) return HK_OK;
 
     const PreparedLayout PL = prepared_layout(shape->d);
     const char *pp = static_cast<const char *>(params->prepared);
@@ -674,6 +673,18 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     pa.count = reinterpret_cast<int32_t *>(ws + p.off_count);
     pa.last_rows = reinterpret_cast<int32_t *>(ws + p.off_last);
     pa.n_rows = reinterpret_cast<int32_t *>(ws + p.off_rows);
+    pa.kv_table = reinterpret_cast<int32_t *>(ws + p.off_kvtab);
+    pa.kv_len = reinterpret_cast<int32_t *>(ws + p.off_kvlen);
+    pa.kv_cu = reinterpret_cast<int64_t *>(ws + p.off_kvcu);
+    if (hk::launch_paged_index(pa, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    if (kv) {
+        // attention over the cached tokens alone, through the KV view of the table; how many there are only the
+        // device knows (the launch is sized for all tokens being cached)
+        t.block_table = pa.kv_table; t.seq_len = pa.kv_len; t.cu_tokens = pa.kv_cu; t.total_dev = pa.kv_cu + B;
+        t.out = ws + p.off_outc;
+        t.lse = reinterpret_cast<float2 *>(ws + p.off_lse);
+        if (hk::launch_paged_decode(t, hs) != hipSuccess) return HK_ERR_LAUNCH;
+    }
     if (hk::launch_paged_absorbed(pa, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }

@@ -101,7 +101,8 @@ struct PagedAttnArgs {
     int n_waves;                       // attn_wavefronts(H, total_tokens, 0) -- pairs' tokens counted as one line
     float *partial;                    // [n_waves + B H, dh + 2] fp32
     void *out;                         // [B, H, dh] fp16
-    bool skip_act;                     // attend over the KV blocks only (needs P_kv > 0); K_regen, V_regen are not read
+    const int64_t *total_dev;          // optional (device): the sum of seq_len when only the device knows it; total_tokens
+                                       // is then an upper bound (it sizes the launch)
     float2 *lse;                       // optional [B H]: (maximum in the log2 domain, denominator) of every pair; (., 0) when empty
 };
 // Single-query attention of B requests of different lengths over a block-table-addressed hybrid cache.
@@ -137,8 +138,14 @@ struct PagedAbsorbedArgs {
     int max_blocks, block_tokens, n_act_used;
     int32_t *list;                     // [B, max_blocks] scratch: the checkpoint blocks of every request in logical order
     int32_t *count, *last_rows, *n_rows;   // [B] scratch each: their number, the rows of the last one, the request's checkpoint rows
+    int32_t *kv_table;                 // [B, max_blocks] scratch: the KV blocks of every request in logical order
+    int32_t *kv_len;                   // [B] scratch: the request's cached tokens
+    int64_t *kv_cu;                    // [B + 1] scratch: their prefix sums
 };
-// The same over a paged cache: the checkpoint rows of a request are found through its row of the block table.
+// The same over a paged cache: launch_paged_index builds the two views of the block table (checkpoint blocks, KV
+// blocks), the caller runs launch_paged_decode over the KV view (total_dev = kv_cu + B), launch_paged_absorbed does
+// the checkpoint part and the join.
+hipError_t launch_paged_index(const PagedAbsorbedArgs &a, hipStream_t s);
 hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &a, hipStream_t s);
 
 }  // namespace hk

@@ -50,17 +50,19 @@ __device__ __forceinline__ int request_of(const int64_t *__restrict__ cu, int B,
     return lo;
 }
 
-template <int DH, bool SKIP>
+template <int DH>
 __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
     const _Float16 *__restrict__ q,
     const _Float16 *__restrict__ K_pool, const _Float16 *__restrict__ V_pool,      // KV blocks
     const _Float16 *__restrict__ K_regen, const _Float16 *__restrict__ V_regen,    // regenerated ACT blocks
     const int32_t *__restrict__ table, int max_blocks, int P_kv, int P_act,
     const int32_t *__restrict__ seq_len, const int64_t *__restrict__ cu,
-    int B, int H, int blk_log2, int64_t total, int W, float scale_log2e,
+    int B, int H, int blk_log2, int64_t total_host, const int64_t *__restrict__ total_dev, int W, float scale_log2e,
     float *__restrict__ partial)
 {
     constexpr int LPR = DH / 8, RPL = 64 / LPR, NL = LPR;
+    // positions of the line: known to the host, or (tables built on the device) H * total_dev[0] <= the host's bound
+    const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
@@ -99,8 +101,6 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
             // last token are redirected to the last token's block and row, and masked below.
             int64_t kv_base[4];          // element offset of (block, head h, token 0 of the pair) in its pool
             bool kv_act[4];
-            bool kv_skip[4];             // skip_act: the tokens of ACT blocks take no part (they are attended elsewhere);
-                                         // their loads go to KV block 0 and their scores are masked
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int bi = (tb >> blk_log2) + j;
@@ -108,8 +108,6 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
                 const int32_t e = __builtin_amdgcn_readfirstlane(tab[bi]);
                 bool is_act = e < 0;
                 int pb = is_act ? ~e : e;
-                kv_skip[j] = SKIP && is_act;
-                if (kv_skip[j]) { is_act = false; pb = 0; }                       // skip_act implies P_kv > 0
                 if ((is_act ? P_act : P_kv) <= 0) { is_act = !is_act; pb = 0; }   // a corrupt table cannot leave
                 const int P = is_act ? P_act : P_kv;                              // the pools (one is not empty)
                 pb = pb < P ? pb : P - 1;
@@ -126,26 +124,14 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
                 const int j = (i * RPL) >> blk_log2;               // 0..3, wavefront-uniform
                 const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
                 const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
-                const bool sk = SKIP && (j == 0 ? kv_skip[0] : j == 1 ? kv_skip[1] : j == 2 ? kv_skip[2] : kv_skip[3]);
-                if (sk) {                                          // wavefront-uniform: the rows of a skipped block are not fetched
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) kr[i][e] = (_Float16)0.f;
-                } else {
-                    kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? K_regen : K_pool) + b + lane_off(i)));
-                }
+                kr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? K_regen : K_pool) + b + lane_off(i)));
             }
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
                 const int j = (i * RPL) >> blk_log2;
                 const int64_t b = j == 0 ? kv_base[0] : j == 1 ? kv_base[1] : j == 2 ? kv_base[2] : kv_base[3];
                 const bool a = j == 0 ? kv_act[0] : j == 1 ? kv_act[1] : j == 2 ? kv_act[2] : kv_act[3];
-                const bool sk = SKIP && (j == 0 ? kv_skip[0] : j == 1 ? kv_skip[1] : j == 2 ? kv_skip[2] : kv_skip[3]);
-                if (sk) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) vr[i][e] = (_Float16)0.f;
-                } else {
-                    vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? V_regen : V_pool) + b + lane_off(i)));
-                }
+                vr[i] = __builtin_nontemporal_load(reinterpret_cast<const half8_t *>((a ? V_regen : V_pool) + b + lane_off(i)));
             }
 
             float pd[NL];
@@ -163,9 +149,7 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
             }
             // lane (g, c) now owns the score of token tb + c*RPL + g
             const int my_t = tb + c * RPL + g;
-            const int my_j = (c * RPL) >> blk_log2;              // the block (of the tile's four) of this lane's token
-            const bool skipped = SKIP && (my_j == 0 ? kv_skip[0] : my_j == 1 ? kv_skip[1] : my_j == 2 ? kv_skip[2] : kv_skip[3]);
-            const float s = (my_t >= t_first && my_t < t_last && !skipped) ? pd[0] * scale_log2e : -INFINITY;
+            const float s = (my_t >= t_first && my_t < t_last) ? pd[0] * scale_log2e : -INFINITY;
 
             float m_tile = s;
 #pragma unroll
@@ -212,9 +196,10 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
 template <int DH>
 __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict__ partial,
                                                          const int32_t *__restrict__ seq_len, const int64_t *__restrict__ cu,
-                                                         int H, int64_t total, int W, _Float16 *__restrict__ out,
-                                                         float2 *__restrict__ lse)
+                                                         int H, int64_t total_host, const int64_t *__restrict__ total_dev, int W,
+                                                         _Float16 *__restrict__ out, float2 *__restrict__ lse)
 {
+    const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;   // > 0 whenever a pair has tokens
     const int pair = blockIdx.x, e = threadIdx.x;
     const int r = pair / H, h = pair % H;
     const int len = seq_len[r];
@@ -241,7 +226,7 @@ __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict
         o = __builtin_fmaf(wgt, src[i * (DH + 2) + 2 + e], o);
         l = __builtin_fmaf(wgt, src[i * (DH + 2) + 1], l);
     }
-    out[(int64_t)pair * DH + e] = (_Float16)(l > 0.f ? o / l : 0.f);   // l == 0: every token of the pair was skipped
+    out[(int64_t)pair * DH + e] = (_Float16)(o / l);
     if (lse && e == 0) lse[pair] = make_float2(mx, l);
 }
 
@@ -254,18 +239,17 @@ hipError_t launch_dh(const PagedAttnArgs &a, hipStream_t s)
     while ((1 << blk_log2) < a.block_tokens) ++blk_log2;
     if (total > 0) {
         const unsigned blocks = (unsigned)((a.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
-        auto kern = a.skip_act ? paged_decode_kernel<DH, true> : paged_decode_kernel<DH, false>;
-        hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), 0, s,
+        hipLaunchKernelGGL(paged_decode_kernel<DH>, dim3(blocks), dim3(kThreads), 0, s,
                            static_cast<const _Float16 *>(a.q),
                            static_cast<const _Float16 *>(a.K_pool), static_cast<const _Float16 *>(a.V_pool),
                            static_cast<const _Float16 *>(a.K_regen), static_cast<const _Float16 *>(a.V_regen),
                            a.block_table, a.max_blocks, a.P_kv, a.P_act, a.seq_len, a.cu_tokens,
-                           a.B, a.H, blk_log2, total, a.n_waves, scale_log2e, a.partial);
+                           a.B, a.H, blk_log2, total, a.total_dev, a.n_waves, scale_log2e, a.partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(paged_merge_kernel<DH>, dim3((unsigned)(a.B * a.H)), dim3(DH), 0, s,
-                       a.partial, a.seq_len, a.cu_tokens, a.H, total > 0 ? total : 1, a.n_waves > 0 ? a.n_waves : 1,
+                       a.partial, a.seq_len, a.cu_tokens, a.H, total > 0 ? total : 1, a.total_dev, a.n_waves > 0 ? a.n_waves : 1,
                        static_cast<_Float16 *>(a.out), a.lse);
     return hipGetLastError();
 }
@@ -276,7 +260,6 @@ hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (a.block_tokens < 16 || (a.block_tokens & (a.block_tokens - 1)) != 0) return hipErrorInvalidValue;
-    if (a.skip_act && a.P_kv <= 0) return hipErrorInvalidValue;
     if (a.total_tokens > 0 && (a.n_waves <= 0 || (int64_t)a.n_waves > (int64_t)a.H * a.total_tokens)) return hipErrorInvalidValue;
     if (a.head_dim == 128) return launch_dh<128>(a, s);
     if (a.head_dim == 64) return launch_dh<64>(a, s);
