@@ -297,12 +297,13 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape,
 
 /*
  * hk_paged_decode_attn without regenerating K/V: the two ideas above together.  Same arguments and the same
- * result up to rounding as hk_paged_decode_attn (Sec. 4.1, 4.2.1; Eq. 7, 3, 4).  The KV blocks take the
- * block-table attention kernel with the checkpoint blocks skipped; the checkpoint blocks of every request
- * are found through its table row and take the steps of hk_hybrid_decode_attn_absorbed (scores per block,
- * softmax per request over its own number of checkpoint rows, weighted row sum through the block list);
- * the two parts are joined through their softmax maxima and denominators.  A request without tokens gets
- * an all-zero output.  n_heads <= 128, B <= 65535; workspace: hk_paged_absorbed_workspace_bytes.
+ * result up to rounding as hk_paged_decode_attn (Sec. 4.1, 4.2.1; Eq. 7, 3, 4).  Every request's row of the
+ * block table is split on the device into its KV blocks and its checkpoint blocks, each in logical order.  The
+ * KV blocks take the block-table attention kernel; the checkpoint blocks take the steps of
+ * hk_hybrid_decode_attn_absorbed (scores per block, softmax per request over its own number of checkpoint
+ * rows, weighted row sum through the block list); the two parts are joined through their softmax maxima and
+ * denominators.  A request without tokens gets an all-zero output.  n_heads <= 128, B <= 65535; workspace:
+ * hk_paged_absorbed_workspace_bytes (scratch only; the table, seq_len and cu_tokens are not written).
  */
 size_t hk_paged_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache);
 int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t B, const hk_paged_cache *cache,
