@@ -152,7 +152,8 @@ def make_batch(cfg: LayerConfig, sequences=None, threads: int = 8) -> dict:
 
 def scatter_into_blocks(cfg: LayerConfig, batch: dict, seq_len, block_tokens: int, act_fraction: float, seed: int) -> dict:
     """Lays a contiguous hybrid context out as a paged cache: request b keeps ``seq_len[b]`` tokens; each of
-    its logical blocks becomes an ACT block with probability ``act_fraction`` and a KV block otherwise;
+    its logical blocks becomes an ACT block with probability ``act_fraction`` (one number, or one per request)
+    and a KV block otherwise;
     physical block numbers are a random permutation of each pool (with spare, never referenced blocks).
     ``batch`` needs ``act_full [B, L, d]`` (the layer inputs of every token) and ``K_full, V_full [B, H, L, dh]``
     (their K/V rows).  Data movement only: no arithmetic of the method."""
@@ -160,7 +161,8 @@ def scatter_into_blocks(cfg: LayerConfig, batch: dict, seq_len, block_tokens: in
     B, H, dh, d, bt = cfg.B, cfg.n_heads, cfg.head_dim, cfg.d, block_tokens
     n_blocks = [(int(n) + bt - 1) // bt for n in seq_len]
     max_blocks = max(max(n_blocks), 1)
-    kinds = [rng.random(nb) < act_fraction for nb in n_blocks]
+    frac = np.broadcast_to(np.asarray(act_fraction, dtype=np.float64), (B,))
+    kinds = [rng.random(nb) < frac[b] for b, nb in enumerate(n_blocks)]
     n_act = int(sum(int(k.sum()) for k in kinds))
     n_kv = int(sum(n_blocks)) - n_act
     P_act, P_kv = n_act + 2, n_kv + 3

@@ -141,6 +141,8 @@ GPU_CASES = [
     ("dh128_bt32", 1024, 8, 5, 700, 32, 0.4, None),
     ("all_kv", 512, 4, 4, 200, 16, 0.0, None),
     ("all_act", 512, 4, 3, 130, 64, 1.0, None),
+    # requests of one kind each beside mixed ones: the cached and the checkpoint part of a request can be empty
+    ("one_kind_each", 512, 4, 6, 210, 16, [0.0, 1.0, 0.5, 1.0, 0.0, 0.9], [210, 209, 100, 16, 17, 0]),
     ("opt6.7b_shape", 4096, 32, 32, 1024, 16, 0.5, None),     # the benchmark layer with ragged requests
 ]
 
