@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2501_01792_amd import synth
-from test_gpu_parity import MAX_ABS, REL_L2, SMALL, _cfg, _check, _gpu, _oracle_hybrid, _run_hybrid, hk  # noqa: F401
+from test_gpu_parity import SMALL, _cfg, _check, _gpu, _oracle_hybrid, _run_hybrid, hk  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 

@@ -4,8 +4,6 @@ seeded fp16 inputs.
 Tolerances (the contract of the benchmark): max abs error <= 2e-2 and relative L2 error
 <= 5e-3, for the attention output and, elementwise, for the regenerated K/V.
 """
-import dataclasses
-
 import numpy as np
 import pytest
 import torch
