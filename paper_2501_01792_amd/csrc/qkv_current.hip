@@ -36,36 +36,45 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-constexpr int kMaxVec = 20;              // rows of up to 64 * 8 * 20 = 10240 elements are held in registers
+constexpr int kMaxVec = 5;               // rows of up to 256 * 8 * 5 = 10240 elements are held in registers
 
-// xhat[r, :] = ((x[r, :] - mean) * rstd) * gamma + beta in fp32, rounded once to fp16.
-template <int NV>
+// xhat[r, :] = ((x[r, :] - mean) * rstd) * gamma + beta in fp32, rounded once to fp16.  One workgroup per row; the
+// row, gamma and beta are requested together (the launch is short and cold: one memory latency instead of two),
+// mean and centred sum of squares come from the register copy.
 __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict__ x, const _Float16 *__restrict__ gamma,
                                                       const _Float16 *__restrict__ beta, _Float16 *__restrict__ xhat,
                                                       _Float16 *__restrict__ act_dst, int64_t act_row_stride,
-                                                      int B, int d, float eps)
+                                                      int d, float eps)
 {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= B) return;                // whole wavefront leaves together; no barrier in this kernel
-    const half8_t *p = reinterpret_cast<const half8_t *>(x + (int64_t)row * d);
-    const int nvec = d >> 3;
-    half8_t v[NV];
+    __shared__ float red[2][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;                        // grid = rows
+    const half8_t *p = reinterpret_cast<const half8_t *>(x + row * d);
+    const half8_t *g8 = reinterpret_cast<const half8_t *>(gamma), *b8 = reinterpret_cast<const half8_t *>(beta);
+    const int nvec = d >> 3;                               // <= 256 kMaxVec (checked by the launcher)
+    const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    half8_t v[kMaxVec], g[kMaxVec], be[kMaxVec];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int idx = lane + 64 * i;
-        v[i] = idx < nvec ? p[idx] : half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < kMaxVec; ++i) {
+        const int idx = tid + 256 * i;
+        const bool ok = idx < nvec;
+        v[i] = ok ? p[idx] : zero;
+        g[i] = ok ? g8[idx] : zero;
+        be[i] = ok ? b8[idx] : zero;
     }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i)
+    for (int i = 0; i < kMaxVec; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) s += (float)v[i][j];
-    const float mean = wave_sum(s) / (float)d;
+    s = wave_sum(s);
+    if (lane == 0) red[0][wave] = s;
+    __syncthreads();
+    const float mean = (red[0][0] + red[0][1] + red[0][2] + red[0][3]) / (float)d;
     float sq = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        if (lane + 64 * i < nvec) {
+    for (int i = 0; i < kMaxVec; ++i) {
+        if (tid + 256 * i < nvec) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float c = (float)v[i][j] - mean;
@@ -73,18 +82,20 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
             }
         }
     }
-    const float rstd = 1.0f / __builtin_sqrtf(wave_sum(sq) / (float)d + eps);
-    half8_t *dst = reinterpret_cast<half8_t *>(xhat + (int64_t)row * d);
-    half8_t *ckpt = act_dst ? reinterpret_cast<half8_t *>(act_dst + (int64_t)row * act_row_stride) : nullptr;
+    sq = wave_sum(sq);
+    if (lane == 0) red[1][wave] = sq;
+    __syncthreads();
+    const float rstd = 1.0f / __builtin_sqrtf((red[1][0] + red[1][1] + red[1][2] + red[1][3]) / (float)d + eps);
+    half8_t *dst = reinterpret_cast<half8_t *>(xhat + row * d);
+    half8_t *ckpt = act_dst ? reinterpret_cast<half8_t *>(act_dst + row * act_row_stride) : nullptr;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int idx = lane + 64 * i;
+    for (int i = 0; i < kMaxVec; ++i) {
+        const int idx = tid + 256 * i;
         if (idx < nvec) {
-            const half8_t g = reinterpret_cast<const half8_t *>(gamma)[idx], be = reinterpret_cast<const half8_t *>(beta)[idx];
             half8_t o;
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                o[j] = (_Float16)__builtin_fmaf(((float)v[i][j] - mean) * rstd, (float)g[j], (float)be[j]);
+                o[j] = (_Float16)__builtin_fmaf(((float)v[i][j] - mean) * rstd, (float)g[i][j], (float)be[i][j]);
             dst[idx] = o;
             if (ckpt) ckpt[idx] = v[i];
         }
@@ -159,13 +170,12 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(
     }
 }
 
-template <int NV>
 hipError_t launch_ln_rows(const QkvArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(ln_rows_kernel<NV>, dim3((unsigned)((a.B + 3) / 4)), dim3(256), 0, s,
+    hipLaunchKernelGGL(ln_rows_kernel, dim3((unsigned)a.B), dim3(256), 0, s,
                        static_cast<const _Float16 *>(a.x), static_cast<const _Float16 *>(a.ln_w),
                        static_cast<const _Float16 *>(a.ln_b), static_cast<_Float16 *>(a.xhat),
-                       static_cast<_Float16 *>(a.act_dst), a.act_row_stride, a.B, a.d, a.eps);
+                       static_cast<_Float16 *>(a.act_dst), a.act_row_stride, a.d, a.eps);
     return hipGetLastError();
 }
 
@@ -188,14 +198,8 @@ hipError_t launch_block(const QkvArgs &a, int parts, int steps_per_part, hipStre
 hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    if (a.B > kQkvMaxRows || a.d % 64 != 0 || a.d > 64 * 8 * kMaxVec) return hipErrorInvalidValue;
-    hipError_t e;
-    const int nv = (a.d / 8 + 63) / 64;
-    if (nv <= 4) e = launch_ln_rows<4>(a, s);
-    else if (nv <= 8) e = launch_ln_rows<8>(a, s);
-    else if (nv <= 12) e = launch_ln_rows<12>(a, s);
-    else if (nv <= 16) e = launch_ln_rows<16>(a, s);
-    else e = launch_ln_rows<kMaxVec>(a, s);
+    if (a.B > kQkvMaxRows || a.d % 64 != 0 || a.d > 256 * 8 * kMaxVec) return hipErrorInvalidValue;
+    hipError_t e = launch_ln_rows(a, s);
     if (e != hipSuccess) return e;
     int parts, steps_per_part;
     qkv_parts(a.d, &parts, &steps_per_part);
