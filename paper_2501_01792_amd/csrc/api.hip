@@ -392,13 +392,24 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
     return HK_OK;
 }
 
+namespace {
+
+// Floats of fp32 partial sums that hk_qkv_current needs for B rows (rows are taken kQkvMaxRows at a time).
+size_t qkv_part_floats(int d, int64_t B)
+{
+    const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
+    int parts, steps_per_part;
+    hk::qkv_parts(d, &parts, &steps_per_part);
+    return (size_t)parts * rows * 3 * d;
+}
+
+}  // namespace
+
 size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
 {
     if (check_shape(shape) != HK_OK || B < 0 || B > (1 << 24)) return 0;
     const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
-    int parts, steps_per_part;
-    hk::qkv_parts(shape->d, &parts, &steps_per_part);
-    const size_t bytes = align_up(rows * (size_t)shape->d * 2) + align_up((size_t)parts * rows * 3 * shape->d * sizeof(float));
+    const size_t bytes = align_up(rows * (size_t)shape->d * 2) + align_up(qkv_part_floats(shape->d, B) * sizeof(float));
     return bytes > 0 ? bytes : kAlign;
 }
 
@@ -438,6 +449,7 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
         a.ln_w = params->ln_w; a.ln_b = params->ln_b; a.Wq = Wq; a.bq = bq; a.Wkv = params->Wkv; a.bkv = params->bkv;
         a.xhat = workspace;
         a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows) * d * 2));
+        a.part_floats = qkv_part_floats(d, B);
         a.q_out = static_cast<char *>(q_out) + (size_t)b0 * d * 2;
         a.K_dst = K_dst ? static_cast<char *>(K_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;
         a.V_dst = V_dst ? static_cast<char *>(V_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;

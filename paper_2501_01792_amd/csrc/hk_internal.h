@@ -74,6 +74,7 @@ struct QkvArgs {
     const void *Wkv, *bkv; // [2d, d], [2d]
     void *xhat;            // [B, d] fp16 scratch
     float *part;           // [parts, B, 3d] fp32 scratch (parts from qkv_parts)
+    size_t part_floats;    // its capacity in floats
     void *q_out;           // [B, H, dh]
     void *K_dst, *V_dst;   // [B, H, L_cap, dh] or both null: no K/V row is produced
     void *act_dst;         // null, or where row b of x is copied: act_dst + b * act_row_stride (elements)

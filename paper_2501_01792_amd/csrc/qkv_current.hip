@@ -203,6 +203,7 @@ hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
     if (e != hipSuccess) return e;
     int parts, steps_per_part;
     qkv_parts(a.d, &parts, &steps_per_part);
+    if ((size_t)parts * a.B * 3 * a.d > a.part_floats) return hipErrorInvalidValue;   // the scratch is too small for this cut
     switch ((a.B + 31) / 32) {
     case 1: e = launch_block<1>(a, parts, steps_per_part, s); break;
     case 2: e = launch_block<2>(a, parts, steps_per_part, s); break;
@@ -219,15 +220,16 @@ hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-// Parts of the reduction axis (d / 64 steps): enough workgroups to fill the chip about three times when Q, K
-// and V are produced, at least 4 steps per part, no empty part.  The same cut is used when only Q is
-// produced, so that q does not depend on whether K/V are asked for (the order of the fp32 sums is the same),
-// and the scratch size is one function of d.
+// Parts of the reduction axis (d / 64 steps): about two workgroups per compute unit when Q, K and V are produced
+// (measured cold on d = 4096 .. 9216: more parts cost more in fp32 partial sums than they gain in parallelism,
+// fewer leave the Q-only call with too few workgroups), at least 4 steps per part, no empty part.  The same cut
+// is used when only Q is produced, so that q does not depend on whether K/V are asked for (the order of the
+// fp32 sums is the same), and the scratch size is a function of d and the row count alone.
 void qkv_parts(int d, int *parts, int *steps_per_part)
 {
     const int steps = d / 64;
     const int blocks = (d + 127) / 128 + (2 * d + 127) / 128;
-    int want = (768 + blocks - 1) / blocks;
+    int want = 512 / blocks;
     if (want > steps / 4) want = steps / 4;
     if (want < 1) want = 1;
     if (want > 16) want = 16;
