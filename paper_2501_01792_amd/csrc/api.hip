@@ -270,12 +270,21 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
 
 namespace {
 
+// Floats of the output projection's partial sums for B sequences (taken kAbsorbMaxBatch at a time).
+size_t absorbed_proj_floats(const hk_shape *s, int64_t B)
+{
+    int parts, steps_per_part;
+    hk::absorbed_project_parts(s->d, s->n_heads, &parts, &steps_per_part);
+    const size_t rows = (size_t)(B < hk::kAbsorbMaxBatch ? B : hk::kAbsorbMaxBatch);
+    return (size_t)parts * rows * s->d;
+}
+
 struct AbsorbedPlan {
     int64_t M, BH;
     int n_waves;               // wavefronts of the attention kernel over the cached segment
     int Lp;
     float scale;
-    size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_partial, total;
+    size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_proj, off_partial, total;
 };
 
 int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, AbsorbedPlan *p)
@@ -299,6 +308,7 @@ int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act
     p->off_y = take(act ? bh * s->d * 2 : 0);
     p->off_outc = take(act ? bh * s->head_dim * 2 : 0);
     p->off_lse = take(act ? bh * sizeof(float2) : 0);
+    p->off_proj = take(act ? absorbed_proj_floats(s, B) * sizeof(float) : 0);
     p->n_waves = 0;
     p->off_partial = end;
     if (L_kv > 0 && p->BH > 0) {
@@ -386,6 +396,8 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
     a.out_c = ws + p.off_outc;
     a.lse_c = reinterpret_cast<const float2 *>(ws + p.off_lse);
     a.out = out;
+    a.proj_part = reinterpret_cast<float *>(ws + p.off_proj);
+    a.proj_part_floats = absorbed_proj_floats(shape, B);
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d; a.L_act = L_act; a.L_kv = L_kv;
     a.scale = p.scale; a.eps = shape->ln_eps;
     if (hk::launch_absorbed(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
@@ -562,7 +574,7 @@ struct PagedAbsorbedPlan {
     int n_waves, Lp;
     float scale;
     size_t off_stats, off_prep, off_u, off_raw, off_w, off_sums, off_y, off_outc, off_lse, off_list, off_count, off_last,
-        off_rows, off_kvtab, off_kvlen, off_kvcu, off_partial, total;
+        off_rows, off_kvtab, off_kvlen, off_kvcu, off_proj, off_partial, total;
 };
 
 int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedAbsorbedPlan *p)
@@ -595,6 +607,7 @@ int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache 
     p->off_kvtab = take(act ? b * c->max_blocks * sizeof(int32_t) : 0);
     p->off_kvlen = take(act ? b * sizeof(int32_t) : 0);
     p->off_kvcu = take(act ? (b + 1) * sizeof(int64_t) : 0);
+    p->off_proj = take(act ? absorbed_proj_floats(s, B) * sizeof(float) : 0);
     p->off_partial = end;
     // the attention over the KV blocks alone: sized for every token being cached (the device knows the true number)
     p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, hk::kPagedResidentWaves);
@@ -676,6 +689,8 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     a.out_c = ws + p.off_outc;
     a.lse_c = reinterpret_cast<const float2 *>(ws + p.off_lse);
     a.out = out;
+    a.proj_part = reinterpret_cast<float *>(ws + p.off_proj);
+    a.proj_part_floats = absorbed_proj_floats(shape, B);
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d;
     a.L_act = cache->max_blocks * cache->block_tokens; a.L_kv = kv ? 1 : 0;
     a.scale = p.scale; a.eps = shape->ln_eps;

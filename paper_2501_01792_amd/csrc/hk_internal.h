@@ -123,12 +123,15 @@ struct AbsorbedArgs {
     const void *out_c;         // [B, H, dh] fp16: attention over the cached segment alone (unused when L_kv == 0)
     const float2 *lse_c;       // [B, H]: its (maximum, denominator)
     void *out;                 // [B, H, dh] fp16
+    float *proj_part;          // optional scratch [parts, min(B, kAbsorbMaxBatch), d] fp32 (absorbed_project_parts): with it large
+    size_t proj_part_floats;   //   layers take the projection that cuts the reduction axis over workgroups; its capacity
     int B, H, head_dim, d, L_act, L_kv;
     float scale, eps;
 };
 constexpr int kAbsorbMaxHeads = 128;   // heads (rows of the small operand of the score product) per sequence
 constexpr int kAbsorbMaxBatch = 128;   // sequences one launch of the output projection takes
 int absorbed_row_pitch(int L_act);     // elements between the rows of w_raw and w
+void absorbed_project_parts(int d, int H, int *parts, int *steps_per_part);   // how the output projection cuts its reduction axis
 // The checkpoint part of the decode attention without regenerating K/V (see absorbed.hip).
 hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s);
 

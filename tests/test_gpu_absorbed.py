@@ -36,6 +36,12 @@ SHAPES = SMALL + [
     # 65536 checkpoint rows or more select the score kernel with 128-row workgroups; 1030 rows per sequence
     # leave a last workgroup with 6 rows (three of its wavefronts own none)
     _cfg("block_rows", 256, 4, 64, 1030, 0.0, 26),
+    # layers of 5120 features or more take the output projection that cuts the reduction axis over workgroups
+    # (a head per workgroup, partial sums, a join kernel): head_dim 128 and 64, 1 and 2 row blocks of sequences,
+    # and more than 128 sequences (two launches, the second with 2 rows)
+    _cfg("wide_dh128", 5120, 40, 3, 24, 0.25, 27),
+    _cfg("wide_dh64", 5120, 80, 45, 10, 0.2, 28),
+    _cfg("wide_batch130", 5120, 40, 130, 6, 0.5, 29),
 ]
 
 
