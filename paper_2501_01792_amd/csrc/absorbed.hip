@@ -33,6 +33,8 @@ namespace {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4_t *lds_short4_ptr;
 
 constexpr float kNegBig = -1.0e30f;
 
@@ -117,6 +119,9 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     for (int q = 0; q < 4; ++q) t_rd[q] = ln * 128 + (((2 * q + lh) ^ ((ln >> 1) & 7)) << 4);
     unsigned char *my = smem + wave * kColStage;
     unsigned char *tile = smem + 4 * kColStage;
+    // source address of this lane in the transposing reads of the private block: lane 16 g + t points at row
+    // 8 (g / 2) + t / 4, columns 16 (g % 2) + 4 (t % 4) .. + 3 (of column block nb: + 32 nb; second read: 4 rows on)
+    const int tr_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * XS + 2 * (16 * ((lane >> 4) & 1) + 4 * (lane & 3));
 
     float16_t acc[RB][NB];
 #pragma unroll
@@ -190,12 +195,16 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
                             *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = sv[u][j];
+                        // bf[nb][i] = element (row 8 lh + i, column 32 nb + ln) of the block, by two transposing reads:
+                        // ds_read_b64_tr_b16 hands lane t of a 16-lane group the four rows that the group's lanes
+                        // 4 j + t / 4 .. point at, at column 4 (source lane % 4) + ... = t of the group's 16 columns
                         half8_t bf[NB];
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                            for (int i = 0; i < 8; ++i)
-                                bf[nb][i] = *reinterpret_cast<const _Float16 *>(my + (8 * lh + i) * XS + 2 * (32 * nb + ln));
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(my + tr_off + 64 * nb));
+                            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(my + tr_off + 64 * nb + 4 * XS));
+                            bf[nb] = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                        }
 #pragma unroll
                         for (int rb = 0; rb < RB; ++rb) {
                             const half8_t af = *reinterpret_cast<const half8_t *>(tile + (gg * RB + rb) * kTileBytes + t_rd[q]);
