@@ -57,8 +57,8 @@ __device__ __forceinline__ float wave_max(float v)
 // The streamed operand S is row-major and the reduction runs over its ROWS, so it reaches the matrix cores
 // transposed.  Every wavefront owns a block of 64 columns and walks all R rows in steps of 16: whole 128-byte
 // pieces of 16 rows go from HBM to registers (kDepth - 1 steps in flight) and row-wise into the wavefront's
-// private LDS block, from which every lane picks the 8 values of its column (rows padded by 16 bytes: the two
-// half-wavefronts then use disjoint banks).  The small operand A (few rows, reduction axis contiguous, zero
+// private LDS block, from which every lane takes the 8 values of its column with two transposing reads
+// (ds_read_b64_tr_b16; rows 192 bytes apart, so that the four rows one such read touches fall on disjoint banks).  The small operand A (few rows, reduction axis contiguous, zero
 // beyond R up to the next multiple of 64) is the same for the four wavefronts of a workgroup: it is fetched
 // once per 64 reduction elements with whole-line loads, two tiles ahead, and shared through a double-buffered
 // LDS tile (one barrier per 64 reduction elements).  The result (minus an optional per-row constant, in fp32)
@@ -76,7 +76,8 @@ struct ColArgs {
 };
 
 constexpr int kColBlock = 64;                              // columns of one wavefront
-constexpr int kColStage = 32 * (2 * kColBlock + 16);       // bytes of private LDS per wavefront: 32 rows of 128 + 16 bytes
+constexpr int kColPitch = 2 * kColBlock + 64;               // bytes between rows of a wavefront's private LDS block
+constexpr int kColStage = 32 * kColPitch;                  // bytes of private LDS per wavefront
 constexpr int kTileBytes = 32 * 128;                       // 32 operand rows x 64 reduction elements
 
 template <int RB>
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NB = kColBlock / 32;
-    constexpr int XS = 2 * kColBlock + 16;                 // bytes between rows of the private LDS block
+    constexpr int XS = kColPitch;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     int c0 = (blockIdx.x * 4 + wave) * kColBlock;
