@@ -46,7 +46,9 @@ CASES = [
     synth.LayerConfig("rows33", 1024, 8, 33, 8, 0.5, 42),            # two row blocks, ragged
     synth.LayerConfig("rows130_dh64", 1280, 20, 130, 8, 0.5, 43),    # more rows than one launch takes; d/64 = 20 steps
     synth.CONFIGS["opt6.7b"],
+    synth.CONFIGS["opt13b"],                                         # B = 64, d = 5120
     synth.CONFIGS["opt30b"],                                         # B = 128, d = 7168
+    synth.CONFIGS["opt66b"],                                         # B = 64, d = 9216: the reduction axis in 2 parts
 ]
 
 
