@@ -397,16 +397,24 @@ def make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu_tokens, 
 
 def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_tokens, layer_params,
                       n_act_used=None, out=None, ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None,
-                      absorbed=False):
+                      absorbed=False, cu_tokens=None, total_tokens=None):
     """hk_paged_decode_attn: ``q[B,H,dh]``, pools, ``block_table[B,max_blocks]`` int32, ``seq_len[B]`` int32 (GPU
-    tensors) -> ``out[B,H,dh]``.  The prefix sums and the host-side total are derived here from ``seq_len``.
-    ``absorbed`` selects hk_paged_decode_attn_absorbed (the same step without regenerating K/V)."""
+    tensors) -> ``out[B,H,dh]``.  ``cu_tokens[B+1]`` int64 (GPU) and ``total_tokens`` are the prefix sums of
+    ``seq_len`` and their last element; when not given they are derived here (a device scan and a copy to the
+    host, which a caller that keeps its tables on the device between steps, or captures the step in a graph,
+    passes in instead).  ``absorbed`` selects hk_paged_decode_attn_absorbed (the same step without regenerating
+    K/V)."""
     import torch
     B, H, dh = q.shape
     shape = make_shape(H * dh, H, ln_eps, softmax_scale)
-    cu = torch.zeros(B + 1, dtype=torch.int64, device=q.device)
-    cu[1:] = torch.cumsum(seq_len.to(torch.int64), 0)
-    total = int(cu[-1].item())
+    if cu_tokens is None or total_tokens is None:
+        cu = torch.zeros(B + 1, dtype=torch.int64, device=q.device)
+        cu[1:] = torch.cumsum(seq_len.to(torch.int64), 0)
+        total = int(cu[-1].item())
+    else:
+        if cu_tokens.dtype != torch.int64 or cu_tokens.numel() != B + 1 or not cu_tokens.is_cuda:
+            raise ValueError("cu_tokens: int64 GPU tensor of B + 1 elements")
+        cu, total = cu_tokens, int(total_tokens)
     cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used)
     if out is None:
         out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)

@@ -99,8 +99,16 @@ def measure_paged(args):
     lp = lp + (hk.prepare_layer(*lp, H),)
     tb, sl = torch.from_numpy(table).cuda(), torch.from_numpy(lens.astype(np.int32)).cuda()
     out = torch.empty(B, H, dh, device="cuda", dtype=f16)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)).cuda()   # the tables live on the device
+    total = int(lens.sum())
+    shape = hk.make_shape(d, H)
+    cache = hk.make_paged_cache(Kp if n_kv else None, Vp if n_kv else None, Ap if n_act else None, tb, sl, cu, total, bt, n_act)
+    size_fn = hk.lib().hk_paged_absorbed_workspace_bytes if args.absorbed else hk.lib().hk_paged_workspace_bytes
+    import ctypes
+    ws = hk.new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))))
     call = lambda: hk.paged_decode_attn(q, Kp if n_kv else None, Vp if n_kv else None, Ap if n_act else None, tb, sl, bt, lp,
-                                        n_act_used=n_act, out=out, absorbed=args.absorbed)
+                                        n_act_used=n_act, out=out, absorbed=args.absorbed, cu_tokens=cu, total_tokens=total,
+                                        workspace=ws)
     for _ in range(2):
         call()
     ts = []

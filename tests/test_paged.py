@@ -199,3 +199,59 @@ def test_paged_decode_without_a_kv_pool(absorbed):
     ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
                                 paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
     _check("out", out.cpu().numpy(), ref)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("absorbed", [False, True], ids=["regenerating", "absorbed"])
+def test_paged_decode_replayed_from_a_graph(absorbed):
+    """The paged step captured in a HIP graph (tables, prefix sums and workspace on the device, nothing allocated
+    inside): every replay, with eager work and synchronisations in between and the inputs changed before the
+    last one, equals the eager result.  The entry point without regeneration sizes its launch on the host and
+    reads the number of cached tokens from the device, inside the graph."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("paged_graph", 512, 4, 5, 180, 0.5, 54)
+    p, batch = _context(cfg, 9)
+    seq_len = [180, 7, 64, 0, 131]
+    bt = 16
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, [0.5, 1.0, 0.0, 0.5, 0.3], seed=10)
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    q, Kp, Vp, Ap = g(batch["q"]), g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"])
+    tb, sl = g(paged["block_table"]), g(paged["seq_len"])
+    cu = g(np.concatenate([[0], np.cumsum(seq_len)]).astype(np.int64))
+    total = int(sum(seq_len))
+    shape = hk.make_shape(cfg.d, cfg.n_heads)
+    cache = hk.make_paged_cache(Kp, Vp, Ap, tb, sl, cu, total, bt, paged["n_act_used"])
+    size_fn = hk.lib().hk_paged_absorbed_workspace_bytes if absorbed else hk.lib().hk_paged_workspace_bytes
+    ws = hk.new_workspace(int(size_fn(ctypes.byref(shape), cfg.B, ctypes.byref(cache))))
+    out = torch.empty(cfg.B, cfg.n_heads, cfg.head_dim, dtype=torch.float16, device="cuda")
+    run = lambda stream: hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=paged["n_act_used"], out=out,
+                                              absorbed=absorbed, cu_tokens=cu, total_tokens=total, workspace=ws, stream=stream)
+    run(None)                                                  # eager (also sets kernel attributes before the capture)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
+                                paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
+    _check("eager", eager.cpu().numpy(), ref)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(torch.cuda.current_stream())
+    for i in range(3):
+        out.fill_(7.0)
+        ws.view(torch.uint8).fill_(0xff)                       # stale scratch must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d differs from the eager result" % i
+        (q.float().sum() + Kp.float().sum()).item()            # eager work between the replays
+    q.mul_(0.5)                                                # new inputs, same addresses
+    run(None)
+    torch.cuda.synchronize()
+    eager2 = out.clone()
+    out.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager2)
+    assert not torch.equal(eager2, eager)
