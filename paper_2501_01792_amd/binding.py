@@ -313,18 +313,19 @@ def hk_qkv_workspace_bytes(shape: hk_shape, B: int) -> int:
 
 def qkv_current(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, q_out=None, K_dst=None, V_dst=None, tok_pos=0,
                 act_dst=None, act_pos=0, ln_eps=1e-5, workspace=None, stream=None):
-    """hk_qkv_current: ``x_cur[B, d]`` fp16 -> ``q[B, H, dh]``; writes the token's K/V row ``tok_pos`` into
-    ``K_dst, V_dst[B, H, L_cap, dh]`` and/or its input row ``act_pos`` into ``act_dst[B, act_cap, d]`` when given."""
+    """hk_qkv_current: ``x_cur[B, d]`` (fp16, or bf16 with every other tensor) -> ``q[B, H, dh]``; writes the
+    token's K/V row ``tok_pos`` into ``K_dst, V_dst[B, H, L_cap, dh]`` and/or its input row ``act_pos`` into
+    ``act_dst[B, act_cap, d]`` when given."""
     import torch
-    f16 = torch.float16
+    f16 = x_cur.dtype if x_cur.dtype == torch.bfloat16 else torch.float16
     B, d = x_cur.shape
-    shape = make_shape(d, n_heads, ln_eps)
+    shape = make_shape(d, n_heads, ln_eps, dtype=_dtype_code(x_cur))
     dh = d // n_heads
     if q_out is None:
         q_out = torch.empty((B, n_heads, dh), dtype=f16, device=x_cur.device)
     if workspace is None:
         workspace = new_workspace(hk_qkv_workspace_bytes(shape, B), x_cur.device)
-    lp = _params(ln_w, ln_b, Wkv, bkv)
+    lp = _params(ln_w, ln_b, Wkv, bkv, el=f16)
     L_cap = 0 if K_dst is None else K_dst.shape[2]
     act_cap = 0 if act_dst is None else act_dst.shape[1]
     st = lib().hk_qkv_current(ctypes.byref(shape), _dev_ptr(x_cur, "x_cur", f16), B, ctypes.byref(lp),

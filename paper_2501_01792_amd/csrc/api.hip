@@ -419,7 +419,7 @@ size_t qkv_part_floats(int d, int64_t B)
 
 size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
 {
-    if (check_shape(shape) != HK_OK || B < 0 || B > (1 << 24)) return 0;
+    if (check_shape(shape, true) != HK_OK || B < 0 || B > (1 << 24)) return 0;
     const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
     const size_t bytes = align_up(rows * (size_t)shape->d * 2) + align_up(qkv_part_floats(shape->d, B) * sizeof(float));
     return bytes > 0 ? bytes : kAlign;
@@ -432,7 +432,7 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
                    void *act_dst, int32_t act_cap, int32_t act_pos,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
-    int st = check_shape(shape);
+    int st = check_shape(shape, true);
     if (st != HK_OK) return st;
     if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
     if ((K_dst == nullptr) != (V_dst == nullptr)) return HK_ERR_NULL;
@@ -468,7 +468,7 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
         a.act_dst = act_dst ? static_cast<char *>(act_dst) + ((size_t)b0 * act_cap + act_pos) * d * 2 : nullptr;
         a.act_row_stride = (int64_t)act_cap * d;
         a.B = rows; a.d = d; a.n_heads = shape->n_heads; a.head_dim = shape->head_dim;
-        a.L_cap = L_cap; a.tok_pos = tok_pos; a.eps = shape->ln_eps;
+        a.L_cap = L_cap; a.tok_pos = tok_pos; a.eps = shape->ln_eps; a.dtype = shape->dtype;
         if (hk::launch_qkv_current(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     }
     return HK_OK;

@@ -7,6 +7,7 @@
 namespace hk {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16v_t __attribute__((ext_vector_type(16)));
 
 template <int DT>
 struct Elem;
@@ -20,6 +21,10 @@ struct Elem<0> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
     }
+    static __device__ __forceinline__ float16v_t mfma_32x32x16(V8 a, V8 b, float16v_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
     static __device__ __forceinline__ float dot2(V2 a, V2 b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
 };
 
@@ -31,6 +36,10 @@ struct Elem<1> {
     static __device__ __forceinline__ float4_t mfma_16x16x32(V8 a, V8 b, float4_t c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float16v_t mfma_32x32x16(V8 a, V8 b, float16v_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
     static __device__ __forceinline__ float dot2(V2 a, V2 b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
 };

@@ -81,6 +81,7 @@ struct QkvArgs {
     int64_t act_row_stride;
     int B, d, n_heads, head_dim, L_cap, tok_pos;
     float eps;
+    int dtype;             // 0: fp16, 1: bf16 (every 16-bit tensor above)
 };
 constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel takes
 // How the projection of the current tokens cuts the reduction axis over workgroups.

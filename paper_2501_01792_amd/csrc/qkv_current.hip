@@ -19,6 +19,7 @@
 //               takes to fill the chip; every part leaves an fp32 partial result in scratch.
 //   qkv_finish: sums the parts, adds the bias, rounds to fp16 and scatters to q / K / V.
 #include "hk_internal.h"
+#include "elem.h"
 #include "skinny_mma.h"
 
 namespace hk {
@@ -38,21 +39,28 @@ __device__ __forceinline__ float wave_sum(float v)
 
 constexpr int kMaxVec = 5;               // rows of up to 256 * 8 * 5 = 10240 elements are held in registers
 
-// xhat[r, :] = ((x[r, :] - mean) * rstd) * gamma + beta in fp32, rounded once to fp16.  One workgroup per row; the
+// xhat[r, :] = ((x[r, :] - mean) * rstd) * gamma + beta in fp32, rounded once to the storage type.  One workgroup per row; the
 // row, gamma and beta are requested together (the launch is short and cold: one memory latency instead of two),
 // mean and centred sum of squares come from the register copy.
-__global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict__ x, const _Float16 *__restrict__ gamma,
-                                                      const _Float16 *__restrict__ beta, _Float16 *__restrict__ xhat,
-                                                      _Float16 *__restrict__ act_dst, int64_t act_row_stride,
+template <int DT>
+__global__ __launch_bounds__(256) void ln_rows_kernel(const typename Elem<DT>::T *__restrict__ x,
+                                                      const typename Elem<DT>::T *__restrict__ gamma,
+                                                      const typename Elem<DT>::T *__restrict__ beta,
+                                                      typename Elem<DT>::T *__restrict__ xhat,
+                                                      typename Elem<DT>::T *__restrict__ act_dst, int64_t act_row_stride,
                                                       int d, float eps)
 {
+    typedef typename Elem<DT>::T elem_t;
+    typedef typename Elem<DT>::V8 half8_t;
     __shared__ float red[2][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;                        // grid = rows
     const half8_t *p = reinterpret_cast<const half8_t *>(x + row * d);
     const half8_t *g8 = reinterpret_cast<const half8_t *>(gamma), *b8 = reinterpret_cast<const half8_t *>(beta);
     const int nvec = d >> 3;                               // <= 256 kMaxVec (checked by the launcher)
-    const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    half8_t zero;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) zero[j] = (elem_t)0.f;
     half8_t v[kMaxVec], g[kMaxVec], be[kMaxVec];
 #pragma unroll
     for (int i = 0; i < kMaxVec; ++i) {
@@ -95,7 +103,7 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
             half8_t o;
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                o[j] = (_Float16)__builtin_fmaf(((float)v[i][j] - mean) * rstd, (float)g[i][j], (float)be[i][j]);
+                o[j] = (elem_t)__builtin_fmaf(((float)v[i][j] - mean) * rstd, (float)g[i][j], (float)be[i][j]);
             dst[idx] = o;
             if (ckpt) ckpt[idx] = v[i];
         }
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const _Float16 *__restrict
 
 // Feature blocks: 128 rows of Wq (ceil(d / 128) blocks), then 128 rows of [Wk; Wv] (ceil(2d / 128) blocks),
 // so that a block never straddles the two weight arrays.  Partials: part[ks][m][n], n in [0, 3d) fp32.
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void qkv_block_kernel(
     const _Float16 *__restrict__ xhat, const _Float16 *__restrict__ Wq, const _Float16 *__restrict__ Wkv,
     float *__restrict__ part, int B, int d, int q_blocks, int steps_per_part)
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(256) void qkv_block_kernel(
     float16_t acc[RB];
     float m1[4], m2[4];
     _Float16 first[4];
-    skinny::block_product<RB, true, false>(W, n_rows, d, xhat, B, d, k_begin, k_steps, smem, acc, m1, m2, first);
+    skinny::block_product<RB, true, false, DT>(W, n_rows, d, xhat, B, d, k_begin, k_steps, smem, acc, m1, m2, first);
     // acc[rb][r]: row (sequence) 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature 32 wave + lane%32 of the block
     const int ln = lane & 31, lh = lane >> 5;
     const int c = 32 * wave + ln;
@@ -140,14 +148,16 @@ __global__ __launch_bounds__(256) void qkv_block_kernel(
     }
 }
 
-// out[m][n] = fp16(sum_ks part[ks][m][n] + bias[n]), 4 features per thread, scattered to q / K / V.
+// out[m][n] = sum_ks part[ks][m][n] + bias[n], rounded to the storage type, 4 features per thread, scattered to q / K / V.
+template <int DT>
 __global__ __launch_bounds__(256) void qkv_finish_kernel(
-    const float *__restrict__ part, int parts, const _Float16 *__restrict__ bq, const _Float16 *__restrict__ bkv,
-    _Float16 *__restrict__ q_out, _Float16 *__restrict__ K_dst, _Float16 *__restrict__ V_dst,
+    const float *__restrict__ part, int parts, const typename Elem<DT>::T *__restrict__ bq,
+    const typename Elem<DT>::T *__restrict__ bkv, typename Elem<DT>::T *__restrict__ q_out,
+    typename Elem<DT>::T *__restrict__ K_dst, typename Elem<DT>::T *__restrict__ V_dst,
     int B, int d, int n_out, int n_heads, int head_dim, int L_cap, int tok_pos)
 {
-    typedef float float4_t __attribute__((ext_vector_type(4)));
-    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    typedef typename Elem<DT>::T elem_t;
+    typedef elem_t half4_t __attribute__((ext_vector_type(4)));
     const int per_row = n_out / 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)B * per_row) return;
@@ -157,33 +167,36 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(
     float4_t sum = *reinterpret_cast<const float4_t *>(src);
     for (int ks = 1; ks < parts; ++ks) sum += *reinterpret_cast<const float4_t *>(src + ks * stride);
     const int which = n / d, nn = n - which * d;                           // 0: q, 1: k, 2: v
-    const _Float16 *bias = which == 0 ? bq + nn : bkv + (which - 1) * d + nn;
+    const elem_t *bias = which == 0 ? bq + nn : bkv + (which - 1) * d + nn;
     half4_t o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = (_Float16)(sum[i] + (float)bias[i]);
+    for (int i = 0; i < 4; ++i) o[i] = (elem_t)(sum[i] + (float)bias[i]);
     if (which == 0) {
         *reinterpret_cast<half4_t *>(q_out + (int64_t)m * d + nn) = o;
     } else {
         const int h = nn / head_dim, e = nn % head_dim;
-        _Float16 *dst = which == 1 ? K_dst : V_dst;
+        elem_t *dst = which == 1 ? K_dst : V_dst;
         *reinterpret_cast<half4_t *>(dst + (((int64_t)m * n_heads + h) * L_cap + tok_pos) * head_dim + e) = o;
     }
 }
 
+template <int DT>
 hipError_t launch_ln_rows(const QkvArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(ln_rows_kernel, dim3((unsigned)a.B), dim3(256), 0, s,
-                       static_cast<const _Float16 *>(a.x), static_cast<const _Float16 *>(a.ln_w),
-                       static_cast<const _Float16 *>(a.ln_b), static_cast<_Float16 *>(a.xhat),
-                       static_cast<_Float16 *>(a.act_dst), a.act_row_stride, a.d, a.eps);
+    typedef typename Elem<DT>::T elem_t;
+    hipLaunchKernelGGL(ln_rows_kernel<DT>, dim3((unsigned)a.B), dim3(256), 0, s,
+                       static_cast<const elem_t *>(a.x), static_cast<const elem_t *>(a.ln_w),
+                       static_cast<const elem_t *>(a.ln_b), static_cast<elem_t *>(a.xhat),
+                       static_cast<elem_t *>(a.act_dst), a.act_row_stride, a.d, a.eps);
     return hipGetLastError();
 }
 
-template <int RB>
+// The operands are handed to skinny::block_product as 16-bit elements of either format (same size and addressing).
+template <int RB, int DT>
 hipError_t launch_block(const QkvArgs &a, int parts, int steps_per_part, hipStream_t s)
 {
     const int q_blocks = (a.d + 127) / 128, kv_blocks = a.K_dst ? (2 * a.d + 127) / 128 : 0;
-    auto kern = qkv_block_kernel<RB>;
+    auto kern = qkv_block_kernel<RB, DT>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
@@ -193,31 +206,38 @@ hipError_t launch_block(const QkvArgs &a, int parts, int steps_per_part, hipStre
     return hipGetLastError();
 }
 
+template <int DT>
+hipError_t launch_dt(const QkvArgs &a, hipStream_t s)
+{
+    typedef typename Elem<DT>::T elem_t;
+    hipError_t e = launch_ln_rows<DT>(a, s);
+    if (e != hipSuccess) return e;
+    int parts, steps_per_part;
+    qkv_parts(a.d, &parts, &steps_per_part);
+    if ((size_t)parts * a.B * 3 * a.d > a.part_floats) return hipErrorInvalidValue;   // the scratch is too small for this cut
+    switch ((a.B + 31) / 32) {
+    case 1: e = launch_block<1, DT>(a, parts, steps_per_part, s); break;
+    case 2: e = launch_block<2, DT>(a, parts, steps_per_part, s); break;
+    case 3: e = launch_block<3, DT>(a, parts, steps_per_part, s); break;
+    default: e = launch_block<4, DT>(a, parts, steps_per_part, s); break;
+    }
+    if (e != hipSuccess) return e;
+    const int n_out = (a.K_dst ? 3 : 1) * a.d;
+    const int64_t threads = (int64_t)a.B * (n_out / 4);
+    hipLaunchKernelGGL(qkv_finish_kernel<DT>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       a.part, parts, static_cast<const elem_t *>(a.bq), static_cast<const elem_t *>(a.bkv),
+                       static_cast<elem_t *>(a.q_out), static_cast<elem_t *>(a.K_dst), static_cast<elem_t *>(a.V_dst),
+                       a.B, a.d, n_out, a.n_heads, a.head_dim, a.L_cap, a.tok_pos);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (a.B > kQkvMaxRows || a.d % 64 != 0 || a.d > 256 * 8 * kMaxVec) return hipErrorInvalidValue;
-    hipError_t e = launch_ln_rows(a, s);
-    if (e != hipSuccess) return e;
-    int parts, steps_per_part;
-    qkv_parts(a.d, &parts, &steps_per_part);
-    if ((size_t)parts * a.B * 3 * a.d > a.part_floats) return hipErrorInvalidValue;   // the scratch is too small for this cut
-    switch ((a.B + 31) / 32) {
-    case 1: e = launch_block<1>(a, parts, steps_per_part, s); break;
-    case 2: e = launch_block<2>(a, parts, steps_per_part, s); break;
-    case 3: e = launch_block<3>(a, parts, steps_per_part, s); break;
-    default: e = launch_block<4>(a, parts, steps_per_part, s); break;
-    }
-    if (e != hipSuccess) return e;
-    const int n_out = (a.K_dst ? 3 : 1) * a.d;
-    const int64_t threads = (int64_t)a.B * (n_out / 4);
-    hipLaunchKernelGGL(qkv_finish_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
-                       a.part, parts, static_cast<const _Float16 *>(a.bq), static_cast<const _Float16 *>(a.bkv),
-                       static_cast<_Float16 *>(a.q_out), static_cast<_Float16 *>(a.K_dst), static_cast<_Float16 *>(a.V_dst),
-                       a.B, a.d, n_out, a.n_heads, a.head_dim, a.L_cap, a.tok_pos);
-    return hipGetLastError();
+    return a.dtype == 1 ? launch_dt<1>(a, s) : launch_dt<0>(a, s);
 }
 
 // Parts of the reduction axis (d / 64 steps): about two workgroups per compute unit when Q, K and V are produced

@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem.h"
+
 namespace hk {
 namespace skinny {
 
@@ -239,12 +241,15 @@ constexpr int block_lds_bytes() { return 4 * kBlockBytes + 2 * RB * kBlockBytes;
 
 // row_of(r) is the address of streamed row r, r < n_rows (rows need not be evenly spaced: they may sit in
 // blocks scattered over a pool).
-template <int RB, bool NT, bool STATS, typename RowOf>
+// DT = 1: the operands are bfloat16 (same size and addressing; passed as _Float16 pointers, reinterpreted for the
+// MFMA); STATS is for fp16 only.
+template <int RB, bool NT, bool STATS, int DT = 0, typename RowOf>
 __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
                                                    const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                                    int k_begin, int k_steps, unsigned char *smem,
                                                    float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
 {
+    static_assert(DT == 0 || !STATS, "row moments are taken in fp16");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g_row = lane >> 3, g_chunk = lane & 7;
@@ -342,7 +347,12 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         const half8_t af = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlockBytes + rd_off[jj]);
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
+                        if constexpr (DT == 1) {
+                            typedef typename Elem<1>::V8 bf8_t;
+                            acc[rb] = Elem<1>::mfma_32x32x16(__builtin_bit_cast(bf8_t, af), __builtin_bit_cast(bf8_t, wf), acc[rb]);
+                        } else {
+                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
+                        }
                     }
                 }
                 __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
@@ -361,13 +371,13 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
 }
 
 // Evenly spaced rows: S is the first row of the block, ld_s the distance between rows.
-template <int RB, bool NT, bool STATS>
+template <int RB, bool NT, bool STATS, int DT = 0>
 __device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, int n_rows, int64_t ld_s,
                                               const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                               int k_begin, int k_steps, unsigned char *smem,
                                               float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
 {
-    block_product_rows<RB, NT, STATS>([=](int r) { return S + (int64_t)r * ld_s; }, n_rows, A, a_rows, ld_a, k_begin, k_steps,
+    block_product_rows<RB, NT, STATS, DT>([=](int r) { return S + (int64_t)r * ld_s; }, n_rows, A, a_rows, ld_a, k_begin, k_steps,
                                       smem, acc, m1, m2, first);
 }
 

@@ -73,13 +73,15 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
     bf = hk.make_shape(768, 12, dtype=hk.HK_DTYPE_BF16)                      # bf16: taken by the step ...
     assert _attn(bf, ratio=0.25) == hk.HK_ERR_RATIO and _attn(bf, q=None) == hk.HK_ERR_NULL
     assert hk.hk_workspace_bytes(bf, 4, 128, 128) > 0 and hk.hk_prepared_bytes(bf) == hk.hk_prepared_bytes(hk.make_shape(768, 12))
-    # ... and by no other entry point
+    # ... and by the QKV generation of the current token (same checks as in fp16: here the misplaced token) ...
     lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+    assert hk.hk_qkv_workspace_bytes(bf, 4) == hk.hk_qkv_workspace_bytes(ok, 4) > 0
+    assert hk.lib().hk_qkv_current(ctypes.byref(bf), FAKE, 4, ctypes.byref(lp), FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8,
+                                   None, 0, 0, FAKE, 1 << 40, None) == hk.HK_ERR_SHAPE
+    # ... and by no other entry point
     assert hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(bf), FAKE, FAKE, FAKE, 128, FAKE, 128, 4, ctypes.byref(lp), 0.5,
                                                    FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_DTYPE
     assert hk.hk_absorbed_workspace_bytes(bf, 4, 128, 128) == 0
-    assert hk.lib().hk_qkv_current(ctypes.byref(bf), FAKE, 4, ctypes.byref(lp), FAKE, FAKE, FAKE, FAKE, FAKE, 8, 1,
-                                   None, 0, 0, FAKE, 1 << 40, None) == hk.HK_ERR_DTYPE
     assert _attn(hk.make_shape(768, 12, attn_splits=65)) == hk.HK_ERR_SHAPE
     assert _attn(hk.make_shape(768, 12, gemm_tile=64)) == hk.HK_ERR_SHAPE
     assert _attn(ok, ratio=1.5) == hk.HK_ERR_RATIO

@@ -1,4 +1,4 @@
-"""GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn with HK_DTYPE_BF16)
+"""GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn, hk_qkv_current with HK_DTYPE_BF16)
 against the CPU oracle fed with the same bf16-rounded inputs.
 
 The benchmark's tolerance is stated for fp16.  A bf16 value carries 8 significant bits, so the output
@@ -107,3 +107,36 @@ def test_bf16_full_size_opt6p7b_sampled(hk, oracle):
         ref.append(oracle.decode_attention(h["q"][b:b + 1, hd:hd + 1], Kb[None, None], Vb[None, None])[0, 0])
         got.append(out[b, hd])
     _check("out[sampled (b,h)]", torch.stack(got), np.stack(ref))
+
+
+@pytest.mark.parametrize("cfg", [synth.LayerConfig("tiny", 768, 12, 4, 256, 0.5, 0),
+                                 synth.LayerConfig("rows33", 1024, 8, 33, 8, 0.5, 42),
+                                 synth.LayerConfig("rows130_dh64", 1280, 20, 130, 8, 0.5, 43),
+                                 synth.CONFIGS["opt6.7b"]], ids=lambda c: c.name)
+def test_bf16_qkv_current_matches_oracle(hk, oracle, cfg):
+    """QKV generation of the current token in bf16: q, the K/V rows written into the caches, the checkpoint copy."""
+    print("case", cfg, flush=True)
+    p, c = synth.make_params(cfg), synth.make_current_token(cfg)
+    g, h = {}, {}
+    for k, v in {**p, **c}.items():
+        g[k], h[k] = _bf16(v)
+    B, H, dh, d = cfg.B, cfg.n_heads, cfg.head_dim, cfg.d
+    L_cap, pos, act_cap, apos = 5, 3, 4, 1
+    K = torch.full((B, H, L_cap, dh), 7.0, dtype=torch.bfloat16, device="cuda")
+    V = torch.full((B, H, L_cap, dh), -7.0, dtype=torch.bfloat16, device="cuda")
+    A = torch.full((B, act_cap, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    q = hk.qkv_current(g["x_cur"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], g["Wq"], g["bq"], H,
+                       K_dst=K, V_dst=V, tok_pos=pos, act_dst=A, act_pos=apos)
+    torch.cuda.synchronize()
+    assert q.dtype == torch.bfloat16
+    rq, rk, rv = oracle.qkv_current(h["x_cur"], h["ln_w"], h["ln_b"], h["Wq"], h["bq"], h["Wkv"], h["bkv"], H)
+    _check("q", q, rq)
+    _check("k", K[:, :, pos], rk)
+    _check("v", V[:, :, pos], rv)
+    assert torch.equal(A[:, apos], g["x_cur"])                     # the checkpoint is the layer input, bit for bit
+    keep = [i for i in range(L_cap) if i != pos]
+    assert (K[:, :, keep] == 7.0).all() and (V[:, :, keep] == -7.0).all()
+    assert (A[:, [i for i in range(act_cap) if i != apos]] == 3.0).all()
+    q2 = hk.qkv_current(g["x_cur"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], g["Wq"], g["bq"], H)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2)                                      # q does not depend on whether K/V are produced
