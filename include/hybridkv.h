@@ -14,9 +14,10 @@
  *     passed by pointer and read before the call returns.
  *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16), the precision of the paper's
  *     models (Sec. 6.1); accumulation is fp32.  hk_prepare_layer, hk_regen_kv,
- *     the hybrid step (hk_hybrid_decode_attn, _marked) and hk_qkv_current, with
- *     their size queries, also take bfloat16 (HK_DTYPE_BF16: every fp16 tensor
- *     below is bf16 instead); the other entry points return HK_ERR_DTYPE for it.
+ *     the hybrid step (hk_hybrid_decode_attn, _marked), hk_qkv_current and
+ *     hk_paged_decode_attn, with their size queries, also take bfloat16
+ *     (HK_DTYPE_BF16: every fp16 tensor below is bf16 instead); the two entry
+ *     points that do not regenerate K/V (_absorbed) return HK_ERR_DTYPE for it.
  *   - The library allocates nothing.  Scratch memory is the caller's
  *     `workspace` (device, 256-byte aligned, at least hk_workspace_bytes()).
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the

@@ -382,10 +382,11 @@ def minibatch_balance(T_kv_gen, T_load_kv, n_act_mb, n_kv_mb):
 
 # ----------------------------------------------------------------------------- paged hybrid cache
 def make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu_tokens, total_tokens, block_tokens,
-                     n_act_used=None) -> hk_paged_cache:
-    """Fills an hk_paged_cache from GPU tensors (pools may be None when empty)."""
+                     n_act_used=None, el=None) -> hk_paged_cache:
+    """Fills an hk_paged_cache from GPU tensors (pools may be None when empty; ``el``: their element type,
+    fp16 unless given)."""
     import torch
-    f16 = torch.float16
+    f16 = el or torch.float16
     P_kv = 0 if K_pool is None else K_pool.shape[0]
     P_act = 0 if act_pool is None else act_pool.shape[0]
     ptr = lambda t, name, dt: (_dev_ptr(t, name, dt).value if t is not None else None)
@@ -407,7 +408,8 @@ def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_t
     K/V)."""
     import torch
     B, H, dh = q.shape
-    shape = make_shape(H * dh, H, ln_eps, softmax_scale)
+    el = q.dtype if q.dtype == torch.bfloat16 else torch.float16
+    shape = make_shape(H * dh, H, ln_eps, softmax_scale, dtype=_dtype_code(q))
     if cu_tokens is None or total_tokens is None:
         cu = torch.zeros(B + 1, dtype=torch.int64, device=q.device)
         cu[1:] = torch.cumsum(seq_len.to(torch.int64), 0)
@@ -416,16 +418,16 @@ def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_t
         if cu_tokens.dtype != torch.int64 or cu_tokens.numel() != B + 1 or not cu_tokens.is_cuda:
             raise ValueError("cu_tokens: int64 GPU tensor of B + 1 elements")
         cu, total = cu_tokens, int(total_tokens)
-    cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used)
+    cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used, el=el)
     if out is None:
-        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+        out = torch.empty((B, H, dh), dtype=el, device=q.device)
     size_fn = lib().hk_paged_absorbed_workspace_bytes if absorbed else lib().hk_paged_workspace_bytes
     entry = lib().hk_paged_decode_attn_absorbed if absorbed else lib().hk_paged_decode_attn
     if workspace is None:
         workspace = new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))), q.device)
-    lp = _params(*layer_params) if layer_params is not None else None
-    st = entry(ctypes.byref(shape), _dev_ptr(q, "q", torch.float16), B, ctypes.byref(cache),
-                                    ctypes.byref(lp) if lp is not None else None, _dev_ptr(out, "out", torch.float16),
+    lp = _params(*layer_params, el=el) if layer_params is not None else None
+    st = entry(ctypes.byref(shape), _dev_ptr(q, "q", el), B, ctypes.byref(cache),
+                                    ctypes.byref(lp) if lp is not None else None, _dev_ptr(out, "out", el),
                                     _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_paged_decode_attn_absorbed" if absorbed else "hk_paged_decode_attn")

@@ -483,9 +483,9 @@ struct PagedPlan {
     size_t off_k, off_v, off_stats, off_prep, off_partial, total;
 };
 
-int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p)
+int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p, bool allow_bf16 = false)
 {
-    int st = check_shape(s);
+    int st = check_shape(s, allow_bf16);
     if (st != HK_OK) return st;
     if (!c) return HK_ERR_NULL;
     if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
@@ -504,7 +504,7 @@ int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, Paged
     p->off_stats = 2 * kv_bytes;
     size_t end = p->off_stats + align_up((size_t)p->M * sizeof(float2));
     p->off_prep = end;
-    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile)) end += prepared_layout(s->d).total;
+    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile, s->dtype)) end += prepared_layout(s->d).total;
     p->off_partial = end;
     p->n_waves = hk::attn_wavefronts(s->n_heads, c->total_tokens, 0, hk::kPagedResidentWaves);
     end += align_up(((size_t)p->n_waves + (size_t)B * s->n_heads) * (s->head_dim + 2) * sizeof(float));
@@ -517,7 +517,7 @@ int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, Paged
 size_t hk_paged_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache)
 {
     PagedPlan p;
-    if (make_paged_plan(shape, B, cache, &p) != HK_OK) return 0;
+    if (make_paged_plan(shape, B, cache, &p, true) != HK_OK) return 0;
     return p.total > 0 ? p.total : kAlign;
 }
 
@@ -526,7 +526,7 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     PagedPlan p;
-    int st = make_paged_plan(shape, B, cache, &p);
+    int st = make_paged_plan(shape, B, cache, &p, true);
     if (st != HK_OK) return st;
     if (B == 0) return HK_OK;
     if (!q || !out || !workspace || !cache->block_table || !cache->seq_len || !cache->cu_tokens) return HK_ERR_NULL;
@@ -563,7 +563,7 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
-    a.total_dev = nullptr; a.lse = nullptr;
+    a.total_dev = nullptr; a.lse = nullptr; a.dtype = shape->dtype;
     if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -659,7 +659,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     t.P_kv = cache->P_kv; t.P_act = 0; t.block_tokens = cache->block_tokens;
     t.B = B; t.H = shape->n_heads; t.head_dim = shape->head_dim; t.scale = p.scale; t.n_waves = p.n_waves;
     t.partial = reinterpret_cast<float *>(ws + p.off_partial);
-    t.out = out; t.total_dev = nullptr; t.lse = nullptr;
+    t.out = out; t.total_dev = nullptr; t.lse = nullptr; t.dtype = 0;
     if (!act) {                                            // no checkpoint block in use: the block-table attention is the whole step
         if (hk::launch_paged_decode(t, hs) != hipSuccess) return HK_ERR_LAUNCH;
         return HK_OK;

@@ -106,6 +106,7 @@ struct PagedAttnArgs {
     const int64_t *total_dev;          // optional (device): the sum of seq_len when only the device knows it; total_tokens
                                        // is then an upper bound (it sizes the launch)
     float2 *lse;                       // optional [B H]: (maximum in the log2 domain, denominator) of every pair; (., 0) when empty
+    int dtype;                         // 0: fp16, 1: bf16 (q, the pools, out)
 };
 // Single-query attention of B requests of different lengths over a block-table-addressed hybrid cache.
 hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);

@@ -13,26 +13,26 @@
 // rows, which never straddles a block), and tiles are aligned to 64 tokens inside a pair so that the
 // rows of one load instruction share a block.
 #include "hk_internal.h"
+#include "elem.h"
 
 namespace hk {
 namespace {
-
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = 4;
 constexpr int kTile = 64;
 constexpr float kNegBig = -1.0e30f;
 
-__device__ __forceinline__ float dot8(half8_t a, half8_t b)
+template <int DT>
+__device__ __forceinline__ float dot8(typename Elem<DT>::V8 a, typename Elem<DT>::V8 b)
 {
+    typedef typename Elem<DT>::V2 half2_t;
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         half2_t x = {a[2 * j], a[2 * j + 1]};
         half2_t y = {b[2 * j], b[2 * j + 1]};
-        s = __builtin_amdgcn_fdot2(x, y, s, false);
+        s = Elem<DT>::dot2(x, y, s);
     }
     return s;
 }
@@ -50,16 +50,17 @@ __device__ __forceinline__ int request_of(const int64_t *__restrict__ cu, int B,
     return lo;
 }
 
-template <int DH>
+template <int DH, int DT>
 __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
-    const _Float16 *__restrict__ q,
-    const _Float16 *__restrict__ K_pool, const _Float16 *__restrict__ V_pool,      // KV blocks
-    const _Float16 *__restrict__ K_regen, const _Float16 *__restrict__ V_regen,    // regenerated ACT blocks
+    const typename Elem<DT>::T *__restrict__ q,
+    const typename Elem<DT>::T *__restrict__ K_pool, const typename Elem<DT>::T *__restrict__ V_pool,      // KV blocks
+    const typename Elem<DT>::T *__restrict__ K_regen, const typename Elem<DT>::T *__restrict__ V_regen,    // regenerated ACT blocks
     const int32_t *__restrict__ table, int max_blocks, int P_kv, int P_act,
     const int32_t *__restrict__ seq_len, const int64_t *__restrict__ cu,
     int B, int H, int blk_log2, int64_t total_host, const int64_t *__restrict__ total_dev, int W, float scale_log2e,
     float *__restrict__ partial)
 {
+    typedef typename Elem<DT>::V8 half8_t;
     constexpr int LPR = DH / 8, RPL = 64 / LPR, NL = LPR;
     // positions of the line: known to the host, or (tables built on the device) H * total_dev[0] <= the host's bound
     const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
 
             float pd[NL];
 #pragma unroll
-            for (int i = 0; i < NL; ++i) pd[i] = dot8(qv, kr[i]);
+            for (int i = 0; i < NL; ++i) pd[i] = dot8<DT>(qv, kr[i]);
 #pragma unroll
             for (int hh = NL / 2; hh >= 1; hh >>= 1) {
                 const bool up = (c & hh) != 0;
@@ -193,18 +194,18 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
 }
 
 // Merge of the partials of one (request, head): positions [H cu[r] + h len, + len) of the line.
-template <int DH>
+template <int DH, int DT>
 __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict__ partial,
                                                          const int32_t *__restrict__ seq_len, const int64_t *__restrict__ cu,
                                                          int H, int64_t total_host, const int64_t *__restrict__ total_dev, int W,
-                                                         _Float16 *__restrict__ out, float2 *__restrict__ lse)
+                                                         typename Elem<DT>::T *__restrict__ out, float2 *__restrict__ lse)
 {
     const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;   // > 0 whenever a pair has tokens
     const int pair = blockIdx.x, e = threadIdx.x;
     const int r = pair / H, h = pair % H;
     const int len = seq_len[r];
     if (len <= 0) {                      // no context: the softmax is over nothing; define the output as zero
-        out[(int64_t)pair * DH + e] = (_Float16)0.f;
+        out[(int64_t)pair * DH + e] = (typename Elem<DT>::T)0.f;
         if (lse && e == 0) lse[pair] = make_float2(kNegBig, 0.f);
         return;
     }
@@ -226,31 +227,32 @@ __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict
         o = __builtin_fmaf(wgt, src[i * (DH + 2) + 2 + e], o);
         l = __builtin_fmaf(wgt, src[i * (DH + 2) + 1], l);
     }
-    out[(int64_t)pair * DH + e] = (_Float16)(o / l);
+    out[(int64_t)pair * DH + e] = (typename Elem<DT>::T)(o / l);
     if (lse && e == 0) lse[pair] = make_float2(mx, l);
 }
 
-template <int DH>
+template <int DH, int DT>
 hipError_t launch_dh(const PagedAttnArgs &a, hipStream_t s)
 {
+    typedef typename Elem<DT>::T elem_t;
     const int64_t total = (int64_t)a.H * a.total_tokens;
     const float scale_log2e = a.scale * 1.4426950408889634f;
     int blk_log2 = 0;
     while ((1 << blk_log2) < a.block_tokens) ++blk_log2;
     if (total > 0) {
         const unsigned blocks = (unsigned)((a.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
-        hipLaunchKernelGGL(paged_decode_kernel<DH>, dim3(blocks), dim3(kThreads), 0, s,
-                           static_cast<const _Float16 *>(a.q),
-                           static_cast<const _Float16 *>(a.K_pool), static_cast<const _Float16 *>(a.V_pool),
-                           static_cast<const _Float16 *>(a.K_regen), static_cast<const _Float16 *>(a.V_regen),
+        hipLaunchKernelGGL((paged_decode_kernel<DH, DT>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const elem_t *>(a.q),
+                           static_cast<const elem_t *>(a.K_pool), static_cast<const elem_t *>(a.V_pool),
+                           static_cast<const elem_t *>(a.K_regen), static_cast<const elem_t *>(a.V_regen),
                            a.block_table, a.max_blocks, a.P_kv, a.P_act, a.seq_len, a.cu_tokens,
                            a.B, a.H, blk_log2, total, a.total_dev, a.n_waves, scale_log2e, a.partial);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(paged_merge_kernel<DH>, dim3((unsigned)(a.B * a.H)), dim3(DH), 0, s,
+    hipLaunchKernelGGL((paged_merge_kernel<DH, DT>), dim3((unsigned)(a.B * a.H)), dim3(DH), 0, s,
                        a.partial, a.seq_len, a.cu_tokens, a.H, total > 0 ? total : 1, a.total_dev, a.n_waves > 0 ? a.n_waves : 1,
-                       static_cast<_Float16 *>(a.out), a.lse);
+                       static_cast<elem_t *>(a.out), a.lse);
     return hipGetLastError();
 }
 
@@ -261,8 +263,8 @@ hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s)
     if (a.B <= 0) return hipSuccess;
     if (a.block_tokens < 16 || (a.block_tokens & (a.block_tokens - 1)) != 0) return hipErrorInvalidValue;
     if (a.total_tokens > 0 && (a.n_waves <= 0 || (int64_t)a.n_waves > (int64_t)a.H * a.total_tokens)) return hipErrorInvalidValue;
-    if (a.head_dim == 128) return launch_dh<128>(a, s);
-    if (a.head_dim == 64) return launch_dh<64>(a, s);
+    if (a.head_dim == 128) return a.dtype == 1 ? launch_dh<128, 1>(a, s) : launch_dh<128, 0>(a, s);
+    if (a.head_dim == 64) return a.dtype == 1 ? launch_dh<64, 1>(a, s) : launch_dh<64, 0>(a, s);
     return hipErrorInvalidValue;
 }
 

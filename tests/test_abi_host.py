@@ -78,7 +78,7 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
     assert hk.hk_qkv_workspace_bytes(bf, 4) == hk.hk_qkv_workspace_bytes(ok, 4) > 0
     assert hk.lib().hk_qkv_current(ctypes.byref(bf), FAKE, 4, ctypes.byref(lp), FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8,
                                    None, 0, 0, FAKE, 1 << 40, None) == hk.HK_ERR_SHAPE
-    # ... and by no other entry point
+    # ... but not by the entry points that do not regenerate K/V
     assert hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(bf), FAKE, FAKE, FAKE, 128, FAKE, 128, 4, ctypes.byref(lp), 0.5,
                                                    FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_DTYPE
     assert hk.hk_absorbed_workspace_bytes(bf, 4, 128, 128) == 0

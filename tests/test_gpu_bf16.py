@@ -1,4 +1,5 @@
-"""GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn, hk_qkv_current with HK_DTYPE_BF16)
+"""GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn, hk_qkv_current,
+hk_paged_decode_attn with HK_DTYPE_BF16)
 against the CPU oracle fed with the same bf16-rounded inputs.
 
 The benchmark's tolerance is stated for fp16.  A bf16 value carries 8 significant bits, so the output
@@ -140,3 +141,36 @@ def test_bf16_qkv_current_matches_oracle(hk, oracle, cfg):
     q2 = hk.qkv_current(g["x_cur"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], g["Wq"], g["bq"], H)
     torch.cuda.synchronize()
     assert torch.equal(q, q2)                                      # q does not depend on whether K/V are produced
+
+
+@pytest.mark.parametrize("case", [("dh64_bt16", 768, 12, 6, 300, 16, 0.5, [300, 1, 16, 0, 97, 255]),
+                                  ("dh128_bt32", 1024, 8, 5, 700, 32, 0.4, [700, 33, 512, 64, 699]),
+                                  ("all_kv", 512, 4, 4, 200, 16, 0.0, [200, 17, 128, 1])], ids=lambda c: c[0])
+def test_bf16_paged_decode_matches_oracle(hk, case):
+    """hk_paged_decode_attn in bf16 (block-table attention over KV blocks and regenerated checkpoint blocks)
+    against the paged oracle fed with the same bf16-rounded pools, parameters and queries."""
+    from oracle import paged_oracle as pgo
+    from test_paged import _context
+    name, d, H, B, L, bt, frac, seq_len = case
+    print("case", case, flush=True)
+    cfg = synth.LayerConfig(name, d, H, B, L, 0.5, 56)
+    p, batch = _context(cfg, 13)
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, frac, seed=14)
+    g, h = {}, {}
+    for k, v in {**p, "q": batch["q"], "K_pool": paged["K_pool"], "V_pool": paged["V_pool"], "act_pool": paged["act_pool"]}.items():
+        g[k], h[k] = _bf16(v)
+    tb = torch.from_numpy(paged["block_table"]).cuda()
+    sl = torch.from_numpy(paged["seq_len"]).cuda()
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    out = hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"])
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16
+    ref = pgo.paged_decode_attn(h["q"], h["K_pool"], h["V_pool"], h["act_pool"], paged["block_table"], paged["seq_len"], bt,
+                                h["ln_w"], h["ln_b"], h["Wkv"], h["bkv"], H)
+    _check("out", out, ref)
+    for b in range(B):
+        if seq_len[b] == 0:
+            assert (out[b] == 0).all()
+    with pytest.raises(hk.HybridKVError):                          # the entry point without regeneration is fp16 only
+        hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"],
+                             absorbed=True)
