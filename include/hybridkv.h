@@ -255,6 +255,24 @@ typedef struct hk_paged_cache {
 } hk_paged_cache;
 
 /*
+ * hk_qkv_current with the write-back into a paged cache (Sec. 4.2.2 on the block layout of Sec. 4.1): the input
+ * token of request r is token seq_len[r] - 1 of its context, i.e. seq_len already counts it and its logical
+ * block has its entry in the table (which kind of block a new block is, is the caller's policy: Eq. 11,
+ * hk_next_block_type).  Its K and V rows go to row (seq_len[r] - 1) % block_tokens of that KV block, or, when the
+ * entry names an ACT block, its layer input x_cur[r] goes to that row of the ACT block.  q is produced for every
+ * request.  The POOLS ARE WRITTEN by this call (one row of one block per request; the struct declares them const
+ * for the calls that only read them); block_table and seq_len are read; cu_tokens, total_tokens and n_act_used
+ * are not used.  A request with seq_len[r] == 0 and an entry outside its pool (KV: >= P_kv, ACT: >= P_act) are
+ * not written.  K and V are not computed when there is no KV pool (P_kv == 0).  Other arguments, workspace
+ * (hk_qkv_workspace_bytes) and errors as for hk_qkv_current; block_tokens not a power of two in 16 .. 1024 or
+ * max_blocks <= 0: HK_ERR_SHAPE.  fp16 or bf16.
+ */
+int hk_qkv_current_paged(const hk_shape *shape, const void *x_cur, int32_t B,
+                         const hk_layer_params *params, const void *Wq, const void *bq,
+                         void *q_out, const hk_paged_cache *cache,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The hybrid-cache decode step on a paged cache: regenerate the K/V rows of the ACT blocks in use
  * (Sec. 3.3, Eq. 7, over the whole activation pool prefix as one GEMM), then for the decode query of
  * every (request, head) attend over all of the request's tokens through the block table (Eq. 3, 4).

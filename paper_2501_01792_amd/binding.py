@@ -107,6 +107,9 @@ def lib():
         L.hk_paged_absorbed_workspace_bytes.argtypes = L.hk_paged_workspace_bytes.argtypes
         L.hk_paged_decode_attn_absorbed.restype = ctypes.c_int
         L.hk_paged_decode_attn_absorbed.argtypes = L.hk_paged_decode_attn.argtypes
+        L.hk_qkv_current_paged.restype = ctypes.c_int
+        L.hk_qkv_current_paged.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp, vp,
+                                           ctypes.POINTER(hk_paged_cache), vp, sz, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.hk_fit_line.restype = ctypes.c_int
         L.hk_fit_line.argtypes = [dp, dp, i32, ctypes.POINTER(hk_line), dp]
@@ -335,6 +338,30 @@ def qkv_current(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, q_out=None, K_dst=
                               _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_qkv_current")
+    return q_out
+
+
+def qkv_current_paged(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, K_pool, V_pool, act_pool, block_table, seq_len,
+                      block_tokens, q_out=None, ln_eps=1e-5, workspace=None, stream=None):
+    """hk_qkv_current_paged: ``x_cur[B, d]`` -> ``q[B, H, dh]``; the token of request r (token ``seq_len[r] - 1``)
+    is written into the block its table entry names: K/V rows into ``K_pool, V_pool``, or the layer input into
+    ``act_pool`` (pools may be None when empty; they are modified in place)."""
+    import torch
+    f16 = x_cur.dtype if x_cur.dtype == torch.bfloat16 else torch.float16
+    B, d = x_cur.shape
+    shape = make_shape(d, n_heads, ln_eps, dtype=_dtype_code(x_cur))
+    if q_out is None:
+        q_out = torch.empty((B, n_heads, d // n_heads), dtype=f16, device=x_cur.device)
+    if workspace is None:
+        workspace = new_workspace(hk_qkv_workspace_bytes(shape, B), x_cur.device)
+    lp = _params(ln_w, ln_b, Wkv, bkv, el=f16)
+    cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, None, 0, block_tokens, el=f16)
+    st = lib().hk_qkv_current_paged(ctypes.byref(shape), _dev_ptr(x_cur, "x_cur", f16), B, ctypes.byref(lp),
+                                    _dev_ptr(Wq, "Wq", f16), _dev_ptr(bq, "bq", f16), _dev_ptr(q_out, "q_out", f16),
+                                    ctypes.byref(cache), _dev_ptr(workspace, "workspace"), workspace.numel(),
+                                    _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_qkv_current_paged")
     return q_out
 
 

@@ -425,16 +425,38 @@ size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
     return bytes > 0 ? bytes : kAlign;
 }
 
-int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
-                   const hk_layer_params *params, const void *Wq, const void *bq,
-                   void *q_out,
-                   void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
-                   void *act_dst, int32_t act_cap, int32_t act_pos,
-                   void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+
+// paged == nullptr: the stores are contiguous (K_dst, V_dst, act_dst with their capacities and positions);
+// otherwise they are the pools of *paged and the destination of every row comes from its block table.
+int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
+             const hk_layer_params *params, const void *Wq, const void *bq,
+             void *q_out,
+             void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
+             void *act_dst, int32_t act_cap, int32_t act_pos, const hk_paged_cache *paged,
+             void *workspace, size_t workspace_bytes, void *stream)
 {
     int st = check_shape(shape, true);
     if (st != HK_OK) return st;
     if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
+    int blk_log2 = 0;
+    if (paged) {
+        const int bt = paged->block_tokens;
+        if (bt < 16 || bt > 1024 || (bt & (bt - 1)) != 0) return HK_ERR_SHAPE;
+        if (paged->P_kv < 0 || paged->P_act < 0 || paged->max_blocks <= 0) return HK_ERR_SHAPE;
+        if ((long double)((long double)paged->P_kv + paged->P_act) * bt * shape->d > 4.0e12L) return HK_ERR_SHAPE;
+        if ((long double)B * paged->max_blocks > 2.0e9L) return HK_ERR_SHAPE;
+        while ((1 << blk_log2) < bt) ++blk_log2;
+        // the pools are this call's outputs (the struct declares them const for the calls that only read them)
+        K_dst = paged->P_kv > 0 ? const_cast<void *>(paged->K_pool) : nullptr;
+        V_dst = paged->P_kv > 0 ? const_cast<void *>(paged->V_pool) : nullptr;
+        act_dst = paged->P_act > 0 ? const_cast<void *>(paged->act_pool) : nullptr;
+        if (B > 0 && (!paged->block_table || !paged->seq_len)) return HK_ERR_NULL;
+        if (B > 0 && paged->P_kv > 0 && (!K_dst || !V_dst)) return HK_ERR_NULL;
+        if (B > 0 && paged->P_act > 0 && !act_dst) return HK_ERR_NULL;
+        if (!aligned(paged->block_table, 4) || !aligned(paged->seq_len, 4)) return HK_ERR_ALIGN;
+        L_cap = 1; tok_pos = 0; act_cap = 1; act_pos = 0;
+    }
     if ((K_dst == nullptr) != (V_dst == nullptr)) return HK_ERR_NULL;
     if (K_dst && (L_cap <= 0 || tok_pos < 0 || tok_pos >= L_cap)) return HK_ERR_SHAPE;
     if (act_dst && (act_cap <= 0 || act_pos < 0 || act_pos >= act_cap)) return HK_ERR_SHAPE;
@@ -463,15 +485,43 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
         a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows) * d * 2));
         a.part_floats = qkv_part_floats(d, B);
         a.q_out = static_cast<char *>(q_out) + (size_t)b0 * d * 2;
-        a.K_dst = K_dst ? static_cast<char *>(K_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;
-        a.V_dst = V_dst ? static_cast<char *>(V_dst) + (size_t)b0 * L_cap * d * 2 : nullptr;
-        a.act_dst = act_dst ? static_cast<char *>(act_dst) + ((size_t)b0 * act_cap + act_pos) * d * 2 : nullptr;
+        a.K_dst = K_dst ? static_cast<char *>(K_dst) + (paged ? 0 : (size_t)b0 * L_cap * d * 2) : nullptr;
+        a.V_dst = V_dst ? static_cast<char *>(V_dst) + (paged ? 0 : (size_t)b0 * L_cap * d * 2) : nullptr;
+        a.act_dst = act_dst ? static_cast<char *>(act_dst) + (paged ? 0 : ((size_t)b0 * act_cap + act_pos) * d * 2) : nullptr;
         a.act_row_stride = (int64_t)act_cap * d;
         a.B = rows; a.d = d; a.n_heads = shape->n_heads; a.head_dim = shape->head_dim;
         a.L_cap = L_cap; a.tok_pos = tok_pos; a.eps = shape->ln_eps; a.dtype = shape->dtype;
+        a.block_table = nullptr; a.seq_len = nullptr; a.max_blocks = 0; a.blk_log2 = 0; a.P_kv = 0; a.P_act = 0;
+        if (paged) {
+            a.block_table = paged->block_table + (size_t)b0 * paged->max_blocks; a.seq_len = paged->seq_len + b0;
+            a.max_blocks = paged->max_blocks; a.blk_log2 = blk_log2; a.P_kv = paged->P_kv; a.P_act = paged->P_act;
+        }
         if (hk::launch_qkv_current(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     }
     return HK_OK;
+}
+
+}  // namespace
+
+int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
+                   const hk_layer_params *params, const void *Wq, const void *bq,
+                   void *q_out,
+                   void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
+                   void *act_dst, int32_t act_cap, int32_t act_pos,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qkv_impl(shape, x_cur, B, params, Wq, bq, q_out, K_dst, V_dst, L_cap, tok_pos, act_dst, act_cap, act_pos, nullptr,
+                    workspace, workspace_bytes, stream);
+}
+
+int hk_qkv_current_paged(const hk_shape *shape, const void *x_cur, int32_t B,
+                         const hk_layer_params *params, const void *Wq, const void *bq,
+                         void *q_out, const hk_paged_cache *cache,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cache) return HK_ERR_NULL;
+    return qkv_impl(shape, x_cur, B, params, Wq, bq, q_out, nullptr, nullptr, 0, 0, nullptr, 0, 0, cache,
+                    workspace, workspace_bytes, stream);
 }
 
 namespace {

@@ -82,6 +82,12 @@ struct QkvArgs {
     int B, d, n_heads, head_dim, L_cap, tok_pos;
     float eps;
     int dtype;             // 0: fp16, 1: bf16 (every 16-bit tensor above)
+    // Write-back into a paged cache instead (block_table != nullptr): row b is token seq_len[b] - 1 of request b;
+    // its logical block's table entry names the KV block (K_dst, V_dst are then the pools [P_kv, H, 2^blk_log2, dh])
+    // or the ACT block (act_dst is then the pool [P_act, 2^blk_log2, d]) that takes the row.  Requests without
+    // tokens and entries outside the pools are not written.
+    const int32_t *block_table, *seq_len;
+    int max_blocks, blk_log2, P_kv, P_act;
 };
 constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel takes
 // How the projection of the current tokens cuts the reduction axis over workgroups.

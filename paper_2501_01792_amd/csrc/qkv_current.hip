@@ -37,6 +37,24 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Where the current token of a request goes in a paged cache (QkvArgs): its table entry and its row in the block,
+// or row < 0 when the request has no token or the table has no entry for it.
+struct PagedDst {
+    const int32_t *block_table, *seq_len;      // block_table == nullptr: contiguous stores
+    int max_blocks, blk_log2, P_kv, P_act;
+};
+__device__ __forceinline__ void paged_slot(const PagedDst &p, int b, int32_t &entry, int &row)
+{
+    row = -1;
+    entry = 0;
+    const int t = p.seq_len[b] - 1;
+    if (t < 0) return;
+    const int bi = t >> p.blk_log2;
+    if (bi >= p.max_blocks) return;
+    entry = p.block_table[(int64_t)b * p.max_blocks + bi];
+    row = t & ((1 << p.blk_log2) - 1);
+}
+
 constexpr int kMaxVec = 5;               // rows of up to 256 * 8 * 5 = 10240 elements are held in registers
 
 // xhat[r, :] = ((x[r, :] - mean) * rstd) * gamma + beta in fp32, rounded once to the storage type.  One workgroup per row; the
@@ -48,7 +66,7 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const typename Elem<DT>::T
                                                       const typename Elem<DT>::T *__restrict__ beta,
                                                       typename Elem<DT>::T *__restrict__ xhat,
                                                       typename Elem<DT>::T *__restrict__ act_dst, int64_t act_row_stride,
-                                                      int d, float eps)
+                                                      int d, float eps, PagedDst pd)
 {
     typedef typename Elem<DT>::T elem_t;
     typedef typename Elem<DT>::V8 half8_t;
@@ -96,6 +114,13 @@ __global__ __launch_bounds__(256) void ln_rows_kernel(const typename Elem<DT>::T
     const float rstd = 1.0f / __builtin_sqrtf((red[1][0] + red[1][1] + red[1][2] + red[1][3]) / (float)d + eps);
     half8_t *dst = reinterpret_cast<half8_t *>(xhat + row * d);
     half8_t *ckpt = act_dst ? reinterpret_cast<half8_t *>(act_dst + row * act_row_stride) : nullptr;
+    if (pd.block_table) {                                  // paged: the row of the ACT block named by the table, if it is one
+        int32_t entry;
+        int r;
+        paged_slot(pd, (int)row, entry, r);
+        ckpt = (act_dst && r >= 0 && entry < 0 && ~entry < pd.P_act)
+                   ? reinterpret_cast<half8_t *>(act_dst + ((((int64_t)~entry) << pd.blk_log2) + r) * d) : nullptr;
+    }
 #pragma unroll
     for (int i = 0; i < kMaxVec; ++i) {
         const int idx = tid + 256 * i;
@@ -154,7 +179,7 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(
     const float *__restrict__ part, int parts, const typename Elem<DT>::T *__restrict__ bq,
     const typename Elem<DT>::T *__restrict__ bkv, typename Elem<DT>::T *__restrict__ q_out,
     typename Elem<DT>::T *__restrict__ K_dst, typename Elem<DT>::T *__restrict__ V_dst,
-    int B, int d, int n_out, int n_heads, int head_dim, int L_cap, int tok_pos)
+    int B, int d, int n_out, int n_heads, int head_dim, int L_cap, int tok_pos, PagedDst pd)
 {
     typedef typename Elem<DT>::T elem_t;
     typedef elem_t half4_t __attribute__((ext_vector_type(4)));
@@ -176,8 +201,21 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(
     } else {
         const int h = nn / head_dim, e = nn % head_dim;
         elem_t *dst = which == 1 ? K_dst : V_dst;
-        *reinterpret_cast<half4_t *>(dst + (((int64_t)m * n_heads + h) * L_cap + tok_pos) * head_dim + e) = o;
+        if (pd.block_table) {                              // paged: the row of the KV block named by the table, if it is one
+            int32_t entry;
+            int r;
+            paged_slot(pd, m, entry, r);
+            if (r >= 0 && entry >= 0 && entry < pd.P_kv)
+                *reinterpret_cast<half4_t *>(dst + (((((int64_t)entry * n_heads + h)) << pd.blk_log2) + r) * head_dim + e) = o;
+        } else {
+            *reinterpret_cast<half4_t *>(dst + (((int64_t)m * n_heads + h) * L_cap + tok_pos) * head_dim + e) = o;
+        }
     }
+}
+
+PagedDst paged_dst(const QkvArgs &a)
+{
+    return PagedDst{a.block_table, a.seq_len, a.max_blocks, a.blk_log2, a.P_kv, a.P_act};
 }
 
 template <int DT>
@@ -187,7 +225,7 @@ hipError_t launch_ln_rows(const QkvArgs &a, hipStream_t s)
     hipLaunchKernelGGL(ln_rows_kernel<DT>, dim3((unsigned)a.B), dim3(256), 0, s,
                        static_cast<const elem_t *>(a.x), static_cast<const elem_t *>(a.ln_w),
                        static_cast<const elem_t *>(a.ln_b), static_cast<elem_t *>(a.xhat),
-                       static_cast<elem_t *>(a.act_dst), a.act_row_stride, a.d, a.eps);
+                       static_cast<elem_t *>(a.act_dst), a.act_row_stride, a.d, a.eps, paged_dst(a));
     return hipGetLastError();
 }
 
@@ -227,7 +265,7 @@ hipError_t launch_dt(const QkvArgs &a, hipStream_t s)
     hipLaunchKernelGGL(qkv_finish_kernel<DT>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
                        a.part, parts, static_cast<const elem_t *>(a.bq), static_cast<const elem_t *>(a.bkv),
                        static_cast<elem_t *>(a.q_out), static_cast<elem_t *>(a.K_dst), static_cast<elem_t *>(a.V_dst),
-                       a.B, a.d, n_out, a.n_heads, a.head_dim, a.L_cap, a.tok_pos);
+                       a.B, a.d, n_out, a.n_heads, a.head_dim, a.L_cap, a.tok_pos, paged_dst(a));
     return hipGetLastError();
 }
 
@@ -237,6 +275,8 @@ hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (a.B > kQkvMaxRows || a.d % 64 != 0 || a.d > 256 * 8 * kMaxVec) return hipErrorInvalidValue;
+    if (a.block_table && (!a.seq_len || a.max_blocks <= 0 || a.blk_log2 < 4 || a.blk_log2 > 10 || a.P_kv < 0 || a.P_act < 0))
+        return hipErrorInvalidValue;
     return a.dtype == 1 ? launch_dt<1>(a, s) : launch_dt<0>(a, s);
 }
 

@@ -262,3 +262,157 @@ def test_paged_decode_replayed_from_a_graph(absorbed):
     torch.cuda.synchronize()
     assert torch.equal(out, eager2)
     assert not torch.equal(eager2, eager)
+
+
+def test_qkv_current_paged_rejects_bad_arguments():
+    """Every check of hk_qkv_current_paged runs on the host before a launch: no GPU is touched here."""
+    FAKE = 0x10000
+    ok = hk.make_shape(768, 12)
+    lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
+
+    def cache(**kw):
+        f = dict(K_pool=FAKE, V_pool=FAKE, act_pool=FAKE, block_table=FAKE, seq_len=FAKE, cu_tokens=None,
+                 total_tokens=0, P_kv=8, P_act=8, n_act_used=0, block_tokens=16, max_blocks=8)
+        f.update(kw)
+        return hk.hk_paged_cache(**f)
+
+    def call(shape=ok, x=FAKE, B=4, c=None, lp=lp, Wq=FAKE, bq=FAKE, q=FAKE, ws=FAKE, n=1 << 40, null_cache=False):
+        c = c or cache()
+        return hk.lib().hk_qkv_current_paged(ctypes.byref(shape), x, B, ctypes.byref(lp), Wq, bq, q,
+                                             None if null_cache else ctypes.byref(c), ws, n, None)
+
+    assert call(null_cache=True) == hk.HK_ERR_NULL
+    assert call(c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE and call(c=cache(block_tokens=8)) == hk.HK_ERR_SHAPE
+    assert call(c=cache(max_blocks=0)) == hk.HK_ERR_SHAPE and call(c=cache(P_kv=-1)) == hk.HK_ERR_SHAPE
+    assert call(shape=hk.make_shape(768, 11)) == hk.HK_ERR_SHAPE
+    assert call(c=cache(block_table=None)) == hk.HK_ERR_NULL and call(c=cache(seq_len=None)) == hk.HK_ERR_NULL
+    assert call(c=cache(K_pool=None)) == hk.HK_ERR_NULL and call(c=cache(act_pool=None)) == hk.HK_ERR_NULL
+    assert call(c=cache(P_kv=0, K_pool=None, V_pool=None), x=None) == hk.HK_ERR_NULL     # no KV pool is fine, no input is not
+    assert call(x=None) == hk.HK_ERR_NULL and call(q=None) == hk.HK_ERR_NULL and call(Wq=None) == hk.HK_ERR_NULL
+    assert call(c=cache(seq_len=FAKE + 2)) == hk.HK_ERR_ALIGN and call(c=cache(K_pool=FAKE + 8)) == hk.HK_ERR_ALIGN
+    assert call(n=hk.hk_qkv_workspace_bytes(ok, 4) - 1) == hk.HK_ERR_WORKSPACE
+    assert call(B=0, x=None) == hk.HK_OK
+    bf = hk.make_shape(768, 12, dtype=hk.HK_DTYPE_BF16)
+    assert call(shape=bf, c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE and call(shape=bf, x=None) == hk.HK_ERR_NULL
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("case", [("mixed", 768, 12, 7, 16, True), ("rows130", 512, 8, 130, 32, True),
+                                  ("no_kv_pool", 512, 4, 5, 16, False)], ids=lambda c: c[0])
+def test_qkv_current_paged_writes_the_row_its_table_names(case, dtype):
+    """hk_qkv_current_paged: q for every request; the token's K/V rows land in the row of the KV block its table
+    entry names, or its layer input in the row of the ACT block; nothing else in the pools changes; a request
+    without tokens and entries outside the pools are not written; the same q as hk_qkv_current."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    name, d, H, B, bt, with_kv = case
+    print("case", case, dtype, flush=True)
+    dh = d // H
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float16
+    cfg = synth.LayerConfig(name, d, H, B, 8, 0.5, 57)
+    p, c = synth.make_params(cfg), synth.make_current_token(cfg)
+    g, h = {}, {}
+    for k, v in {**p, **c}.items():
+        t = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(tdt)
+        g[k], h[k] = t.cuda(), t.float().numpy().astype(np.float64)
+    rng = np.random.default_rng(58)
+    max_blocks = 6
+    P_kv, P_act = (B + 3, B + 2) if with_kv else (0, B + 2)
+    seq_len = rng.integers(1, max_blocks * bt + 1, B).astype(np.int32)
+    seq_len[0] = max_blocks * bt                           # the last row of the last block
+    if B > 2:
+        seq_len[1] = 0                                     # no token: nothing is written for it
+        seq_len[2] = bt + 1                                # the first row of a fresh block
+    table = np.full((B, max_blocks), 0x7fffffff, dtype=np.int32)
+    kv_ids, act_ids = rng.permutation(max(P_kv, 1)), rng.permutation(P_act)
+    kinds = []
+    for b in range(B):
+        t = int(seq_len[b]) - 1
+        is_act = (not with_kv) or bool(rng.random() < 0.5)
+        kinds.append(is_act)
+        if t >= 0:
+            table[b, t // bt] = ~int(act_ids[b % P_act]) if is_act else int(kv_ids[b % P_kv])
+    if B > 4 and with_kv:
+        table[4, (int(seq_len[4]) - 1) // bt] = P_kv + 5   # a KV entry outside the pool: not written
+    Kp = torch.full((max(P_kv, 1), H, bt, dh), 7.0, dtype=tdt, device="cuda")
+    Vp = torch.full((max(P_kv, 1), H, bt, dh), -7.0, dtype=tdt, device="cuda")
+    Ap = torch.full((P_act, bt, d), 3.0, dtype=tdt, device="cuda")
+    q = hk.qkv_current_paged(g["x_cur"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], g["Wq"], g["bq"], H,
+                             Kp if with_kv else None, Vp if with_kv else None, Ap,
+                             torch.from_numpy(table).cuda(), torch.from_numpy(seq_len).cuda(), bt)
+    torch.cuda.synchronize()
+    rq, rk, rv = ho.qkv_current(h["x_cur"], h["ln_w"], h["ln_b"], h["Wq"], h["bq"], h["Wkv"], h["bkv"], H)
+    tol_abs = (lambda ref: 2.0 ** -7 * np.abs(ref).max()) if dtype == "bf16" else (lambda ref: MAX_ABS)
+
+    def check(name_, got, ref):
+        got = got.float().cpu().numpy().astype(np.float64)
+        err, rel = np.abs(got - ref).max(), np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+        print("%s: max_abs=%.3e rel_l2=%.3e" % (name_, err, rel), flush=True)
+        assert err <= tol_abs(ref) and rel <= REL_L2, (name_, err, rel)
+
+    check("q", q, rq)
+    Kexp = torch.full_like(Kp, 7.0); Vexp = torch.full_like(Vp, -7.0); Aexp = torch.full_like(Ap, 3.0)
+    written_k, written_a = [], []
+    for b in range(B):
+        t = int(seq_len[b]) - 1
+        if t < 0:
+            continue
+        e, r = int(table[b, t // bt]), t % bt
+        if e >= 0 and with_kv and e < P_kv:
+            written_k.append((b, e, r))
+        elif e < 0 and ~e < P_act:
+            written_a.append((b, ~e, r))
+    for b, e, r in written_k:
+        check("k[%d]" % b, Kp[e, :, r], rk[b]); check("v[%d]" % b, Vp[e, :, r], rv[b])
+        Kexp[e, :, r] = Kp[e, :, r]; Vexp[e, :, r] = Vp[e, :, r]
+    for b, e, r in written_a:
+        assert torch.equal(Ap[e, r], g["x_cur"][b])        # the checkpoint is the layer input, bit for bit
+        Aexp[e, r] = Ap[e, r]
+    assert torch.equal(Kp, Kexp) and torch.equal(Vp, Vexp) and torch.equal(Ap, Aexp)   # nothing else was touched
+    assert len(written_a) > 0 and (len(written_k) > 0 or not with_kv)
+    q2 = hk.qkv_current(g["x_cur"], g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"], g["Wq"], g["bq"], H)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("absorbed", [False, True], ids=["regenerating", "absorbed"])
+def test_paged_decode_step_with_current_token(absorbed):
+    """The whole paged decode step of a layer from this library: QKV generation of the input tokens with the
+    write-back into the blocks their tables name (hk_qkv_current_paged), then the attention of the generated
+    queries over the paged context including those tokens; against the oracle given the finished pools."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("paged_step", 768, 12, 6, 120, 0.5, 59)
+    H, d, bt = cfg.n_heads, cfg.d, 16
+    p, batch = _context(cfg, 15)
+    cur = synth.make_current_token(cfg)
+    seq_len = [120, 1, 17, 64, 0, 99]
+    oq, ok_, ov = ho.qkv_current(cur["x_cur"], p["ln_w"], p["ln_b"], cur["Wq"], cur["bq"], p["Wkv"], p["bkv"], H)
+    for b, n in enumerate(seq_len):                        # the input token is the last token of its request
+        if n > 0:
+            batch["act_full"][b, n - 1] = cur["x_cur"][b]
+            batch["K_full"][b, :, n - 1] = ok_[b].astype(np.float16)
+            batch["V_full"][b, :, n - 1] = ov[b].astype(np.float16)
+    batch["q"] = oq.astype(np.float16)
+    paged = synth.scatter_into_blocks(cfg, batch, seq_len, bt, [0.5, 0.0, 1.0, 0.5, 0.5, 0.4], seed=16)
+    ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
+                                paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    Kp, Vp, Ap = g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"])
+    for b, n in enumerate(seq_len):                        # the pools before the step: the input token's row is not there yet
+        if n > 0:
+            e, r = int(paged["block_table"][b, (n - 1) // bt]), (n - 1) % bt
+            if e >= 0:
+                Kp[e, :, r] = 99.0; Vp[e, :, r] = -99.0
+            else:
+                Ap[~e, r] = 99.0
+    tb, sl = g(paged["block_table"]), g(paged["seq_len"])
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    q = hk.qkv_current_paged(g(cur["x_cur"]), *lp, g(cur["Wq"]), g(cur["bq"]), H, Kp, Vp, Ap, tb, sl, bt)
+    out = hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=paged["n_act_used"], absorbed=absorbed)
+    torch.cuda.synchronize()
+    _check("q", q.cpu().numpy(), oq)
+    _check("out", out.cpu().numpy(), ref)
+    assert (out[4] == 0).all()                             # the request without tokens
