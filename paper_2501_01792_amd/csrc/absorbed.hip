@@ -18,11 +18,15 @@
 //
 // Kernels (B sequences, H heads, L_act checkpoint rows per sequence):
 //   carry   U[h,b,:]  = q[b,h,:] W'_K,h          rows of W' reduced       column_product (MFMA)
-//   scores  raw[b,h,t] = x[b,t,:] . U[h,b,:]     rows of x streamed       skinny::slab_product (MFMA); also the
-//                                                                         LayerNorm statistics of the rows
+//   scores  raw[b,h,t] = x[b,t,:] . U[h,b,:]     rows of x streamed       skinny::slab_product, or block_product from
+//                                                                         65536 rows on (MFMA); also the LayerNorm
+//                                                                         statistics of the rows
 //   softmax w[b,h,t]  = p_t rstd_t / l           one wavefront per (b,h)
 //   gather  Y[b,h,:]  = sum_t w[b,h,t] x[b,t,:] - sum_t w[b,h,t] mean_t   rows of x reduced   column_product (MFMA)
-//   project o[b,h,:]  = W'_V,h Y[b,h,:] + b'_V   rows of W' streamed      skinny::slab_product (MFMA), joins the cached part
+//   project o[b,h,:]  = W'_V,h Y[b,h,:] + b'_V   rows of W' streamed      skinny::slab_product (MFMA), joins the cached part;
+//                                                                         layers of 5120 features or more: block_product
+//                                                                         with the reduction axis cut over workgroups, then
+//                                                                         a join kernel
 #include "hk_internal.h"
 #include "kv_gemm_common.h"
 #include "skinny_mma.h"
