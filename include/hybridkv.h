@@ -323,6 +323,11 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape,
  * rows, weighted row sum through the block list); the two parts are joined through their softmax maxima and
  * denominators.  A request without tokens gets an all-zero output.  n_heads <= 128, B <= 65535; workspace:
  * hk_paged_absorbed_workspace_bytes (scratch only; the table, seq_len and cu_tokens are not written).
+ * When n_act_used > 0 every length and every table entry is read on the device at run time and cu_tokens is not
+ * read at all; total_tokens (which sizes the launch and the workspace) may then be any upper bound of the sum of
+ * seq_len, and n_act_used any upper bound up to P_act of the ACT blocks the table names.  With such bounds one
+ * HIP graph that holds hk_qkv_current_paged and this call serves successive decode steps while only device
+ * memory changes between its replays (new input rows, lengths, table entries).
  */
 size_t hk_paged_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache);
 int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t B, const hk_paged_cache *cache,

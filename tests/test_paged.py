@@ -416,3 +416,85 @@ def test_paged_decode_step_with_current_token(absorbed):
     _check("q", q.cpu().numpy(), oq)
     _check("out", out.cpu().numpy(), ref)
     assert (out[4] == 0).all()                             # the request without tokens
+
+
+@pytest.mark.gpu
+def test_paged_decode_loop_replayed_from_one_graph():
+    """A device-resident decode loop: QKV generation with the paged write-back and the attention without
+    regeneration, captured ONCE in a HIP graph with total_tokens and n_act_used given as upper bounds, then
+    replayed for successive decode steps while only device memory changes between the replays (the new input
+    rows, the lengths; the tables were laid out ahead).  Every step is checked against the oracle run on the
+    pools as they then are."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("paged_loop", 512, 8, 4, 64, 0.5, 60)
+    H, d, B, bt, max_blocks, steps = cfg.n_heads, cfg.d, cfg.B, 16, 6, 4
+    p, batch = _context(cfg, 17)
+    cur = synth.make_current_token(cfg)
+    lens0 = [30, 16, 0, 47]                                # the second request starts a new block at once, the third is empty
+    paged = synth.scatter_into_blocks(cfg, batch, lens0, bt, 0.5, seed=18)
+    n_kv0, n_act0 = paged["K_pool"].shape[0], paged["act_pool"].shape[0]
+    # room for the blocks the loop will open, and the table laid out ahead (the policy's choice of kinds is not tested here)
+    extra = B * 2
+    Kp = np.concatenate([paged["K_pool"], np.zeros((extra,) + paged["K_pool"].shape[1:], np.float16)])
+    Vp = np.concatenate([paged["V_pool"], np.zeros((extra,) + paged["V_pool"].shape[1:], np.float16)])
+    Ap = np.concatenate([paged["act_pool"], np.zeros((extra,) + paged["act_pool"].shape[1:], np.float16)])
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    table[:, :paged["block_table"].shape[1]] = paged["block_table"]
+    nk, na = n_kv0, n_act0
+    for b in range(B):
+        for i in range((lens0[b] + bt - 1) // bt, min(max_blocks, (lens0[b] + steps + bt - 1) // bt)):
+            if (b + i) % 2:
+                table[b, i] = ~na; na += 1
+            else:
+                table[b, i] = nk; nk += 1
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    Kg, Vg, Ag, tb = g(Kp), g(Vp), g(Ap), g(table)
+    sl = g(np.asarray(lens0, np.int32))
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    lp = lp + (hk.prepare_layer(*lp, H),)
+    Wq, bq = g(cur["Wq"]), g(cur["bq"])
+    x = torch.zeros(B, d, dtype=torch.float16, device="cuda")
+    q = torch.empty(B, H, d // H, dtype=torch.float16, device="cuda")
+    out = torch.empty_like(q)
+    bound = B * max_blocks * bt                            # more tokens than the loop will ever hold
+    cu_stale = torch.zeros(B + 1, dtype=torch.int64, device="cuda")   # not read when checkpoint blocks may be in use
+    shape = hk.make_shape(d, H)
+    cache = hk.make_paged_cache(Kg, Vg, Ag, tb, sl, cu_stale, bound, bt, Ag.shape[0])
+    ws_q = hk.new_workspace(hk.hk_qkv_workspace_bytes(shape, B))
+    ws_a = hk.new_workspace(int(hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))))
+
+    def step(stream):
+        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kg, Vg, Ag, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
+        hk.paged_decode_attn(q, Kg, Vg, Ag, tb, sl, bt, lp, n_act_used=Ag.shape[0], out=out, absorbed=True,
+                             cu_tokens=cu_stale, total_tokens=bound, workspace=ws_a, stream=stream)
+
+    rng = np.random.default_rng(19)
+    graph = None
+    for s in range(steps):
+        x_np = rng.standard_normal((B, d)).astype(np.float16)
+        x.copy_(g(x_np))
+        sl.add_(1)                                         # every request takes one more token (device state only)
+        torch.cuda.synchronize()
+        if graph is None:
+            saved = [t.clone() for t in (Kg, Vg, Ag)]
+            step(None)                                     # eager once (kernel attributes), then undone
+            torch.cuda.synchronize()
+            for t, c in zip((Kg, Vg, Ag), saved):
+                t.copy_(c)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step(torch.cuda.current_stream())
+        out.fill_(5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        lens = sl.cpu().numpy()
+        oq, _, _ = ho.qkv_current(x_np, p["ln_w"], p["ln_b"], cur["Wq"], cur["bq"], p["Wkv"], p["bkv"], H)
+        ref = pgo.paged_decode_attn(q.cpu().numpy(), Kg.cpu().numpy(), Vg.cpu().numpy(), Ag.cpu().numpy(), table, lens, bt,
+                                    p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
+        _check("q step %d" % s, q.cpu().numpy(), oq)
+        _check("out step %d" % s, out.cpu().numpy(), ref)
+        for b in range(B):                                 # the token is where the table says, bit for bit when a checkpoint
+            e, r = int(table[b, (lens[b] - 1) // bt]), (lens[b] - 1) % bt
+            if e < 0:
+                assert torch.equal(Ag[~e, r], x[b])
