@@ -1,7 +1,7 @@
 """Timing of the entry points beside the benchmark's path (bench.py times the hybrid step itself):
 
     python -m paper_2501_01792_amd.measure qkv   [--config opt6.7b] [--iters 20]
-    python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged] [--absorbed]
+    python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged] [--absorbed] [--graph]
 
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
@@ -111,6 +111,15 @@ def measure_paged(args):
                                         workspace=ws)
     for _ in range(2):
         call()
+    torch.cuda.synchronize()
+    if args.graph:                                             # the step replayed from a HIP graph (nothing is allocated inside)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            hk.paged_decode_attn(q, Kp if n_kv else None, Vp if n_kv else None, Ap if n_act else None, tb, sl, bt, lp,
+                                 n_act_used=n_act, out=out, absorbed=args.absorbed, cu_tokens=cu, total_tokens=total,
+                                 workspace=ws, stream=torch.cuda.current_stream())
+        call = graph.replay
+        call()
     ts = []
     for _ in range(args.iters):
         e0, e1 = _events(torch)
@@ -124,7 +133,7 @@ def measure_paged(args):
     print(json.dumps({"entry": "hk_paged_decode_attn_absorbed" if args.absorbed else "hk_paged_decode_attn",
                       "workload": "%s: B=%d H=%d dh=%d L%s%d, %d-token blocks, %.0f %% ACT blocks" %
                                   (cfg.name, B, H, dh, "<=" if args.ragged else "=", L, bt, 100 * args.act_fraction),
-                      "iters": args.iters, "ms": ms, "min_ms": float(np.min(ts)), "tokens": tokens, "act_blocks": n_act,
+                      "iters": args.iters, "replayed_from_graph": bool(args.graph), "ms": ms, "min_ms": float(np.min(ts)), "tokens": tokens, "act_blocks": n_act,
                       "kv_blocks": n_kv, "attention_bytes": attn_bytes, "regen_flop": regen_flop,
                       "attention_GBps_if_all_time_were_attention": attn_bytes / (ms * 1e-3) / 1e9}))
     return 0
@@ -139,6 +148,7 @@ def main():
     ap.add_argument("--act-fraction", type=float, default=0.0)
     ap.add_argument("--ragged", action="store_true")
     ap.add_argument("--absorbed", action="store_true", help="paged: the entry point that does not regenerate K/V")
+    ap.add_argument("--graph", action="store_true", help="paged: time the step replayed from a HIP graph")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
