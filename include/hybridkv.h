@@ -239,8 +239,10 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
  *                  row r are read.  ACT entries must be < n_act_used, KV entries < P_kv.
  *   seq_len        [B] int32, device: tokens of request r; the last block may be partly filled
  *   cu_tokens      [B + 1] int64, device: exclusive prefix sums of seq_len
- *   total_tokens   HOST copy of cu_tokens[B] (the library sizes its launch from it)
- *   n_act_used     ACT blocks 0 .. n_act_used - 1 of the pool are in use: they are the ones regenerated
+ *   total_tokens   HOST copy of cu_tokens[B], or any upper bound of it: the library sizes its launch and its
+ *                  workspace from it; the kernels read the lengths, the prefix sums and their total on the device
+ *   n_act_used     ACT blocks 0 .. n_act_used - 1 of the pool are in use: they are the ones regenerated (an upper
+ *                  bound regenerates blocks that no table names, which costs time and changes no result)
  */
 typedef struct hk_paged_cache {
     const void *K_pool, *V_pool;

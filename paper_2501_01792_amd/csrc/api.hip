@@ -613,7 +613,8 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.scale = p.scale; a.n_waves = p.n_waves;
     a.partial = reinterpret_cast<float *>(ws + p.off_partial);
     a.out = out;
-    a.total_dev = nullptr; a.lse = nullptr; a.dtype = shape->dtype;
+    // the kernels take the number of tokens from the device (cu_tokens[B]); the host's total_tokens sizes the launch
+    a.total_dev = cache->cu_tokens + B; a.lse = nullptr; a.dtype = shape->dtype;
     if (hk::launch_paged_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -709,7 +710,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     t.P_kv = cache->P_kv; t.P_act = 0; t.block_tokens = cache->block_tokens;
     t.B = B; t.H = shape->n_heads; t.head_dim = shape->head_dim; t.scale = p.scale; t.n_waves = p.n_waves;
     t.partial = reinterpret_cast<float *>(ws + p.off_partial);
-    t.out = out; t.total_dev = nullptr; t.lse = nullptr; t.dtype = 0;
+    t.out = out; t.total_dev = cache->cu_tokens ? cache->cu_tokens + B : nullptr; t.lse = nullptr; t.dtype = 0;
     if (!act) {                                            // no checkpoint block in use: the block-table attention is the whole step
         if (hk::launch_paged_decode(t, hs) != hipSuccess) return HK_ERR_LAUNCH;
         return HK_OK;

@@ -419,12 +419,13 @@ def test_paged_decode_step_with_current_token(absorbed):
 
 
 @pytest.mark.gpu
-def test_paged_decode_loop_replayed_from_one_graph():
-    """A device-resident decode loop: QKV generation with the paged write-back and the attention without
-    regeneration, captured ONCE in a HIP graph with total_tokens and n_act_used given as upper bounds, then
-    replayed for successive decode steps while only device memory changes between the replays (the new input
-    rows, the lengths; the tables were laid out ahead).  Every step is checked against the oracle run on the
-    pools as they then are."""
+@pytest.mark.parametrize("absorbed", [True, False], ids=["absorbed", "regenerating"])
+def test_paged_decode_loop_replayed_from_one_graph(absorbed):
+    """A device-resident decode loop: QKV generation with the paged write-back and the attention (with and
+    without regeneration), captured ONCE in a HIP graph with total_tokens and n_act_used given as upper bounds,
+    then replayed for successive decode steps while only device memory changes between the replays (the new
+    input rows, the lengths and their prefix sums; the tables were laid out ahead).  Every step is checked
+    against the oracle run on the pools as they then are."""
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a GPU; there is no CPU path")
     cfg = synth.LayerConfig("paged_loop", 512, 8, 4, 64, 0.5, 60)
@@ -458,16 +459,17 @@ def test_paged_decode_loop_replayed_from_one_graph():
     q = torch.empty(B, H, d // H, dtype=torch.float16, device="cuda")
     out = torch.empty_like(q)
     bound = B * max_blocks * bt                            # more tokens than the loop will ever hold
-    cu_stale = torch.zeros(B + 1, dtype=torch.int64, device="cuda")   # not read when checkpoint blocks may be in use
-    shape = hk.make_shape(d, H)
-    cache = hk.make_paged_cache(Kg, Vg, Ag, tb, sl, cu_stale, bound, bt, Ag.shape[0])
+    cu_dev = torch.zeros(B + 1, dtype=torch.int64, device="cuda")     # kept up to date on the device (the form without
+    shape = hk.make_shape(d, H)                                        # regeneration does not even read it)
+    cache = hk.make_paged_cache(Kg, Vg, Ag, tb, sl, cu_dev, bound, bt, Ag.shape[0])
     ws_q = hk.new_workspace(hk.hk_qkv_workspace_bytes(shape, B))
-    ws_a = hk.new_workspace(int(hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))))
+    size_fn = hk.lib().hk_paged_absorbed_workspace_bytes if absorbed else hk.lib().hk_paged_workspace_bytes
+    ws_a = hk.new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))))
 
     def step(stream):
         hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kg, Vg, Ag, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
-        hk.paged_decode_attn(q, Kg, Vg, Ag, tb, sl, bt, lp, n_act_used=Ag.shape[0], out=out, absorbed=True,
-                             cu_tokens=cu_stale, total_tokens=bound, workspace=ws_a, stream=stream)
+        hk.paged_decode_attn(q, Kg, Vg, Ag, tb, sl, bt, lp, n_act_used=Ag.shape[0], out=out, absorbed=absorbed,
+                             cu_tokens=cu_dev, total_tokens=bound, workspace=ws_a, stream=stream)
 
     rng = np.random.default_rng(19)
     graph = None
@@ -475,6 +477,7 @@ def test_paged_decode_loop_replayed_from_one_graph():
         x_np = rng.standard_normal((B, d)).astype(np.float16)
         x.copy_(g(x_np))
         sl.add_(1)                                         # every request takes one more token (device state only)
+        cu_dev[1:] = torch.cumsum(sl, 0)
         torch.cuda.synchronize()
         if graph is None:
             saved = [t.clone() for t in (Kg, Vg, Ag)]
