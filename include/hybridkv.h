@@ -390,6 +390,29 @@ enum { HK_BLOCK_KV = 0, HK_BLOCK_ACT = 1 };
 int hk_next_block_type(int64_t n_act, int64_t n_kv, int64_t act_host, int64_t kv_host);
 
 /*
+ * The bookkeeping of one decode step of a paged cache, on the DEVICE (Sec. 4.1; Eq. 11 with the arithmetic of
+ * hk_next_block_type): every active request takes one more token.  A request whose last block is full (or that has
+ * no block yet) opens logical block seq_len / block_tokens: of the kind that keeps its own #ACT : #KV nearest
+ * act_host : kv_host (counted over its table row), with the next free physical block of that pool, handed out in
+ * request order; its table entry is written (KV block id, or ~id for an ACT block).  Then seq_len[r] += 1 and
+ * cu_tokens becomes the prefix sums of the new lengths.  After this call hk_qkv_current_paged finds the row of
+ * every input token, and the attention calls find the new lengths; none of it touches the host, so all of them can
+ * sit in one captured graph.
+ *   block_table [B, max_blocks] int32, seq_len [B] int32, cu_tokens [B + 1] int64: device, read and written
+ *   counters    [4] int32, device, read and written: [0] KV blocks in use, [1] ACT blocks in use (the next free
+ *               block of a pool is its count; the caller frees by rebuilding tables and counts), [2] running
+ *               count of requests that could not grow, [3] unused
+ *   active      [B] int32, device, or NULL: nonzero = the request takes a token (NULL: all do)
+ * A request cannot grow, keeps its length and is counted in counters[2], when its table row is full or the pool of
+ * the kind it is due has no free block (the other pool is not tried: the ratio is the caller's memory plan).
+ * B <= 65535.  Host checks: HK_ERR_SHAPE (sizes, block_tokens not a power of two in 16 .. 1024, a negative or
+ * all-zero ratio), HK_ERR_NULL, HK_ERR_ALIGN.  B == 0 is a successful no-op.
+ */
+int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, int32_t *counters, const int32_t *active,
+                    int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
+                    int64_t act_host, int64_t kv_host, void *stream);
+
+/*
  * Eq. 12 and 13 for one mini-batch: *balance = T_kv_gen(#ACT_mb) / T_load_kv(#KV_mb) and
  * *cost = F_b = max(balance, 1 / balance).  Both times must be positive.
  */

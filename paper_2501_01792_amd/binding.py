@@ -107,6 +107,8 @@ def lib():
         L.hk_paged_absorbed_workspace_bytes.argtypes = L.hk_paged_workspace_bytes.argtypes
         L.hk_paged_decode_attn_absorbed.restype = ctypes.c_int
         L.hk_paged_decode_attn_absorbed.argtypes = L.hk_paged_decode_attn.argtypes
+        L.hk_paged_append.restype = ctypes.c_int
+        L.hk_paged_append.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_int64, ctypes.c_int64, vp]
         L.hk_qkv_current_paged.restype = ctypes.c_int
         L.hk_qkv_current_paged.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp, vp,
                                            ctypes.POINTER(hk_paged_cache), vp, sz, vp]
@@ -363,6 +365,21 @@ def qkv_current_paged(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, K_pool, V_po
     if st != HK_OK:
         raise HybridKVError(st, "hk_qkv_current_paged")
     return q_out
+
+
+def paged_append(block_table, seq_len, cu_tokens, counters, P_kv, P_act, block_tokens, act_host, kv_host, active=None,
+                 stream=None):
+    """hk_paged_append: one more token for every (active) request, in place on the device: ``block_table[B,
+    max_blocks]`` int32, ``seq_len[B]`` int32, ``cu_tokens[B+1]`` int64, ``counters[4]`` int32 (KV blocks in use,
+    ACT blocks in use, requests that could not grow, unused), ``active[B]`` int32 or None."""
+    import torch
+    B, max_blocks = block_table.shape
+    st = lib().hk_paged_append(_dev_ptr(block_table, "block_table", torch.int32), _dev_ptr(seq_len, "seq_len", torch.int32),
+                               _dev_ptr(cu_tokens, "cu_tokens", torch.int64), _dev_ptr(counters, "counters", torch.int32),
+                               _dev_ptr(active, "active", torch.int32), B, max_blocks, int(block_tokens), int(P_kv), int(P_act),
+                               int(act_host), int(kv_host), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_paged_append")
 
 
 # ----------------------------------------------------------------------------- host-only policy arithmetic (Sec. 4.3)

@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhybridkv.so")
-SOURCES = ["api.hip", "ln_stats.hip", "kv_gemm.hip", "kv_gemm_fold.hip", "flash_decode.hip", "paged_decode.hip", "qkv_current.hip", "absorbed.hip", "policy.hip", "probe.hip"]
+SOURCES = ["api.hip", "ln_stats.hip", "kv_gemm.hip", "kv_gemm_fold.hip", "flash_decode.hip", "paged_decode.hip", "paged_append.hip", "qkv_current.hip", "absorbed.hip", "policy.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -783,3 +783,23 @@ const char *hk_status_string(int status)
 }
 
 }  // extern "C"
+
+int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, int32_t *counters, const int32_t *active,
+                    int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
+                    int64_t act_host, int64_t kv_host, void *stream)
+{
+    if (B < 0 || B > 65535 || max_blocks <= 0 || P_kv < 0 || P_act < 0) return HK_ERR_SHAPE;
+    if (block_tokens < 16 || block_tokens > 1024 || (block_tokens & (block_tokens - 1)) != 0) return HK_ERR_SHAPE;
+    if ((long double)max_blocks * block_tokens > 2.0e9L) return HK_ERR_SHAPE;
+    if (act_host < 0 || kv_host < 0 || act_host + kv_host == 0 || act_host > (1LL << 31) || kv_host > (1LL << 31)) return HK_ERR_SHAPE;
+    if (B == 0) return HK_OK;
+    if (!block_table || !seq_len || !cu_tokens || !counters) return HK_ERR_NULL;
+    if (!aligned(block_table, 4) || !aligned(seq_len, 4) || !aligned(cu_tokens, 8) || !aligned(counters, 4) || !aligned(active, 4))
+        return HK_ERR_ALIGN;
+    hk::PagedAppendArgs a;
+    a.block_table = block_table; a.seq_len = seq_len; a.cu_tokens = cu_tokens; a.counters = counters; a.active = active;
+    a.B = B; a.max_blocks = max_blocks; a.block_tokens = block_tokens; a.P_kv = P_kv; a.P_act = P_act;
+    a.act_host = act_host; a.kv_host = kv_host;
+    if (hk::launch_paged_append(a, static_cast<hipStream_t>(stream)) != hipSuccess) return HK_ERR_LAUNCH;
+    return HK_OK;
+}

@@ -157,6 +157,17 @@ struct PagedAbsorbedArgs {
 // The same over a paged cache: launch_paged_index builds the two views of the block table (checkpoint blocks, KV
 // blocks), the caller runs launch_paged_decode over the KV view (total_dev = kv_cu + B), launch_paged_absorbed does
 // the checkpoint part and the join.
+struct PagedAppendArgs {
+    int32_t *block_table;              // [B, max_blocks]
+    int32_t *seq_len;                  // [B]
+    int64_t *cu_tokens;                // [B + 1]
+    int32_t *counters;                 // [4]: KV blocks in use, ACT blocks in use, requests that could not grow (running sum), -
+    const int32_t *active;             // optional [B]: nonzero = the request takes a token
+    int B, max_blocks, block_tokens, P_kv, P_act;
+    int64_t act_host, kv_host;         // the ratio every request keeps (Eq. 11)
+};
+// One token more for every active request, with the block bookkeeping that goes with it (see paged_append.hip).
+hipError_t launch_paged_append(const PagedAppendArgs &a, hipStream_t s);
 hipError_t launch_paged_index(const PagedAbsorbedArgs &a, hipStream_t s);
 hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &a, hipStream_t s);
 

@@ -421,11 +421,12 @@ def test_paged_decode_step_with_current_token(absorbed):
 @pytest.mark.gpu
 @pytest.mark.parametrize("absorbed", [True, False], ids=["absorbed", "regenerating"])
 def test_paged_decode_loop_replayed_from_one_graph(absorbed):
-    """A device-resident decode loop: QKV generation with the paged write-back and the attention (with and
-    without regeneration), captured ONCE in a HIP graph with total_tokens and n_act_used given as upper bounds,
-    then replayed for successive decode steps while only device memory changes between the replays (the new
-    input rows, the lengths and their prefix sums; the tables were laid out ahead).  Every step is checked
-    against the oracle run on the pools as they then are."""
+    """A device-resident decode loop: the block bookkeeping of the step (hk_paged_append: lengths, prefix sums, new
+    blocks by the ratio rule), QKV generation with the paged write-back and the attention (with and without
+    regeneration), captured ONCE in a HIP graph with total_tokens and n_act_used given as upper bounds, then
+    replayed for successive decode steps; the host only writes the new input rows in between.  Every step is
+    checked against the oracles: tables, lengths and counters bit for bit, q and the output within tolerance on
+    the pools as they then are."""
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a GPU; there is no CPU path")
     cfg = synth.LayerConfig("paged_loop", 512, 8, 4, 64, 0.5, 60)
@@ -435,23 +436,18 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
     lens0 = [30, 16, 0, 47]                                # the second request starts a new block at once, the third is empty
     paged = synth.scatter_into_blocks(cfg, batch, lens0, bt, 0.5, seed=18)
     n_kv0, n_act0 = paged["K_pool"].shape[0], paged["act_pool"].shape[0]
-    # room for the blocks the loop will open, and the table laid out ahead (the policy's choice of kinds is not tested here)
+    # room for the blocks the loop will open; they are handed out on the device by hk_paged_append (host ratio 1:1),
+    # after the blocks the initial context occupies (its KV blocks are scattered over the whole initial pool)
     extra = B * 2
     Kp = np.concatenate([paged["K_pool"], np.zeros((extra,) + paged["K_pool"].shape[1:], np.float16)])
     Vp = np.concatenate([paged["V_pool"], np.zeros((extra,) + paged["V_pool"].shape[1:], np.float16)])
     Ap = np.concatenate([paged["act_pool"], np.zeros((extra,) + paged["act_pool"].shape[1:], np.float16)])
     table = np.full((B, max_blocks), 0x7fffffff, np.int32)
     table[:, :paged["block_table"].shape[1]] = paged["block_table"]
-    nk, na = n_kv0, n_act0
-    for b in range(B):
-        for i in range((lens0[b] + bt - 1) // bt, min(max_blocks, (lens0[b] + steps + bt - 1) // bt)):
-            if (b + i) % 2:
-                table[b, i] = ~na; na += 1
-            else:
-                table[b, i] = nk; nk += 1
+    counters = np.asarray([n_kv0, paged["n_act_used"], 0, 0], np.int32)
     g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     Kg, Vg, Ag, tb = g(Kp), g(Vp), g(Ap), g(table)
-    sl = g(np.asarray(lens0, np.int32))
+    sl, cn = g(np.asarray(lens0, np.int32)), g(counters)
     lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
     lp = lp + (hk.prepare_layer(*lp, H),)
     Wq, bq = g(cur["Wq"]), g(cur["bq"])
@@ -467,6 +463,7 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
     ws_a = hk.new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))))
 
     def step(stream):
+        hk.paged_append(tb, sl, cu_dev, cn, Kg.shape[0], Ag.shape[0], bt, 1, 1, stream=stream)
         hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kg, Vg, Ag, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
         hk.paged_decode_attn(q, Kg, Vg, Ag, tb, sl, bt, lp, n_act_used=Ag.shape[0], out=out, absorbed=absorbed,
                              cu_tokens=cu_dev, total_tokens=bound, workspace=ws_a, stream=stream)
@@ -475,15 +472,15 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
     graph = None
     for s in range(steps):
         x_np = rng.standard_normal((B, d)).astype(np.float16)
-        x.copy_(g(x_np))
-        sl.add_(1)                                         # every request takes one more token (device state only)
-        cu_dev[1:] = torch.cumsum(sl, 0)
+        x.copy_(g(x_np))                                   # the only thing the host does between the steps
         torch.cuda.synchronize()
+        ref_table, ref_lens, ref_cu, ref_cnt = pgo.paged_append(tb.cpu().numpy(), sl.cpu().numpy(), cn.cpu().numpy(), None, bt,
+                                                                Kg.shape[0], Ag.shape[0], 1, 1)
         if graph is None:
-            saved = [t.clone() for t in (Kg, Vg, Ag)]
+            saved = [t.clone() for t in (Kg, Vg, Ag, tb, sl, cn, cu_dev)]
             step(None)                                     # eager once (kernel attributes), then undone
             torch.cuda.synchronize()
-            for t, c in zip((Kg, Vg, Ag), saved):
+            for t, c in zip((Kg, Vg, Ag, tb, sl, cn, cu_dev), saved):
                 t.copy_(c)
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
@@ -491,7 +488,9 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
         out.fill_(5.0)
         graph.replay()
         torch.cuda.synchronize()
-        lens = sl.cpu().numpy()
+        lens, table = sl.cpu().numpy(), tb.cpu().numpy()
+        assert np.array_equal(table, ref_table) and np.array_equal(lens, ref_lens) and np.array_equal(cn.cpu().numpy(), ref_cnt)
+        assert np.array_equal(cu_dev.cpu().numpy(), ref_cu)
         oq, _, _ = ho.qkv_current(x_np, p["ln_w"], p["ln_b"], cur["Wq"], cur["bq"], p["Wkv"], p["bkv"], H)
         ref = pgo.paged_decode_attn(q.cpu().numpy(), Kg.cpu().numpy(), Vg.cpu().numpy(), Ag.cpu().numpy(), table, lens, bt,
                                     p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
@@ -501,3 +500,102 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
             e, r = int(table[b, (lens[b] - 1) // bt]), (lens[b] - 1) % bt
             if e < 0:
                 assert torch.equal(Ag[~e, r], x[b])
+
+
+# ------------------------------------------------------------------ the bookkeeping of a decode step (Eq. 11)
+def test_paged_append_oracle_pins():
+    """The append oracle against what the paper and arithmetic fix: the worked example of Sec. 4.3 (host ratio 3:1,
+    a request with five checkpoint and two KV blocks opens a checkpoint block); over a long run every request's
+    checkpoint share stays within one block of the host share; blocks are handed out once each, in order, inside
+    their pools; lengths grow by one; a full table row and an exhausted pool stop a request and are counted."""
+    bt = 16
+    table = np.full((1, 16), 0x7fffffff, np.int32)
+    table[0, :7] = [~0, ~1, 0, ~2, ~3, 1, ~4]              # five checkpoint blocks, two KV blocks, all full
+    t, l, cu, c = pgo.paged_append(table, [7 * bt], [2, 5, 0, 0], None, bt, 100, 100, 3, 1)
+    assert t[0, 7] == ~5 and l[0] == 7 * bt + 1 and list(c) == [2, 6, 0, 0] and list(cu) == [0, 7 * bt + 1]
+    # a long run from empty: ratios, uniqueness, bounds, lengths
+    B, max_blocks, act_host, kv_host = 5, 40, 3, 2
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    lens, cnt = np.zeros(B, np.int32), np.zeros(4, np.int32)
+    rng = np.random.default_rng(3)
+    for step in range(30 * bt):
+        active = (rng.random(B) < 0.8).astype(np.int32)
+        table2, lens2, cu, cnt = pgo.paged_append(table, lens, cnt, active, bt, 1000, 1000, act_host, kv_host)
+        assert np.array_equal(lens2, lens + active) and np.array_equal(cu[1:], np.cumsum(lens2)) and cu[0] == 0
+        table, lens = table2, lens2
+        for b in range(B):
+            n = (int(lens[b]) + bt - 1) // bt
+            n_act = int((table[b, :n] < 0).sum())
+            assert abs(n_act * (act_host + kv_host) - act_host * n) <= act_host + kv_host     # within one block of the share
+            assert (table[b, n:] == 0x7fffffff).all()
+    kv = sorted(int(e) for e in table.ravel() if 0 <= e < 0x7fffffff)
+    act = sorted(int(~e) for e in table.ravel() if e < 0)
+    assert kv == list(range(cnt[0])) and act == list(range(cnt[1])) and cnt[2] == 0
+    # a full row, and an exhausted pool
+    t, l, _, c = pgo.paged_append(np.zeros((1, 2), np.int32), [2 * bt], [2, 0, 0, 0], None, bt, 10, 10, 1, 1)
+    assert l[0] == 2 * bt and c[2] == 1
+    t, l, _, c = pgo.paged_append(np.full((2, 4), 0x7fffffff, np.int32), [0, 0], [0, 1, 0, 0], None, bt, 10, 1, 1, 0)
+    assert list(l) == [0, 0] and c[2] == 2 and c[1] == 1   # only checkpoint blocks are due and their pool is full
+
+
+def test_paged_append_rejects_bad_arguments():
+    FAKE = 0x10000
+    def call(table=FAKE, sl=FAKE, cu=FAKE, cnt=FAKE, active=None, B=4, max_blocks=8, bt=16, P_kv=8, P_act=8, a=3, k=1):
+        return hk.lib().hk_paged_append(table, sl, cu, cnt, active, B, max_blocks, bt, P_kv, P_act, a, k, None)
+    assert call(bt=24) == hk.HK_ERR_SHAPE and call(bt=8) == hk.HK_ERR_SHAPE and call(max_blocks=0) == hk.HK_ERR_SHAPE
+    assert call(a=0, k=0) == hk.HK_ERR_SHAPE and call(a=-1) == hk.HK_ERR_SHAPE and call(B=65536) == hk.HK_ERR_SHAPE
+    assert call(P_kv=-1) == hk.HK_ERR_SHAPE
+    assert call(table=None) == hk.HK_ERR_NULL and call(sl=None) == hk.HK_ERR_NULL and call(cu=None) == hk.HK_ERR_NULL
+    assert call(cnt=None) == hk.HK_ERR_NULL
+    assert call(cu=FAKE + 4) == hk.HK_ERR_ALIGN and call(active=FAKE + 2) == hk.HK_ERR_ALIGN
+    assert call(B=0, table=None) == hk.HK_OK
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", [("small", 5, 12, 16, 40, 40, 3, 1, 60), ("many_requests", 700, 6, 16, 900, 2000, 2, 3, 40),
+                                  ("tight_pools", 9, 10, 32, 7, 11, 1, 1, 200), ("only_act", 4, 8, 16, 0, 30, 1, 0, 50)],
+                         ids=lambda c: c[0])
+def test_paged_append_matches_oracle(case):
+    """hk_paged_append step by step against the oracle: tables, lengths, prefix sums and counters, bit for bit
+    (integer work), with random active masks, from empty requests, through full table rows and exhausted pools."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    name, B, max_blocks, bt, P_kv, P_act, act_host, kv_host, steps = case
+    print("case", case, flush=True)
+    rng = np.random.default_rng(7)
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    lens = np.zeros(B, np.int32)
+    cnt = np.zeros(4, np.int32)
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    tb, sl, cn = g(table), g(lens), g(cnt)
+    cu = torch.full((B + 1,), -1, dtype=torch.int64, device="cuda")
+    for s in range(steps):
+        active = None if s % 5 == 0 else (rng.random(B) < 0.7).astype(np.int32)
+        # a few big strides so that rows fill up and pools run dry within the test
+        if s == 3:
+            bump = (rng.integers(0, max_blocks, B) * bt).astype(np.int32)
+            lens_np = sl.cpu().numpy()
+            # only lengths at a block boundary may jump (their tables stay consistent: whole blocks are laid out by hand)
+            table_np, cnt_np = tb.cpu().numpy(), cn.cpu().numpy()
+            for b in range(B):
+                if lens_np[b] % bt == 0 and bump[b] > 0 and lens_np[b] + bump[b] <= max_blocks * bt:
+                    i0 = lens_np[b] // bt
+                    for i in range(i0, i0 + bump[b] // bt):
+                        if cnt_np[1] < P_act:
+                            table_np[b, i] = ~int(cnt_np[1]); cnt_np[1] += 1
+                        elif cnt_np[0] < P_kv:
+                            table_np[b, i] = int(cnt_np[0]); cnt_np[0] += 1
+                        else:
+                            break
+                    else:
+                        lens_np[b] += bump[b]
+            tb.copy_(g(table_np)); sl.copy_(g(lens_np)); cn.copy_(g(cnt_np))
+        ref_t, ref_l, ref_cu, ref_c = pgo.paged_append(tb.cpu().numpy(), sl.cpu().numpy(), cn.cpu().numpy(), active, bt,
+                                                       P_kv, P_act, act_host, kv_host)
+        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, active=None if active is None else g(active))
+        torch.cuda.synchronize()
+        assert np.array_equal(tb.cpu().numpy(), ref_t), "table, step %d" % s
+        assert np.array_equal(sl.cpu().numpy(), ref_l), "lengths, step %d" % s
+        assert np.array_equal(cu.cpu().numpy(), ref_cu), "prefix sums, step %d" % s
+        assert np.array_equal(cn.cpu().numpy(), ref_c), "counters, step %d" % s
+    assert name != "tight_pools" or int(cn[2]) > 0          # the case did run into its limits
