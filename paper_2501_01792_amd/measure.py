@@ -3,12 +3,16 @@
     python -m paper_2501_01792_amd.measure qkv   [--config opt6.7b] [--iters 20]
     python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged] [--absorbed] [--graph]
 
+    python -m paper_2501_01792_amd.measure loop  [--config opt6.7b] [--block-tokens 16] [--act-fraction 0.5] [--ragged] [--iters 20]
+
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
 token) COLD: the weights of one layer fit in the 256 MB last-level cache, which a real decoder of dozens of
 layers would have evicted by the time a layer comes round again, so a 512 MiB buffer is read between calls.
 ``paged`` measures hk_paged_decode_attn (Sec. 4.1, 5.1: block table, ragged requests) on the workload's
-B, H, L with blocks of ``--block-tokens`` tokens scattered over the pools in random order.
+B, H, L with blocks of ``--block-tokens`` tokens scattered over the pools in random order.  ``loop`` measures one
+decode step of a layer on that paged cache as a serving loop would run it: hk_paged_append, hk_qkv_current_paged and
+hk_paged_decode_attn_absorbed captured once in a HIP graph and replayed, the context growing by a token per replay.
 """
 import argparse
 import json
@@ -139,9 +143,91 @@ def measure_paged(args):
     return 0
 
 
+def measure_loop(args):
+    import ctypes
+    import torch
+    from . import binding as hk, synth
+    cfg = synth.CONFIGS[args.config]
+    B, d, H, dh, L, bt = cfg.B, cfg.d, cfg.n_heads, cfg.head_dim, cfg.L, args.block_tokens
+    f16 = torch.float16
+    rng = np.random.default_rng(cfg.seed)
+    room = args.iters + 8                                      # tokens every request will take during the run
+    lens = (rng.integers(L // 2, L + 1 - room, B) if args.ragged else np.full(B, L - room)).astype(np.int32)
+    nb = (lens + bt - 1) // bt
+    max_blocks = int((lens.max() + room + bt - 1) // bt)
+    kinds = [rng.random(n) < args.act_fraction for n in nb]
+    n_act = int(sum(int(k.sum()) for k in kinds)); n_kv = int(nb.sum()) - n_act
+    spare = B * ((room + bt - 1) // bt + 1)
+    P_kv, P_act = n_kv + spare, n_act + spare
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    pa, pk = rng.permutation(max(n_act, 1)), rng.permutation(max(n_kv, 1))
+    ia = ik = 0
+    for b in range(B):
+        for i in range(nb[b]):
+            if kinds[b][i]:
+                table[b, i] = ~int(pa[ia]); ia += 1
+            else:
+                table[b, i] = int(pk[ik]); ik += 1
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen, device="cuda") * std + mean).to(f16)
+    kv_std = 0.02 * d ** 0.5
+    Kp = torch.empty(P_kv, H, bt, dh, device="cuda", dtype=f16)
+    Vp = torch.empty_like(Kp)
+    step = max(1, (1 << 28) // (H * bt * dh))
+    for i in range(0, P_kv, step):
+        Kp[i:i + step] = rn(*Kp[i:i + step].shape, std=kv_std)
+        Vp[i:i + step] = rn(*Vp[i:i + step].shape, std=kv_std)
+    Ap = rn(P_act, bt, d)
+    x = rn(B, d)
+    Wq, bq = rn(d, d, std=0.02), rn(d, std=0.01)
+    Wkv, bkv = rn(2 * d, d, std=0.02), rn(2 * d, std=0.01)
+    ln_w, ln_b = rn(d, std=0.02, mean=1.0), rn(d, std=0.02)
+    lp = (ln_w, ln_b, Wkv, bkv)
+    lp = lp + (hk.prepare_layer(*lp, H),)
+    tb, sl = torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda()
+    cn = torch.tensor([n_kv, n_act, 0, 0], dtype=torch.int32, device="cuda")
+    cu = torch.zeros(B + 1, dtype=torch.int64, device="cuda")
+    q = torch.empty(B, H, dh, device="cuda", dtype=f16)
+    out = torch.empty_like(q)
+    bound = int(lens.sum()) + B * room                          # an upper bound of the tokens during the run
+    shape = hk.make_shape(d, H)
+    cache = hk.make_paged_cache(Kp, Vp, Ap, tb, sl, cu, bound, bt, P_act)
+    ws_q = hk.new_workspace(hk.hk_qkv_workspace_bytes(shape, B))
+    ws_a = hk.new_workspace(int(hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))))
+    act_host, kv_host = max(1, round(100 * args.act_fraction)), max(0, 100 - round(100 * args.act_fraction))
+
+    def one_step(stream):
+        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, stream=stream)
+        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kp, Vp, Ap, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
+        hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=P_act, out=out, absorbed=True, cu_tokens=cu,
+                             total_tokens=bound, workspace=ws_a, stream=stream)
+
+    for _ in range(2):
+        one_step(None)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_step(torch.cuda.current_stream())
+    graph.replay()
+    ts = []
+    for _ in range(args.iters):
+        e0, e1 = _events(torch)
+        e0.record(); graph.replay(); e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = float(np.mean(ts))
+    stuck = int(cn[2].item())
+    print(json.dumps({"entry": "hk_paged_append + hk_qkv_current_paged + hk_paged_decode_attn_absorbed, one HIP graph",
+                      "workload": "%s: B=%d H=%d dh=%d L%s%d, %d-token blocks, %.0f %% ACT blocks" %
+                                  (cfg.name, B, H, dh, "<=" if args.ragged else "=", L, bt, 100 * args.act_fraction),
+                      "iters": args.iters, "ms": ms, "min_ms": float(np.min(ts)), "decode_tokens_per_s_per_layer": B / (ms * 1e-3),
+                      "tokens_in_context_at_end": int(sl.sum().item()), "requests_that_could_not_grow": stuck}))
+    return 0 if stuck == 0 else 1
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["qkv", "paged"])
+    ap.add_argument("what", choices=["qkv", "paged", "loop"])
     ap.add_argument("--config", default=None)
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--block-tokens", type=int, default=16)
@@ -159,6 +245,9 @@ def main():
     if args.what == "qkv":
         args.config = args.config or "opt6.7b"
         return measure_qkv(args)
+    if args.what == "loop":
+        args.config = args.config or "opt6.7b"
+        return measure_loop(args)
     args.config = args.config or "opt66b"
     return measure_paged(args)
 
