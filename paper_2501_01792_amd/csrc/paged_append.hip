@@ -58,10 +58,18 @@ __global__ __launch_bounds__(kThreads) void paged_append_kernel(int32_t *__restr
             if (idx >= max_blocks) {
                 stuck = true;
             } else {
-                long long n_act = 0, n_kv = 0;
-                for (int i = 0; i < idx; ++i) {
-                    if (table[(int64_t)b * max_blocks + i] < 0) ++n_act; else ++n_kv;
+                // the kinds of the blocks the request holds; the loads of a pass do not depend on each other
+                const int32_t *row = table + (int64_t)b * max_blocks;
+                int acts = 0, i = 0;
+                for (; i + 8 <= idx; i += 8) {
+                    int32_t e[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) e[j] = row[i + j];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acts += e[j] < 0;
                 }
+                for (; i < idx; ++i) acts += row[i] < 0;
+                const long long n_act = acts, n_kv = idx - acts;
                 if (kv_host == 0) want_act = true;
                 else if (act_host == 0) want_act = false;
                 else {
