@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float
 
 // softmax over the checkpoint rows of one (sequence, head), one wavefront each.  In the log2 domain:
 //   s_t = sl (rstd_t raw_t + k_t c1 + c2),  k_t = -(mean_t - x_t[0]) rstd_t,  c1 = q . c_K,h,  c2 = q . b'_K,h,
-//   sl = scale log2(e);   w_t = fp16(2^(s_t - m) rstd_t / l), zero from L_act to the padded row end;
+//   sl = scale log2(e);   w_t = fp16(2^(s_t - m) rstd_t / l), zero from L_act to the next multiple of 64;
 //   sums = (m, l, sum_t w_t mean_t with the stored w_t, -)
 __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q,
                                                                const float *__restrict__ raw, const float4 *__restrict__ stats,
@@ -423,11 +423,14 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     l = wave_sum(l);
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     _Float16 *wr = w + (int64_t)bh * Lp;
+    // w is read (by the weighted row sum) up to the next multiple of 64 past the sequence's own rows, and must be
+    // zero from L_act on; what lies beyond, up to the pitch, is never read
+    const int fill = (L_act + 63) & ~63;                   // <= Lp
     float mu = 0.f;
 #pragma unroll
     for (int i = 0; i < kKeep; ++i) {
         const int t = lane + 64 * i;
-        if (t < Lp) {
+        if (t < fill) {
             _Float16 wt = (_Float16)0.f;
             if (t < L_act) {
                 wt = (_Float16)(__builtin_amdgcn_exp2f(sc[i] - mx) * rs[i] * inv);
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
             wr[t] = wt;
         }
     }
-    for (int t = lane + 64 * kKeep; t < Lp; t += 64) {
+    for (int t = lane + 64 * kKeep; t < fill; t += 64) {
         _Float16 wt = (_Float16)0.f;
         if (t < L_act) {
             float4 s4;
