@@ -84,7 +84,7 @@ def sweep(args):
     """Ratio sweep of one workload (Sec. 4.3): per KV fraction r the time of regeneration
     (LayerNorm statistics + projection: the paper's T_kv_gen of the (1-r) B L checkpointed tokens)
     and of attention, the least-squares line T_kv_gen(n) = a n + b over the sweep (the paper fits
-    the same line, Sec. 4.3 "Sampling-based linear regression"), and the ratio r* at which
+    the same line, Sec. 4.3), and the ratio r* at which
     T_kv_gen((1-r) n) = T_load_w + T_load_kv(r n) (Eq. 8-10) for stated host-link bandwidths.
     The link is modelled (bytes / bandwidth), not measured: there is no host offload on this path.
     Inputs are drawn on the GPU with the distributions of the benchmark recipe (timing only)."""
@@ -345,7 +345,8 @@ def main():
 
     # What a loop of nothing but fp16 MFMAs sustains on this GPU: with random operands the shader
     # clock drops, so that rate (not the published peak) is the practical ceiling of the GEMM.
-    result["mfma_rate_probe_tflops"] = {"zero_operands": hk.probe_mfma_rate(False), "random_operands": hk.probe_mfma_rate(True)}
+    from paper_2501_01792_amd import probe
+    result["mfma_rate_probe_tflops"] = {"zero_operands": probe.mfma_rate(False), "random_operands": probe.mfma_rate(True)}
     if roofline.get("bound") == "mfma":
         roofline["frac_of_probe_random"] = roofline["achieved"] / result["mfma_rate_probe_tflops"]["random_operands"]
 

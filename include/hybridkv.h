@@ -13,7 +13,7 @@
  *     16-byte aligned.  hk_shape / hk_layer_params themselves are HOST structs
  *     passed by pointer and read before the call returns.
  *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16), the precision of the paper's
- *     models (Sec. 6.1); accumulation is fp32.  hk_prepare_layer, hk_regen_kv,
+ *     models (Sec. 5.1); accumulation is fp32.  hk_prepare_layer, hk_regen_kv,
  *     the hybrid step (hk_hybrid_decode_attn, _marked), hk_qkv_current and
  *     hk_paged_decode_attn, with their size queries, also take bfloat16
  *     (HK_DTYPE_BF16: every fp16 tensor below is bf16 instead); the two entry
@@ -176,7 +176,15 @@ int hk_hybrid_decode_attn(const hk_shape *shape,
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * hk_hybrid_decode_attn with per-kernel time stamps, for measurement: the same
+ * Where hk_hybrid_decode_attn leaves the regenerated rows: byte offsets, from the start of its workspace, of
+ * K [B,H,L_act,dh] and of V [B,H,L_act,dh] (a test or a caller that wants to keep them reads them there after the
+ * stream has run).  Host-only.  HK_OK or the status the step itself would give for the shape.
+ */
+int hk_regen_offsets(const hk_shape *shape, int32_t B, int32_t L_act, size_t *k_offset, size_t *v_offset);
+
+/*
+ * NOT A PRODUCT CALL: a measurement aid for benchmarks and profilers.
+ * hk_hybrid_decode_attn with per-kernel time stamps: the same
  * step (Sec. 4.2.2; Eq. 7, 3, 4) and the same arguments, plus `events`, a HOST
  * array of n_events hipEvent_t handles (passed as void*; NULL entries are
  * skipped) owned by the caller.  The library records, on `stream`,
@@ -265,13 +273,16 @@ typedef struct hk_paged_cache {
  * request.  The POOLS ARE WRITTEN by this call (one row of one block per request; the struct declares them const
  * for the calls that only read them); block_table and seq_len are read; cu_tokens, total_tokens and n_act_used
  * are not used.  A request with seq_len[r] == 0 and an entry outside its pool (KV: >= P_kv, ACT: >= P_act) are
- * not written.  K and V are not computed when there is no KV pool (P_kv == 0).  Other arguments, workspace
+ * not written.  store_mask ([B] int32, device, or NULL = store all): a request whose entry is zero gets its q
+ * and NOTHING is written for it.  A decode loop passes the `grew` array of hk_paged_append here: a request that took
+ * no token in this step (inactive, table row full, pool exhausted) still has seq_len[r] - 1 pointing at its last
+ * CACHED token, which an unmasked call would overwrite with the current input.  K and V are not computed when there is no KV pool (P_kv == 0).  Other arguments, workspace
  * (hk_qkv_workspace_bytes) and errors as for hk_qkv_current; block_tokens not a power of two in 16 .. 1024 or
  * max_blocks <= 0: HK_ERR_SHAPE.  fp16 or bf16.
  */
 int hk_qkv_current_paged(const hk_shape *shape, const void *x_cur, int32_t B,
                          const hk_layer_params *params, const void *Wq, const void *bq,
-                         void *q_out, const hk_paged_cache *cache,
+                         void *q_out, const hk_paged_cache *cache, const int32_t *store_mask,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -343,7 +354,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
  */
 
 /* A linear time model T(n) = slope * n + offset over a block (or token) count n: the form the paper
- * fits to its samples of T_kv_gen and T_load_kv ("Sampling-based linear regression"). */
+ * fits to its samples of T_kv_gen and T_load_kv (Sec. 4.3, the regression over sampled token counts). */
 typedef struct hk_line {
     double slope, offset;
 } hk_line;
@@ -352,7 +363,7 @@ typedef struct hk_line {
  * coefficient of determination.  HK_ERR_SHAPE when all n[i] are equal. */
 int hk_fit_line(const double *n, const double *t, int32_t count, hk_line *line, double *r2);
 
-/* Parameters of Algorithm 1 ("Hybrid Cache Allocation Policy"). */
+/* Parameters of Algorithm 1 (the allocation of host memory to checkpoint and KV blocks). */
 typedef struct hk_alloc_params {
     double T_load_w;       /* weight load latency of one decoder block */
     hk_line T_kv_gen;      /* KV generation (recompute) latency of n checkpoint blocks; slope > 0 */
@@ -403,13 +414,15 @@ int hk_next_block_type(int64_t n_act, int64_t n_kv, int64_t act_host, int64_t kv
  *               block of a pool is its count; the caller frees by rebuilding tables and counts), [2] running
  *               count of requests that could not grow, [3] unused
  *   active      [B] int32, device, or NULL: nonzero = the request takes a token (NULL: all do)
+ *   grew        [B] int32, device, or NULL; written: 1 = the request took its token in this call, 0 = it did not
+ *               (inactive, or it could not grow).  It is the store_mask of the hk_qkv_current_paged call that follows.
  * A request cannot grow, keeps its length and is counted in counters[2], when its table row is full or the pool of
  * the kind it is due has no free block (the other pool is not tried: the ratio is the caller's memory plan).
  * B <= 65535.  Host checks: HK_ERR_SHAPE (sizes, block_tokens not a power of two in 16 .. 1024, a negative or
  * all-zero ratio), HK_ERR_NULL, HK_ERR_ALIGN.  B == 0 is a successful no-op.
  */
 int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, int32_t *counters, const int32_t *active,
-                    int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
+                    int32_t *grew, int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
                     int64_t act_host, int64_t kv_host, void *stream);
 
 /*
@@ -418,21 +431,6 @@ int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, 
  */
 int hk_minibatch_balance(const hk_line *T_kv_gen, const hk_line *T_load_kv, double n_act_mb, double n_kv_mb,
                          double *balance, double *cost);
-
-/*
- * Measurement aid (no operation of the paper): runs a loop of back-to-back
- * v_mfma_f32_16x16x32_f16 (the projection kernel's instruction) on every
- * compute unit (4 wavefronts each, `iters` x 64 instructions per wavefront,
- * 1 Mflop per iteration and wavefront) with all-zero (random_operands == 0) or
- * random fp16 operands and returns the sustained rate in TFLOP/s through
- * `tflops_out` (HOST pointer).  `sink` is device scratch of at least
- * (number of compute units) * 1024 bytes.  Synchronises the stream.  The rate
- * with random operands is the practical ceiling of an fp16 kernel built on
- * that instruction on the GPU at hand (the 32x32x16 form sustains ~15 % less);
- * it is reported next to the projection kernel's roofline figure.
- */
-int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
-                       float *tflops_out, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *hk_status_string(int status);

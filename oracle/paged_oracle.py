@@ -49,18 +49,19 @@ def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_t
     return out
 
 
-def paged_append(block_table, seq_len, counters, active, block_tokens, P_kv, P_act, act_host, kv_host):
+def paged_append(block_table, seq_len, counters, active, block_tokens, P_kv, P_act, act_host, kv_host, with_grew=False):
     """One decode step of the paged cache's bookkeeping (Sec. 4.1; Eq. 11), request by request in order: every
     active request takes one more token; a request whose last block is full opens a new logical block of the kind
     ``policy_oracle.next_block_type`` gives for its own block counts, with the next free block of that pool
     (``counters[0]`` KV blocks and ``counters[1]`` ACT blocks are in use); a request whose table row is full or
     whose pool is exhausted keeps its length and is counted in ``counters[2]``.  Works on copies; returns
-    ``(block_table, seq_len, cu_tokens, counters)``."""
+    ``(block_table, seq_len, cu_tokens, counters)``, with ``with_grew`` also which requests took their token."""
     from oracle import policy_oracle as po
     table = np.array(block_table, dtype=np.int32, copy=True)
     lens = np.array(seq_len, dtype=np.int32, copy=True)
     cnt = [int(c) for c in counters]
     B, max_blocks = table.shape
+    grew = np.zeros(B, dtype=np.int32)
     for b in range(B):
         if active is not None and not active[b]:
             continue
@@ -85,5 +86,7 @@ def paged_append(block_table, seq_len, counters, active, block_tokens, P_kv, P_a
                 table[b, i] = cnt[0]
                 cnt[0] += 1
         lens[b] = n + 1
+        grew[b] = 1
     cu = np.concatenate([[0], np.cumsum(lens.astype(np.int64))]).astype(np.int64)
-    return table, lens, cu, np.asarray(cnt, dtype=np.int32)
+    res = (table, lens, cu, np.asarray(cnt, dtype=np.int32))
+    return res + (grew,) if with_grew else res

@@ -1,8 +1,8 @@
 """TEST INFRASTRUCTURE -- NOT PART OF THE PRODUCT PATH.
 
 Plain Python/numpy statement of the cache-management policy arithmetic of Sec. 4.3, in the paper's
-order and notation: the least-squares line of the time samples ("Sampling-based linear
-regression"), Algorithm 1 (initial_cache_allocation, alloc_remaining), the ratio-keeping block
+order and notation: the least-squares line of the time samples (the regression over
+sampled token counts), Algorithm 1 (initial_cache_allocation, alloc_remaining), the ratio-keeping block
 choice of Eq. 11 and the balance metric of Eq. 12-13.  Library routines (numpy.polyfit,
 numpy.linalg.solve, fractions.Fraction) serve as steps.  It imports nothing from the GPU package.
 

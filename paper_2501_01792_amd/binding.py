@@ -108,10 +108,10 @@ def lib():
         L.hk_paged_decode_attn_absorbed.restype = ctypes.c_int
         L.hk_paged_decode_attn_absorbed.argtypes = L.hk_paged_decode_attn.argtypes
         L.hk_paged_append.restype = ctypes.c_int
-        L.hk_paged_append.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_int64, ctypes.c_int64, vp]
+        L.hk_paged_append.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_int64, ctypes.c_int64, vp]
         L.hk_qkv_current_paged.restype = ctypes.c_int
         L.hk_qkv_current_paged.argtypes = [ctypes.POINTER(hk_shape), vp, i32, ctypes.POINTER(hk_layer_params), vp, vp, vp,
-                                           ctypes.POINTER(hk_paged_cache), vp, sz, vp]
+                                           ctypes.POINTER(hk_paged_cache), vp, vp, sz, vp]
         dp = ctypes.POINTER(ctypes.c_double)
         L.hk_fit_line.restype = ctypes.c_int
         L.hk_fit_line.argtypes = [dp, dp, i32, ctypes.POINTER(hk_line), dp]
@@ -122,8 +122,8 @@ def lib():
         L.hk_minibatch_balance.restype = ctypes.c_int
         L.hk_minibatch_balance.argtypes = [ctypes.POINTER(hk_line), ctypes.POINTER(hk_line), ctypes.c_double,
                                            ctypes.c_double, dp, dp]
-        L.hk_probe_mfma_rate.restype = ctypes.c_int
-        L.hk_probe_mfma_rate.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
+        L.hk_regen_offsets.restype = ctypes.c_int
+        L.hk_regen_offsets.argtypes = [shp, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.hk_status_string.restype = ctypes.c_char_p
         L.hk_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -152,15 +152,13 @@ def hk_regen_workspace_bytes(shape: hk_shape, B: int, L_act: int) -> int:
     return int(lib().hk_regen_workspace_bytes(ctypes.byref(shape), B, L_act))
 
 
-def probe_mfma_rate(random_operands: bool, iters: int = 10000, stream=None) -> float:
-    """hk_probe_mfma_rate: sustained TFLOP/s of a pure fp16 MFMA loop with zero / random operands."""
-    sink = new_workspace(1 << 20)
-    out = ctypes.c_float()
-    st = lib().hk_probe_mfma_rate(1 if random_operands else 0, iters, _dev_ptr(sink, "sink"), sink.numel(),
-                                  ctypes.byref(out), _stream_ptr(stream))
+def hk_regen_offsets(shape: hk_shape, B: int, L_act: int):
+    """hk_regen_offsets: byte offsets of the regenerated K and V inside the workspace of hk_hybrid_decode_attn."""
+    k, v = ctypes.c_size_t(), ctypes.c_size_t()
+    st = lib().hk_regen_offsets(ctypes.byref(shape), B, L_act, ctypes.byref(k), ctypes.byref(v))
     if st != HK_OK:
-        raise HybridKVError(st, "hk_probe_mfma_rate")
-    return float(out.value)
+        raise HybridKVError(st, "hk_regen_offsets")
+    return int(k.value), int(v.value)
 
 
 # ----------------------------------------------------------------------------- torch-facing calls
@@ -275,8 +273,8 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
         raise HybridKVError(st, "hk_hybrid_decode_attn")
     if return_regen:
         n = B * H * L_act * dh
-        v_off = (2 * n + 255) // 256 * 256
-        K = workspace[:2 * n].view(f16).view(B, H, L_act, dh)
+        k_off, v_off = hk_regen_offsets(shape, B, L_act)
+        K = workspace[k_off:k_off + 2 * n].view(f16).view(B, H, L_act, dh)
         V = workspace[v_off:v_off + 2 * n].view(f16).view(B, H, L_act, dh)
         return out, K, V
     return out
@@ -344,10 +342,11 @@ def qkv_current(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, q_out=None, K_dst=
 
 
 def qkv_current_paged(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, K_pool, V_pool, act_pool, block_table, seq_len,
-                      block_tokens, q_out=None, ln_eps=1e-5, workspace=None, stream=None):
+                      block_tokens, q_out=None, ln_eps=1e-5, workspace=None, stream=None, store_mask=None):
     """hk_qkv_current_paged: ``x_cur[B, d]`` -> ``q[B, H, dh]``; the token of request r (token ``seq_len[r] - 1``)
     is written into the block its table entry names: K/V rows into ``K_pool, V_pool``, or the layer input into
-    ``act_pool`` (pools may be None when empty; they are modified in place)."""
+    ``act_pool`` (pools may be None when empty; they are modified in place).  ``store_mask[B]`` int32 or None: zero =
+    nothing is stored for the request (pass the ``grew`` array of ``paged_append``)."""
     import torch
     f16 = x_cur.dtype if x_cur.dtype == torch.bfloat16 else torch.float16
     B, d = x_cur.shape
@@ -360,23 +359,24 @@ def qkv_current_paged(x_cur, ln_w, ln_b, Wkv, bkv, Wq, bq, n_heads, K_pool, V_po
     cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, None, 0, block_tokens, el=f16)
     st = lib().hk_qkv_current_paged(ctypes.byref(shape), _dev_ptr(x_cur, "x_cur", f16), B, ctypes.byref(lp),
                                     _dev_ptr(Wq, "Wq", f16), _dev_ptr(bq, "bq", f16), _dev_ptr(q_out, "q_out", f16),
-                                    ctypes.byref(cache), _dev_ptr(workspace, "workspace"), workspace.numel(),
-                                    _stream_ptr(stream))
+                                    ctypes.byref(cache), _dev_ptr(store_mask, "store_mask", torch.int32),
+                                    _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_qkv_current_paged")
     return q_out
 
 
 def paged_append(block_table, seq_len, cu_tokens, counters, P_kv, P_act, block_tokens, act_host, kv_host, active=None,
-                 stream=None):
+                 stream=None, grew=None):
     """hk_paged_append: one more token for every (active) request, in place on the device: ``block_table[B,
     max_blocks]`` int32, ``seq_len[B]`` int32, ``cu_tokens[B+1]`` int64, ``counters[4]`` int32 (KV blocks in use,
-    ACT blocks in use, requests that could not grow, unused), ``active[B]`` int32 or None."""
+    ACT blocks in use, requests that could not grow, unused), ``active[B]`` int32 or None, ``grew[B]`` int32 or None
+    (written: 1 where the request took its token)."""
     import torch
     B, max_blocks = block_table.shape
     st = lib().hk_paged_append(_dev_ptr(block_table, "block_table", torch.int32), _dev_ptr(seq_len, "seq_len", torch.int32),
                                _dev_ptr(cu_tokens, "cu_tokens", torch.int64), _dev_ptr(counters, "counters", torch.int32),
-                               _dev_ptr(active, "active", torch.int32), B, max_blocks, int(block_tokens), int(P_kv), int(P_act),
+                               _dev_ptr(active, "active", torch.int32), _dev_ptr(grew, "grew", torch.int32), B, max_blocks, int(block_tokens), int(P_kv), int(P_act),
                                int(act_host), int(kv_host), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_paged_append")
@@ -446,22 +446,18 @@ def paged_decode_attn(q, K_pool, V_pool, act_pool, block_table, seq_len, block_t
                       absorbed=False, cu_tokens=None, total_tokens=None):
     """hk_paged_decode_attn: ``q[B,H,dh]``, pools, ``block_table[B,max_blocks]`` int32, ``seq_len[B]`` int32 (GPU
     tensors) -> ``out[B,H,dh]``.  ``cu_tokens[B+1]`` int64 (GPU) and ``total_tokens`` are the prefix sums of
-    ``seq_len`` and their last element; when not given they are derived here (a device scan and a copy to the
-    host, which a caller that keeps its tables on the device between steps, or captures the step in a graph,
-    passes in instead).  ``absorbed`` selects hk_paged_decode_attn_absorbed (the same step without regenerating
+    ``seq_len`` and ``total_tokens`` their last element or an upper bound of it; the caller keeps them (on the device
+    hk_paged_append maintains the prefix sums).  ``absorbed`` selects hk_paged_decode_attn_absorbed (the same step without regenerating
     K/V)."""
     import torch
     B, H, dh = q.shape
     el = q.dtype if q.dtype == torch.bfloat16 else torch.float16
     shape = make_shape(H * dh, H, ln_eps, softmax_scale, dtype=_dtype_code(q))
     if cu_tokens is None or total_tokens is None:
-        cu = torch.zeros(B + 1, dtype=torch.int64, device=q.device)
-        cu[1:] = torch.cumsum(seq_len.to(torch.int64), 0)
-        total = int(cu[-1].item())
-    else:
-        if cu_tokens.dtype != torch.int64 or cu_tokens.numel() != B + 1 or not cu_tokens.is_cuda:
-            raise ValueError("cu_tokens: int64 GPU tensor of B + 1 elements")
-        cu, total = cu_tokens, int(total_tokens)
+        raise ValueError("cu_tokens (int64 GPU tensor of B + 1 prefix sums) and total_tokens are required")
+    if cu_tokens.dtype != torch.int64 or cu_tokens.numel() != B + 1 or not cu_tokens.is_cuda:
+        raise ValueError("cu_tokens: int64 GPU tensor of B + 1 elements")
+    cu, total = cu_tokens, int(total_tokens)
     cache = make_paged_cache(K_pool, V_pool, act_pool, block_table, seq_len, cu, total, block_tokens, n_act_used, el=el)
     if out is None:
         out = torch.empty((B, H, dh), dtype=el, device=q.device)

@@ -257,7 +257,8 @@ hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
 {
     auto kern = column_product_kernel<RB>;
     constexpr int lds = col_lds_bytes<RB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     const int blocks_x = (p.n_cols / kColBlock + 3) / 4;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks_x, (unsigned)batches), dim3(256), lds, s, p);
@@ -577,7 +578,8 @@ hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = block_mode ? absorbed_scores_block_kernel<RB> : absorbed_scores_kernel<RB>;
     const int lds = block_mode ? skinny::block_lds_bytes<RB>() : skinny::lds_bytes<RB>() + skinny::kMomentBytes;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,
@@ -590,7 +592,8 @@ hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
 {
     auto kern = absorbed_project_kernel<RB>;
     constexpr int lds = skinny::lds_bytes<RB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     const int64_t bh0 = (int64_t)b0 * a.H;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.head_dim / skinny::kSlab * a.H)), dim3(256), lds, s,
@@ -610,7 +613,8 @@ hipError_t launch_project_block(const AbsorbedArgs &a, int b0, int Bc, hipStream
     if ((size_t)parts * Bc * a.d > a.proj_part_floats) return hipErrorInvalidValue;
     auto kern = absorbed_project_block_kernel<RB>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     const int64_t bh0 = (int64_t)b0 * a.H;
     hipLaunchKernelGGL(kern, dim3((unsigned)a.H, (unsigned)parts), dim3(256), lds, s,
@@ -833,7 +837,8 @@ hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2,
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = paged_scores_kernel<RB>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.act), static_cast<const _Float16 *>(a.U), a.w_raw, a.stats,

@@ -180,6 +180,17 @@ size_t hk_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_
     return p.total > 0 ? p.total : kAlign;
 }
 
+int hk_regen_offsets(const hk_shape *shape, int32_t B, int32_t L_act, size_t *k_offset, size_t *v_offset)
+{
+    if (!k_offset || !v_offset) return HK_ERR_NULL;
+    Plan p;
+    const int st = make_plan(shape, B, 0, L_act, false, &p);     // the offsets do not depend on L_kv
+    if (st != HK_OK) return st;
+    *k_offset = p.off_k;
+    *v_offset = p.off_v;
+    return HK_OK;
+}
+
 int hk_regen_kv(const hk_shape *shape, const void *act, int32_t B, int32_t L_act,
                 const hk_layer_params *params, void *K_out, void *V_out, int32_t L_cap, int32_t tok_off,
                 void *workspace, size_t workspace_bytes, void *stream)
@@ -433,7 +444,7 @@ int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
              const hk_layer_params *params, const void *Wq, const void *bq,
              void *q_out,
              void *K_dst, void *V_dst, int32_t L_cap, int32_t tok_pos,
-             void *act_dst, int32_t act_cap, int32_t act_pos, const hk_paged_cache *paged,
+             void *act_dst, int32_t act_cap, int32_t act_pos, const hk_paged_cache *paged, const int32_t *store_mask,
              void *workspace, size_t workspace_bytes, void *stream)
 {
     int st = check_shape(shape, true);
@@ -454,7 +465,7 @@ int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
         if (B > 0 && (!paged->block_table || !paged->seq_len)) return HK_ERR_NULL;
         if (B > 0 && paged->P_kv > 0 && (!K_dst || !V_dst)) return HK_ERR_NULL;
         if (B > 0 && paged->P_act > 0 && !act_dst) return HK_ERR_NULL;
-        if (!aligned(paged->block_table, 4) || !aligned(paged->seq_len, 4)) return HK_ERR_ALIGN;
+        if (!aligned(paged->block_table, 4) || !aligned(paged->seq_len, 4) || !aligned(store_mask, 4)) return HK_ERR_ALIGN;
         L_cap = 1; tok_pos = 0; act_cap = 1; act_pos = 0;
     }
     if ((K_dst == nullptr) != (V_dst == nullptr)) return HK_ERR_NULL;
@@ -491,9 +502,10 @@ int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
         a.act_row_stride = (int64_t)act_cap * d;
         a.B = rows; a.d = d; a.n_heads = shape->n_heads; a.head_dim = shape->head_dim;
         a.L_cap = L_cap; a.tok_pos = tok_pos; a.eps = shape->ln_eps; a.dtype = shape->dtype;
-        a.block_table = nullptr; a.seq_len = nullptr; a.max_blocks = 0; a.blk_log2 = 0; a.P_kv = 0; a.P_act = 0;
+        a.block_table = nullptr; a.seq_len = nullptr; a.store_mask = nullptr; a.max_blocks = 0; a.blk_log2 = 0; a.P_kv = 0; a.P_act = 0;
         if (paged) {
             a.block_table = paged->block_table + (size_t)b0 * paged->max_blocks; a.seq_len = paged->seq_len + b0;
+            a.store_mask = store_mask ? store_mask + b0 : nullptr;
             a.max_blocks = paged->max_blocks; a.blk_log2 = blk_log2; a.P_kv = paged->P_kv; a.P_act = paged->P_act;
         }
         if (hk::launch_qkv_current(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
@@ -511,16 +523,16 @@ int hk_qkv_current(const hk_shape *shape, const void *x_cur, int32_t B,
                    void *workspace, size_t workspace_bytes, void *stream)
 {
     return qkv_impl(shape, x_cur, B, params, Wq, bq, q_out, K_dst, V_dst, L_cap, tok_pos, act_dst, act_cap, act_pos, nullptr,
-                    workspace, workspace_bytes, stream);
+                    nullptr, workspace, workspace_bytes, stream);
 }
 
 int hk_qkv_current_paged(const hk_shape *shape, const void *x_cur, int32_t B,
                          const hk_layer_params *params, const void *Wq, const void *bq,
-                         void *q_out, const hk_paged_cache *cache,
+                         void *q_out, const hk_paged_cache *cache, const int32_t *store_mask,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!cache) return HK_ERR_NULL;
-    return qkv_impl(shape, x_cur, B, params, Wq, bq, q_out, nullptr, nullptr, 0, 0, nullptr, 0, 0, cache,
+    return qkv_impl(shape, x_cur, B, params, Wq, bq, q_out, nullptr, nullptr, 0, 0, nullptr, 0, 0, cache, store_mask,
                     workspace, workspace_bytes, stream);
 }
 
@@ -785,7 +797,7 @@ const char *hk_status_string(int status)
 }  // extern "C"
 
 int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, int32_t *counters, const int32_t *active,
-                    int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
+                    int32_t *grew, int32_t B, int32_t max_blocks, int32_t block_tokens, int32_t P_kv, int32_t P_act,
                     int64_t act_host, int64_t kv_host, void *stream)
 {
     if (B < 0 || B > 65535 || max_blocks <= 0 || P_kv < 0 || P_act < 0) return HK_ERR_SHAPE;
@@ -794,10 +806,11 @@ int hk_paged_append(int32_t *block_table, int32_t *seq_len, int64_t *cu_tokens, 
     if (act_host < 0 || kv_host < 0 || act_host + kv_host == 0 || act_host > (1LL << 31) || kv_host > (1LL << 31)) return HK_ERR_SHAPE;
     if (B == 0) return HK_OK;
     if (!block_table || !seq_len || !cu_tokens || !counters) return HK_ERR_NULL;
-    if (!aligned(block_table, 4) || !aligned(seq_len, 4) || !aligned(cu_tokens, 8) || !aligned(counters, 4) || !aligned(active, 4))
+    if (!aligned(block_table, 4) || !aligned(seq_len, 4) || !aligned(cu_tokens, 8) || !aligned(counters, 4) || !aligned(active, 4) ||
+        !aligned(grew, 4))
         return HK_ERR_ALIGN;
     hk::PagedAppendArgs a;
-    a.block_table = block_table; a.seq_len = seq_len; a.cu_tokens = cu_tokens; a.counters = counters; a.active = active;
+    a.block_table = block_table; a.seq_len = seq_len; a.cu_tokens = cu_tokens; a.counters = counters; a.active = active; a.grew = grew;
     a.B = B; a.max_blocks = max_blocks; a.block_tokens = block_tokens; a.P_kv = P_kv; a.P_act = P_act;
     a.act_host = act_host; a.kv_host = kv_host;
     if (hk::launch_paged_append(a, static_cast<hipStream_t>(stream)) != hipSuccess) return HK_ERR_LAUNCH;

@@ -25,6 +25,7 @@
 //     with a finite "-infinity" so that fully masked tiles need no special case.
 #include "hk_internal.h"
 #include "elem.h"
+#include "attn_ranges.h"
 
 namespace hk {
 namespace {
@@ -49,8 +50,7 @@ __device__ __forceinline__ float dot8(typename Elem<DT>::V8 a, typename Elem<DT>
     return s;
 }
 
-// First position of the range of wavefront w when `total` positions are cut into W ranges.
-__host__ __device__ inline int64_t range_begin(int64_t w, int64_t total, int64_t W) { return (w * total) / W; }
+using ranges::range_begin;
 
 template <int DH, int DT>
 __global__ __launch_bounds__(kThreads) void flash_decode_kernel(
@@ -182,14 +182,7 @@ __global__ __launch_bounds__(DH) void merge_partials_kernel(const float *__restr
 {
     const int bh = blockIdx.x, e = threadIdx.x;
     const int64_t lo = (int64_t)bh * L, hi = lo + L - 1;       // first and last position of the pair
-    // wavefront holding position x: the last one whose range begins at or before x
-    auto owner = [&](int64_t x) {
-        int64_t w = (x * W) / total;
-        while (w + 1 < W && range_begin(w + 1, total, W) <= x) ++w;
-        while (w > 0 && range_begin(w, total, W) > x) --w;
-        return (int)w;
-    };
-    const int w_first = owner(lo), w_last = owner(hi);
+    const int w_first = ranges::owner(lo, total, W), w_last = ranges::owner(hi, total, W);
     const float *src = partial + ((int64_t)w_first + bh) * (DH + 2);
     const int n = w_last - w_first + 1;
     float mx = kNegBig;

@@ -4,7 +4,20 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace hk {
+
+// Host-side facts that do not change while the process lives, asked of the runtime once per device instead of
+// on every launch (device_info.hip).
+// The current device's ordinal and its number of compute units.
+hipError_t current_device_cus(int *dev, int *cus);
+// Raises the dynamic-LDS limit of `kernel` to `bytes` on the current device.  `once` belongs to the call site
+// (one per kernel instantiation): the runtime call is made the first time the site runs on a device.
+struct LdsOnce {
+    std::atomic<uint64_t> done{0};     // bit i: set on device i
+};
+hipError_t allow_dynamic_lds(const void *kernel, int bytes, LdsOnce &once);
 
 // Per-row LayerNorm statistics of act[M, d] (fp16, or bf16 with dtype 1) in fp32.
 // stats[r] = (rstd_r, -mean_r * rstd_r), so that (x - mean) * rstd == fma(x, stats.x, stats.y).
@@ -87,6 +100,7 @@ struct QkvArgs {
     // or the ACT block (act_dst is then the pool [P_act, 2^blk_log2, d]) that takes the row.  Requests without
     // tokens and entries outside the pools are not written.
     const int32_t *block_table, *seq_len;
+    const int32_t *store_mask;     // paged only, optional [B]: zero = the request's row is not stored (q is still produced)
     int max_blocks, blk_log2, P_kv, P_act;
 };
 constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel takes
@@ -163,6 +177,7 @@ struct PagedAppendArgs {
     int64_t *cu_tokens;                // [B + 1]
     int32_t *counters;                 // [4]: KV blocks in use, ACT blocks in use, requests that could not grow (running sum), -
     const int32_t *active;             // optional [B]: nonzero = the request takes a token
+    int32_t *grew;                     // optional [B], written: 1 = the request took its token, 0 = it did not (inactive or stuck)
     int B, max_blocks, block_tokens, P_kv, P_act;
     int64_t act_host, kv_host;         // the ratio every request keeps (Eq. 11)
 };

@@ -171,8 +171,8 @@ hipError_t launch_tile(const KvGemmArgs &a, hipStream_t s)
     const int tiles_m = (int)tiles_m64;
     auto kern = kv_gemm_kernel<BM, BN, WAVES_M, WAVES_N, GROUP_M>;
     constexpr size_t smem = sizeof(Smem<BM, BN>);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), (int)smem, lds_once);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES_M * WAVES_N), smem, s,
                        static_cast<const _Float16 *>(a.act), a.stats,

@@ -348,7 +348,8 @@ hipError_t fold_dt(const KvGemmArgs &a, int grid, int tiles_m, int tiles_n, hipS
     typedef typename Elem<DT>::T elem_t;
     auto kern = kv_gemm_fold_kernel<4, DT>;
     static_assert(kRingBytes == 160 * 1024, "the ring uses the whole 160 KiB LDS of a CU");
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kRingBytes);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), kRingBytes, lds_once);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FNT), kRingBytes, s,
                        static_cast<const elem_t *>(a.act), a.stats,
@@ -375,10 +376,8 @@ hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s)
     const int tiles_m = (int)tiles_m64;
     const int n_tiles = tiles_m * tiles_n;
     int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const hipError_t e = current_device_cus(&dev, &cus);
     if (e != hipSuccess) return e;
-    if (cus <= 0) return hipErrorInvalidValue;
     const int grid = n_tiles < cus ? n_tiles : cus;            // one resident workgroup per compute unit
     return a.dtype == 1 ? fold_dt<1>(a, grid, tiles_m, tiles_n, s) : fold_dt<0>(a, grid, tiles_m, tiles_n, s);
 }

@@ -37,7 +37,8 @@ __device__ __forceinline__ int block_rank(bool flag, int *scratch, int *total)
 
 __global__ __launch_bounds__(kThreads) void paged_append_kernel(int32_t *__restrict__ table, int32_t *__restrict__ seq_len,
                                                                 int64_t *__restrict__ cu, int32_t *__restrict__ counters,
-                                                                const int32_t *__restrict__ active, int B, int max_blocks,
+                                                                const int32_t *__restrict__ active, int32_t *__restrict__ grew,
+                                                                int B, int max_blocks,
                                                                 int blk_log2, int P_kv, int P_act, int64_t act_host, int64_t kv_host)
 {
     __shared__ int scratch[kThreads / 64];
@@ -93,6 +94,7 @@ __global__ __launch_bounds__(kThreads) void paged_append_kernel(int32_t *__restr
         }
         const int new_len = ok ? len + 1 : len;
         if (in && ok) seq_len[b] = new_len;
+        if (in && grew) grew[b] = ok ? 1 : 0;                        // whether the request holds a new token after this call
         int n_fail;
         block_rank(grows && !ok, scratch, &n_fail);
         failed += n_fail;
@@ -137,7 +139,7 @@ hipError_t launch_paged_append(const PagedAppendArgs &a, hipStream_t s)
     int blk_log2 = 0;
     while ((1 << blk_log2) < a.block_tokens) ++blk_log2;
     hipLaunchKernelGGL(paged_append_kernel, dim3(1), dim3(kThreads), 0, s, a.block_table, a.seq_len, a.cu_tokens, a.counters,
-                       a.active, a.B, a.max_blocks, blk_log2, a.P_kv, a.P_act, a.act_host, a.kv_host);
+                       a.active, a.grew, a.B, a.max_blocks, blk_log2, a.P_kv, a.P_act, a.act_host, a.kv_host);
     return hipGetLastError();
 }
 

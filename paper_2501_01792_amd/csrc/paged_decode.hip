@@ -2,8 +2,8 @@
 // list of logical blocks of `block_tokens` tokens, each either a KV block (its K/V rows sit in the KV
 // pool) or an ACT block (its checkpoints sit in the activation pool; its K/V rows have just been
 // regenerated into a pool of the same shape as the KV pool).  A per-request block table maps logical
-// block -> (kind, physical block number).  Requests have their own lengths.  This is the role the
-// paper gives its PagedAttention extension "across diverse KV buffer types" (Sec. 5.1).
+// block -> (kind, physical block number).  Requests have their own lengths.  This is the role of the
+// paper's attention kernel that reads both kinds of buffer (Sec. 5.1).
 //
 // Same organisation as the contiguous kernel (flash_decode.hip): the token positions of all
 // (request, head) pairs form one line, pair-major, of H * sum(len) positions; it is cut into W equal
@@ -14,6 +14,7 @@
 // rows of one load instruction share a block.
 #include "hk_internal.h"
 #include "elem.h"
+#include "attn_ranges.h"
 
 namespace hk {
 namespace {
@@ -37,7 +38,8 @@ __device__ __forceinline__ float dot8(typename Elem<DT>::V8 a, typename Elem<DT>
     return s;
 }
 
-__host__ __device__ inline int64_t range_begin(int64_t w, int64_t total, int64_t W) { return (w * total) / W; }
+using ranges::effective_waves;
+using ranges::range_begin;
 
 // Request that holds position p of the pair-major line: the last r with H * cu[r] <= p (cu has B + 1 entries).
 __device__ __forceinline__ int request_of(const int64_t *__restrict__ cu, int B, int H, int64_t p)
@@ -64,6 +66,10 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(
     constexpr int LPR = DH / 8, RPL = 64 / LPR, NL = LPR;
     // positions of the line: known to the host, or (tables built on the device) H * total_dev[0] <= the host's bound
     const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;
+    // The launch may be sized for more positions than the device finds (an upper bound on the host): then only
+    // the first `total` wavefronts work, so that no range between two working wavefronts is empty and every
+    // partial slot the merge reads has been written.  The merge derives the same number.
+    W = effective_waves(W, total);
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
@@ -201,22 +207,17 @@ __global__ __launch_bounds__(DH) void paged_merge_kernel(const float *__restrict
                                                          typename Elem<DT>::T *__restrict__ out, float2 *__restrict__ lse)
 {
     const int64_t total = total_dev ? (int64_t)H * total_dev[0] : total_host;   // > 0 whenever a pair has tokens
+    W = effective_waves(W, total);       // as in the streaming kernel: no empty range among the working wavefronts
     const int pair = blockIdx.x, e = threadIdx.x;
     const int r = pair / H, h = pair % H;
     const int len = seq_len[r];
-    if (len <= 0) {                      // no context: the softmax is over nothing; define the output as zero
+    if (len <= 0 || total <= 0) {        // no context: the softmax is over nothing; define the output as zero
         out[(int64_t)pair * DH + e] = (typename Elem<DT>::T)0.f;
         if (lse && e == 0) lse[pair] = make_float2(kNegBig, 0.f);
         return;
     }
     const int64_t lo = (int64_t)H * cu[r] + (int64_t)h * len, hi = lo + len - 1;
-    auto owner = [&](int64_t x) {
-        int64_t w = (x * W) / total;
-        while (w + 1 < W && range_begin(w + 1, total, W) <= x) ++w;
-        while (w > 0 && range_begin(w, total, W) > x) --w;
-        return (int)w;
-    };
-    const int w_first = owner(lo), w_last = owner(hi);
+    const int w_first = ranges::owner(lo, total, W), w_last = ranges::owner(hi, total, W);
     const float *src = partial + ((int64_t)w_first + pair) * (DH + 2);
     const int n = w_last - w_first + 1;
     float mx = kNegBig;

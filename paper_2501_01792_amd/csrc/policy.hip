@@ -1,5 +1,5 @@
 // Cache-management policy arithmetic on the host (Sec. 4.3): the linear time models and their
-// least-squares fit ("Sampling-based linear regression"), the two-step host block allocation
+// least-squares fit (the regression over sampled token counts), the two-step host block allocation
 // (Algorithm 1), the ratio-keeping choice of the next block type (Eq. 11) and the mini-batch balance
 // metric (Eq. 12, 13).  Plain double arithmetic, no device code, no allocation.
 #include "../../include/hybridkv.h"
@@ -55,34 +55,44 @@ int hk_host_block_allocation(const hk_alloc_params *p, hk_alloc_result *out)
     if (!(p->S_kv > 0.0) || !std::isfinite(p->S_kv) || !std::isfinite(p->T_load_w) || !(p->T_load_w >= 0.0)) return HK_ERR_SHAPE;
     if (!(p->n_act_gpu >= 0.0) || !std::isfinite(p->n_act_gpu)) return HK_ERR_SHAPE;
     if (!std::isfinite(p->M_host) || !std::isfinite(p->S_weight) || !(p->S_weight >= 0.0)) return HK_ERR_SHAPE;
-    const double S_act = 0.5 * p->S_kv;
+    const hk_line &gen = p->T_kv_gen, &load = p->T_load_kv;
 
-    // Step 1 (initial_cache_allocation): what the weight load leaves over after the GPU-resident
-    // checkpoints have been regenerated is filled with host checkpoints; a deficit with host KV blocks.
-    double act_init = 0.0, kv_init = 0.0;
-    const double T_budget = p->T_load_w - eval(p->T_kv_gen, p->n_act_gpu);
-    if (T_budget >= 0.0)
-        act_init = std::floor(solve_for(p->T_kv_gen, T_budget));
-    else
-        kv_init = std::floor(solve_for(p->T_load_kv, -T_budget));
+    // First stage (Algorithm 1, initial allocation).  While one layer's weights cross the link the GPU
+    // regenerates its resident checkpoints; `gap` is how much longer the link is busy.  A positive gap is
+    // closed by host checkpoints whose regeneration lasts that long, a negative one by host KV blocks whose
+    // transfer lasts that long.  Whole blocks only.
+    const double gap = p->T_load_w - eval(gen, p->n_act_gpu);
+    const double first_act = gap >= 0.0 ? std::floor(solve_for(gen, gap)) : 0.0;
+    const double first_kv = gap >= 0.0 ? 0.0 : std::floor(solve_for(load, -gap));
 
-    // Step 2 (alloc_remaining): fill the remaining host memory with x checkpoint and y KV blocks such
-    // that  S_act x + S_kv y = M_remaining  and  T_kv_gen(x) = T_load_kv(y).
-    const double M_occupied = S_act * act_init + p->S_kv * kv_init;
-    const double M_remaining = p->M_host - p->S_weight - M_occupied;
+    // Second stage (Algorithm 1, remaining allocation).  Count the bytes that are left in units of a checkpoint
+    // block (half a KV block): u = 2 * bytes / S_kv.  The split (x checkpoint, y KV blocks) fills them,
+    //     x + 2 y = u,
+    // and takes equal time on both sides,
+    //     gen.slope x + gen.offset = load.slope y + load.offset.
+    // Eliminating x:  y = (gen.slope u + gen.offset - load.offset) / (load.slope + 2 gen.slope),  x = u - 2 y.
+    // A negative count means one kind alone is already the slower side: it gets nothing, the other kind all.
+    const double bytes_left = p->M_host - p->S_weight - 0.5 * p->S_kv * first_act - p->S_kv * first_kv;
     double x = 0.0, y = 0.0;
-    if (M_remaining > 0.0) {
-        const double a = p->T_kv_gen.slope, b = p->T_kv_gen.offset, c = p->T_load_kv.slope, e = p->T_load_kv.offset;
-        // y = (a x + b - e) / c  ->  S_act x + S_kv (a x + b - e) / c = M_remaining
-        x = (M_remaining - p->S_kv * (b - e) / c) / (S_act + p->S_kv * a / c);
-        y = (a * x + b - e) / c;
-        if (x < 0.0) { x = 0.0; y = M_remaining / p->S_kv; }          // all of it KV blocks
-        if (y < 0.0) { y = 0.0; x = M_remaining / S_act; }            // all of it checkpoint blocks
+    if (bytes_left > 0.0) {
+        const double u = 2.0 * bytes_left / p->S_kv;
+        y = (gen.slope * u + gen.offset - load.offset) / (load.slope + 2.0 * gen.slope);
+        x = u - 2.0 * y;
+        if (x < 0.0) { x = 0.0; y = 0.5 * u; }
+        if (y < 0.0) { y = 0.0; x = u; }
     }
-    out->act_init = (int64_t)act_init;
-    out->kv_init = (int64_t)kv_init;
-    out->act_remain = (int64_t)std::floor(x);
-    out->kv_remain = (int64_t)std::floor(y);
+    x = std::floor(x);
+    y = std::floor(y);
+    // counts are reported as 64-bit integers: anything that does not fit comfortably is an input error
+    const double limit = 4611686018427387904.0;                           // 2^62
+    const double all[4] = {first_act, first_kv, x, y};
+    for (double v : all)
+        if (!(v >= 0.0) || !(v < limit)) return HK_ERR_SHAPE;
+    if (!(first_act + x < limit) || !(first_kv + y < limit)) return HK_ERR_SHAPE;
+    out->act_init = (int64_t)first_act;
+    out->kv_init = (int64_t)first_kv;
+    out->act_remain = (int64_t)x;
+    out->kv_remain = (int64_t)y;
     out->act_host = out->act_init + out->act_remain;
     out->kv_host = out->kv_init + out->kv_remain;
     return HK_OK;

@@ -38,15 +38,18 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // Where the current token of a request goes in a paged cache (QkvArgs): its table entry and its row in the block,
-// or row < 0 when the request has no token or the table has no entry for it.
+// or row < 0 when the request has no token, the table has no entry for it, or the caller's mask says that the
+// token is not to be stored.
 struct PagedDst {
     const int32_t *block_table, *seq_len;      // block_table == nullptr: contiguous stores
+    const int32_t *store_mask;                 // optional: zero = the request's token is not stored
     int max_blocks, blk_log2, P_kv, P_act;
 };
 __device__ __forceinline__ void paged_slot(const PagedDst &p, int b, int32_t &entry, int &row)
 {
     row = -1;
     entry = 0;
+    if (p.store_mask && p.store_mask[b] == 0) return;
     const int t = p.seq_len[b] - 1;
     if (t < 0) return;
     const int bi = t >> p.blk_log2;
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(
 
 PagedDst paged_dst(const QkvArgs &a)
 {
-    return PagedDst{a.block_table, a.seq_len, a.max_blocks, a.blk_log2, a.P_kv, a.P_act};
+    return PagedDst{a.block_table, a.seq_len, a.store_mask, a.max_blocks, a.blk_log2, a.P_kv, a.P_act};
 }
 
 template <int DT>
@@ -236,7 +239,8 @@ hipError_t launch_block(const QkvArgs &a, int parts, int steps_per_part, hipStre
     const int q_blocks = (a.d + 127) / 128, kv_blocks = a.K_dst ? (2 * a.d + 127) / 128 : 0;
     auto kern = qkv_block_kernel<RB, DT>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static LdsOnce lds_once;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(q_blocks + kv_blocks), (unsigned)parts), dim3(256), lds, s,
                        static_cast<const _Float16 *>(a.xhat), static_cast<const _Float16 *>(a.Wq),

@@ -196,9 +196,12 @@ def measure_loop(args):
     ws_a = hk.new_workspace(int(hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(shape), B, ctypes.byref(cache))))
     act_host, kv_host = max(1, round(100 * args.act_fraction)), max(0, 100 - round(100 * args.act_fraction))
 
+    grew = torch.zeros(B, dtype=torch.int32, device="cuda")
+
     def one_step(stream):
-        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, stream=stream)
-        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kp, Vp, Ap, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
+        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, stream=stream, grew=grew)
+        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kp, Vp, Ap, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream,
+                             store_mask=grew)
         hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=P_act, out=out, absorbed=True, cu_tokens=cu,
                              total_tokens=bound, workspace=ws_a, stream=stream)
 

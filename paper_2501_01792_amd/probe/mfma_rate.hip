@@ -1,11 +1,13 @@
-// Measurement aid: the matrix-core rate this GPU sustains on a loop of nothing but
+// Measurement aid of the benchmark (its own small library, libhkprobe.so; not part of libhybridkv and no
+// operation of the paper): the matrix-core rate this GPU sustains on a loop of nothing but
 // v_mfma_f32_16x16x32_f16 (the instruction of the projection kernel, on its 8 x 8 grid of accumulator
 // blocks), with all-zero or with random operands.  On MI355X the two differ widely (the shader clock
 // drops under random fp16 operands), so the second number is the practical ceiling against which the
 // projection kernel's fraction of the published peak should be read.  The accumulators are pinned to
 // their registers by inline asm: left to the register allocator, a loop over 64 four-register
 // accumulators gets shuffled between register files and measures the shuffling.
-#include "../../include/hybridkv.h"
+#include <stddef.h>
+#include <stdint.h>
 #include <hip/hip_runtime.h>
 
 namespace {
@@ -46,9 +48,14 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float *sink, int iters, 
 
 }  // namespace
 
-extern "C" int hk_probe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
-                                  float *tflops_out, void *stream)
+// Runs the loop on every compute unit (4 wavefronts each, `iters` x 64 instructions per wavefront) and returns the
+// sustained rate in TFLOP/s through tflops_out (host).  `sink` is device scratch of at least (compute units) * 1024
+// bytes.  Synchronises the stream.  Returns 0, or a negative number: -1 null pointer, -2 bad iteration count,
+// -5 sink too small, -7 a HIP call failed.
+extern "C" int hkprobe_mfma_rate(int32_t random_operands, int32_t iters, float *sink, size_t sink_bytes,
+                                 float *tflops_out, void *stream)
 {
+    enum { HK_OK = 0, HK_ERR_NULL = -1, HK_ERR_SHAPE = -2, HK_ERR_WORKSPACE = -5, HK_ERR_LAUNCH = -7 };
     if (!sink || !tflops_out) return HK_ERR_NULL;
     if (iters <= 0 || iters > (1 << 22)) return HK_ERR_SHAPE;
     int dev = 0, cus = 0;

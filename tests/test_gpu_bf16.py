@@ -162,7 +162,10 @@ def test_bf16_paged_decode_matches_oracle(hk, case):
     tb = torch.from_numpy(paged["block_table"]).cuda()
     sl = torch.from_numpy(paged["seq_len"]).cuda()
     lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
-    out = hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"])
+    cs = np.concatenate([[0], np.cumsum(np.asarray(seq_len, dtype=np.int64))]).astype(np.int64)
+    cu = {"cu_tokens": torch.from_numpy(cs).cuda(), "total_tokens": int(cs[-1])}
+    out = hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"],
+                               **cu)
     torch.cuda.synchronize()
     assert out.dtype == torch.bfloat16
     ref = pgo.paged_decode_attn(h["q"], h["K_pool"], h["V_pool"], h["act_pool"], paged["block_table"], paged["seq_len"], bt,
@@ -173,4 +176,4 @@ def test_bf16_paged_decode_matches_oracle(hk, case):
             assert (out[b] == 0).all()
     with pytest.raises(hk.HybridKVError):                          # the entry point without regeneration is fp16 only
         hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"],
-                             absorbed=True)
+                             absorbed=True, **cu)

@@ -15,6 +15,12 @@ MAX_ABS = 2e-2
 REL_L2 = 5e-3
 
 
+def _prefix_sums(seq_len):
+    """cu_tokens (int64, on the GPU) and their total, from the request lengths the test holds on the host."""
+    cu = np.concatenate([[0], np.cumsum(np.asarray(seq_len, dtype=np.int64))]).astype(np.int64)
+    return {"cu_tokens": torch.from_numpy(cu).cuda(), "total_tokens": int(cu[-1])}
+
+
 def _context(cfg, rng_seed):
     """Contiguous context of cfg.B requests of cfg.L tokens: layer inputs of every token and K/V rows (any
     numbers: a cache may hold anything) in fp16, plus layer parameters and queries."""
@@ -173,7 +179,7 @@ def test_paged_decode_matches_oracle(case, absorbed):
     lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
     out = hk.paged_decode_attn(g(batch["q"]), g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"]),
                                g(paged["block_table"]), g(paged["seq_len"]), bt, lp, n_act_used=paged["n_act_used"],
-                               absorbed=absorbed)
+                               absorbed=absorbed, **_prefix_sums(seq_len))
     torch.cuda.synchronize()
     out = out.cpu().numpy()
     # the oracle walks the same tables; on the big case only a sample of the requests
@@ -201,7 +207,7 @@ def test_paged_decode_without_a_kv_pool(absorbed):
     g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
     out = hk.paged_decode_attn(g(batch["q"]), None, None, g(paged["act_pool"]), g(paged["block_table"]), g(paged["seq_len"]), bt, lp,
-                               n_act_used=paged["n_act_used"], absorbed=absorbed)
+                               n_act_used=paged["n_act_used"], absorbed=absorbed, **_prefix_sums(seq_len))
     torch.cuda.synchronize()
     ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
                                 paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], cfg.n_heads)
@@ -276,10 +282,10 @@ def test_qkv_current_paged_rejects_bad_arguments():
         f.update(kw)
         return hk.hk_paged_cache(**f)
 
-    def call(shape=ok, x=FAKE, B=4, c=None, lp=lp, Wq=FAKE, bq=FAKE, q=FAKE, ws=FAKE, n=1 << 40, null_cache=False):
+    def call(shape=ok, x=FAKE, B=4, c=None, lp=lp, Wq=FAKE, bq=FAKE, q=FAKE, ws=FAKE, n=1 << 40, null_cache=False, mask=None):
         c = c or cache()
         return hk.lib().hk_qkv_current_paged(ctypes.byref(shape), x, B, ctypes.byref(lp), Wq, bq, q,
-                                             None if null_cache else ctypes.byref(c), ws, n, None)
+                                             None if null_cache else ctypes.byref(c), mask, ws, n, None)
 
     assert call(null_cache=True) == hk.HK_ERR_NULL
     assert call(c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE and call(c=cache(block_tokens=8)) == hk.HK_ERR_SHAPE
@@ -292,6 +298,7 @@ def test_qkv_current_paged_rejects_bad_arguments():
     assert call(c=cache(seq_len=FAKE + 2)) == hk.HK_ERR_ALIGN and call(c=cache(K_pool=FAKE + 8)) == hk.HK_ERR_ALIGN
     assert call(n=hk.hk_qkv_workspace_bytes(ok, 4) - 1) == hk.HK_ERR_WORKSPACE
     assert call(B=0, x=None) == hk.HK_OK
+    assert call(mask=FAKE + 2) == hk.HK_ERR_ALIGN and call(mask=FAKE, x=None) == hk.HK_ERR_NULL
     bf = hk.make_shape(768, 12, dtype=hk.HK_DTYPE_BF16)
     assert call(shape=bf, c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE and call(shape=bf, x=None) == hk.HK_ERR_NULL
 
@@ -411,7 +418,8 @@ def test_paged_decode_step_with_current_token(absorbed):
     tb, sl = g(paged["block_table"]), g(paged["seq_len"])
     lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
     q = hk.qkv_current_paged(g(cur["x_cur"]), *lp, g(cur["Wq"]), g(cur["bq"]), H, Kp, Vp, Ap, tb, sl, bt)
-    out = hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=paged["n_act_used"], absorbed=absorbed)
+    out = hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=paged["n_act_used"], absorbed=absorbed,
+                               **_prefix_sums(seq_len))
     torch.cuda.synchronize()
     _check("q", q.cpu().numpy(), oq)
     _check("out", out.cpu().numpy(), ref)
@@ -462,9 +470,12 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
     size_fn = hk.lib().hk_paged_absorbed_workspace_bytes if absorbed else hk.lib().hk_paged_workspace_bytes
     ws_a = hk.new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))))
 
+    grew = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+
     def step(stream):
-        hk.paged_append(tb, sl, cu_dev, cn, Kg.shape[0], Ag.shape[0], bt, 1, 1, stream=stream)
-        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kg, Vg, Ag, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream)
+        hk.paged_append(tb, sl, cu_dev, cn, Kg.shape[0], Ag.shape[0], bt, 1, 1, stream=stream, grew=grew)
+        hk.qkv_current_paged(x, *lp[:4], Wq, bq, H, Kg, Vg, Ag, tb, sl, bt, q_out=q, workspace=ws_q, stream=stream,
+                             store_mask=grew)
         hk.paged_decode_attn(q, Kg, Vg, Ag, tb, sl, bt, lp, n_act_used=Ag.shape[0], out=out, absorbed=absorbed,
                              cu_tokens=cu_dev, total_tokens=bound, workspace=ws_a, stream=stream)
 
@@ -490,7 +501,7 @@ def test_paged_decode_loop_replayed_from_one_graph(absorbed):
         torch.cuda.synchronize()
         lens, table = sl.cpu().numpy(), tb.cpu().numpy()
         assert np.array_equal(table, ref_table) and np.array_equal(lens, ref_lens) and np.array_equal(cn.cpu().numpy(), ref_cnt)
-        assert np.array_equal(cu_dev.cpu().numpy(), ref_cu)
+        assert np.array_equal(cu_dev.cpu().numpy(), ref_cu) and (grew == 1).all()
         oq, _, _ = ho.qkv_current(x_np, p["ln_w"], p["ln_b"], cur["Wq"], cur["bq"], p["Wkv"], p["bkv"], H)
         ref = pgo.paged_decode_attn(q.cpu().numpy(), Kg.cpu().numpy(), Vg.cpu().numpy(), Ag.cpu().numpy(), table, lens, bt,
                                     p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
@@ -532,22 +543,26 @@ def test_paged_append_oracle_pins():
     act = sorted(int(~e) for e in table.ravel() if e < 0)
     assert kv == list(range(cnt[0])) and act == list(range(cnt[1])) and cnt[2] == 0
     # a full row, and an exhausted pool
-    t, l, _, c = pgo.paged_append(np.zeros((1, 2), np.int32), [2 * bt], [2, 0, 0, 0], None, bt, 10, 10, 1, 1)
-    assert l[0] == 2 * bt and c[2] == 1
+    t, l, _, c, gr = pgo.paged_append(np.zeros((1, 2), np.int32), [2 * bt], [2, 0, 0, 0], None, bt, 10, 10, 1, 1, with_grew=True)
+    assert l[0] == 2 * bt and c[2] == 1 and list(gr) == [0]
+    # which requests took their token: the active ones that were not stopped
+    _, l, _, _, gr = pgo.paged_append(np.zeros((3, 2), np.int32), [2 * bt, 5, 7], [3, 0, 0, 0], [1, 0, 1], bt, 10, 10, 1, 1,
+                                      with_grew=True)
+    assert list(gr) == [0, 0, 1] and list(l) == [2 * bt, 5, 8]
     t, l, _, c = pgo.paged_append(np.full((2, 4), 0x7fffffff, np.int32), [0, 0], [0, 1, 0, 0], None, bt, 10, 1, 1, 0)
     assert list(l) == [0, 0] and c[2] == 2 and c[1] == 1   # only checkpoint blocks are due and their pool is full
 
 
 def test_paged_append_rejects_bad_arguments():
     FAKE = 0x10000
-    def call(table=FAKE, sl=FAKE, cu=FAKE, cnt=FAKE, active=None, B=4, max_blocks=8, bt=16, P_kv=8, P_act=8, a=3, k=1):
-        return hk.lib().hk_paged_append(table, sl, cu, cnt, active, B, max_blocks, bt, P_kv, P_act, a, k, None)
+    def call(table=FAKE, sl=FAKE, cu=FAKE, cnt=FAKE, active=None, B=4, max_blocks=8, bt=16, P_kv=8, P_act=8, a=3, k=1, grew=None):
+        return hk.lib().hk_paged_append(table, sl, cu, cnt, active, grew, B, max_blocks, bt, P_kv, P_act, a, k, None)
     assert call(bt=24) == hk.HK_ERR_SHAPE and call(bt=8) == hk.HK_ERR_SHAPE and call(max_blocks=0) == hk.HK_ERR_SHAPE
     assert call(a=0, k=0) == hk.HK_ERR_SHAPE and call(a=-1) == hk.HK_ERR_SHAPE and call(B=65536) == hk.HK_ERR_SHAPE
     assert call(P_kv=-1) == hk.HK_ERR_SHAPE
     assert call(table=None) == hk.HK_ERR_NULL and call(sl=None) == hk.HK_ERR_NULL and call(cu=None) == hk.HK_ERR_NULL
     assert call(cnt=None) == hk.HK_ERR_NULL
-    assert call(cu=FAKE + 4) == hk.HK_ERR_ALIGN and call(active=FAKE + 2) == hk.HK_ERR_ALIGN
+    assert call(cu=FAKE + 4) == hk.HK_ERR_ALIGN and call(active=FAKE + 2) == hk.HK_ERR_ALIGN and call(grew=FAKE + 2) == hk.HK_ERR_ALIGN
     assert call(B=0, table=None) == hk.HK_OK
 
 
@@ -590,12 +605,102 @@ def test_paged_append_matches_oracle(case):
                     else:
                         lens_np[b] += bump[b]
             tb.copy_(g(table_np)); sl.copy_(g(lens_np)); cn.copy_(g(cnt_np))
-        ref_t, ref_l, ref_cu, ref_c = pgo.paged_append(tb.cpu().numpy(), sl.cpu().numpy(), cn.cpu().numpy(), active, bt,
-                                                       P_kv, P_act, act_host, kv_host)
-        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, active=None if active is None else g(active))
+        ref_t, ref_l, ref_cu, ref_c, ref_g = pgo.paged_append(tb.cpu().numpy(), sl.cpu().numpy(), cn.cpu().numpy(), active, bt,
+                                                              P_kv, P_act, act_host, kv_host, with_grew=True)
+        grew = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        hk.paged_append(tb, sl, cu, cn, P_kv, P_act, bt, act_host, kv_host, active=None if active is None else g(active),
+                        grew=grew)
         torch.cuda.synchronize()
+        assert np.array_equal(grew.cpu().numpy(), ref_g), "grew, step %d" % s
         assert np.array_equal(tb.cpu().numpy(), ref_t), "table, step %d" % s
         assert np.array_equal(sl.cpu().numpy(), ref_l), "lengths, step %d" % s
         assert np.array_equal(cu.cpu().numpy(), ref_cu), "prefix sums, step %d" % s
         assert np.array_equal(cn.cpu().numpy(), ref_c), "counters, step %d" % s
     assert name != "tight_pools" or int(cn[2]) > 0          # the case did run into its limits
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("absorbed", [False, True], ids=["regenerating", "absorbed"])
+@pytest.mark.parametrize("lens", [[2], [40], [1, 0, 33]], ids=["len2", "len40", "three"])
+def test_paged_decode_with_a_loose_token_bound(lens, absorbed):
+    """total_tokens may be any upper bound of the tokens the device finds (a graph captured for a long context
+    serves a short one): with H * tokens far below the wavefronts the bound launches, the wavefronts past the
+    device's total must drop out and the merge must read written partials only.  Bound = 4096 tokens against
+    2 .. 40 real ones, 72 heads, workspace filled with NaN patterns beforehand."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    H, dh, bt, max_blocks = 72, 128, 16, 256
+    B = len(lens)
+    cfg = synth.LayerConfig("loose_bound", H * dh, H, B, max(lens), 0.5, 61)
+    p, batch = _context(cfg, 21)
+    paged = synth.scatter_into_blocks(cfg, batch, lens, bt, 0.5, seed=22)
+    g = lambda x: None if x is None or x.shape[0] == 0 else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    table[:, :paged["block_table"].shape[1]] = paged["block_table"]
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    q, Kp, Vp, Ap = g(batch["q"]), g(paged["K_pool"]), g(paged["V_pool"]), g(paged["act_pool"])
+    tb, sl = g(table), g(paged["seq_len"])
+    cu = g(np.concatenate([[0], np.cumsum(lens)]).astype(np.int64))
+    bound = 4096
+    shape = hk.make_shape(cfg.d, H)
+    cache = hk.make_paged_cache(Kp, Vp, Ap, tb, sl, cu, bound, bt, paged["n_act_used"])
+    size_fn = hk.lib().hk_paged_absorbed_workspace_bytes if absorbed else hk.lib().hk_paged_workspace_bytes
+    ws = hk.new_workspace(int(size_fn(ctypes.byref(shape), B, ctypes.byref(cache))))
+    ws.fill_(0xff)                                             # fp32 NaN in every partial slot
+    out = hk.paged_decode_attn(q, Kp, Vp, Ap, tb, sl, bt, lp, n_act_used=paged["n_act_used"], absorbed=absorbed,
+                               cu_tokens=cu, total_tokens=bound, workspace=ws)
+    torch.cuda.synchronize()
+    ref = pgo.paged_decode_attn(batch["q"], paged["K_pool"], paged["V_pool"], paged["act_pool"], paged["block_table"],
+                                paged["seq_len"], bt, p["ln_w"], p["ln_b"], p["Wkv"], p["bkv"], H)
+    _check("out", out.cpu().numpy(), ref)
+
+
+@pytest.mark.gpu
+def test_paged_decode_loop_leaves_requests_that_did_not_grow_alone():
+    """A decode loop in which one request is inactive and another cannot grow (its table row is full): the
+    `grew` array of hk_paged_append masks the write-back of hk_qkv_current_paged, so the last cached token of
+    those requests, a KV row or a checkpoint, stays as it was; the requests that grew get their rows."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("paged_mask", 512, 8, 5, 48, 0.5, 62)
+    H, d, B, bt, max_blocks = cfg.n_heads, cfg.d, cfg.B, 16, 3
+    p, batch = _context(cfg, 23)
+    cur = synth.make_current_token(cfg)
+    lens0 = [48, 20, 33, 48, 7]                            # requests 0 and 3 fill their table rows (3 blocks of 16)
+    paged = synth.scatter_into_blocks(cfg, batch, lens0, bt, [0.0, 0.5, 0.5, 1.0, 0.5], seed=24)
+    g = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    extra = 4
+    Kg = g(np.concatenate([paged["K_pool"], np.zeros((extra,) + paged["K_pool"].shape[1:], np.float16)]))
+    Vg = g(np.concatenate([paged["V_pool"], np.zeros((extra,) + paged["V_pool"].shape[1:], np.float16)]))
+    Ag = g(np.concatenate([paged["act_pool"], np.zeros((extra,) + paged["act_pool"].shape[1:], np.float16)]))
+    table = np.full((B, max_blocks), 0x7fffffff, np.int32)
+    table[:, :paged["block_table"].shape[1]] = paged["block_table"]
+    tb, sl = g(table), g(np.asarray(lens0, np.int32))
+    cn = g(np.asarray([paged["K_pool"].shape[0], paged["n_act_used"], 0, 0], np.int32))
+    cu = torch.zeros(B + 1, dtype=torch.int64, device="cuda")
+    active = g(np.asarray([1, 0, 1, 1, 1], np.int32))      # request 1 sits this step out
+    grew = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    lp = tuple(g(p[k]) for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    K0, V0, A0 = Kg.clone(), Vg.clone(), Ag.clone()
+    hk.paged_append(tb, sl, cu, cn, Kg.shape[0], Ag.shape[0], bt, 1, 1, active=active, grew=grew)
+    q = hk.qkv_current_paged(g(cur["x_cur"]), *lp, g(cur["Wq"]), g(cur["bq"]), H, Kg, Vg, Ag, tb, sl, bt, store_mask=grew)
+    torch.cuda.synchronize()
+    assert grew.cpu().tolist() == [0, 0, 1, 0, 1] and int(cn[2]) == 2
+    lens, table = sl.cpu().numpy(), tb.cpu().numpy()
+    assert lens.tolist() == [48, 20, 34, 48, 8]
+    oq, ok_, ov = ho.qkv_current(cur["x_cur"], p["ln_w"], p["ln_b"], cur["Wq"], cur["bq"], p["Wkv"], p["bkv"], H)
+    _check("q", q.cpu().numpy(), oq)                       # every request gets its query
+    Kexp, Vexp, Aexp = K0.clone(), V0.clone(), A0.clone()
+    for b in (2, 4):                                       # only the rows of the requests that grew may differ
+        e, r = int(table[b, (lens[b] - 1) // bt]), (lens[b] - 1) % bt
+        if e >= 0:
+            _check("k[%d]" % b, Kg[e, :, r].cpu().numpy(), ok_[b]); _check("v[%d]" % b, Vg[e, :, r].cpu().numpy(), ov[b])
+            Kexp[e, :, r] = Kg[e, :, r]; Vexp[e, :, r] = Vg[e, :, r]
+        else:
+            assert torch.equal(Ag[~e, r], g(cur["x_cur"])[b])
+            Aexp[~e, r] = Ag[~e, r]
+    assert torch.equal(Kg, Kexp) and torch.equal(Vg, Vexp) and torch.equal(Ag, Aexp)
+    # without the mask the same call does overwrite the last cached token of the three others: the hazard is real
+    hk.qkv_current_paged(g(cur["x_cur"]), *lp, g(cur["Wq"]), g(cur["bq"]), H, Kg, Vg, Ag, tb, sl, bt)
+    torch.cuda.synchronize()
+    assert not (torch.equal(Kg, Kexp) and torch.equal(Ag, Aexp))

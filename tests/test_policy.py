@@ -55,6 +55,62 @@ def test_oracle_algorithm1_by_hand():
     assert r == {"act_init": 0, "kv_init": 3, "act_remain": 202, "kv_remain": 50, "act_host": 202, "kv_host": 53}
 
 
+def test_oracle_algorithm1_step1_with_intercepts_by_hand():
+    """Step 1 of Algorithm 1 with lines that do not pass through the origin, both branches, by hand:
+    T_kv_gen(n) = 2 n + 6, T_load_kv(n) = 8 n + 4, #ACT_GPU = 20 (so the GPU-resident checkpoints take 46).
+      T_load_w = 100: T_budget = 54 >= 0 -> 2 n + 6 = 54 -> ACT_init = 24 (a sign slip on the intercept gives 30)
+      T_load_w = 10:  T_budget = -36 < 0 -> 8 n + 4 = 36 -> KV_init = 4    (a sign slip gives 5)
+      T_load_w = 49:  T_budget = 3 < the intercept 6 -> no block count gives so short a time: ACT_init = 0
+      T_load_w = 44:  T_budget = -2, shorter than T_load_kv(0) = 4 -> KV_init = 0."""
+    gen, load = (2.0, 6.0), (8.0, 4.0)
+    assert po.initial_cache_allocation(100.0, gen, load, 20) == (24, 0)
+    assert po.initial_cache_allocation(10.0, gen, load, 20) == (0, 4)
+    assert po.initial_cache_allocation(49.0, gen, load, 20) == (0, 0)
+    assert po.initial_cache_allocation(44.0, gen, load, 20) == (0, 0)
+    # fractional solutions round down to whole blocks: T_budget = 55 -> n = 24.5; T_budget = -39 -> n = 4.375
+    assert po.initial_cache_allocation(101.0, gen, load, 20) == (24, 0)
+    assert po.initial_cache_allocation(7.0, gen, load, 20) == (0, 4)
+    # the whole algorithm on the first instance: S_KV = 4, M_Host = 1000, S_weight = 380
+    #   M_occupied = 2 * 24 = 48, M_remaining = 572; 2 x + 4 y = 572 and 2 x + 6 = 8 y + 4
+    #   -> x = 4 y - 1 -> 12 y = 574 -> y = 47.83, x = 190.33 -> 190 ACT, 47 KV; totals 214 and 47
+    r = po.host_block_allocation(100.0, gen, load, 20, 1000.0, 380.0, 4.0)
+    assert r == {"act_init": 24, "kv_init": 0, "act_remain": 190, "kv_remain": 47, "act_host": 214, "kv_host": 47}
+
+
+def test_oracle_algorithm1_step1_closes_the_time_gap():
+    """The property step 1 states, on its real-valued solution (recovered here to within the floor): the
+    regeneration time of ACT_init blocks equals T_budget, or the load time of KV_init blocks equals -T_budget;
+    exactly one of the two is non-zero unless the gap is shorter than the line's intercept."""
+    rng = np.random.default_rng(11)
+    seen = set()
+    for _ in range(400):
+        gen = (rng.uniform(0.1, 3.0), rng.uniform(0.0, 5.0))
+        load = (rng.uniform(0.5, 12.0), rng.uniform(0.0, 5.0))
+        n_gpu = int(rng.integers(0, 100))
+        T_w = rng.uniform(0.0, 400.0)
+        T_budget = T_w - (gen[0] * n_gpu + gen[1])
+        act, kv = po.initial_cache_allocation(T_w, gen, load, n_gpu)
+        assert act >= 0 and kv >= 0 and (act == 0 or kv == 0)
+        if T_budget >= 0:
+            assert kv == 0
+            if T_budget >= gen[1]:
+                # floor: T_kv_gen(act) <= T_budget < T_kv_gen(act + 1)
+                assert gen[0] * act + gen[1] <= T_budget + 1e-9 < gen[0] * (act + 1) + gen[1] + 1e-9
+                seen.add("act")
+            else:
+                assert act == 0
+                seen.add("act0")
+        else:
+            assert act == 0
+            if -T_budget >= load[1]:
+                assert load[0] * kv + load[1] <= -T_budget + 1e-9 < load[0] * (kv + 1) + load[1] + 1e-9
+                seen.add("kv")
+            else:
+                assert kv == 0
+                seen.add("kv0")
+    assert seen == {"act", "act0", "kv", "kv0"}
+
+
 def test_oracle_algorithm1_invariants():
     """What step 2 states must hold for its real-valued solution (re-derived here with numpy's solver on
     the system as printed): the memory is filled exactly and the two times are equal; rounding down to
@@ -123,10 +179,20 @@ def test_c_host_block_allocation_matches_oracle():
     S_kv = 16 * 4 * 7168 * 48
     c = (31.85, (0.0045, 0.02), (0.018, 0.01), 1024.0, 800e9, 60e9, float(S_kv))
     assert hk.host_block_allocation(*c) == po.host_block_allocation(*c)
+    # lines with intercepts, both branches of step 1 (the hand-computed instances of the oracle's pin)
+    for T_w in (100.0, 10.0, 49.0, 44.0, 101.0, 7.0):
+        c = (T_w, (2.0, 6.0), (8.0, 4.0), 20, 1000.0, 380.0, 4.0)
+        assert hk.host_block_allocation(*c) == po.host_block_allocation(*c), c
     p = hk.hk_alloc_params(1.0, hk.hk_line(0.0, 0.0), hk.hk_line(1.0, 0.0), 0.0, 10.0, 0.0, 1.0)
     r = hk.hk_alloc_result()
     assert hk.lib().hk_host_block_allocation(ctypes.byref(p), ctypes.byref(r)) == hk.HK_ERR_SHAPE   # zero slope
     assert hk.lib().hk_host_block_allocation(None, ctypes.byref(r)) == hk.HK_ERR_NULL
+    # block counts that do not fit 62 bits are refused instead of being cast (huge memory, tiny blocks or slopes)
+    for bad in (hk.hk_alloc_params(1.0, hk.hk_line(1.0, 0.0), hk.hk_line(1.0, 0.0), 0.0, 1e300, 0.0, 1.0),
+                hk.hk_alloc_params(1e30, hk.hk_line(1e-300, 0.0), hk.hk_line(1.0, 0.0), 0.0, 10.0, 0.0, 1.0),
+                hk.hk_alloc_params(0.0, hk.hk_line(1.0, 0.0), hk.hk_line(1e-300, 0.0), 1e30, 10.0, 0.0, 1.0),
+                hk.hk_alloc_params(1.0, hk.hk_line(1.0, 0.0), hk.hk_line(1.0, 0.0), 0.0, 1e19, 0.0, 1e-3)):
+        assert hk.lib().hk_host_block_allocation(ctypes.byref(bad), ctypes.byref(r)) == hk.HK_ERR_SHAPE
 
 
 def test_c_fit_line_and_balance_match_oracle():
