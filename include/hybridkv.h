@@ -59,7 +59,8 @@ typedef enum hk_status {
     HK_ERR_ALIGN = -4,     /* a data pointer is not 16-byte aligned (workspace: 256) */
     HK_ERR_WORKSPACE = -5, /* workspace_bytes smaller than hk_workspace_bytes() */
     HK_ERR_DTYPE = -6,     /* a dtype the entry point does not take */
-    HK_ERR_LAUNCH = -7     /* the HIP runtime reported an error at launch */
+    HK_ERR_LAUNCH = -7,    /* the HIP runtime reported an error at launch */
+    HK_ERR_STATIC_LIMIT = -8 /* hk_hybrid_decode_attn_static: the problem needs more than HK_STATIC_SCRATCH_BYTES of scratch */
 } hk_status;
 
 enum { HK_DTYPE_F16 = 0, HK_DTYPE_BF16 = 1 };
@@ -174,6 +175,30 @@ int hk_hybrid_decode_attn(const hk_shape *shape,
                           const hk_layer_params *params, float ratio,
                           void *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hk_hybrid_decode_attn for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same step, same arguments minus the workspace,
+ * same kernels, bit-identical result.  The scratch memory (regenerated K/V, row statistics, attention partials) is a
+ * static device array inside the library, HK_STATIC_SCRATCH_BYTES per GPU, held by every GPU the library's code is
+ * loaded on until the process ends.  The call allocates nothing and frees nothing.
+ *   - A problem whose scratch need exceeds the array is refused with HK_ERR_STATIC_LIMIT before anything is launched.
+ *     The need is hk_workspace_bytes(shape, B, L_kv, L_act), less hk_prepared_bytes(shape) when params->prepared is
+ *     given (large regenerations run on a prepared layer; a caller that brings one saves the room for it -- with
+ *     d = 4096 that room alone is 64 MiB, so large layers need a prepared layer here).
+ *   - All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams, or threads)
+ *     race on it; the caller orders them.  The array keeps the last call's contents; nothing in it needs clearing
+ *     (every byte a kernel of the step reads has been written earlier in the same call).
+ *   - The first call on a GPU looks the array's address up (no allocation; the runtime may load the library's code
+ *     object then): make one call on a GPU before capturing the step into a graph there.
+ */
+enum { HK_STATIC_SCRATCH_BYTES = 32 << 20 };
+int hk_hybrid_decode_attn_static(const hk_shape *shape,
+                                 const void *q,
+                                 const void *K_cache, const void *V_cache, int32_t L_kv,
+                                 const void *act, int32_t L_act, int32_t B,
+                                 const hk_layer_params *params, float ratio,
+                                 void *out, void *stream);
 
 /*
  * Where hk_hybrid_decode_attn leaves the regenerated rows: byte offsets, from the start of its workspace, of

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(HERE, "libhybridkv.so")
 
 HK_OK = 0
 HK_ERR_NULL, HK_ERR_SHAPE, HK_ERR_RATIO, HK_ERR_ALIGN = -1, -2, -3, -4
-HK_ERR_WORKSPACE, HK_ERR_DTYPE, HK_ERR_LAUNCH = -5, -6, -7
+HK_ERR_WORKSPACE, HK_ERR_DTYPE, HK_ERR_LAUNCH, HK_ERR_STATIC_LIMIT = -5, -6, -7, -8
+HK_STATIC_SCRATCH_BYTES = 32 << 20
 HK_DTYPE_F16 = 0
 HK_DTYPE_BF16 = 1
 HK_MAX_SPLITS = 64
@@ -89,6 +90,8 @@ def lib():
                                             vp, vp, sz, vp]
         L.hk_hybrid_decode_attn_marked.restype = ctypes.c_int
         L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
+        L.hk_hybrid_decode_attn_static.restype = ctypes.c_int
+        L.hk_hybrid_decode_attn_static.argtypes = [shp, vp, vp, vp, i32, vp, i32, i32, lpp, ctypes.c_float, vp, vp]
         L.hk_absorbed_workspace_bytes.restype = sz
         L.hk_absorbed_workspace_bytes.argtypes = [shp, i32, i32, i32]
         L.hk_hybrid_decode_attn_absorbed.restype = ctypes.c_int
@@ -277,6 +280,24 @@ def hybrid_decode_attn(q, K_cache, V_cache, act, layer_params, ratio, out=None, 
         K = workspace[k_off:k_off + 2 * n].view(f16).view(B, H, L_act, dh)
         V = workspace[v_off:v_off + 2 * n].view(f16).view(B, H, L_act, dh)
         return out, K, V
+    return out
+
+
+def hybrid_decode_attn_static(q, K_cache, V_cache, act, layer_params, ratio, out, ln_eps=1e-5, softmax_scale=0.0,
+                              attn_splits=0, gemm_tile=0, stream=None):
+    """hk_hybrid_decode_attn_static: the step of ``hybrid_decode_attn`` on the library's static scratch array
+    (no workspace, nothing allocated: ``out`` must be given)."""
+    B, H, dh = q.shape
+    L_kv = 0 if K_cache is None else K_cache.shape[2]
+    L_act = 0 if act is None else act.shape[1]
+    f16 = q.dtype
+    shape = make_shape(H * dh, H, ln_eps, softmax_scale, attn_splits, gemm_tile, dtype=_dtype_code(q))
+    lp = _params(*layer_params[:4], prepared=layer_params[4] if len(layer_params) > 4 else None, el=f16)
+    st = lib().hk_hybrid_decode_attn_static(ctypes.byref(shape), _dev_ptr(q, "q", f16), _dev_ptr(K_cache, "K_cache", f16),
+                                            _dev_ptr(V_cache, "V_cache", f16), L_kv, _dev_ptr(act, "act", f16), L_act, B,
+                                            ctypes.byref(lp), float(ratio), _dev_ptr(out, "out", f16), _stream_ptr(stream))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_hybrid_decode_attn_static")
     return out
 
 

@@ -4,6 +4,7 @@
 #include "../../include/hybridkv.h"
 #include "hk_internal.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 
@@ -44,7 +45,9 @@ struct PreparedLayout {
 PreparedLayout prepared_layout(int d);
 
 // Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
-int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p, bool allow_bf16 = true)
+// prep_room = false: the caller brings a prepared layer, no room for one is planned.
+int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p, bool allow_bf16 = true,
+              bool prep_room = true)
 {
     int st = check_shape(s, allow_bf16);
     if (st != HK_OK) return st;
@@ -64,7 +67,7 @@ int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool re
     // The large-problem projection kernel works on a prepared layer; room to prepare one per call, for
     // callers that do not bring their own.
     p->off_prep = end;
-    if (p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile, s->dtype)) end += prepared_layout(s->d).total;
+    if (prep_room && p->M > 0 && hk::kv_gemm_uses_prepared(p->M, s->d, s->gemm_tile, s->dtype)) end += prepared_layout(s->d).total;
     p->off_partial = end;
     p->n_waves = 0;
     if (!regen_only && L_kv + L_act > 0 && p->BH > 0) {
@@ -223,22 +226,52 @@ int hk_hybrid_decode_attn(const hk_shape *shape, const void *q,
                                         workspace, workspace_bytes, stream, nullptr, 0);
 }
 
-int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
-                                 const void *K_cache, const void *V_cache, int32_t L_kv,
-                                 const void *act, int32_t L_act, int32_t B,
-                                 const hk_layer_params *params, float ratio,
-                                 void *out, void *workspace, size_t workspace_bytes, void *stream,
-                                 void **events, int32_t n_events)
+}  // extern "C"
+
+namespace {
+
+// ---- the step for callers that cannot allocate: scratch in a static device array of the library ----
+// One copy per GPU, held from the loading of the library's code on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[HK_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxScratchDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxScratchDevices];     // device address of `scratch` on device i (null: not looked up yet)
+
+// Device address of this GPU's copy of `scratch`.  The array's name is only a host-side handle: the address
+// comes from the runtime, once per device, with that device current.
+int static_scratch_ptr(void **ptr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return HK_ERR_LAUNCH;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HK_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return HK_OK;
+}
+
+// The hybrid step on a given scratch buffer.  static_scratch: the buffer is the library's own array instead
+// (`workspace` is ignored, workspace_bytes is the array's size, and a caller that brings a prepared layer needs no
+// room for one); its address is looked up only after every check has passed.
+int hybrid_step(const hk_shape *shape, const void *q,
+                const void *K_cache, const void *V_cache, int32_t L_kv,
+                const void *act, int32_t L_act, int32_t B,
+                const hk_layer_params *params, float ratio,
+                void *out, void *workspace, size_t workspace_bytes, bool static_scratch, void *stream,
+                void **events, int32_t n_events)
 {
     Plan p;
-    int st = make_plan(shape, B, L_kv, L_act, false, &p);
+    int st = make_plan(shape, B, L_kv, L_act, false, &p, true, !(static_scratch && params && params->prepared));
     if (st != HK_OK) return st;
     const int64_t L = (int64_t)L_kv + L_act;
     if (L == 0) return HK_ERR_SHAPE;
     if (!(ratio >= 0.f && ratio <= 1.f)) return HK_ERR_RATIO;
     if (std::fabs((double)ratio * (double)L - (double)L_kv) > 0.5 + 1e-6 * (double)L) return HK_ERR_RATIO;
     if (B == 0) return HK_OK;
-    if (!q || !out || !workspace) return HK_ERR_NULL;
+    if (static_scratch && workspace_bytes < p.total) return HK_ERR_STATIC_LIMIT;      // before the pointer checks: it is about sizes alone
+    if (!q || !out || (!workspace && !static_scratch)) return HK_ERR_NULL;
     if (L_kv > 0 && (!K_cache || !V_cache)) return HK_ERR_NULL;
     if (L_act > 0) {
         st = check_params(params);
@@ -246,9 +279,13 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
         if (!act) return HK_ERR_NULL;
         if (!aligned(act, 16)) return HK_ERR_ALIGN;
     }
-    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign)) return HK_ERR_ALIGN;
+    if (!aligned(q, 16) || !aligned(out, 16) || (!static_scratch && !aligned(workspace, kAlign))) return HK_ERR_ALIGN;
     if (L_kv > 0 && (!aligned(K_cache, 16) || !aligned(V_cache, 16))) return HK_ERR_ALIGN;
     if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+    if (static_scratch) {
+        st = static_scratch_ptr(&workspace);
+        if (st != HK_OK) return st;
+    }
 
     char *ws = static_cast<char *>(workspace);
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -277,6 +314,31 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
     if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     if (!mk.put(4)) return HK_ERR_LAUNCH;
     return HK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
+                                 const void *K_cache, const void *V_cache, int32_t L_kv,
+                                 const void *act, int32_t L_act, int32_t B,
+                                 const hk_layer_params *params, float ratio,
+                                 void *out, void *workspace, size_t workspace_bytes, void *stream,
+                                 void **events, int32_t n_events)
+{
+    return hybrid_step(shape, q, K_cache, V_cache, L_kv, act, L_act, B, params, ratio, out, workspace, workspace_bytes, false,
+                       stream, events, n_events);
+}
+
+int hk_hybrid_decode_attn_static(const hk_shape *shape, const void *q,
+                                 const void *K_cache, const void *V_cache, int32_t L_kv,
+                                 const void *act, int32_t L_act, int32_t B,
+                                 const hk_layer_params *params, float ratio,
+                                 void *out, void *stream)
+{
+    return hybrid_step(shape, q, K_cache, V_cache, L_kv, act, L_act, B, params, ratio, out, nullptr, HK_STATIC_SCRATCH_BYTES, true,
+                       stream, nullptr, 0);
 }
 
 namespace {
@@ -790,6 +852,7 @@ const char *hk_status_string(int status)
     case HK_ERR_WORKSPACE: return "HK_ERR_WORKSPACE: workspace too small";
     case HK_ERR_DTYPE: return "HK_ERR_DTYPE: unsupported dtype";
     case HK_ERR_LAUNCH: return "HK_ERR_LAUNCH: HIP reported a launch error";
+    case HK_ERR_STATIC_LIMIT: return "HK_ERR_STATIC_LIMIT: the problem needs more scratch than the library's static buffer (HK_STATIC_SCRATCH_BYTES) holds";
     default: return "unknown hk_status";
     }
 }
