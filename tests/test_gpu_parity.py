@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from paper_2501_01792_amd import synth
+from tile_walk import tile_walk_rows as _tile_walk_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -189,10 +190,10 @@ def test_repeatable(hk):
 
 # ------------------------------------------------------------------ full benchmark sizes, sampled
 def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99, prepared=False):
-    """Runs the GPU path on the whole config and checks (a) regenerated K/V of randomly sampled
-    checkpoint rows and (b) the attention output of sampled (sequence, head) pairs against the
-    oracle, which computes exactly those outputs from the same inputs (all K/V rows of the
-    sampled head, via Eq. 7 restricted to that head's weight rows)."""
+    """Runs the GPU path on the whole config and checks (a) regenerated K/V of sampled checkpoint rows -- rows
+    placed by the projection kernel's tile walk (_tile_walk_rows) plus random ones -- and (b) the attention output
+    of sampled (sequence, head) pairs against the oracle, which computes exactly those outputs from the same
+    inputs (all K/V rows of the sampled head, via Eq. 7 restricted to that head's weight rows)."""
     batch = synth.make_batch(cfg, threads=16)
     print("  inputs drawn", flush=True)
     out, K, V = _run_hybrid(hk, cfg, batch, prepared=prepared)
@@ -200,17 +201,26 @@ def _sampled_oracle_check(hk, oracle, cfg, n_rows=48, n_pairs=3, seed=99, prepar
     H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
     rng = np.random.default_rng(seed)
     if cfg.L_act:
-        rows = [(int(rng.integers(cfg.B)), int(rng.integers(cfg.L_act))) for _ in range(n_rows)]
+        strata = _tile_walk_rows(cfg)
+        for label, m in strata:
+            print("  stratum: %s -> row %d" % (label, m), flush=True)
+        rows = [(m // cfg.L_act, m % cfg.L_act) for _, m in strata]
+        rows += [(int(rng.integers(cfg.B)), int(rng.integers(cfg.L_act))) for _ in range(n_rows)]
         rows += [(0, 0), (cfg.B - 1, cfg.L_act - 1)]
         x = np.stack([batch["act"][b, t] for b, t in rows])
         xh = oracle.layernorm(x, batch["ln_w"], batch["ln_b"])
         kv = oracle.kv_projection(xh, batch["Wkv"], batch["bkv"])           # [rows, 2d]
         got_k = np.stack([K[b, :, t, :].reshape(d) for b, t in rows])
         got_v = np.stack([V[b, :, t, :].reshape(d) for b, t in rows])
+        print("  %d rows (%d placed by the tile walk)" % (len(rows), len(strata)), flush=True)
         _check("K_regen[sampled rows]", got_k, kv[:, :d])
         _check("V_regen[sampled rows]", got_v, kv[:, d:])
+        # every sampled row on its own as well: one bad row must not hide in the norm of a hundred good ones
+        for i, (b, t) in enumerate(rows):
+            e = max(np.abs(got_k[i].astype(np.float64) - kv[i, :d]).max(), np.abs(got_v[i].astype(np.float64) - kv[i, d:]).max())
+            assert e <= MAX_ABS, ("row", b, t, e)
     pairs = [(int(rng.integers(cfg.B)), int(rng.integers(H))) for _ in range(n_pairs)]
-    pairs += [(cfg.B - 1, H - 1)]
+    pairs += [(0, 0), (cfg.B - 1, H - 1)]
     got, ref = [], []
     for b, h in pairs:
         Kb = batch["K_cache"][b, h].astype(np.float64)
@@ -249,7 +259,7 @@ FULL = [
 def test_full_size_configs_sampled(hk, oracle, cfg):
     print("case", cfg, flush=True)
     torch.cuda.empty_cache()
-    _sampled_oracle_check(hk, oracle, cfg, n_rows=24, n_pairs=2, prepared=True)
+    _sampled_oracle_check(hk, oracle, cfg, n_rows=16, n_pairs=2, prepared=True)
     torch.cuda.empty_cache()
 
 
