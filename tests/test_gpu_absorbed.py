@@ -137,6 +137,8 @@ BIG = {
     "opt6.7b": synth.CONFIGS["opt6.7b"],
     "opt13b": synth.CONFIGS["opt13b"],
     "opt30b": synth.CONFIGS["opt30b"],                     # 131072 checkpoint rows: 128-row workgroups, 56 heads
+    "opt66b": synth.CONFIGS["opt66b"],                     # 262144 checkpoint rows, d = 9216, 72 heads (3 head blocks)
+    "opt66b@r0.5": synth.CONFIGS["opt66b"].with_ratio(0.5),   # the same layer with half of the context cached: the join
     "block_heads72": _cfg("block_heads72", 4608, 72, 17, 4000, 0.02, 27),   # the same kernel with 3 head blocks, ragged
     "dh64_big": _cfg("dh64_big", 2048, 32, 16, 2048, 0.5, 31),
     "one_long_sequence": _cfg("one_long_sequence", 1024, 8, 1, 40000, 0.1, 32),   # 36000 checkpoint rows of one sequence
