@@ -177,6 +177,37 @@ int hk_hybrid_decode_attn(const hk_shape *shape,
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The step of hk_hybrid_decode_attn issued on two streams (Sec. 4.2.2: the engine overlaps KV generation with the
+ * work that does not depend on it; inside one GPU that work is the attention over the cached segment).  On
+ * `side_stream`: the attention of every query over the cached K/V alone.  On `stream`: the regeneration (Eq. 7), then
+ * the attention over the regenerated rows alone.  The two results are joined on `stream` through their softmax
+ * maxima and denominators (Eq. 3, 4 over the union).  Same result as hk_hybrid_decode_attn up to rounding (the two
+ * segment outputs are rounded to the storage type before the join), not bit for bit; bit-identical to itself when
+ * side_stream == stream.
+ *   stream, side_stream   hipStream_t; side_stream may equal stream (then everything runs in order on it)
+ *   fork_event, join_event  two hipEvent_t owned by the caller (the library creates nothing); the library records
+ *                         fork on stream behind the LayerNorm statistics kernel (which is bound by HBM like the
+ *                         attention: only the projection is worth running beside), makes side_stream wait for it,
+ *                         records join on side_stream after its work
+ *                         and makes stream wait for join: on return all later work on `stream` is ordered after
+ *                         both parts, and side_stream is free again once join has completed
+ *   gemm_cus              > 0: the persistent projection kernel occupies at most this many compute units, which
+ *                         leaves the others to the side stream's kernel (it otherwise holds every compute unit's
+ *                         registers and LDS, and the two kernels take turns); 0: all of them
+ *   workspace             needs hk_two_stream_workspace_bytes(shape, B, L_kv, L_act)
+ * With L_kv == 0 or L_act == 0 there is nothing to overlap and the call is hk_hybrid_decode_attn on `stream`.
+ * Errors as for hk_hybrid_decode_attn; the events must not be NULL when both segments have tokens.
+ */
+size_t hk_two_stream_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);
+int hk_hybrid_decode_attn_two_stream(const hk_shape *shape,
+                                     const void *q,
+                                     const void *K_cache, const void *V_cache, int32_t L_kv,
+                                     const void *act, int32_t L_act, int32_t B,
+                                     const hk_layer_params *params, float ratio,
+                                     void *out, void *workspace, size_t workspace_bytes,
+                                     void *stream, void *side_stream, void *fork_event, void *join_event, int32_t gemm_cus);
+
+/*
  * hk_hybrid_decode_attn for callers that cannot allocate and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same step, same arguments minus the workspace,
  * same kernels, bit-identical result.  The scratch memory (regenerated K/V, row statistics, attention partials) is a

@@ -92,6 +92,11 @@ def lib():
         L.hk_hybrid_decode_attn_marked.argtypes = L.hk_hybrid_decode_attn.argtypes + [ctypes.POINTER(vp), i32]
         L.hk_hybrid_decode_attn_static.restype = ctypes.c_int
         L.hk_hybrid_decode_attn_static.argtypes = [shp, vp, vp, vp, i32, vp, i32, i32, lpp, ctypes.c_float, vp, vp]
+        L.hk_two_stream_workspace_bytes.restype = sz
+        L.hk_two_stream_workspace_bytes.argtypes = [shp, i32, i32, i32]
+        L.hk_hybrid_decode_attn_two_stream.restype = ctypes.c_int
+        L.hk_hybrid_decode_attn_two_stream.argtypes = [shp, vp, vp, vp, i32, vp, i32, i32, lpp, ctypes.c_float, vp, vp, sz,
+                                                       vp, vp, vp, vp, i32]
         L.hk_absorbed_workspace_bytes.restype = sz
         L.hk_absorbed_workspace_bytes.argtypes = [shp, i32, i32, i32]
         L.hk_hybrid_decode_attn_absorbed.restype = ctypes.c_int
@@ -298,6 +303,37 @@ def hybrid_decode_attn_static(q, K_cache, V_cache, act, layer_params, ratio, out
                                             ctypes.byref(lp), float(ratio), _dev_ptr(out, "out", f16), _stream_ptr(stream))
     if st != HK_OK:
         raise HybridKVError(st, "hk_hybrid_decode_attn_static")
+    return out
+
+
+def hk_two_stream_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int) -> int:
+    return int(lib().hk_two_stream_workspace_bytes(ctypes.byref(shape), B, L_kv, L_act))
+
+
+def hybrid_decode_attn_two_stream(q, K_cache, V_cache, act, layer_params, ratio, side_stream, events, out=None, gemm_cus=0,
+                                  ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None):
+    """hk_hybrid_decode_attn_two_stream: the step with the attention over the cached segment on ``side_stream``
+    (a torch stream; None = the same stream) beside the regeneration on ``stream``.  ``events``: a
+    ``hipevents.EventSet`` of at least 2 (fork, join)."""
+    import torch
+    B, H, dh = q.shape
+    L_kv = 0 if K_cache is None else K_cache.shape[2]
+    L_act = 0 if act is None else act.shape[1]
+    f16 = q.dtype
+    shape = make_shape(H * dh, H, ln_eps, softmax_scale, dtype=_dtype_code(q))
+    if out is None:
+        out = torch.empty((B, H, dh), dtype=f16, device=q.device)
+    if workspace is None:
+        workspace = new_workspace(hk_two_stream_workspace_bytes(shape, B, L_kv, L_act), q.device)
+    lp = _params(*layer_params[:4], prepared=layer_params[4] if len(layer_params) > 4 else None, el=f16)
+    main = _stream_ptr(stream)
+    side = main if side_stream is None else _stream_ptr(side_stream)
+    st = lib().hk_hybrid_decode_attn_two_stream(
+        ctypes.byref(shape), _dev_ptr(q, "q", f16), _dev_ptr(K_cache, "K_cache", f16), _dev_ptr(V_cache, "V_cache", f16), L_kv,
+        _dev_ptr(act, "act", f16), L_act, B, ctypes.byref(lp), float(ratio), _dev_ptr(out, "out", f16),
+        _dev_ptr(workspace, "workspace"), workspace.numel(), main, side, events.array[0], events.array[1], int(gemm_cus))
+    if st != HK_OK:
+        raise HybridKVError(st, "hk_hybrid_decode_attn_two_stream")
     return out
 
 

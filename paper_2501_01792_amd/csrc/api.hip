@@ -109,7 +109,7 @@ struct Marks {
 
 int regen_impl(const hk_shape *s, const void *act, int64_t L_act, const hk_layer_params *lp,
                void *K_out, void *V_out, int L_cap, int tok_off, float2 *stats, void *prep_scratch, int64_t M,
-               hipStream_t stream, const Marks &mk)
+               hipStream_t stream, const Marks &mk, int cu_limit = 0)
 {
     const void *prepared = lp->prepared;
     if (!prepared && hk::kv_gemm_uses_prepared(M, s->d, s->gemm_tile, s->dtype)) {
@@ -136,6 +136,7 @@ int regen_impl(const hk_shape *s, const void *act, int64_t L_act, const hk_layer
     }
     g.K_out = K_out; g.V_out = V_out; g.M = M; g.d = s->d; g.n_heads = s->n_heads; g.head_dim = s->head_dim;
     g.L_act = (int)L_act; g.L_cap = L_cap; g.tok_off = tok_off; g.tile = s->gemm_tile; g.dtype = s->dtype;
+    g.cu_limit = cu_limit;
     if (hk::launch_kv_gemm(g, stream) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
 }
@@ -229,6 +230,32 @@ int hk_hybrid_decode_attn(const hk_shape *shape, const void *q,
 }  // extern "C"
 
 namespace {
+
+// ---- the step on two streams: the attention over the cached segment beside the regeneration ----
+struct TwoStreamPlan {
+    Plan base;                 // regenerated K/V, statistics, room for a prepared layer (its partials are not used)
+    int waves_c, waves_r;      // wavefronts of the attention over the cached / the regenerated segment
+    size_t off_part_c, off_part_r, off_out_c, off_out_r, off_lse_c, off_lse_r, total;
+};
+
+int make_two_stream_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, TwoStreamPlan *p)
+{
+    const int st = make_plan(s, B, L_kv, L_act, false, &p->base);
+    if (st != HK_OK) return st;
+    const size_t bh = (size_t)p->base.BH;
+    size_t end = p->base.off_partial;                          // the single-stream partials are not needed: reuse their place
+    auto take = [&](size_t bytes) { const size_t at = end; end += align_up(bytes); return at; };
+    p->waves_c = L_kv > 0 && bh > 0 ? hk::attn_wavefronts((int64_t)bh, L_kv, s->attn_splits) : 0;
+    p->waves_r = L_act > 0 && bh > 0 ? hk::attn_wavefronts((int64_t)bh, L_act, s->attn_splits) : 0;
+    p->off_part_c = take(((size_t)p->waves_c + bh) * (s->head_dim + 2) * sizeof(float));
+    p->off_part_r = take(((size_t)p->waves_r + bh) * (s->head_dim + 2) * sizeof(float));
+    p->off_out_c = take(bh * s->head_dim * 2);
+    p->off_out_r = take(bh * s->head_dim * 2);
+    p->off_lse_c = take(bh * sizeof(float2));
+    p->off_lse_r = take(bh * sizeof(float2));
+    p->total = end > p->base.total ? end : p->base.total;      // never less than the single-stream step needs (the fallback)
+    return HK_OK;
+}
 
 // ---- the step for callers that cannot allocate: scratch in a static device array of the library ----
 // One copy per GPU, held from the loading of the library's code on that GPU until the process ends.
@@ -329,6 +356,80 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape, const void *q,
 {
     return hybrid_step(shape, q, K_cache, V_cache, L_kv, act, L_act, B, params, ratio, out, workspace, workspace_bytes, false,
                        stream, events, n_events);
+}
+
+size_t hk_two_stream_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act)
+{
+    TwoStreamPlan p;
+    if (make_two_stream_plan(shape, B, L_kv, L_act, &p) != HK_OK) return 0;
+    return p.total > 0 ? p.total : kAlign;
+}
+
+int hk_hybrid_decode_attn_two_stream(const hk_shape *shape, const void *q,
+                                     const void *K_cache, const void *V_cache, int32_t L_kv,
+                                     const void *act, int32_t L_act, int32_t B,
+                                     const hk_layer_params *params, float ratio,
+                                     void *out, void *workspace, size_t workspace_bytes,
+                                     void *stream, void *side_stream, void *fork_event, void *join_event, int32_t gemm_cus)
+{
+    TwoStreamPlan p;
+    int st = make_two_stream_plan(shape, B, L_kv, L_act, &p);
+    if (st != HK_OK) return st;
+    if (gemm_cus < 0) return HK_ERR_SHAPE;
+    if (workspace_bytes < p.total) return HK_ERR_WORKSPACE;
+    // Only one segment: there is nothing to run side by side, the single-stream step is the step.
+    if (L_kv == 0 || L_act == 0 || B == 0)
+        return hybrid_step(shape, q, K_cache, V_cache, L_kv, act, L_act, B, params, ratio, out, workspace, workspace_bytes, false,
+                           stream, nullptr, 0);
+    if (!(ratio >= 0.f && ratio <= 1.f)) return HK_ERR_RATIO;
+    const int64_t L = (int64_t)L_kv + L_act;
+    if (std::fabs((double)ratio * (double)L - (double)L_kv) > 0.5 + 1e-6 * (double)L) return HK_ERR_RATIO;
+    if (!q || !out || !workspace || !K_cache || !V_cache || !act || !fork_event || !join_event) return HK_ERR_NULL;
+    st = check_params(params);
+    if (st != HK_OK) return st;
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, kAlign) || !aligned(act, 16) || !aligned(K_cache, 16) ||
+        !aligned(V_cache, 16))
+        return HK_ERR_ALIGN;
+
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t main_s = static_cast<hipStream_t>(stream), side_s = static_cast<hipStream_t>(side_stream);
+    hipEvent_t fork = static_cast<hipEvent_t>(fork_event), join = static_cast<hipEvent_t>(join_event);
+    // main stream: LayerNorm statistics, fork, projection (on gemm_cus compute units when asked).  The fork sits
+    // behind the statistics kernel: that kernel and the attention are both bound by HBM and gain nothing from
+    // running side by side, the projection is bound by the matrix cores.
+    void *K_regen = ws + p.base.off_k, *V_regen = ws + p.base.off_v;
+    hipEvent_t marks[2] = {nullptr, fork};                     // Marks slot 1: recorded after the statistics kernel
+    st = regen_impl(shape, act, L_act, params, K_regen, V_regen, L_act, 0, reinterpret_cast<float2 *>(ws + p.base.off_stats),
+                    ws + p.base.off_prep, p.base.M, main_s, Marks{marks, 2, main_s}, gemm_cus);
+    if (st != HK_OK) return st;
+    // side stream: the attention over the cached segment, which needs nothing the regeneration produces
+    if (hipStreamWaitEvent(side_s, fork, 0) != hipSuccess) return HK_ERR_LAUNCH;
+    hk::AttnArgs a;
+    a.q = q;
+    a.K0 = K_cache; a.V0 = V_cache; a.L0 = L_kv;
+    a.K1 = nullptr; a.V1 = nullptr; a.L1 = 0;
+    a.BH = (int)p.base.BH; a.head_dim = shape->head_dim; a.scale = p.base.scale;
+    a.n_waves = p.waves_c;
+    a.partial = reinterpret_cast<float *>(ws + p.off_part_c);
+    a.out = ws + p.off_out_c;
+    a.lse = reinterpret_cast<float2 *>(ws + p.off_lse_c);
+    a.dtype = shape->dtype;
+    a.after_main = nullptr;
+    if (hk::launch_flash_decode(a, side_s) != hipSuccess) return HK_ERR_LAUNCH;
+    if (hipEventRecord(join, side_s) != hipSuccess) return HK_ERR_LAUNCH;
+    // main stream again: the attention over the regenerated rows
+    a.K0 = K_regen; a.V0 = V_regen; a.L0 = L_act;
+    a.n_waves = p.waves_r;
+    a.partial = reinterpret_cast<float *>(ws + p.off_part_r);
+    a.out = ws + p.off_out_r;
+    a.lse = reinterpret_cast<float2 *>(ws + p.off_lse_r);
+    if (hk::launch_flash_decode(a, main_s) != hipSuccess) return HK_ERR_LAUNCH;
+    if (hipStreamWaitEvent(main_s, join, 0) != hipSuccess) return HK_ERR_LAUNCH;
+    if (hk::launch_segment_join(ws + p.off_out_c, reinterpret_cast<const float2 *>(ws + p.off_lse_c), ws + p.off_out_r,
+                                reinterpret_cast<const float2 *>(ws + p.off_lse_r), out, (int)p.base.BH, shape->head_dim,
+                                shape->dtype, main_s) != hipSuccess)
+        return HK_ERR_LAUNCH;
+    return HK_OK;
 }
 
 int hk_hybrid_decode_attn_static(const hk_shape *shape, const void *q,

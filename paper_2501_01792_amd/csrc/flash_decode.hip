@@ -218,7 +218,46 @@ hipError_t launch_dh(const AttnArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// out = (w_a out_a + w_b out_b) / (w_a + w_b), w_x = l_x 2^(m_x - max(m_a, m_b)): the log-sum-exp join of two token
+// segments.  A segment without tokens has denominator 0 and drops out.  4 elements per thread.
+template <int DT>
+__global__ __launch_bounds__(256) void segment_join_kernel(const typename Elem<DT>::T *__restrict__ out_a, const float2 *__restrict__ lse_a,
+                                                           const typename Elem<DT>::T *__restrict__ out_b, const float2 *__restrict__ lse_b,
+                                                           typename Elem<DT>::T *__restrict__ out, int64_t n4, int dh4)
+{
+    typedef typename Elem<DT>::T elem_t;
+    typedef elem_t half4_t __attribute__((ext_vector_type(4)));
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n4) return;
+    const int64_t bh = idx / dh4;
+    const float2 sa = lse_a[bh], sb = lse_b[bh];
+    const float m = fmaxf(sa.x, sb.x);
+    const float wa = sa.y * __builtin_amdgcn_exp2f(sa.x - m), wb = sb.y * __builtin_amdgcn_exp2f(sb.x - m);
+    const half4_t a = reinterpret_cast<const half4_t *>(out_a)[idx], b = reinterpret_cast<const half4_t *>(out_b)[idx];
+    const float inv = wa + wb > 0.f ? 1.0f / (wa + wb) : 0.f;
+    half4_t o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (elem_t)((wa * (float)a[j] + wb * (float)b[j]) * inv);
+    reinterpret_cast<half4_t *>(out)[idx] = o;
+}
+
 }  // namespace
+
+hipError_t launch_segment_join(const void *out_a, const float2 *lse_a, const void *out_b, const float2 *lse_b, void *out,
+                               int BH, int head_dim, int dtype, hipStream_t s)
+{
+    if (BH <= 0) return hipSuccess;
+    if (head_dim % 4 != 0) return hipErrorInvalidValue;
+    const int64_t n4 = (int64_t)BH * (head_dim / 4);
+    const unsigned blocks = (unsigned)((n4 + 255) / 256);
+    if (dtype == 1)
+        hipLaunchKernelGGL(segment_join_kernel<1>, dim3(blocks), dim3(256), 0, s, static_cast<const __bf16 *>(out_a), lse_a,
+                           static_cast<const __bf16 *>(out_b), lse_b, static_cast<__bf16 *>(out), n4, head_dim / 4);
+    else
+        hipLaunchKernelGGL(segment_join_kernel<0>, dim3(blocks), dim3(256), 0, s, static_cast<const _Float16 *>(out_a), lse_a,
+                           static_cast<const _Float16 *>(out_b), lse_b, static_cast<_Float16 *>(out), n4, head_dim / 4);
+    return hipGetLastError();
+}
 
 int attn_wavefronts(int64_t BH, int64_t L, int splits, int resident)
 {

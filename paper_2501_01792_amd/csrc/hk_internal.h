@@ -40,6 +40,8 @@ struct KvGemmArgs {
     int L_act, L_cap, tok_off;
     int tile;              // 0 = choose, else 128 or 256
     int dtype;             // 0: fp16, 1: bf16 (bf16 always takes the 256 x 256 kernel)
+    int cu_limit = 0;      // > 0: the persistent 256 x 256 kernel uses at most this many compute units (the others stay
+                           // free for a kernel on another stream); 0: all of them
 };
 // LayerNorm-fused K/V projection: K_out/V_out rows <- LN(act) x Wkv^T + bkv, head-split.
 hipError_t launch_kv_gemm(const KvGemmArgs &a, hipStream_t s);
@@ -79,6 +81,10 @@ constexpr int kAttnMaxWaves = 1 << 20;
 int attn_wavefronts(int64_t BH, int64_t L, int splits, int resident = kAttnResidentWaves);
 // Single-query attention over the two token segments taken as one context.
 hipError_t launch_flash_decode(const AttnArgs &a, hipStream_t s);
+// Joins the attention results of two disjoint token segments of the same (sequence, head) pairs: out_x [BH, dh]
+// (16-bit) with lse_x [BH] = (maximum in the log2 domain, softmax denominator) each -> out [BH, dh].
+hipError_t launch_segment_join(const void *out_a, const float2 *lse_a, const void *out_b, const float2 *lse_b, void *out,
+                               int BH, int head_dim, int dtype, hipStream_t s);
 
 struct QkvArgs {
     const void *x;         // [B, d] fp16: layer input of the current token of every sequence

@@ -378,6 +378,7 @@ hipError_t launch_kv_gemm_fold(const KvGemmArgs &a, hipStream_t s)
     int dev = 0, cus = 0;
     const hipError_t e = current_device_cus(&dev, &cus);
     if (e != hipSuccess) return e;
+    if (a.cu_limit > 0 && a.cu_limit < cus) cus = a.cu_limit;  // leave the rest of the chip to a kernel on another stream
     const int grid = n_tiles < cus ? n_tiles : cus;            // one resident workgroup per compute unit
     return a.dtype == 1 ? fold_dt<1>(a, grid, tiles_m, tiles_n, s) : fold_dt<0>(a, grid, tiles_m, tiles_n, s);
 }

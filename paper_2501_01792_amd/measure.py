@@ -4,6 +4,7 @@
     python -m paper_2501_01792_amd.measure paged [--config opt66b] [--block-tokens 16] [--act-fraction 0.0] [--ragged] [--absorbed] [--graph]
 
     python -m paper_2501_01792_amd.measure loop  [--config opt6.7b] [--block-tokens 16] [--act-fraction 0.5] [--ragged] [--iters 20]
+    python -m paper_2501_01792_amd.measure overlap [--config opt6.7b] [--iters 20]
 
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
@@ -13,6 +14,8 @@ layers would have evicted by the time a layer comes round again, so a 512 MiB bu
 B, H, L with blocks of ``--block-tokens`` tokens scattered over the pools in random order.  ``loop`` measures one
 decode step of a layer on that paged cache as a serving loop would run it: hk_paged_append, hk_qkv_current_paged and
 hk_paged_decode_attn_absorbed captured once in a HIP graph and replayed, the context growing by a token per replay.
+``overlap`` measures hk_hybrid_decode_attn_two_stream (the attention over the cached segment on a side stream beside the
+regeneration) against the single-stream step, with the projection kernel on all compute units and on all but 8, 16, 32.
 """
 import argparse
 import json
@@ -228,9 +231,64 @@ def measure_loop(args):
     return 0 if stuck == 0 else 1
 
 
+def measure_overlap(args):
+    import time
+    import torch
+    from . import binding as hk, synth
+    from .hipevents import EventSet
+    cfg = synth.CONFIGS[args.config]
+    if cfg.L_kv == 0 or cfg.L_act == 0:
+        cfg = cfg.with_ratio(0.5)                              # both segments are needed for anything to overlap
+    B, d, H, dh = cfg.B, cfg.d, cfg.n_heads, cfg.head_dim
+    f16 = torch.float16
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen, device="cuda") * std + mean).to(f16)
+    kv_std = 0.02 * d ** 0.5
+    lp = (rn(d, std=0.02, mean=1.0), rn(d, std=0.02), rn(2 * d, d, std=0.02), rn(2 * d, std=0.01))
+    lp = lp + (hk.prepare_layer(*lp, H),)
+    q = rn(B, H, dh, std=kv_std)
+    act = torch.empty(B, cfg.L_act, d, device="cuda", dtype=f16)
+    Kc = torch.empty(B, H, cfg.L_kv, dh, device="cuda", dtype=f16)
+    Vc = torch.empty_like(Kc)
+    for b in range(B):
+        act[b] = rn(cfg.L_act, d)
+        Kc[b] = rn(H, cfg.L_kv, dh, std=kv_std)
+        Vc[b] = rn(H, cfg.L_kv, dh, std=kv_std)
+    shape = hk.make_shape(d, H)
+    out = torch.empty(B, H, dh, device="cuda", dtype=f16)
+    ws1 = hk.new_workspace(hk.hk_workspace_bytes(shape, B, cfg.L_kv, cfg.L_act))
+    ws2 = hk.new_workspace(hk.hk_two_stream_workspace_bytes(shape, B, cfg.L_kv, cfg.L_act))
+    side = torch.cuda.Stream()
+    ev = EventSet(2)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+
+    def timed(call):
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.iters):
+            call()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.iters * 1e3
+
+    res = {"single_stream_entry_point_ms": timed(lambda: hk.hybrid_decode_attn(q, Kc, Vc, act, lp, cfg.ratio, out=out, workspace=ws1)),
+           "two_stream_call_on_one_stream_ms": timed(lambda: hk.hybrid_decode_attn_two_stream(q, Kc, Vc, act, lp, cfg.ratio, None, ev,
+                                                                                               out=out, workspace=ws2))}
+    for free in ((0, 8, 16, 32) if args.free_cus is None else (args.free_cus,)):
+        res["two_streams_gemm_on_%d_cus_ms" % (cus - free)] = timed(
+            lambda: hk.hybrid_decode_attn_two_stream(q, Kc, Vc, act, lp, cfg.ratio, side, ev, out=out, workspace=ws2,
+                                                     gemm_cus=0 if free == 0 else cus - free))
+    ev.destroy()
+    print(json.dumps({"entry": "hk_hybrid_decode_attn_two_stream", "compute_units": cus,
+                      "workload": "%s: B=%d d=%d H=%d L_kv=%d L_act=%d" % (cfg.name, B, d, H, cfg.L_kv, cfg.L_act),
+                      "iters": args.iters, "result": res}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["qkv", "paged", "loop"])
+    ap.add_argument("what", choices=["qkv", "paged", "loop", "overlap"])
     ap.add_argument("--config", default=None)
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--block-tokens", type=int, default=16)
@@ -238,6 +296,7 @@ def main():
     ap.add_argument("--ragged", action="store_true")
     ap.add_argument("--absorbed", action="store_true", help="paged: the entry point that does not regenerate K/V")
     ap.add_argument("--graph", action="store_true", help="paged: time the step replayed from a HIP graph")
+    ap.add_argument("--free-cus", type=int, default=None, help="overlap: only this carve-out (compute units left to the side stream)")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -251,6 +310,9 @@ def main():
     if args.what == "loop":
         args.config = args.config or "opt6.7b"
         return measure_loop(args)
+    if args.what == "overlap":
+        args.config = args.config or "opt6.7b"
+        return measure_overlap(args)
     args.config = args.config or "opt66b"
     return measure_paged(args)
 

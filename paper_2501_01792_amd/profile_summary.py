@@ -26,7 +26,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 KERNELS = ("column_product|paged_scores|paged_index|paged_prefix|paged_append|row_stats|absorbed_scores_block|"
            "absorbed_scores|absorbed_softmax|absorbed_project_block|absorbed_project|absorbed_join|absorbed_stream|"
            "qkv_block|qkv_fused|ln_rows|qkv_finish|paged_decode|paged_merge|kv_gemm_fold|kv_gemm|prepare_layer|"
-           "flash_decode|merge_partials|mfma_rate|ln_stats[a-z_]*")
+           "flash_decode|merge_partials|segment_join|mfma_rate|ln_stats[a-z_]*")
 
 # counter groups, each within what one pass can hold (8 SQ, 4 TCC, 2 GRBM)
 GROUPS = [
@@ -99,8 +99,10 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--limit", type=int, default=240, help="seconds per pass")
     ap.add_argument("--skip", default="", help="comma-separated counter groups to leave out (mfma, wait, l2, traffic)")
-    ap.add_argument("rest", nargs="*")
-    args = ap.parse_args()
+    ap.add_argument("--timeline", type=int, default=0, help="also list start and end (us, relative) of the last N kernel "
+                    "dispatches of the trace with their streams: shows whether kernels of two streams ran side by side")
+    args, rest = ap.parse_known_args()
+    args.rest = [a for a in rest if a != "--"]                 # what follows belongs to the measured program
     skip = set(x for x in args.skip.split(",") if x)
 
     if args.what == "hybrid":
@@ -123,6 +125,18 @@ def main():
     out += ["Kernel durations", "  command: " + shown, "",
             "  %-34s %6s %12s %12s %12s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "pct")]
     out += ["  %-34s %6d %12.1f %12.1f %12.1f %7.2f" % r for r in stats]
+    if args.timeline > 0:
+        path = glob.glob(os.path.join(d, "**", "p_kernel_trace.csv"), recursive=True)[0]
+        rows = [r for r in csv.DictReader(open(path)) if short(r["Kernel_Name"]) and short(r["Kernel_Name"]) != CALIBRATION]
+        rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+        rows = rows[-args.timeline:]
+        t0 = int(rows[0]["Start_Timestamp"])
+        out += ["", "Timeline of the last %d dispatches (us from the first of them; a kernel that starts before the previous "
+                "one ends runs beside it)" % len(rows),
+                "  %-34s %10s %12s %12s %10s" % ("kernel", "stream", "start_us", "end_us", "dur_us")]
+        for r in rows:
+            s0, s1 = (int(r["Start_Timestamp"]) - t0) / 1e3, (int(r["End_Timestamp"]) - t0) / 1e3
+            out.append("  %-34s %10s %12.1f %12.1f %10.1f" % (short(r["Kernel_Name"]), r.get("Stream_Id", r.get("Queue_Id", "?")), s0, s1, s1 - s0))
     avg_us = {r[0]: r[2] for r in stats}
     # counter groups are listed for the kernels that matter: at least 0.5 % of the kernel time, never the calibration copy
     listed = set(r[0] for r in stats if r[5] >= 0.5 and r[0] != CALIBRATION)
@@ -192,7 +206,7 @@ def main():
         import json
         try:
             j = json.loads(line)
-            keep = {k: j[k] for k in ("metric", "value", "unit", "ms_per_step", "ms", "min_ms", "kernel_ms", "workload", "entry") if k in j}
+            keep = {k: j[k] for k in ("metric", "value", "unit", "ms_per_step", "ms", "min_ms", "kernel_ms", "workload", "entry", "result") if k in j}
             if isinstance(j.get("config"), dict):
                 keep["workload"] = j["config"].get("workload")
             for k in ("roofline", "roofline_attn"):
