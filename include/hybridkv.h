@@ -278,7 +278,8 @@ int hk_hybrid_decode_attn_marked(const hk_shape *shape,
  *   q_out     [B, H, dh] fp16
  *   K_dst, V_dst [B, H, L_cap, dh] fp16, both NULL or both given; only row tok_pos is written
  *   act_dst   [B, act_cap, d] fp16 or NULL; only row act_pos is written
- *   workspace needs hk_qkv_workspace_bytes(shape, B)
+ *   workspace needs hk_qkv_workspace_bytes(shape, B) (a token amount: the call is a single kernel that keeps its
+ *             intermediate values on chip; the argument is kept so that callers need not change)
  * B == 0 is a successful no-op.
  */
 size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B);

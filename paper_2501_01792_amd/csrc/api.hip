@@ -578,25 +578,10 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
     return HK_OK;
 }
 
-namespace {
-
-// Floats of fp32 partial sums that hk_qkv_current needs for B rows (rows are taken kQkvMaxRows at a time).
-size_t qkv_part_floats(int d, int64_t B)
-{
-    const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
-    int parts, steps_per_part;
-    hk::qkv_parts(d, &parts, &steps_per_part);
-    return (size_t)parts * rows * 3 * d;
-}
-
-}  // namespace
-
 size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
 {
     if (check_shape(shape, true) != HK_OK || B < 0 || B > (1 << 24)) return 0;
-    const size_t rows = (size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows);
-    const size_t bytes = align_up(rows * (size_t)shape->d * 2) + align_up(qkv_part_floats(shape->d, B) * sizeof(float));
-    return bytes > 0 ? bytes : kAlign;
+    return kAlign;                                             // the call is one kernel that needs no scratch; the argument stays
 }
 
 namespace {
@@ -649,15 +634,12 @@ int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
 
     const int d = shape->d;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    // rows are taken kQkvMaxRows at a time; the scratch row block is reused (same stream: ordered)
+    // rows are taken kQkvMaxRows at a time
     for (int32_t b0 = 0; b0 < B; b0 += hk::kQkvMaxRows) {
         hk::QkvArgs a;
         const int rows = B - b0 < hk::kQkvMaxRows ? B - b0 : hk::kQkvMaxRows;
         a.x = static_cast<const char *>(x_cur) + (size_t)b0 * d * 2;
         a.ln_w = params->ln_w; a.ln_b = params->ln_b; a.Wq = Wq; a.bq = bq; a.Wkv = params->Wkv; a.bkv = params->bkv;
-        a.xhat = workspace;
-        a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)(B < hk::kQkvMaxRows ? B : hk::kQkvMaxRows) * d * 2));
-        a.part_floats = qkv_part_floats(d, B);
         a.q_out = static_cast<char *>(q_out) + (size_t)b0 * d * 2;
         a.K_dst = K_dst ? static_cast<char *>(K_dst) + (paged ? 0 : (size_t)b0 * L_cap * d * 2) : nullptr;
         a.V_dst = V_dst ? static_cast<char *>(V_dst) + (paged ? 0 : (size_t)b0 * L_cap * d * 2) : nullptr;

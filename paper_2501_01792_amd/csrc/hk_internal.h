@@ -91,9 +91,6 @@ struct QkvArgs {
     const void *ln_w, *ln_b;
     const void *Wq, *bq;   // [d, d], [d]
     const void *Wkv, *bkv; // [2d, d], [2d]
-    void *xhat;            // [B, d] fp16 scratch
-    float *part;           // [parts, B, 3d] fp32 scratch (parts from qkv_parts)
-    size_t part_floats;    // its capacity in floats
     void *q_out;           // [B, H, dh]
     void *K_dst, *V_dst;   // [B, H, L_cap, dh] or both null: no K/V row is produced
     void *act_dst;         // null, or where row b of x is copied: act_dst + b * act_row_stride (elements)
@@ -110,8 +107,6 @@ struct QkvArgs {
     int max_blocks, blk_log2, P_kv, P_act;
 };
 constexpr int kQkvMaxRows = 128;       // rows one launch of the skinny kernel takes
-// How the projection of the current tokens cuts the reduction axis over workgroups.
-void qkv_parts(int d, int *parts, int *steps_per_part);
 // LayerNorm + Q (and K/V) projection of B <= kQkvMaxRows current-token rows, with write-back.
 hipError_t launch_qkv_current(const QkvArgs &a, hipStream_t s);
 

@@ -181,7 +181,7 @@ def test_qkv_current_rejects_bad_arguments():
     """Every check of hk_qkv_current runs on the host before a launch: no GPU is touched here."""
     ok = hk.make_shape(768, 12)
     need = hk.hk_qkv_workspace_bytes(ok, 4)
-    assert need >= 4 * 768 * 2
+    assert need > 0                                              # a token amount: the call keeps its intermediates on chip
     assert hk.hk_qkv_workspace_bytes(hk.make_shape(768, 11), 4) == 0
     assert hk.hk_qkv_workspace_bytes(ok, 1000) == hk.hk_qkv_workspace_bytes(ok, 128)      # rows go 128 at a time
     lp = hk.hk_layer_params(FAKE, FAKE, FAKE, FAKE, None)
