@@ -17,16 +17,18 @@
 // than 32x32x16 (half the accumulator register traffic per flop).  The reduction axis advances in k blocks of 64; a k block
 // of one operand is a "unit" of 256 rows x 128 bytes = 32 KiB, and the 160 KiB of LDS are a ring of
 // 5 units through which the units of all the workgroup's tiles stream in consumption order
-// (activations of block g, weights of block g, activations of block g+1, ...): the loads run
+// (weights of block g, activations of block g, weights of block g+1, ...): the loads run
 // across tile boundaries, so only the first tile of a workgroup sees a cold pipeline.
 //   * Loads are buffer_load ... lds, 16 bytes per lane; the 8 lanes of an LDS row fetch one whole
 //     128-byte line of a global row (half-line requests halve the useful rate of the L2 channels).
 //     The XOR swizzle of the 16-byte chunk index, (row / 2) % 8, is applied on the global side; it
 //     makes the 16-row x 4-chunk fragment reads (ds_read_b128) conflict-free.
-//   * While k block g is consumed (2 sub-steps of k = 32, 64 MFMAs each per wavefront) the activations
-//     of block g+2 are issued during its first half and the weights of block g+2 right after the
-//     barrier early in its second half, into the slot that barrier has just freed.  One barrier per
-//     k block.
+//   * While k block g is consumed (2 sub-steps of k = 32, 64 MFMAs each per wavefront) the weights
+//     of block g+2 are issued during its first half (into the ring's spare slot) and the activations of
+//     block g+2 behind the barrier early in its second half, into a slot that barrier has just freed.
+//     One barrier per k block.  The weights, which the eight XCDs all read and which miss their L2 more
+//     often, get the longer flight.  The byte offsets of a tile's 8 + 8 loads are computed once per tile;
+//     a load in the main loop costs its issue slot and no vector arithmetic.
 //   * Fragments (8 + 8 per sub-step) are double-buffered in registers; every MFMA slot carries at most
 //     one LDS read and one direct load.
 //   * End of a tile: a row table (destination offset + statistics per row) is built in the one
@@ -53,6 +55,10 @@ constexpr int kRowBytes = FBK * 2;                          // 128-byte LDS rows
 constexpr int kUnitBytes = 256 * kRowBytes;                 // 32 KiB: one operand of one k block
 constexpr int kRingBytes = kSlots * kUnitBytes;             // 160 KiB
 constexpr int kLoadsPerUnit = 8;                            // direct loads one lane issues per unit
+// Order of the two units of a k block in the ring.  The first unit of block g + 2 is fetched early (during block g's
+// first half, into the ring's one spare slot), the second late (behind block g's barrier, into a slot that barrier
+// frees) and has the shorter time to land.
+constexpr bool kWeightsFirst = true;
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -146,7 +152,10 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
 
     // state of the load cursor: the k block whose units are issued next
     __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
-    int a_vmax = 0, b_vmax = 0;                                // clamp: rows past the end read the last valid row
+    // Byte offsets of this lane's 8 + 8 loads of a unit inside the tile's row panels, rows past the end clamped to
+    // the last valid row: worked out once per tile, so that a load in the main loop costs no vector arithmetic (the
+    // position along the reduction axis travels in the scalar offset).
+    int a_voff[kLoadsPerUnit], b_voff[kLoadsPerUnit];
     int ld_j = 0, ld_kb = 0, ld_g = 0;
     auto set_load_tile = [&](int j) {
         int tm, tn;
@@ -160,8 +169,14 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         b_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<elem_t *>(Wp + (int64_t)n0 * d), 0, (int)b_bytes, 0x00020000);
         const int ra = (M - m0 < FBM) ? (int)(M - m0) - 1 : FBM - 1;
         const int rb = (N - n0 < FBN) ? (N - n0) - 1 : FBN - 1;
-        a_vmax = (ra * d + l_chunk * 8) * 2;
-        b_vmax = (rb * d + l_chunk * 8) * 2;
+        const int a_vmax = (ra * d + l_chunk * 8) * 2, b_vmax = (rb * d + l_chunk * 8) * 2;
+#pragma unroll
+        for (int i = 0; i < kLoadsPerUnit; ++i) {
+            const int va = a_voff0 + i * 32 * d * 2;
+            const int vb = b_voff0 + ((i >> 2) * 128 + 2 * (i & 3)) * d * 2;
+            a_voff[i] = va < a_vmax ? va : a_vmax;
+            b_voff[i] = vb < b_vmax ? vb : b_vmax;
+        }
     };
     auto advance_load = [&]() {                                // past the last k block the cursor stays on it
         if (ld_g + 1 < G) {
@@ -170,16 +185,12 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         }
     };
     auto issue_a = [&](int slot, int i) {
-        int v = a_voff0 + i * 32 * d * 2;
-        v = v < a_vmax ? v : a_vmax;
         unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)dst, 16, a_voff[i], ld_kb * (FBK * 2), 0, 0);
     };
     auto issue_b = [&](int slot, int i) {
-        int v = b_voff0 + ((i >> 2) * 128 + 2 * (i & 3)) * d * 2;
-        v = v < b_vmax ? v : b_vmax;
         unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)dst, 16, v, ld_kb * (FBK * 2), 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_ptr_t)dst, 16, b_voff[i], ld_kb * (FBK * 2), 0, 0);
     };
 
     // ---- fragment reads: row (lane % 16) + 16 i of the wavefront's sub-tile, logical chunk 4 ks + lane / 16
@@ -208,58 +219,60 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
 #pragma unroll
-        for (int i = 0; i < kLoadsPerUnit; ++i) issue_a(2 * s, i);
+        for (int i = 0; i < kLoadsPerUnit; ++i) kWeightsFirst ? issue_b(2 * s, i) : issue_a(2 * s, i);
 #pragma unroll
-        for (int i = 0; i < kLoadsPerUnit; ++i) issue_b(2 * s + 1, i);
+        for (int i = 0; i < kLoadsPerUnit; ++i) kWeightsFirst ? issue_a(2 * s + 1, i) : issue_b(2 * s + 1, i);
         advance_load();
     }
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) read_frag(f0, 0, 1, 0, q);
+    for (int q = 0; q < 16; ++q) read_frag(f0, kWeightsFirst ? 1 : 0, kWeightsFirst ? 0 : 1, 0, q);
 
-    int sA = 0, sB = 1;                                        // slots of the units of k block g
+    int s1 = 0, s2 = 1;                                        // slots of the first and the second unit of k block g
     for (int c_j = 0; c_j < my_tiles; ++c_j) {                 // tiles of this workgroup
     float4_t acc[FTM][FTN];
     // one k block; `first`: the tile's first block, whose first MFMAs start from zero accumulators
     auto stage = [&](auto first) {
         constexpr bool FIRST = decltype(first)::value;
         const float4_t zero = {0.f, 0.f, 0.f, 0.f};
-        const int sA1 = next2(sA), sB1 = next2(sB);            // k block g + 1
-        const int sA2 = next2(sA1), sB2 = sA;                  // k block g + 2: units 2g+4, 2g+5
-        // ---- sub-step 0 (f0, k 0..31): fragments of sub-step 1 -> f1; activations of block g+2
+        const int n1 = next2(s1), n2 = next2(s2);              // k block g + 1
+        const int early = next2(n1), late = s1;                // k block g + 2: units 2g+4 (the spare slot), 2g+5 (block g's first)
+        const int sA = kWeightsFirst ? s2 : s1, sB = kWeightsFirst ? s1 : s2;
+        const int sA1 = kWeightsFirst ? n2 : n1, sB1 = kWeightsFirst ? n1 : n2;
+        // ---- sub-step 0 (f0, k 0..31): fragments of sub-step 1 -> f1; first unit of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
             acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7]);
             if (q < 32 && (q & 1) == 0) read_frag(f1, sA, sB, 1, q >> 1);
-            if ((q & 7) == 7) issue_a(sA2, q >> 3);
+            if ((q & 7) == 7) kWeightsFirst ? issue_b(early, q >> 3) : issue_a(early, q >> 3);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // ---- sub-step 1 (f1, k 32..63): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; weights of block g+2
+        // ---- sub-step 1 (f1, k 32..63): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; second unit of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
             acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7]);
             if (q == 3) {
                 // Every LDS read of block g has been issued.  Wait for them and for this wavefront's loads
-                // of block g+1 (the 8 activation loads of block g+2 may fly), then meet the others: after
+                // of block g+1 (the 8 early loads of block g+2 may fly), then meet the others: after
                 // the barrier block g+1 is complete in LDS and the slots of block g may be refilled.
                 asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
                 asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
             if (q >= 4 && q < 36 && (q & 1) == 0) read_frag(f0, sA1, sB1, 0, (q - 4) >> 1);
-            if (q >= 7 && (q & 7) == 7) issue_b(sB2, q >> 3);                // q = 7, 15, .., 63: loads 0..7
+            if (q >= 7 && (q & 7) == 7) kWeightsFirst ? issue_a(late, q >> 3) : issue_b(late, q >> 3);   // q = 7, 15, .., 63: loads 0..7
             __builtin_amdgcn_sched_barrier(0);
         }
         advance_load();
-        sA = sA1; sB = sB1;
+        s1 = n1; s2 = n2;
     };
     stage(std::true_type{});
     for (int c_kb = 1; c_kb < nks - 1; ++c_kb) stage(std::false_type{});
             // ---- end of a tile: LayerNorm statistics, constants of the layer, fp16, head split.
             // What the epilogue needs from memory (the row's statistics, the constants of this lane's output
             // features) is asked for before the tile's last k block, whose MFMAs hide the latency; these
-            // loads are older than the last block's activation loads, so its vmcnt(8) covers them.
+            // loads are older than the last block's early loads, so its vmcnt(8) covers them.
             static_assert(FBM == FNT, "one table row per thread");
             int tm, tn;
             tile_coords<GROUP_M>((int)blockIdx.x + c_j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
@@ -275,9 +288,9 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
             }
     stage(std::false_type{});                                  // the last k block (nks >= 2)
         {
-            // The slot that held the weights of block g (now sB's predecessor) is free until the next
-            // block's activation loads are issued: it holds the row table meanwhile.
-            const int s_tab = sB >= 2 ? sB - 2 : sB + kSlots - 2;        // slot of the weights of block g
+            // The slot that held the second unit of the block just consumed is free until the next
+            // block's late loads are issued: it holds the row table meanwhile.
+            const int s_tab = s2 >= 2 ? s2 - 2 : s2 + kSlots - 2;        // slot of the second unit of block g
             RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
             tab[tid] = my_row;
             __syncthreads();

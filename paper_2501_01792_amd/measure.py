@@ -5,6 +5,7 @@
 
     python -m paper_2501_01792_amd.measure loop  [--config opt6.7b] [--block-tokens 16] [--act-fraction 0.5] [--ragged] [--iters 20]
     python -m paper_2501_01792_amd.measure overlap [--config opt6.7b] [--iters 20]
+    python -m paper_2501_01792_amd.measure gemm    [--config opt66b] [--iters 6]
 
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
@@ -16,6 +17,9 @@ decode step of a layer on that paged cache as a serving loop would run it: hk_pa
 hk_paged_decode_attn_absorbed captured once in a HIP graph and replayed, the context growing by a token per replay.
 ``overlap`` measures hk_hybrid_decode_attn_two_stream (the attention over the cached segment on a side stream beside the
 regeneration) against the single-stream step, with the projection kernel on all compute units and on all but 8, 16, 32.
+``gemm`` measures hk_regen_kv (LayerNorm statistics + projection with bias and head-split stores) on the workload's
+regeneration GEMM (all of its tokens as checkpoints) alternately with a plain library GEMM on the same operands
+(torch.addmm, i.e. hipBLASLt: no LayerNorm, row-major output), as a comparator for what this GPU sustains on the shape.
 """
 import argparse
 import json
@@ -286,9 +290,54 @@ def measure_overlap(args):
     return 0
 
 
+def measure_gemm(args):
+    import torch
+    from . import binding as hk, synth
+    cfg = synth.CONFIGS[args.config]
+    B, d, H, dh = cfg.B, cfg.d, cfg.n_heads, cfg.head_dim
+    L = cfg.L_act if cfg.L_act else cfg.L
+    f16 = torch.float16
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen, device="cuda") * std + mean).to(f16)
+    act = torch.empty(B, L, d, device="cuda", dtype=f16)
+    for b in range(B):
+        act[b] = rn(L, d)
+    W, bias = rn(2 * d, d, std=0.02), rn(2 * d, std=0.01)
+    g, be = rn(d, std=0.02, mean=1.0), rn(d, std=0.02)
+    K = torch.empty(B, H, L, dh, device="cuda", dtype=f16)
+    V = torch.empty_like(K)
+    shape = hk.make_shape(d, H)
+    ws = hk.new_workspace(hk.hk_regen_workspace_bytes(shape, B, L))
+    prep = hk.prepare_layer(g, be, W, bias, H)
+    flop = 4.0 * B * L * d * d
+    ours = lambda: hk.regen_kv(act, g, be, W, bias, H, K_out=K, V_out=V, workspace=ws, prepared=prep)
+    a2 = act.view(B * L, d)
+    out = torch.empty(B * L, 2 * d, device="cuda", dtype=f16)
+    lib = lambda: torch.addmm(bias, a2, W.t(), out=out)
+
+    def timed(f):
+        e0, e1 = _events(torch)
+        e0.record()
+        for _ in range(args.iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.iters
+
+    for _ in range(2):
+        ours(); lib()
+    rounds = []
+    for _ in range(4):
+        t1, t2 = timed(ours), timed(lib)
+        rounds.append({"hk_regen_kv_tflops": flop / t1 / 1e9, "library_gemm_tflops": flop / t2 / 1e9})
+    print(json.dumps({"entry": "hk_regen_kv against torch.addmm (hipBLASLt), alternating, %d launches per figure" % args.iters,
+                      "workload": "%s: M=%d K=%d N=%d" % (cfg.name, B * L, d, 2 * d), "peak_tflops": 2500.0, "rounds": rounds}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["qkv", "paged", "loop", "overlap"])
+    ap.add_argument("what", choices=["qkv", "paged", "loop", "overlap", "gemm"])
     ap.add_argument("--config", default=None)
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--block-tokens", type=int, default=16)
@@ -313,6 +362,11 @@ def main():
     if args.what == "overlap":
         args.config = args.config or "opt6.7b"
         return measure_overlap(args)
+    if args.what == "gemm":
+        args.config = args.config or "opt66b"
+        if args.iters == 20:
+            args.iters = 6
+        return measure_gemm(args)
     args.config = args.config or "opt66b"
     return measure_paged(args)
 

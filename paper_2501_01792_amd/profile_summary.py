@@ -43,7 +43,10 @@ CALIBRATION = "device copy (calibration)"     # the runtime's buffer-copy kernel
 def short(name):
     m = re.search(r"(%s)_kernel(?:<|ILi)?(\d+)?" % KERNELS, name)
     if not m:
-        return CALIBRATION if "rocclr_copyBuffer" in name else None
+        if "Cijk_" in name:                                # a kernel of the vendor GEMM library (comparator runs)
+            mt = re.search(r"MT(\d+x\d+x\d+)", name)
+            return "library_gemm_%s_kernel" % (mt.group(1) if mt else "")
+        return CALIBRATION if "rocclr_copyBuffer" in name else None     # (only used when the program was asked for the 1 GiB copy)
     return m.group(1) + ("<%s>" % m.group(2) if m.group(2) else "") + "_kernel"
 
 
@@ -101,6 +104,8 @@ def main():
     ap.add_argument("--skip", default="", help="comma-separated counter groups to leave out (mfma, wait, l2, traffic)")
     ap.add_argument("--timeline", type=int, default=0, help="also list start and end (us, relative) of the last N kernel "
                     "dispatches of the trace with their streams: shows whether kernels of two streams ran side by side")
+    ap.add_argument("--extra", action="append", default=[], metavar="NAME:C1,C2,...",
+                    help="one more counter pass (at most 8 SQ, 4 TCC, 2 GRBM counters), listed like the built-in groups")
     args, rest = ap.parse_known_args()
     args.rest = [a for a in rest if a != "--"]                 # what follows belongs to the measured program
     skip = set(x for x in args.skip.split(",") if x)
@@ -150,7 +155,7 @@ def main():
         out += ["", "HBM-side traffic counters (per dispatch, KiB)", "  commands: " + shown_f, "            " + shown_w, ""]
         sf = sw = None
         cal = CALIBRATION
-        if cal in f and cal in w:
+        if calib and cal in f and cal in w:
             sf, sw = 1048576.0 / f[cal]["FETCH_SIZE"], 1048576.0 / w[cal]["WRITE_SIZE"]
             out.append("  calibration: a plain 1 GiB device copy (1048576 KiB read, 1048576 KiB written) reads FETCH_SIZE=%.1f, "
                        "WRITE_SIZE=%.1f" % (f[cal]["FETCH_SIZE"], w[cal]["WRITE_SIZE"]))
@@ -168,7 +173,8 @@ def main():
             rate = (fv * sf + wv * sw) * 1024.0 / (avg_us[k] * 1e-6) / 1e9 if k in avg_us else float("nan")
             out.append("  %-34s %14.1f %14.1f %14.1f %14.1f %12.0f" % (k, fv, fv * sf, wv, wv * sw, rate))
 
-    for name, counters in GROUPS:
+    extra = [(e.split(":")[0], e.split(":")[1].split(",")) for e in args.extra]
+    for name, counters in GROUPS + extra:
         if name in skip:
             continue
         dg, shown_g = run_pass(tag, name, ["--pmc"] + counters, prog, args.limit)
