@@ -13,11 +13,9 @@
  *     16-byte aligned.  hk_shape / hk_layer_params themselves are HOST structs
  *     passed by pointer and read before the call returns.
  *   - Storage dtype is IEEE fp16 (HK_DTYPE_F16), the precision of the paper's
- *     models (Sec. 5.1); accumulation is fp32.  hk_prepare_layer, hk_regen_kv,
- *     the hybrid step (hk_hybrid_decode_attn, _marked), hk_qkv_current and
- *     hk_paged_decode_attn, with their size queries, also take bfloat16
- *     (HK_DTYPE_BF16: every fp16 tensor below is bf16 instead); the two entry
- *     points that do not regenerate K/V (_absorbed) return HK_ERR_DTYPE for it.
+ *     models (Sec. 5.1); accumulation is fp32.  Every device entry point and
+ *     size query also takes bfloat16 (HK_DTYPE_BF16: every fp16 tensor below is
+ *     bf16 instead).
  *   - The library allocates nothing.  Scratch memory is the caller's
  *     `workspace` (device, 256-byte aligned, at least hk_workspace_bytes()).
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
@@ -373,6 +371,9 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
  *
  *   n_heads <= 128, B <= 65535; otherwise HK_ERR_SHAPE.
  *   workspace    needs hk_absorbed_workspace_bytes(shape, B, L_kv, L_act); scratch only.
+ * bfloat16 tensors are converted to fp16 as they are loaded and the step computes as it does for fp16 (the
+ * carried query and the weighted row sum keep 11 significant bits); the conversion is exact for magnitudes
+ * from 2^-14 to 65504, larger ones are taken as 65504.
  * A layer without `prepared` is prepared inside the call (one pass over the weights).
  */
 size_t hk_absorbed_workspace_bytes(const hk_shape *shape, int32_t B, int32_t L_kv, int32_t L_act);

@@ -350,13 +350,13 @@ def hybrid_decode_attn_absorbed(q, K_cache, V_cache, act, layer_params, ratio, o
     d = H * dh
     L_kv = 0 if K_cache is None else K_cache.shape[2]
     L_act = 0 if act is None else act.shape[1]
-    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, 0)
+    f16 = q.dtype if q.dtype == torch.bfloat16 else torch.float16   # fp16, or bf16 (every tensor then)
+    shape = make_shape(d, H, ln_eps, softmax_scale, attn_splits, 0, dtype=_dtype_code(q))
     if out is None:
-        out = torch.empty((B, H, dh), dtype=torch.float16, device=q.device)
+        out = torch.empty((B, H, dh), dtype=f16, device=q.device)
     if workspace is None:
         workspace = new_workspace(hk_absorbed_workspace_bytes(shape, B, L_kv, L_act), q.device)
-    lp = _params(*layer_params)
-    f16 = torch.float16
+    lp = _params(*layer_params, el=f16)
     st = lib().hk_hybrid_decode_attn_absorbed(
         ctypes.byref(shape), _dev_ptr(q, "q", f16),
         _dev_ptr(K_cache, "K_cache", f16), _dev_ptr(V_cache, "V_cache", f16), L_kv,

@@ -13,7 +13,10 @@
 // ROUNDED values (sum_k of the stored u_h, sum_t of the stored w_t) and subtracted in fp32 before anything is
 // rounded again, so that a row mean that is large against the row's spread cancels exactly as it does in
 // the LayerNorm, instead of leaving the rounding error of u_h or w_t multiplied by it.  The cached K/V segment goes through the ordinary decode kernel and the two
-// segments are joined by their softmax maxima and denominators.  This is a comparison variant beyond the
+// segments are joined by their softmax maxima and denominators.  Tensors stored as bfloat16 (q, the checkpoints, the
+// prepared weights, the cached segment's output, out) are converted to fp16 where they are loaded, so the
+// arithmetic, and with it the cancellation argument above, is the same for both storage types; u, w, y are fp16
+// either way.  This is a comparison variant beyond the
 // paper's design (which regenerates K/V with a GEMM); the paper's Eq. 3/4/7 define the result.
 //
 // Kernels (B sequences, H heads, L_act checkpoint rows per sequence):
@@ -77,6 +80,7 @@ struct ColArgs {
     // batch z has R_list[z] rows (0: the output rows of z are zero)
     const int32_t *blk_list; int list_pitch, blk_log2;
     const int32_t *R_list;
+    int s_dt, a_dt;                                        // storage types of S and of A (Out is fp16)
 };
 
 constexpr int kColBlock = 64;                              // columns of one wavefront
@@ -87,7 +91,7 @@ constexpr int kTileBytes = 32 * 128;                       // 32 operand rows x 
 template <int RB>
 constexpr int col_lds_bytes() { return 4 * kColStage + 2 * RB * kTileBytes; }
 
-template <int RB>
+template <int RB, int SDT, int ADT>
 __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     auto put_a = [&](int slot, int buf) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kTileBytes + t_wr) = av[slot][rb];
+            *reinterpret_cast<half8_t *>(tile + (buf * RB + rb) * kTileBytes + t_wr) = skinny::to_half8<ADT>(av[slot][rb]);
     };
     if (R <= 0) {                                          // nothing to sum (uniform over the workgroup: no barrier is missed)
         if (live) {
@@ -199,7 +203,7 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
                     if (sc < steps) {
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
-                            *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = sv[u][j];
+                            *reinterpret_cast<half8_t *>(my + (8 * j + g_row) * XS + 16 * g_chunk) = skinny::to_half8<SDT>(sv[u][j]);
                         // bf[nb][i] = element (row 8 lh + i, column 32 nb + ln) of the block, by two transposing reads:
                         // ds_read_b64_tr_b16 hands lane t of a 16-lane group the four rows that the group's lanes
                         // 4 j + t / 4 .. point at, at column 4 (source lane % 4) + ... = t of the group's 16 columns
@@ -252,10 +256,10 @@ __global__ __launch_bounds__(256) void column_product_kernel(ColArgs p)
     }
 }
 
-template <int RB>
-hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
+template <int RB, int SDT, int ADT>
+hipError_t launch_col_as(const ColArgs &p, int batches, hipStream_t s)
 {
-    auto kern = column_product_kernel<RB>;
+    auto kern = column_product_kernel<RB, SDT, ADT>;
     constexpr int lds = col_lds_bytes<RB>();
     static LdsOnce lds_once;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
@@ -263,6 +267,15 @@ hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
     const int blocks_x = (p.n_cols / kColBlock + 3) / 4;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks_x, (unsigned)batches), dim3(256), lds, s, p);
     return hipGetLastError();
+}
+
+template <int RB>
+hipError_t launch_col(const ColArgs &p, int batches, hipStream_t s)
+{
+    if (p.s_dt == 0 && p.a_dt == 0) return launch_col_as<RB, 0, 0>(p, batches, s);
+    if (p.s_dt == 1 && p.a_dt == 1) return launch_col_as<RB, 1, 1>(p, batches, s);
+    if (p.s_dt == 1 && p.a_dt == 0) return launch_col_as<RB, 1, 0>(p, batches, s);
+    return hipErrorInvalidValue;
 }
 
 // A must be readable (and zero beyond R) up to the next multiple of 64 reduction elements.
@@ -296,7 +309,7 @@ __device__ __forceinline__ float4 row_stats(float s1, float s2, float first, int
 
 // Few checkpoint rows in all: a slab of 32 rows per workgroup, the reduction axis cut over its 4 wavefronts
 // (skinny::slab_product), so that even a small problem fills the chip.  Every workgroup reads all of U[:,b,:].
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
                                                               float *__restrict__ raw, float4 *__restrict__ stats,
                                                               int B, int L_act, int Lp, int H, int d, float eps)
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__
     const int t0 = (item % slabs) * skinny::kSlab;
     const int rows = L_act - t0 < skinny::kSlab ? L_act - t0 : skinny::kSlab;
     const _Float16 *S = act + (b * L_act + t0) * d;
-    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false, true>(S, rows, d, U + b * d, H, (int64_t)B * d, d, smem);
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, false, true, DT>(S, rows, d, U + b * d, H, (int64_t)B * d, d, smem);
     for (int idx = tid; idx < H * skinny::kSlab; idx += 256) {
         const int h = idx / skinny::kSlab, c = idx % skinny::kSlab;
         if (c < rows)
@@ -319,13 +332,13 @@ __global__ __launch_bounds__(256) void absorbed_scores_kernel(const _Float16 *__
         float (*mom)[skinny::kSlab][2] = skinny::moments<RB>(smem);
         const float s1 = (mom[0][tid][0] + mom[1][tid][0]) + (mom[2][tid][0] + mom[3][tid][0]);
         const float s2 = (mom[0][tid][1] + mom[1][tid][1]) + (mom[2][tid][1] + mom[3][tid][1]);
-        stats[b * L_act + t0 + tid] = row_stats(s1, s2, (float)S[(int64_t)tid * d], d, eps);
+        stats[b * L_act + t0 + tid] = row_stats(s1, s2, (float)skinny::stored_to_half<DT>(S + (int64_t)tid * d), d, eps);
     }
 }
 
 // Many checkpoint rows: 128 rows per workgroup (skinny::block_product): U is read once per 128 rows instead of
 // once per 32, and scores and statistics are stored straight from registers.
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float16 *__restrict__ act, const _Float16 *__restrict__ U,
                                                                     float *__restrict__ raw, float4 *__restrict__ stats,
                                                                     int B, int L_act, int Lp, int H, int d, float eps)
@@ -342,7 +355,7 @@ __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float
     float16_t acc[RB];
     float m1[4], m2[4];
     _Float16 first[4];
-    skinny::block_product<RB, false, true>(act + (b * L_act + t0) * d, L_act - t0 < 128 ? L_act - t0 : 128, d,
+    skinny::block_product<RB, false, true, DT>(act + (b * L_act + t0) * d, L_act - t0 < 128 ? L_act - t0 : 128, d,
                                            U + b * d, H, (int64_t)B * d, 0, d / 64, smem, acc, m1, m2, first);
     const int ln = lane & 31, lh = lane >> 5;
     if (ln < rows) {
@@ -365,6 +378,7 @@ __global__ __launch_bounds__(256) void absorbed_scores_block_kernel(const _Float
 //   s_t = sl (rstd_t raw_t + k_t c1 + c2),  k_t = -(mean_t - x_t[0]) rstd_t,  c1 = q . c_K,h,  c2 = q . b'_K,h,
 //   sl = scale log2(e);   w_t = fp16(2^(s_t - m) rstd_t / l), zero from L_act to the next multiple of 64;
 //   sums = (m, l, sum_t w_t mean_t with the stored w_t, -)
+template <int DT>
 __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *__restrict__ q,
                                                                const float *__restrict__ raw, const float4 *__restrict__ stats,
                                                                const float *__restrict__ cvec, const float *__restrict__ bvec,
@@ -379,7 +393,7 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     const int L_act = n_rows ? n_rows[b] : L_all;          // sequences may have their own numbers of rows (0: no weight at all)
     float c1 = 0.f, c2 = 0.f;
     for (int e = lane; e < head_dim; e += 64) {
-        const float qe = (float)q[(int64_t)bh * head_dim + e];
+        const float qe = skinny::stored_to_float<DT>(q + (int64_t)bh * head_dim + e);
         c1 = __builtin_fmaf(qe, cvec[h * head_dim + e], c1);
         c2 = __builtin_fmaf(qe, bvec[h * head_dim + e], c2);
     }
@@ -457,7 +471,7 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
 // project: o_a[b,h,e] = W'_V[h dh + e, :] . Y[b,h,:] + b'_V for a slab of 32 output features of one head, then
 // the join with the cached segment's (maximum, denominator, output).  Workgroup ids are regrouped so that the
 // slabs of one head, which share that head's Y rows, run on one XCD.
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *__restrict__ Wv, const _Float16 *__restrict__ Y,
                                                                const float *__restrict__ bv,
                                                                const float4 *__restrict__ sums,
@@ -470,7 +484,7 @@ __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *_
     const int item = gemm::xcd_regroup(blockIdx.x, per_head * H);
     const int h = item / per_head;
     const int n0 = h * head_dim + (item % per_head) * skinny::kSlab;   // first V feature of the slab
-    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, true>(
+    float (*red)[RB * 32][skinny::kSlab] = skinny::slab_product<RB, true, false, DT>(
         Wv + (int64_t)n0 * d, skinny::kSlab, d, Y + (int64_t)h * d, Bc, (int64_t)H * d, d, smem);
     for (int idx = tid; idx < Bc * skinny::kSlab; idx += 256) {
         const int b = idx / skinny::kSlab, c = idx % skinny::kSlab;
@@ -485,18 +499,18 @@ __global__ __launch_bounds__(256) void absorbed_project_kernel(const _Float16 *_
             const float2 sc = lse_c[bh];
             m = fmaxf(sc.x, sa.x);
             wc = sc.y * __builtin_amdgcn_exp2f(sc.x - m);
-            oc = (float)out_c[bh * head_dim + (n - h * head_dim)];
+            oc = skinny::stored_to_float<DT>(out_c + bh * head_dim + (n - h * head_dim));
         }
         const float wa = sa.y * __builtin_amdgcn_exp2f(sa.x - m);
         o = wc + wa > 0.f ? (wc * oc + wa * o) / (wc + wa) : 0.f;
-        out[bh * head_dim + (n - h * head_dim)] = (_Float16)o;
+        skinny::float_to_stored<DT>(out + bh * head_dim + (n - h * head_dim), o);
     }
 }
 
 // project, form for large layers: a workgroup per (head, part of the reduction axis) streams the head's rows of
 // W'_V (head_dim <= 128 of them) once and shares the Y tile of the step through LDS (skinny::block_product),
 // where the slab form above re-reads Y from L2 once per 32 features.  fp32 partial sums part[ks][b][n].
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void absorbed_project_block_kernel(const _Float16 *__restrict__ Wv, const _Float16 *__restrict__ Y,
                                                                      float *__restrict__ part, int Bc, int H, int head_dim, int d,
                                                                      int steps_per_part)
@@ -511,7 +525,7 @@ __global__ __launch_bounds__(256) void absorbed_project_block_kernel(const _Floa
     float16_t acc[RB];
     float m1[4], m2[4];
     _Float16 first[4];
-    skinny::block_product<RB, true, false>(Wv + (int64_t)h * head_dim * d, head_dim, d, Y + (int64_t)h * d, Bc, (int64_t)H * d,
+    skinny::block_product<RB, true, false, DT>(Wv + (int64_t)h * head_dim * d, head_dim, d, Y + (int64_t)h * d, Bc, (int64_t)H * d,
                                            k_begin, k_steps, smem, acc, m1, m2, first);
     // acc[rb][r]: sequence 32 rb + 8 (r/4) + 4 (lane/32) + r%4, feature 32 wave + lane%32 of the head
     const int ln = lane & 31, lh = lane >> 5;
@@ -529,6 +543,7 @@ __global__ __launch_bounds__(256) void absorbed_project_block_kernel(const _Floa
 }
 
 // Sum of the parts, bias, and the join with the cached segment (as in absorbed_project_kernel); 4 features per thread.
+template <int DT>
 __global__ __launch_bounds__(256) void absorbed_join_kernel(const float *__restrict__ part, int parts, const float *__restrict__ bv,
                                                             const float4 *__restrict__ sums,
                                                             const _Float16 *__restrict__ out_c, const float2 *__restrict__ lse_c,
@@ -547,7 +562,7 @@ __global__ __launch_bounds__(256) void absorbed_join_kernel(const float *__restr
     const int64_t bh = (int64_t)b * H + h;
     const float4 sa = sums[bh];
     float m = sa.x, wc = 0.f;
-    half4_t oc = {0, 0, 0, 0};
+    half4_t oc = {0, 0, 0, 0};                             // 4 stored elements, whatever their type
     if (lse_c) {
         const float2 sc = lse_c[bh];
         m = fmaxf(sc.x, sa.x);
@@ -559,7 +574,8 @@ __global__ __launch_bounds__(256) void absorbed_join_kernel(const float *__restr
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const float oa = o[j] + bv[n + j];
-        res[j] = (_Float16)(wc + wa > 0.f ? (wc * (float)oc[j] + wa * oa) / (wc + wa) : 0.f);
+        const float ocj = skinny::stored_to_float<DT>(reinterpret_cast<const _Float16 *>(&oc) + j);
+        skinny::float_to_stored<DT>(reinterpret_cast<_Float16 *>(&res) + j, wc + wa > 0.f ? (wc * ocj + wa * oa) / (wc + wa) : 0.f);
     }
     *reinterpret_cast<half4_t *>(out + (int64_t)b * d + n) = res;
 }
@@ -569,14 +585,14 @@ __global__ __launch_bounds__(256) void absorbed_join_kernel(const float *__restr
 constexpr int kProjectBlockMinD = 5120;
 constexpr int64_t kBlockModeMinRows = 128 * 512;           // from here on 128-row workgroups still fill the chip twice
 
-template <int RB>
-hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
+template <int RB, int DT>
+hipError_t launch_scores_as(const AbsorbedArgs &a, int Lp, hipStream_t s)
 {
     const bool block_mode = (int64_t)a.B * a.L_act >= kBlockModeMinRows;
     const int per = block_mode ? 128 : skinny::kSlab;
     const int64_t items = (int64_t)((a.L_act + per - 1) / per) * a.B;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
-    auto kern = block_mode ? absorbed_scores_block_kernel<RB> : absorbed_scores_kernel<RB>;
+    auto kern = block_mode ? absorbed_scores_block_kernel<RB, DT> : absorbed_scores_kernel<RB, DT>;
     const int lds = block_mode ? skinny::block_lds_bytes<RB>() : skinny::lds_bytes<RB>() + skinny::kMomentBytes;
     static LdsOnce lds_once;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
@@ -588,9 +604,15 @@ hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
 }
 
 template <int RB>
-hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+hipError_t launch_scores(const AbsorbedArgs &a, int Lp, hipStream_t s)
 {
-    auto kern = absorbed_project_kernel<RB>;
+    return a.dt == 1 ? launch_scores_as<RB, 1>(a, Lp, s) : launch_scores_as<RB, 0>(a, Lp, s);
+}
+
+template <int RB, int DT>
+hipError_t launch_project_as(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+{
+    auto kern = absorbed_project_kernel<RB, DT>;
     constexpr int lds = skinny::lds_bytes<RB>();
     static LdsOnce lds_once;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
@@ -606,12 +628,18 @@ hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
 }
 
 template <int RB>
-hipError_t launch_project_block(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+hipError_t launch_project(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+{
+    return a.dt == 1 ? launch_project_as<RB, 1>(a, b0, Bc, s) : launch_project_as<RB, 0>(a, b0, Bc, s);
+}
+
+template <int RB, int DT>
+hipError_t launch_project_block_as(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
 {
     int parts, steps_per_part;
     absorbed_project_parts(a.d, a.H, &parts, &steps_per_part);
     if ((size_t)parts * Bc * a.d > a.proj_part_floats) return hipErrorInvalidValue;
-    auto kern = absorbed_project_block_kernel<RB>;
+    auto kern = absorbed_project_block_kernel<RB, DT>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
     static LdsOnce lds_once;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
@@ -622,12 +650,18 @@ hipError_t launch_project_block(const AbsorbedArgs &a, int b0, int Bc, hipStream
                        a.proj_part, Bc, a.H, a.head_dim, a.d, steps_per_part);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const int64_t threads = (int64_t)Bc * (a.d / 4);
-    hipLaunchKernelGGL(absorbed_join_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(absorbed_join_kernel<DT>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
                        a.proj_part, parts, a.bvec + a.d, a.sums + bh0,
                        a.L_kv > 0 ? static_cast<const _Float16 *>(a.out_c) + bh0 * a.head_dim : nullptr,
                        a.L_kv > 0 ? a.lse_c + bh0 : nullptr,
                        static_cast<_Float16 *>(a.out) + bh0 * a.head_dim, Bc, a.H, a.head_dim, a.d);
     return hipGetLastError();
+}
+
+template <int RB>
+hipError_t launch_project_block(const AbsorbedArgs &a, int b0, int Bc, hipStream_t s)
+{
+    return a.dt == 1 ? launch_project_block_as<RB, 1>(a, b0, Bc, s) : launch_project_block_as<RB, 0>(a, b0, Bc, s);
 }
 
 }  // namespace
@@ -669,6 +703,7 @@ hipError_t launch_carry(const AbsorbedArgs &a, hipStream_t s)
         c.Out = static_cast<_Float16 *>(a.U) + b0 * d; c.o_batch = a.B * d; c.ld_out = d;
         c.shift = nullptr; c.shift_batch = 0; c.shift_stride = 0;
         c.blk_list = nullptr; c.list_pitch = 0; c.blk_log2 = 0; c.R_list = nullptr;
+        c.s_dt = a.dt; c.a_dt = a.dt;                      // prepared weights and queries as stored
         const hipError_t e = launch_column_product(c, a.H, s);
         if (e != hipSuccess) return e;
     }
@@ -681,7 +716,7 @@ hipError_t launch_after_scores(const AbsorbedArgs &a, int Lp, const PagedRows *p
     const int64_t d = a.d;
     hipError_t e;
     const int64_t BH = (int64_t)a.B * a.H;
-    hipLaunchKernelGGL(absorbed_softmax_kernel, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
+    hipLaunchKernelGGL(a.dt == 1 ? absorbed_softmax_kernel<1> : absorbed_softmax_kernel<0>, dim3((unsigned)((BH + 3) / 4)), dim3(256), 0, s,
                        static_cast<const _Float16 *>(a.q), a.w_raw, a.stats, a.cvec, a.bvec,
                        static_cast<_Float16 *>(a.w), a.sums, a.B, a.H, a.head_dim, a.L_act, Lp,
                        a.scale * 1.4426950408889634f, pr ? pr->n_rows : static_cast<const int32_t *>(nullptr),
@@ -695,6 +730,7 @@ hipError_t launch_after_scores(const AbsorbedArgs &a, int Lp, const PagedRows *p
         c.shift = &a.sums[0].z; c.shift_batch = 4 * (int64_t)a.H; c.shift_stride = 4;
         c.blk_list = pr ? pr->blk_list : nullptr; c.list_pitch = pr ? pr->list_pitch : 0; c.blk_log2 = pr ? pr->blk_log2 : 0;
         c.R_list = pr ? pr->n_rows : nullptr;
+        c.s_dt = a.dt; c.a_dt = 0;                         // checkpoint rows as stored, weights w in fp16
         if ((e = launch_column_product(c, a.B, s)) != hipSuccess) return e;
     }
     for (int b0 = 0; b0 < a.B; b0 += kAbsorbMaxBatch) {
@@ -783,7 +819,7 @@ __global__ __launch_bounds__(64) void paged_prefix_kernel(const int32_t *__restr
 // scores of 128 checkpoint rows of one request, as absorbed_scores_block_kernel (U is read once per 128 rows);
 // rows are numbered inside the request in the order of its block list (raw, stats: pitch Lp per request) and
 // found through that list (a block holds at least 16 rows, so the 8 rows of a load share a block).
-template <int RB>
+template <int RB, int DT>
 __global__ __launch_bounds__(256) void paged_scores_kernel(const _Float16 *__restrict__ act_pool, const _Float16 *__restrict__ U,
                                                            float *__restrict__ raw, float4 *__restrict__ stats,
                                                            const int32_t *__restrict__ list, const int32_t *__restrict__ n_rows,
@@ -807,7 +843,7 @@ __global__ __launch_bounds__(256) void paged_scores_kernel(const _Float16 *__res
     float16_t acc[RB];
     float m1[4], m2[4];
     _Float16 first[4];
-    skinny::block_product_rows<RB, false, true>(row_of, n, U + b * d, H, (int64_t)B * d, 0, d / 64, smem, acc, m1, m2, first);
+    skinny::block_product_rows<RB, false, true, DT>(row_of, n, U + b * d, H, (int64_t)B * d, 0, d / 64, smem, acc, m1, m2, first);
     const int rw = r0 + 32 * wave;                         // first row of this wavefront
     const int rows = total - rw < 32 ? (total - rw > 0 ? total - rw : 0) : 32;
     const int ln = lane & 31, lh = lane >> 5;
@@ -827,15 +863,15 @@ __global__ __launch_bounds__(256) void paged_scores_kernel(const _Float16 *__res
     }
 }
 
-template <int RB>
-hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2, hipStream_t s)
+template <int RB, int DT>
+hipError_t launch_paged_scores_as(const PagedAbsorbedArgs &p, int Lp, int blk_log2, hipStream_t s)
 {
     const AbsorbedArgs &a = p.abs;
     const int groups = (a.L_act + 127) / 128;              // of the longest request possible; shorter ones leave early
     const int64_t items = (int64_t)a.B * groups;
     if (items <= 0) return hipSuccess;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
-    auto kern = paged_scores_kernel<RB>;
+    auto kern = paged_scores_kernel<RB, DT>;
     constexpr int lds = skinny::block_lds_bytes<RB>();
     static LdsOnce lds_once;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, lds_once);
@@ -846,12 +882,19 @@ hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2,
     return hipGetLastError();
 }
 
+template <int RB>
+hipError_t launch_paged_scores(const PagedAbsorbedArgs &p, int Lp, int blk_log2, hipStream_t s)
+{
+    return p.abs.dt == 1 ? launch_paged_scores_as<RB, 1>(p, Lp, blk_log2, s) : launch_paged_scores_as<RB, 0>(p, Lp, blk_log2, s);
+}
+
 }  // namespace
 
 hipError_t launch_absorbed(const AbsorbedArgs &a, hipStream_t s)
 {
     if (a.B <= 0 || a.L_act <= 0) return hipSuccess;
-    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
+    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d || (a.dt != 0 && a.dt != 1))
+        return hipErrorInvalidValue;
     const int Lp = absorbed_row_pitch(a.L_act);
     hipError_t e = launch_carry(a, s);
     if (e != hipSuccess) return e;
@@ -889,7 +932,8 @@ hipError_t launch_paged_absorbed(const PagedAbsorbedArgs &p, hipStream_t s)
 {
     const AbsorbedArgs &a = p.abs;
     if (a.B <= 0) return hipSuccess;
-    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d) return hipErrorInvalidValue;
+    if (a.H > kAbsorbMaxHeads || a.d % 64 != 0 || a.B > 65535 || (int64_t)a.H * a.head_dim != a.d || (a.dt != 0 && a.dt != 1))
+        return hipErrorInvalidValue;
     if (p.block_tokens < 16 || (p.block_tokens & (p.block_tokens - 1)) != 0 || p.max_blocks <= 0 || a.L_act != p.max_blocks * p.block_tokens)
         return hipErrorInvalidValue;
     int blk_log2 = 0;

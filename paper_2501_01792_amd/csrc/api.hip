@@ -464,7 +464,7 @@ struct AbsorbedPlan {
 int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, AbsorbedPlan *p)
 {
     Plan base;
-    int st = make_plan(s, B, L_kv, L_act, false, &base, false);
+    int st = make_plan(s, B, L_kv, L_act, false, &base, true);
     if (st != HK_OK) return st;
     if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
     p->M = base.M; p->BH = base.BH; p->scale = base.scale;
@@ -541,7 +541,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
         a.partial = reinterpret_cast<float *>(ws + p.off_partial);
         a.out = L_act > 0 ? static_cast<void *>(ws + p.off_outc) : out;
         a.lse = L_act > 0 ? reinterpret_cast<float2 *>(ws + p.off_lse) : nullptr;
-        a.dtype = 0;
+        a.dtype = shape->dtype;
         a.after_main = nullptr;
         if (hk::launch_flash_decode(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     }
@@ -553,7 +553,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
         char *dst = ws + p.off_prep;
         if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, dst + PL.off_w,
                                      reinterpret_cast<float *>(dst + PL.off_c), reinterpret_cast<float *>(dst + PL.off_b),
-                                     shape->d, hs) != hipSuccess)
+                                     shape->d, hs, shape->dtype) != hipSuccess)
             return HK_ERR_LAUNCH;
         pp = dst;
     }
@@ -573,6 +573,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
     a.proj_part = reinterpret_cast<float *>(ws + p.off_proj);
     a.proj_part_floats = absorbed_proj_floats(shape, B);
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d; a.L_act = L_act; a.L_kv = L_kv;
+    a.dt = shape->dtype;
     a.scale = p.scale; a.eps = shape->ln_eps;
     if (hk::launch_absorbed(a, hs) != hipSuccess) return HK_ERR_LAUNCH;
     return HK_OK;
@@ -788,7 +789,7 @@ struct PagedAbsorbedPlan {
 int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedAbsorbedPlan *p)
 {
     PagedPlan base;                                        // the checks of the paged step
-    int st = make_paged_plan(s, B, c, &base);
+    int st = make_paged_plan(s, B, c, &base, true);
     if (st != HK_OK) return st;
     if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
     const int64_t max_rows = (int64_t)c->max_blocks * c->block_tokens;     // the most checkpoint rows a request can have
@@ -867,7 +868,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     t.P_kv = cache->P_kv; t.P_act = 0; t.block_tokens = cache->block_tokens;
     t.B = B; t.H = shape->n_heads; t.head_dim = shape->head_dim; t.scale = p.scale; t.n_waves = p.n_waves;
     t.partial = reinterpret_cast<float *>(ws + p.off_partial);
-    t.out = out; t.total_dev = cache->cu_tokens ? cache->cu_tokens + B : nullptr; t.lse = nullptr; t.dtype = 0;
+    t.out = out; t.total_dev = cache->cu_tokens ? cache->cu_tokens + B : nullptr; t.lse = nullptr; t.dtype = shape->dtype;
     if (!act) {                                            // no checkpoint block in use: the block-table attention is the whole step
         if (hk::launch_paged_decode(t, hs) != hipSuccess) return HK_ERR_LAUNCH;
         return HK_OK;
@@ -879,7 +880,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
         char *dst = ws + p.off_prep;
         if (hk::launch_prepare_layer(params->Wkv, params->bkv, params->ln_w, params->ln_b, dst + PL.off_w,
                                      reinterpret_cast<float *>(dst + PL.off_c), reinterpret_cast<float *>(dst + PL.off_b),
-                                     shape->d, hs) != hipSuccess)
+                                     shape->d, hs, shape->dtype) != hipSuccess)
             return HK_ERR_LAUNCH;
         pp = dst;
     }
@@ -901,6 +902,7 @@ int hk_paged_decode_attn_absorbed(const hk_shape *shape, const void *q, int32_t 
     a.proj_part_floats = absorbed_proj_floats(shape, B);
     a.B = B; a.H = shape->n_heads; a.head_dim = shape->head_dim; a.d = shape->d;
     a.L_act = cache->max_blocks * cache->block_tokens; a.L_kv = kv ? 1 : 0;
+    a.dt = shape->dtype;
     a.scale = p.scale; a.eps = shape->ln_eps;
     pa.block_table = cache->block_table; pa.seq_len = cache->seq_len;
     pa.max_blocks = cache->max_blocks; pa.block_tokens = cache->block_tokens; pa.n_act_used = cache->n_act_used;

@@ -133,22 +133,23 @@ struct PagedAttnArgs {
 hipError_t launch_paged_decode(const PagedAttnArgs &a, hipStream_t s);
 
 struct AbsorbedArgs {
-    const void *q;             // [B, H, dh] fp16
-    const void *act;           // [B, L_act, d] fp16
+    const void *q;             // [B, H, dh]
+    const void *act;           // [B, L_act, d]
     float4 *stats;             // [B * L_act] scratch: (rstd, mean, -(mean - first element) rstd, -) of every checkpoint row
-    const void *Wp;            // prepared layer: [2d, d] fp16 gamma-scaled weights,
+    const void *Wp;            // prepared layer: [2d, d] gamma-scaled weights,
     const float *cvec, *bvec;  //   [2d] row sums of Wp, [2d] bias with the LayerNorm bias folded in
     void *U;                   // [H, B, d] fp16 scratch: the query carried through the key weights
     float *w_raw;              // [B, H, Lp] fp32 scratch: x_t . U  (Lp = absorbed_row_pitch(L_act))
     void *w;                   // [B, H, Lp] fp16 scratch: softmax weight times rstd, normalised; zero past L_act
     float4 *sums;              // [B, H] scratch: (maximum, sum p, sum w mean, -)
     void *Y;                   // [B, H, d] fp16 scratch: weighted sum of the raw checkpoint rows
-    const void *out_c;         // [B, H, dh] fp16: attention over the cached segment alone (unused when L_kv == 0)
+    const void *out_c;         // [B, H, dh]: attention over the cached segment alone (unused when L_kv == 0)
     const float2 *lse_c;       // [B, H]: its (maximum, denominator)
-    void *out;                 // [B, H, dh] fp16
+    void *out;                 // [B, H, dh]
     float *proj_part;          // optional scratch [parts, min(B, kAbsorbMaxBatch), d] fp32 (absorbed_project_parts): with it large
     size_t proj_part_floats;   //   layers take the projection that cuts the reduction axis over workgroups; its capacity
     int B, H, head_dim, d, L_act, L_kv;
+    int dt;                    // storage type of q, act, Wp, out_c, out (0: fp16, 1: bfloat16); the scratch vectors are fp16
     float scale, eps;
 };
 constexpr int kAbsorbMaxHeads = 128;   // heads (rows of the small operand of the score product) per sequence

@@ -25,6 +25,52 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
+// The kernels built on these products compute in fp16 whatever the storage type of the tensors: an operand stored as
+// bfloat16 (SDT = 1) is converted piece by piece on its way from the load to LDS.  The conversion is exact for
+// magnitudes in fp16's normal range (a bfloat16 has 8 significant bits, an fp16 11); larger magnitudes stop at
+// 65504, and below 2^-14 the low bits are dropped.  Pointers to such operands are passed as _Float16 pointers
+// (same size and addressing).
+typedef unsigned uint4v_t __attribute__((ext_vector_type(4)));
+template <int SDT>
+__device__ __forceinline__ half8_t to_half8(half8_t raw)
+{
+    if constexpr (SDT == 0) {
+        return raw;
+    } else {
+        const uint4v_t u = __builtin_bit_cast(uint4v_t, raw);
+        uint4v_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = __builtin_bit_cast(float, u[e] << 16), hi = __builtin_bit_cast(float, u[e] & 0xffff0000u);
+            o[e] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+        }
+        return __builtin_bit_cast(half8_t, o);
+    }
+}
+// One stored element as fp32, and fp32 to one stored element (round to nearest even).
+template <int SDT>
+__device__ __forceinline__ float stored_to_float(const _Float16 *p)
+{
+    if constexpr (SDT == 0) return (float)*p;
+    else return __builtin_bit_cast(float, (unsigned)*reinterpret_cast<const unsigned short *>(p) << 16);
+}
+template <int SDT>
+__device__ __forceinline__ void float_to_stored(_Float16 *p, float v)
+{
+    if constexpr (SDT == 0) *p = (_Float16)v;
+    else *reinterpret_cast<__bf16 *>(p) = (__bf16)v;
+}
+// One stored element as fp16 (same rule as to_half8).
+template <int SDT>
+__device__ __forceinline__ _Float16 stored_to_half(const _Float16 *p)
+{
+    if constexpr (SDT == 0) return *p;
+    else {
+        const unsigned pk = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(stored_to_float<1>(p), 0.f));
+        return __builtin_bit_cast(_Float16, (unsigned short)(pk & 0xffffu));
+    }
+}
+
 constexpr int kSlab = 32;                // streamed rows per workgroup
 constexpr int kStepK = 64;               // reduction elements per step of one wavefront
 constexpr int kBlockBytes = 32 * kStepK * 2;               // 4 KiB: 32 rows x 128 bytes of one operand, one step
@@ -51,9 +97,9 @@ __device__ __forceinline__ float (*moments(unsigned char *smem))[kSlab][2]
 }
 
 // S: first row of the slab (row stride ld_s elements; rows >= s_rows are not read: the last valid row stands
-// in for them).  A: first small row (row stride ld_a; rows >= a_rows likewise).  d % 64 == 0.
+// in for them), stored as SDT.  A: first small row (row stride ld_a; rows >= a_rows likewise), fp16.  d % 64 == 0.
 // Returns red with red[w][m][c], w = 0..3, the partial sum of k quarter w; a barrier has been passed.
-template <int RB, bool NT, bool STATS = false>
+template <int RB, bool NT, bool STATS = false, int SDT = 0>
 __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, int s_rows, int64_t ld_s,
                                                 const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                                 int d, unsigned char *smem))[RB * 32][kSlab]
@@ -113,7 +159,7 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
     if constexpr (STATS) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const _Float16 c = *(wp[j] - 8 * g_chunk);     // first element of the row
+            const _Float16 c = stored_to_half<SDT>(wp[j] - 8 * g_chunk);   // first element of the row
             shift[j] = half8_t{c, c, c, c, c, c, c, c};
         }
     }
@@ -159,7 +205,7 @@ __device__ __forceinline__ float (*slab_product(const _Float16 *__restrict__ S, 
                     // registers (row-wise) -> LDS -> registers (MFMA operand layout)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        half8_t piece = wv[u][j];
+                        half8_t piece = to_half8<SDT>(wv[u][j]);
                         if constexpr (STATS) {
                             piece -= shift[j];             // the product is taken with the shifted rows
 #pragma unroll
@@ -241,15 +287,13 @@ constexpr int block_lds_bytes() { return 4 * kBlockBytes + 2 * RB * kBlockBytes;
 
 // row_of(r) is the address of streamed row r, r < n_rows (rows need not be evenly spaced: they may sit in
 // blocks scattered over a pool).
-// DT = 1: the operands are bfloat16 (same size and addressing; passed as _Float16 pointers, reinterpreted for the
-// MFMA); STATS is for fp16 only.
-template <int RB, bool NT, bool STATS, int DT = 0, typename RowOf>
+// SDT: storage type of the streamed rows (the small operand A is fp16).
+template <int RB, bool NT, bool STATS, int SDT = 0, typename RowOf>
 __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
                                                    const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                                    int k_begin, int k_steps, unsigned char *smem,
                                                    float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
 {
-    static_assert(DT == 0 || !STATS, "row moments are taken in fp16");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g_row = lane >> 3, g_chunk = lane & 7;
@@ -262,7 +306,7 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
         if (r >= n_rows) r = n_rows - 1;
         const _Float16 *row = row_of(r);
         if constexpr (STATS) {
-            first[j] = row[0];
+            first[j] = stored_to_half<SDT>(row);
             shift[j] = half2_t{first[j], first[j]};
         } else {
             first[j] = (_Float16)0.f;
@@ -328,7 +372,7 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
                 put_a((u + 1) % kDepth, (sc + 1) & 1);     // the tile of step sc + 1, for the next pass
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    half8_t piece = sv[u][j];
+                    half8_t piece = to_half8<SDT>(sv[u][j]);
                     if constexpr (STATS) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -347,12 +391,7 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
                         const half8_t af = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlockBytes + rd_off[jj]);
-                        if constexpr (DT == 1) {
-                            typedef typename Elem<1>::V8 bf8_t;
-                            acc[rb] = Elem<1>::mfma_32x32x16(__builtin_bit_cast(bf8_t, af), __builtin_bit_cast(bf8_t, wf), acc[rb]);
-                        } else {
-                            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
-                        }
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
                     }
                 }
                 __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
@@ -371,13 +410,13 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
 }
 
 // Evenly spaced rows: S is the first row of the block, ld_s the distance between rows.
-template <int RB, bool NT, bool STATS, int DT = 0>
+template <int RB, bool NT, bool STATS, int SDT = 0>
 __device__ __forceinline__ void block_product(const _Float16 *__restrict__ S, int n_rows, int64_t ld_s,
                                               const _Float16 *__restrict__ A, int a_rows, int64_t ld_a,
                                               int k_begin, int k_steps, unsigned char *smem,
                                               float16_t (&acc)[RB], float (&m1)[4], float (&m2)[4], _Float16 (&first)[4])
 {
-    block_product_rows<RB, NT, STATS, DT>([=](int r) { return S + (int64_t)r * ld_s; }, n_rows, A, a_rows, ld_a, k_begin, k_steps,
+    block_product_rows<RB, NT, STATS, SDT>([=](int r) { return S + (int64_t)r * ld_s; }, n_rows, A, a_rows, ld_a, k_begin, k_steps,
                                       smem, acc, m1, m2, first);
 }
 

@@ -78,10 +78,12 @@ def test_hybrid_decode_attn_rejects_bad_arguments():
     assert hk.hk_qkv_workspace_bytes(bf, 4) == hk.hk_qkv_workspace_bytes(ok, 4) > 0
     assert hk.lib().hk_qkv_current(ctypes.byref(bf), FAKE, 4, ctypes.byref(lp), FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8,
                                    None, 0, 0, FAKE, 1 << 40, None) == hk.HK_ERR_SHAPE
-    # ... but not by the entry points that do not regenerate K/V
-    assert hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(bf), FAKE, FAKE, FAKE, 128, FAKE, 128, 4, ctypes.byref(lp), 0.5,
-                                                   FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_DTYPE
-    assert hk.hk_absorbed_workspace_bytes(bf, 4, 128, 128) == 0
+    # ... and by the entry points that do not regenerate K/V (same scratch: their intermediate vectors are fp16 either way)
+    assert hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(bf), FAKE, FAKE, FAKE, 128, FAKE, 128, 4, ctypes.byref(lp), 0.25,
+                                                   FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_RATIO
+    assert hk.lib().hk_hybrid_decode_attn_absorbed(ctypes.byref(bf), FAKE, FAKE, FAKE, 128, None, 128, 4, ctypes.byref(lp), 0.5,
+                                                   FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_NULL
+    assert hk.hk_absorbed_workspace_bytes(bf, 4, 128, 128) == hk.hk_absorbed_workspace_bytes(ok, 4, 128, 128) > 0
     assert _attn(hk.make_shape(768, 12, attn_splits=65)) == hk.HK_ERR_SHAPE
     assert _attn(hk.make_shape(768, 12, gemm_tile=64)) == hk.HK_ERR_SHAPE
     assert _attn(ok, ratio=1.5) == hk.HK_ERR_RATIO

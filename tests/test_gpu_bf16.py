@@ -1,5 +1,5 @@
 """GPU parity of the bfloat16 path (hk_prepare_layer, hk_regen_kv, hk_hybrid_decode_attn, hk_qkv_current,
-hk_paged_decode_attn with HK_DTYPE_BF16)
+hk_paged_decode_attn and the two entry points without regeneration, with HK_DTYPE_BF16)
 against the CPU oracle fed with the same bf16-rounded inputs.
 
 The benchmark's tolerance is stated for fp16.  A bf16 value carries 8 significant bits, so the output
@@ -174,6 +174,98 @@ def test_bf16_paged_decode_matches_oracle(hk, case):
     for b in range(B):
         if seq_len[b] == 0:
             assert (out[b] == 0).all()
-    with pytest.raises(hk.HybridKVError):                          # the entry point without regeneration is fp16 only
-        hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"],
-                             absorbed=True, **cu)
+    out2 = hk.paged_decode_attn(g["q"], g["K_pool"], g["V_pool"], g["act_pool"], tb, sl, bt, lp, n_act_used=paged["n_act_used"],
+                                absorbed=True, **cu)                # the same step without regeneration
+    torch.cuda.synchronize()
+    assert out2.dtype == torch.bfloat16
+    _check("out, without regeneration", out2, ref)
+    for b in range(B):
+        if seq_len[b] == 0:
+            assert (out2[b] == 0).all()
+
+
+# ---- the step without regeneration (hk_hybrid_decode_attn_absorbed) on bf16 tensors.  It converts what it loads to
+# fp16 and computes as it does for fp16 tensors, so its error is that of the fp16 step plus the output rounding to
+# bf16; the oracle sees the same bf16-rounded inputs.  Same bar as the regenerating bf16 step.
+
+def _absorbed_shapes():
+    from test_gpu_absorbed import SHAPES
+    return SHAPES
+
+
+def _run_absorbed_bf16(hk, cfg, g, prepared):
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    if prepared:
+        lp = lp + (hk.prepare_layer(*lp, cfg.n_heads),)
+    out = hk.hybrid_decode_attn_absorbed(g["q"], g["K_cache"] if cfg.L_kv else None, g["V_cache"] if cfg.L_kv else None,
+                                         g["act"] if cfg.L_act else None, lp, cfg.ratio)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16
+    return out
+
+
+@pytest.mark.parametrize("prepared", [False, True])
+@pytest.mark.parametrize("cfg", _absorbed_shapes(), ids=lambda c: c.name)
+def test_bf16_absorbed_step_matches_oracle(hk, oracle, cfg, prepared):
+    print("case", cfg, "prepared", prepared, flush=True)
+    g, h = _inputs(cfg)
+    out = _run_absorbed_bf16(hk, cfg, g, prepared)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, h)
+    _check("out", out, ref_out)
+
+
+def test_bf16_absorbed_rows_with_large_mean(hk, oracle):
+    """Checkpoint rows whose mean is up to 200 times their spread, stored in bf16 (the spread is then a few units of
+    the last place of the stored values): the mean has to cancel as it does in a LayerNorm."""
+    from test_gpu_parity import _cfg
+    cfg = _cfg("shifted", 1024, 8, 2, 130, 0.0, 21)
+    batch = synth.make_batch(cfg)
+    rng = np.random.default_rng(5)
+    batch["act"] = batch["act"].astype(np.float32) * rng.uniform(0.1, 6.0, size=(cfg.B, cfg.L, 1)) \
+        + rng.uniform(-20, 20, size=(cfg.B, cfg.L, 1))
+    g, h = {}, {}
+    for k, v in batch.items():
+        g[k], h[k] = _bf16(v)
+    out = _run_absorbed_bf16(hk, cfg, g, prepared=True)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, h)
+    _check("out", out, ref_out)
+
+
+def test_bf16_absorbed_peaked_scores(hk, oracle):
+    """One checkpoint row that dominates the softmax and one cached row that does, in bf16."""
+    from test_gpu_parity import _cfg
+    cfg = _cfg("peaked", 512, 4, 2, 96, 0.5, 31)
+    batch = synth.make_batch(cfg)
+    batch["q"] = batch["q"].astype(np.float32) * 6
+    batch["K_cache"][0, :, 5, :] = (batch["q"][0] * 0.5).astype(np.float16)
+    batch["act"][1, 7] = (batch["act"][1, 7].astype(np.float32) * 4).astype(np.float16)
+    g, h = {}, {}
+    for k, v in batch.items():
+        g[k], h[k] = _bf16(v)
+    out = _run_absorbed_bf16(hk, cfg, g, prepared=False)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, h)
+    _check("out", out, ref_out)
+
+
+def test_bf16_absorbed_full_size_opt6p7b_sampled(hk, oracle):
+    """The opt6.7b layer in bf16 without regeneration: sampled (sequence, head) outputs against the oracle, and
+    agreement with the regenerating bf16 step on the whole output."""
+    cfg = synth.CONFIGS["opt6.7b"]
+    g, h = _inputs(cfg)
+    out = _run_absorbed_bf16(hk, cfg, g, prepared=True)
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d
+    rng = np.random.default_rng(11)
+    got, ref = [], []
+    for b, hd in [(int(rng.integers(cfg.B)), int(rng.integers(H))) for _ in range(3)] + [(0, 0), (cfg.B - 1, H - 1)]:
+        xh = oracle.layernorm(h["act"][b], h["ln_w"], h["ln_b"])
+        sel = np.r_[hd * dh:(hd + 1) * dh, d + hd * dh:d + (hd + 1) * dh]
+        kvh = oracle.kv_projection(xh, h["Wkv"][sel], h["bkv"][sel])
+        Kb = np.concatenate([h["K_cache"][b, hd], kvh[:, :dh]], axis=0)
+        Vb = np.concatenate([h["V_cache"][b, hd], kvh[:, dh:]], axis=0)
+        ref.append(oracle.decode_attention(h["q"][b:b + 1, hd:hd + 1], Kb[None, None], Vb[None, None])[0, 0])
+        got.append(out[b, hd])
+    _check("out[sampled (b,h)]", torch.stack(got), np.stack(ref))
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    regen = hk.hybrid_decode_attn(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio)
+    torch.cuda.synchronize()
+    _check("without regeneration vs regenerating", out, regen.float().cpu().numpy().astype(np.float64))

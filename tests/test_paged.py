@@ -129,13 +129,16 @@ def test_paged_rejects_bad_arguments():
     s67 = hk.make_shape(4096, 32)
     assert hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(s67), 32, ctypes.byref(big)) < \
         hk.lib().hk_paged_workspace_bytes(ctypes.byref(s67), 32, ctypes.byref(big)) // 4
-    # bfloat16: taken by the regenerating entry point (same checks), refused by the one that does not regenerate
+    # bfloat16: taken by both entry points, with the same checks
     bf = hk.make_shape(768, 12, dtype=hk.HK_DTYPE_BF16)
     assert call(shape=bf, q=None) == hk.HK_ERR_NULL and call(shape=bf, c=cache(block_tokens=24)) == hk.HK_ERR_SHAPE
     assert hk.lib().hk_paged_workspace_bytes(ctypes.byref(bf), 2, ctypes.byref(cache())) >= need     # always a prepared layer inside
-    assert hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(bf), 2, ctypes.byref(cache())) == 0
-    assert hk.lib().hk_paged_decode_attn_absorbed(ctypes.byref(bf), FAKE, 2, ctypes.byref(cache()), ctypes.byref(lp), FAKE, FAKE,
-                                                  1 << 40, None) == hk.HK_ERR_DTYPE
+    assert hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(bf), 2, ctypes.byref(cache())) == \
+        hk.lib().hk_paged_absorbed_workspace_bytes(ctypes.byref(ok), 2, ctypes.byref(cache())) > 0
+    assert hk.lib().hk_paged_decode_attn_absorbed(ctypes.byref(bf), None, 2, ctypes.byref(cache()), ctypes.byref(lp), FAKE, FAKE,
+                                                  1 << 40, None) == hk.HK_ERR_NULL
+    assert hk.lib().hk_paged_decode_attn_absorbed(ctypes.byref(bf), FAKE, 2, ctypes.byref(cache(block_tokens=24)), ctypes.byref(lp),
+                                                  FAKE, FAKE, 1 << 40, None) == hk.HK_ERR_SHAPE
 
 
 # ------------------------------------------------------------------ GPU parity
