@@ -104,11 +104,11 @@ __device__ __forceinline__ void store_tile(const float4_t (&acc)[TM][TN], int la
             half8_t v;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                float a;
-                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));
+                float a;                                   // read in place, in this order: left to itself the compiler
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a) : "a"(acc[i][j][r]));   // reads ahead and spills
                 v[j] = (elem_t)__builtin_fmaf(a, row.rstd, __builtin_fmaf(row.nmr, cn[j], bn[j]));
             }
-            if (row.base >= 0) __builtin_nontemporal_store(v, reinterpret_cast<half8_t *>(dst_base + row.base));
+            __builtin_nontemporal_store(v, reinterpret_cast<half8_t *>(dst_base + row.base));
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -135,7 +135,6 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     const int n_tiles = tiles_m * tiles_n;
     const int my_tiles = (n_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // >= 1: grid <= n_tiles
     const int nks = d / FBK;                                   // host guarantees d % 64 == 0 and nks >= 2
-    const int G = my_tiles * nks;                              // k blocks this workgroup consumes, over all its tiles
 
     // ---- direct-load roles.  One load of a wavefront fills 8 consecutive 128-byte LDS rows (1 KiB): lane l
     // writes row l / 8, physical chunk l % 8, and fetches the logical chunk (l % 8) ^ ((row / 2) % 8) of that
@@ -156,7 +155,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
     // the last valid row: worked out once per tile, so that a load in the main loop costs no vector arithmetic (the
     // position along the reduction axis travels in the scalar offset).
     int a_voff[kLoadsPerUnit], b_voff[kLoadsPerUnit];
-    int ld_j = 0, ld_kb = 0, ld_g = 0;
+    int ld_kb = 0, ld_step = 1;
     auto set_load_tile = [&](int j) {
         int tm, tn;
         tile_coords<GROUP_M>((int)blockIdx.x + j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
@@ -178,11 +177,15 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
             b_voff[i] = vb < b_vmax ? vb : b_vmax;
         }
     };
-    auto advance_load = [&]() {                                // past the last k block the cursor stays on it
-        if (ld_g + 1 < G) {
-            ++ld_g;
-            if (++ld_kb == nks) { ld_kb = 0; ++ld_j; set_load_tile(ld_j); }
-        }
+    // The cursor runs two k blocks ahead of the MFMAs, so it leaves a tile before that tile's last two k blocks are
+    // consumed: the switch is made there, once per tile, and the main loop over k blocks carries no branch for it
+    // (a taken branch costs a single resident wavefront an instruction-fetch bubble).  After the workgroup's last
+    // tile the cursor stays on that tile's last k block: the loads go on, unconditionally, into slots nobody reads.
+    auto next_load_tile = [&](int c_j) {
+        const bool more = c_j + 1 < my_tiles;                 // uniform
+        if (more) set_load_tile(c_j + 1);
+        ld_kb = more ? 0 : nks - 1;
+        ld_step = more ? 1 : 0;
     };
     auto issue_a = [&](int slot, int i) {
         unsigned char *dst = smem + slot * kUnitBytes + dma_wave + i * 4096;
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         for (int i = 0; i < kLoadsPerUnit; ++i) kWeightsFirst ? issue_b(2 * s, i) : issue_a(2 * s, i);
 #pragma unroll
         for (int i = 0; i < kLoadsPerUnit; ++i) kWeightsFirst ? issue_a(2 * s + 1, i) : issue_b(2 * s + 1, i);
-        advance_load();
+        ++ld_kb;
     }
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -244,6 +247,7 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         // ---- sub-step 0 (f0, k 0..31): fragments of sub-step 1 -> f1; first unit of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
+            if (q == 0) __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): every fragment of f0, read long ago, in one wait
             acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7]);
             if (q < 32 && (q & 1) == 0) read_frag(f1, sA, sB, 1, q >> 1);
             if ((q & 7) == 7) kWeightsFirst ? issue_b(early, q >> 3) : issue_a(early, q >> 3);
@@ -252,23 +256,35 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
         // ---- sub-step 1 (f1, k 32..63): wait + barrier; fragments of sub-step 0 of block g+1 -> f0; second unit of block g+2
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
+            if (q == 0) __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): likewise f1
             acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7]);
             if (q == 3) {
-                // Every LDS read of block g has been issued.  Wait for them and for this wavefront's loads
-                // of block g+1 (the 8 early loads of block g+2 may fly), then meet the others: after
+                // Every LDS read of block g has come back (the wait at the top of this sub-step).  Wait for this
+                // wavefront's loads of block g+1 (the 8 early loads of block g+2 may fly), then meet the others: after
                 // the barrier block g+1 is complete in LDS and the slots of block g may be refilled.
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
             }
             if (q >= 4 && q < 36 && (q & 1) == 0) read_frag(f0, sA1, sB1, 0, (q - 4) >> 1);
             if (q >= 7 && (q & 7) == 7) kWeightsFirst ? issue_a(late, q >> 3) : issue_b(late, q >> 3);   // q = 7, 15, .., 63: loads 0..7
             __builtin_amdgcn_sched_barrier(0);
         }
-        advance_load();
+        ld_kb += ld_step;
         s1 = n1; s2 = n2;
     };
-    stage(std::true_type{});
-    for (int c_kb = 1; c_kb < nks - 1; ++c_kb) stage(std::false_type{});
+    if (nks == 2) next_load_tile(c_j);                         // a tile of two k blocks: its first is its last but one
+    stage(std::true_type{});                                   // k block 0 (loads: k block 2)
+    {                                                          // k blocks 1 .. nks - 3 (loads: k blocks 3 .. nks - 1 of this tile),
+        int c_kb = 1;                                          // two per pass: one taken branch per two k blocks
+        for (; c_kb + 1 < nks - 2; c_kb += 2) {
+            stage(std::false_type{});
+            stage(std::false_type{});
+        }
+        if (c_kb < nks - 2) stage(std::false_type{});
+    }
+    if (nks > 2) {
+        next_load_tile(c_j);
+        stage(std::false_type{});                              // k block nks - 2 (loads: k block 0 of the next tile)
+    }
             // ---- end of a tile: LayerNorm statistics, constants of the layer, fp16, head split.
             // What the epilogue needs from memory (the row's statistics, the constants of this lane's output
             // features) is asked for before the tile's last k block, whose MFMAs hide the latency; these
@@ -278,7 +294,11 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
             tile_coords<GROUP_M>((int)blockIdx.x + c_j * (int)gridDim.x, tiles_m, tiles_n, tm, tn);
             const int64_t m0 = (int64_t)tm * FBM;
             const int n0 = tn * FBN;
-            const RowDst my_row = row_dst(m0 + tid, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
+            // Tile rows past the last token stand for the last token: their operand loads were clamped to its row, so
+            // their accumulators equal its accumulators bit for bit, and they store the same bytes to the same place.
+            // The write-out then needs no test per row (a branch per row costs more than the row's arithmetic).
+            const int64_t m_row = m0 + tid < M ? m0 + tid : M - 1;
+            const RowDst my_row = row_dst(m_row, M, n_heads, head_dim, L_act, L_cap, tok_off, stats);
             const int nb = n0 + wn * FWN + FTN * (lane & 15);
             float cn[FTN], bn[FTN];
 #pragma unroll
@@ -286,16 +306,18 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
                 cn[j] = nb < N ? cvec[nb + j] : 0.f;
                 bn[j] = nb < N ? bvec[nb + j] : 0.f;
             }
-    stage(std::false_type{});                                  // the last k block (nks >= 2)
+    stage(std::false_type{});                                  // the last k block (loads: k block 1 of the next tile)
         {
             // The slot that held the second unit of the block just consumed is free until the next
             // block's late loads are issued: it holds the row table meanwhile.
             const int s_tab = s2 >= 2 ? s2 - 2 : s2 + kSlots - 2;        // slot of the second unit of block g
             RowDst *tab = reinterpret_cast<RowDst *>(smem + s_tab * kUnitBytes);
             tab[tid] = my_row;
-            __syncthreads();
+            // Barriers that wait for LDS traffic only: __syncthreads() would also wait for every global access in
+            // flight, i.e. for the next tile's first k blocks (two memory latencies per tile) and for the stores.
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             store_tile<DT, FTM, FTN>(acc, lane, tab, wm * FWM, nb, d, head_dim, L_cap, cn, bn, K_out, V_out);
-            __syncthreads();                                   // the table's slot is about to be refilled
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the table's slot is about to be refilled
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // loads issued past the end land before LDS is released
