@@ -311,7 +311,7 @@ def hk_two_stream_workspace_bytes(shape: hk_shape, B: int, L_kv: int, L_act: int
 
 
 def hybrid_decode_attn_two_stream(q, K_cache, V_cache, act, layer_params, ratio, side_stream, events, out=None, gemm_cus=0,
-                                  ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None):
+                                  ln_eps=1e-5, softmax_scale=0.0, workspace=None, stream=None, gemm_tile=0):
     """hk_hybrid_decode_attn_two_stream: the step with the attention over the cached segment on ``side_stream``
     (a torch stream; None = the same stream) beside the regeneration on ``stream``.  ``events``: a
     ``hipevents.EventSet`` of at least 2 (fork, join)."""
@@ -320,7 +320,7 @@ def hybrid_decode_attn_two_stream(q, K_cache, V_cache, act, layer_params, ratio,
     L_kv = 0 if K_cache is None else K_cache.shape[2]
     L_act = 0 if act is None else act.shape[1]
     f16 = q.dtype
-    shape = make_shape(H * dh, H, ln_eps, softmax_scale, dtype=_dtype_code(q))
+    shape = make_shape(H * dh, H, ln_eps, softmax_scale, 0, gemm_tile, dtype=_dtype_code(q))
     if out is None:
         out = torch.empty((B, H, dh), dtype=f16, device=q.device)
     if workspace is None:

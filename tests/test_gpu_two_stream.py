@@ -78,3 +78,39 @@ def test_two_stream_step(cfg):
     diff = (two.float() - plain.float()).abs().max().item()
     print("vs the single-stream entry point: max_abs=%.3e" % diff, flush=True)
     assert diff <= 4e-3                                       # two extra roundings to fp16 before the join
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,H", [(128, 2), (192, 3), (256, 4), (320, 5), (448, 7), (1024, 8)], ids=lambda v: str(v))
+def test_projection_on_few_compute_units_walks_many_tiles(d, H):
+    """The persistent projection kernel confined to 3 compute units: every workgroup then computes several tiles in a
+    row, with the load cursor crossing from one tile to the next while the matrix cores are two k blocks behind.
+    Layers of 2, 3, 4, 5, 7 and 16 k blocks (a tile's first k block is its last but one, the main loop is empty, has an
+    odd and an even number of passes), a ragged last row tile and a half last column tile; the regenerated K and V
+    rows are checked one by one."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; there is no CPU path")
+    cfg = synth.LayerConfig("walk_d%d" % d, d, H, 3, 801, 100 / 801, 90 + H)     # 3 x 701 = 2103 checkpoint rows: 9 row tiles
+    print("case", cfg, flush=True)
+    b = synth.make_batch(cfg)
+    g = {k: torch.from_numpy(v).cuda() for k, v in b.items()}
+    lp = (g["ln_w"], g["ln_b"], g["Wkv"], g["bkv"])
+    shape = hk.make_shape(d, H, gemm_tile=256)
+    ws = hk.new_workspace(hk.hk_two_stream_workspace_bytes(shape, cfg.B, cfg.L_kv, cfg.L_act), "cuda")
+    ev = EventSet(2)
+    out = hk.hybrid_decode_attn_two_stream(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio, None, ev, gemm_cus=3,
+                                           workspace=ws, gemm_tile=256)
+    torch.cuda.synchronize()
+    n = cfg.B * H * cfg.L_act * cfg.head_dim
+    k_off, v_off = hk.hk_regen_offsets(shape, cfg.B, cfg.L_act)
+    K = ws[k_off:k_off + 2 * n].view(torch.float16).view(cfg.B, H, cfg.L_act, cfg.head_dim).float().cpu().numpy()
+    V = ws[v_off:v_off + 2 * n].view(torch.float16).view(cfg.B, H, cfg.L_act, cfg.head_dim).float().cpu().numpy()
+    ref_out, ref_K, ref_V = ho.hybrid_decode_attn(b["q"], b["K_cache"], b["V_cache"], b["act"], b["ln_w"], b["ln_b"], b["Wkv"],
+                                                  b["bkv"], H)
+    ev.destroy()
+    for name, got, ref in (("K_regen", K, ref_K[:, :, cfg.L_kv:]), ("V_regen", V, ref_V[:, :, cfg.L_kv:]),
+                           ("out", out.float().cpu().numpy(), ref_out)):
+        err = np.abs(got - ref).max()
+        rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+        print("%s: max_abs=%.3e rel_l2=%.3e" % (name, err, rel), flush=True)
+        assert err <= MAX_ABS and rel <= REL_L2, (name, err, rel)
