@@ -385,14 +385,24 @@ __device__ __forceinline__ void block_product_rows(RowOf row_of, int n_rows,
                     }
                     *reinterpret_cast<half8_t *>(my + wr_off[j]) = piece;
                 }
+                // The operand fragments of k piece jj + 1 are read while the MFMAs of piece jj run: left to the
+                // compiler every MFMA waits for its own LDS read (register pressure makes it reuse one register set).
+                half8_t wf[2], af[2][RB];
+                auto read_piece = [&](int jj) {
+                    wf[jj & 1] = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        af[jj & 1][rb] = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlockBytes + rd_off[jj]);
+                };
+                read_piece(0);
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
-                    const half8_t wf = *reinterpret_cast<const half8_t *>(my + rd_off[jj]);
+                    if (jj + 1 < 4) read_piece(jj + 1);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb) {
-                        const half8_t af = *reinterpret_cast<const half8_t *>(tile + ((sc & 1) * RB + rb) * kBlockBytes + rd_off[jj]);
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, wf, acc[rb], 0, 0, 0);
-                    }
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[jj & 1][rb], wf[jj & 1], acc[rb], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
             }

@@ -4,6 +4,7 @@ LDS counters; L2 hit / miss / fabric-read counters), and prints a short text sum
 the commands that produced them.
 
     python3 -m paper_2501_01792_amd.profile_summary hybrid --config opt66b > profiles/hybrid_step_opt66b.txt
+    python3 -m paper_2501_01792_amd.profile_summary hybrid --config opt66b --ratio 0.5 -- --absorbed > profiles/absorbed_step_...txt
     python3 -m paper_2501_01792_amd.profile_summary measure -- paged --config opt66b ... > profiles/paged_step_....txt
 
 This process never touches the GPU: every pass is a child process `rocprofv3 ... -- python3 <program> ...` with a
@@ -112,10 +113,12 @@ def main():
 
     if args.what == "hybrid":
         tag = "hybrid_%s%s" % (args.config, "_r" + args.ratio if args.ratio else "")
+        tag += re.sub(r"[^A-Za-z0-9.]+", "_", " ".join(args.rest)).rstrip("_")
         prog = ["python3", "bench.py", "--config", args.config, "--steps", str(args.steps), "--warmup", "2", "--no-cpu-baseline",
-                "--no-variants", "--no-sweep"] + (["--ratio", args.ratio] if args.ratio else [])
+                "--no-variants", "--no-sweep"] + (["--ratio", args.ratio] if args.ratio else []) + args.rest
         calib = ["--calibrate-copy"]
-        title = "hybrid-cache decode step, workload %s%s" % (args.config, " at KV fraction " + args.ratio if args.ratio else "")
+        title = "hybrid-cache decode step, workload %s%s%s" % (args.config, " at KV fraction " + args.ratio if args.ratio else "",
+                                                              ", bench.py " + " ".join(args.rest) if args.rest else "")
     else:
         tag = "measure_" + re.sub(r"[^A-Za-z0-9.]+", "_", " ".join(args.rest)).strip("_")
         prog = ["python3", "-m", "paper_2501_01792_amd.measure"] + args.rest
