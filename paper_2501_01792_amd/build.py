@@ -13,7 +13,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhybridkv.so")
-PROBE_SRC = os.path.join(HERE, "probe", "mfma_rate.hip")       # the benchmark's measurement aid: a library of its own
+PROBE_SRC = [os.path.join(HERE, "probe", "mfma_rate.hip"),     # measurement aids: a library of their own
+             os.path.join(HERE, "probe", "read_rate.hip")]
 PROBE_LIB = os.path.join(HERE, "probe", "libhkprobe.so")
 SOURCES = ["api.hip", "device_info.hip", "ln_stats.hip", "kv_gemm.hip", "kv_gemm_fold.hip", "flash_decode.hip", "paged_decode.hip", "paged_append.hip", "qkv_current.hip", "absorbed.hip", "policy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -46,7 +47,7 @@ def build(verbose: bool = False) -> str:
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])
     os.replace(tmp, LIB)
     tmp = PROBE_LIB + ".tmp%d" % os.getpid()
-    r = subprocess.run([HIPCC, *FLAGS, "-shared", PROBE_SRC, "-o", tmp], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", *PROBE_SRC, "-o", tmp], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (PROBE_SRC, r.stdout, r.stderr))
     os.replace(tmp, PROBE_LIB)

@@ -6,6 +6,7 @@
     python -m paper_2501_01792_amd.measure loop  [--config opt6.7b] [--block-tokens 16] [--act-fraction 0.5] [--ragged] [--iters 20]
     python -m paper_2501_01792_amd.measure overlap [--config opt6.7b] [--iters 20]
     python -m paper_2501_01792_amd.measure gemm    [--config opt66b] [--iters 6]
+    python -m paper_2501_01792_amd.measure read    [--config opt66b] [--iters 5]
 
 Each prints one JSON line.  Inputs are drawn on the GPU with the scales of the benchmark recipe (timing only;
 parity is the tests' business).  ``qkv`` measures hk_qkv_current (Sec. 4.2.2, QKV generation of the current
@@ -20,6 +21,8 @@ regeneration) against the single-stream step, with the projection kernel on all 
 ``gemm`` measures hk_regen_kv (LayerNorm statistics + projection with bias and head-split stores) on the workload's
 regeneration GEMM (all of its tokens as checkpoints) alternately with a plain library GEMM on the same operands
 (torch.addmm, i.e. hipBLASLt: no LayerNorm, row-major output), as a comparator for what this GPU sustains on the shape.
+``read`` measures how fast the workload's checkpoint rows stream from HBM with the load structure of the streaming
+kernels (32 rows per wavefront, 20 KiB in flight each) for four shapes of one load instruction, plain and non-temporal.
 """
 import argparse
 import json
@@ -335,9 +338,28 @@ def measure_gemm(args):
     return 0
 
 
+def measure_read(args):
+    """The read rate of the checkpoint rows of a workload by shape of one load instruction (probe.read_rate)."""
+    import torch
+    from . import probe, synth
+    cfg = synth.CONFIGS[args.config]
+    rows = cfg.B * (cfg.L_act if cfg.L_act else cfg.L) // 128 * 128
+    row_bytes = cfg.d * 2 // 1024 * 1024
+    buf = torch.ones(rows * row_bytes, dtype=torch.uint8, device="cuda")
+    table = []
+    for nt in (False, True):
+        for rpl in (8, 4, 2, 1):
+            table.append({"rows_per_load": rpl, "bytes_per_row_per_load": 1024 // rpl, "nontemporal": nt,
+                          "GBps": probe.read_rate(buf, rows, row_bytes, rpl, nt, iters=args.iters)})
+    print(json.dumps({"entry": "probe.read_rate (20 loads of 16 bytes per lane in flight per wavefront, 32 rows per wavefront)",
+                      "workload": "%s: %d rows x %d bytes = %.2f GB" % (cfg.name, rows, row_bytes, rows * row_bytes / 1e9),
+                      "peak_GBps": 8000.0, "table": table}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["qkv", "paged", "loop", "overlap", "gemm"])
+    ap.add_argument("what", choices=["qkv", "paged", "loop", "overlap", "gemm", "read"])
     ap.add_argument("--config", default=None)
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--block-tokens", type=int, default=16)
@@ -362,6 +384,8 @@ def main():
     if args.what == "overlap":
         args.config = args.config or "opt6.7b"
         return measure_overlap(args)
+    if args.what == "read":
+        return measure_read(args)
     if args.what == "gemm":
         args.config = args.config or "opt66b"
         if args.iters == 20:

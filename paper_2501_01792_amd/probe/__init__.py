@@ -1,4 +1,5 @@
-"""Measurement aid of the benchmark: what a loop of nothing but fp16 MFMAs sustains on the GPU at hand.
+"""Measurement aids: what a loop of nothing but fp16 MFMAs sustains on the GPU at hand (the benchmark prints it), and
+the rate at which row-major rows stream from HBM for different shapes of one load instruction (``measure read``).
 
 Its own small library (libhkprobe.so, built by ``paper_2501_01792_amd.build``), kept apart from the product
 library: it is no operation of the method and synchronises the stream.
@@ -12,11 +13,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhkprobe.
 _lib = None
 
 
-def mfma_rate(random_operands: bool, iters: int = 10000) -> float:
-    """Sustained TFLOP/s of back-to-back v_mfma_f32_16x16x32_f16 on every compute unit, with all-zero or random
-    fp16 operands (the second is the practical ceiling of an fp16 GEMM on this GPU: the clock drops under
-    operand toggling)."""
-    import torch
+def _load():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
@@ -25,9 +22,38 @@ def mfma_rate(random_operands: bool, iters: int = 10000) -> float:
         _lib.hkprobe_mfma_rate.restype = ctypes.c_int
         _lib.hkprobe_mfma_rate.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
                                            ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
+        _lib.hkprobe_read_rate.restype = ctypes.c_int
+        _lib.hkprobe_read_rate.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
+    return _lib
+
+
+def read_rate(buf, rows: int, row_bytes: int, rows_per_load: int, nontemporal: bool, iters: int = 5) -> float:
+    """GB/s at which ``rows`` x ``row_bytes`` bytes of the GPU tensor ``buf`` stream when every wavefront owns 32 rows
+    and one load instruction covers ``rows_per_load`` rows (8, 4, 2, 1) x 1024 / rows_per_load bytes."""
+    import torch
+    lib = _load()
+    if not buf.is_cuda or buf.numel() * buf.element_size() < rows * row_bytes:
+        raise ValueError("buf: a GPU tensor of at least rows * row_bytes bytes")
+    sink = torch.zeros(rows // 32 + 64, dtype=torch.int32, device="cuda")
+    out = ctypes.c_float()
+    st = lib.hkprobe_read_rate(rows_per_load, 1 if nontemporal else 0, ctypes.c_void_p(buf.data_ptr()), rows, row_bytes,
+                               ctypes.c_void_p(sink.data_ptr()), iters, ctypes.byref(out),
+                               ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != 0:
+        raise RuntimeError("hkprobe_read_rate failed: %d" % st)
+    return float(out.value)
+
+
+def mfma_rate(random_operands: bool, iters: int = 10000) -> float:
+    """Sustained TFLOP/s of back-to-back v_mfma_f32_16x16x32_f16 on every compute unit, with all-zero or random
+    fp16 operands (the second is the practical ceiling of an fp16 GEMM on this GPU: the clock drops under
+    operand toggling)."""
+    import torch
+    lib = _load()
     sink = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
     out = ctypes.c_float()
-    st = _lib.hkprobe_mfma_rate(1 if random_operands else 0, iters, ctypes.c_void_p(sink.data_ptr()), sink.numel(),
+    st = lib.hkprobe_mfma_rate(1 if random_operands else 0, iters, ctypes.c_void_p(sink.data_ptr()), sink.numel(),
                                 ctypes.byref(out), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if st != 0:
         raise RuntimeError("hkprobe_mfma_rate failed: %d" % st)

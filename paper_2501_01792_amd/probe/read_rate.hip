@@ -1,0 +1,100 @@
+// Measurement aid (part of libhkprobe.so, not of libhybridkv and no operation of the paper): the rate at which a
+// row-major matrix of 16-bit elements streams from HBM when every wavefront owns 32 rows and keeps a fixed number
+// of 16-byte-per-lane loads in flight, for different shapes of one load instruction (8 rows x 128 bytes, which is
+// what the MFMA operand staging of the streaming kernels asks for, down to 1 row x 1024 bytes) and for plain and
+// non-temporal loads.  It says what the load structure of those kernels can reach before any arithmetic.
+// Read-only; every address lies inside the caller's buffer.
+#include <stddef.h>
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+namespace {
+
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int kDepth = 20;                                   // loads in flight per wavefront
+
+template <int RPI, bool NT>
+__global__ __launch_bounds__(256) void read_rate_kernel(const unsigned char *base, int64_t ld_bytes, int row_bytes,
+                                                        int rows_total, unsigned *out)
+{
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int row0 = gw * 32;
+    if (row0 + 32 > rows_total) return;                      // whole wavefront; no barrier in this kernel
+    constexpr int LPR = 64 / RPI;                            // lanes per row
+    constexpr int SEG = 16 * LPR;                            // bytes per row per instruction
+    constexpr int G = 32 / RPI;                              // instructions per segment of the 32 rows
+    const int rin = lane / LPR, chunk = lane % LPR;
+    const int total = (row_bytes / SEG) * G;
+    const unsigned char *p0 = base + (int64_t)(row0 + rin) * ld_bytes + chunk * 16;
+    auto load = [&](int idx) {
+        if (idx >= total) idx = total - 1;                   // past the end: the last piece again
+        const int seg = idx / G, rg = idx % G;
+        const uint4v *src = reinterpret_cast<const uint4v *>(p0 + (int64_t)rg * RPI * ld_bytes + (int64_t)seg * SEG);
+        return NT ? __builtin_nontemporal_load(src) : *src;
+    };
+    uint4v buf[kDepth];
+#pragma unroll
+    for (int u = 0; u < kDepth; ++u) buf[u] = load(u);
+    uint4v acc = {0, 0, 0, 0};
+    for (int i = 0; i < total; i += kDepth) {
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            acc ^= buf[u];
+            buf[u] = load(i + kDepth + u);
+        }
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345u) out[gw] = 1;   // keeps the loads alive
+}
+
+template <int RPI, bool NT>
+void launch(const unsigned char *buf, int rows, int row_bytes, unsigned *out, hipStream_t s)
+{
+    hipLaunchKernelGGL((read_rate_kernel<RPI, NT>), dim3(rows / 128), dim3(256), 0, s, buf, (int64_t)row_bytes, row_bytes, rows, out);
+}
+
+}  // namespace
+
+// Streams `rows` x `row_bytes` bytes of `buf` (device; rows a multiple of 128, row_bytes a multiple of 1024) `iters`
+// times after two warm-up launches and returns the rate in GB/s through gbps_out (host).  rows_per_load: 8, 4, 2 or 1.
+// `sink` is device scratch of rows / 32 * 4 bytes.  Synchronises the stream.  Returns 0, or a negative number:
+// -1 null pointer, -2 bad shape, -7 a HIP call failed.
+extern "C" int hkprobe_read_rate(int32_t rows_per_load, int32_t nontemporal, const void *buf, int32_t rows, int32_t row_bytes,
+                                 void *sink, int32_t iters, float *gbps_out, void *stream)
+{
+    if (!buf || !sink || !gbps_out) return -1;
+    if (rows <= 0 || rows % 128 != 0 || row_bytes <= 0 || row_bytes % 1024 != 0 || iters <= 0 || iters > 1000) return -2;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned char *b = static_cast<const unsigned char *>(buf);
+    unsigned *o = static_cast<unsigned *>(sink);
+    auto go = [&]() {
+        const bool nt = nontemporal != 0;
+        switch (rows_per_load) {
+        case 8: nt ? launch<8, true>(b, rows, row_bytes, o, s) : launch<8, false>(b, rows, row_bytes, o, s); return true;
+        case 4: nt ? launch<4, true>(b, rows, row_bytes, o, s) : launch<4, false>(b, rows, row_bytes, o, s); return true;
+        case 2: nt ? launch<2, true>(b, rows, row_bytes, o, s) : launch<2, false>(b, rows, row_bytes, o, s); return true;
+        case 1: nt ? launch<1, true>(b, rows, row_bytes, o, s) : launch<1, false>(b, rows, row_bytes, o, s); return true;
+        default: return false;
+        }
+    };
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return -7;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -7; }
+    int rc = 0;
+    if (!go() || !go()) rc = -2;
+    if (rc == 0) {
+        (void)hipEventRecord(e0, s);
+        for (int i = 0; i < iters; ++i) go();
+        (void)hipEventRecord(e1, s);
+        float ms = 0.f;
+        if (hipGetLastError() != hipSuccess || hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+            ms <= 0.f)
+            rc = -7;
+        else
+            *gbps_out = (float)((double)rows * row_bytes * iters / (ms * 1e-3) / 1e9);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
