@@ -261,14 +261,23 @@ __global__ __launch_bounds__(64 * NW * KS) void qkv_fused_kernel(FusedArgs p)
                             Tp[j] = Elem<DT>::dot2(w2, vec2_t{bv[u][2 * e], bv[u][2 * e + 1]}, Tp[j]);
                         }
                     }
+                    // operand fragments of k piece jj + 1 are read while the MFMAs of piece jj run (left to the
+                    // compiler, every MFMA waits for its own LDS read)
+                    vec8_t wf[2], af[2][RB];
+                    auto read_piece = [&](int jj) {
+                        wf[jj & 1] = *reinterpret_cast<const vec8_t *>(my + rd_off[jj]);
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            af[jj & 1][rb] = *reinterpret_cast<const vec8_t *>(tile + ((sc & 1) * RB + rb) * KB + rd_off[jj]);
+                    };
+                    read_piece(0);
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
-                        const vec8_t wf = *reinterpret_cast<const vec8_t *>(my + rd_off[jj]);
+                        if (jj + 1 < 4) read_piece(jj + 1);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int rb = 0; rb < RB; ++rb) {
-                            const vec8_t af = *reinterpret_cast<const vec8_t *>(tile + ((sc & 1) * RB + rb) * KB + rd_off[jj]);
-                            acc[rb] = Elem<DT>::mfma_32x32x16(af, wf, acc[rb]);
-                        }
+                        for (int rb = 0; rb < RB; ++rb) acc[rb] = Elem<DT>::mfma_32x32x16(af[jj & 1][rb], wf[jj & 1], acc[rb]);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
                 __syncthreads();                           // tile sc + 1 is complete; tile sc is free for sc + 2
