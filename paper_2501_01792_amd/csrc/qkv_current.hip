@@ -180,19 +180,8 @@ __global__ __launch_bounds__(64 * NW * KS) void qkv_fused_kernel(FusedArgs p)
     for (int q = 0; q < P; ++q) { m1[q] = 0.f; m2[q] = 0.f; shift[q] = 0.f; }
     float Gp[4] = {0.f, 0.f, 0.f, 0.f}, Tp[4] = {0.f, 0.f, 0.f, 0.f};        // this lane's part of G, T of weight rows 8 j + g_row
 
-    // the shift of every input row: the mean of its first 64 elements (the 8 lanes of a row hold them), the same in
-    // every group; rounded to the storage type, in which it is subtracted
 #pragma unroll
-    for (int q = 0; q < P; ++q) {
-        const vec8_t h = *reinterpret_cast<const vec8_t *>(rp[q]);
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += (float)h[e];
-#pragma unroll
-        for (int off = 1; off < 8; off <<= 1) s += __shfl_xor(s, off, 64);
-        shift[q] = is_row[q] ? (float)(elem_t)(s * (1.0f / 64.0f)) : 0.f;
-        rp[q] += 64 * (int64_t)k_begin;                                     // from here on: this group's part of the row
-    }
+    for (int q = 0; q < P; ++q) rp[q] += 64 * (int64_t)k_begin;             // this group's part of the row
 
     vec8_t sv[kDepth][4], av[kDepth][P], gv[kDepth], bv[kDepth];
     const int last = my_steps > 0 ? my_steps - 1 : 0;
@@ -241,6 +230,19 @@ __global__ __launch_bounds__(64 * NW * KS) void qkv_fused_kernel(FusedArgs p)
 
 #pragma unroll
     for (int u = 0; u < kDepth - 1; ++u) fetch(u, u);
+    // the shift of every input row: the mean of its first 64 elements (the 8 lanes of a row hold them), the same in
+    // every group; rounded to the storage type, in which it is subtracted.  Asked for behind the first steps' loads,
+    // so that the call's start pays one memory latency, not two.
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        const vec8_t h = *reinterpret_cast<const vec8_t *>(rp[q] - 64 * (int64_t)k_begin);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += (float)h[e];
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) s += __shfl_xor(s, off, 64);
+        shift[q] = is_row[q] ? (float)(elem_t)(s * (1.0f / 64.0f)) : 0.f;
+    }
     put(0, 0, 0);
     __syncthreads();
     for (int s = 0; s < steps_g; s += kDepth) {            // steps_g is the same for every group: the barriers match
