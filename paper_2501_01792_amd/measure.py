@@ -351,9 +351,15 @@ def measure_read(args):
         for rpl in (8, 4, 2, 1):
             table.append({"rows_per_load": rpl, "bytes_per_row_per_load": 1024 // rpl, "nontemporal": nt,
                           "GBps": probe.read_rate(buf, rows, row_bytes, rpl, nt, iters=args.iters)})
+    parts = []
+    for flags, what in ((0, "stream alone, 5 steps of 4 loads in flight"), (1, "+ a workgroup barrier per step"),
+                        (2, "+ 3 loads per thread and step from rows every workgroup shares (L2)"), (3, "+ barrier + shared loads"),
+                        (4, "+ every piece through a private LDS block"), (5, "+ barrier + LDS"), (6, "+ shared loads + LDS"),
+                        (7, "+ barrier + shared loads + LDS")):
+        parts.append({"what": what, "GBps": probe.read_rate(buf, rows, row_bytes, 100 + flags, False, iters=args.iters)})
     print(json.dumps({"entry": "probe.read_rate (20 loads of 16 bytes per lane in flight per wavefront, 32 rows per wavefront)",
                       "workload": "%s: %d rows x %d bytes = %.2f GB" % (cfg.name, rows, row_bytes, rows * row_bytes / 1e9),
-                      "peak_GBps": 8000.0, "table": table}))
+                      "peak_GBps": 8000.0, "table": table, "stream_with_parts_of_a_streaming_mfma_kernel": parts}))
     return 0
 
 

@@ -48,6 +48,68 @@ __global__ __launch_bounds__(256) void read_rate_kernel(const unsigned char *bas
     if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345u) out[gw] = 1;   // keeps the loads alive
 }
 
+// The same stream (8 rows x 128 bytes per load, 4 loads = one step of 32 rows x 64 elements, kDepth / 4 steps in
+// flight) with, one by one, what a streaming MFMA kernel adds around it, so that each addition's cost in read rate
+// can be seen: BAR a workgroup barrier per step; L2 three more 16-byte loads per thread and step from a small
+// region every workgroup shares (the shared operand's tile, an L2 hit); LDS every piece written to a private
+// 4 KiB LDS block and read back in MFMA operand layout.
+template <bool BAR, bool L2, bool LDS>
+__global__ __launch_bounds__(256) void stream_parts_kernel(const unsigned char *base, int64_t ld_bytes, int row_bytes,
+                                                           int rows_total, const unsigned char *shared_rows, unsigned *out)
+{
+    __shared__ __align__(16) unsigned char blocks[4 * 4096];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int gw = blockIdx.x * 4 + wave;
+    const int row0 = gw * 32;                                // rows_total is a multiple of 128: every wavefront has rows
+    const int rin = lane >> 3, chunk = lane & 7;
+    const int steps = row_bytes / 128;
+    const unsigned char *p0 = base + (int64_t)(row0 + rin) * ld_bytes + chunk * 16;
+    const unsigned char *q0 = shared_rows + (int64_t)(tid >> 3) * ld_bytes + (tid & 7) * 16;   // rows 0 .. 31 (+ 32, + 64)
+    unsigned char *my = blocks + wave * 4096;
+    int wr_off[4], rd_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + rin;
+        wr_off[j] = row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+        rd_off[j] = (lane & 31) * 128 + (((2 * j + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4);
+    }
+    constexpr int D = kDepth / 4;                            // steps in flight
+    uint4v sv[D][4], tv[D][3];
+    auto fetch = [&](int slot, int sc) {
+        if (sc >= steps) sc = steps - 1;
+        if (L2) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r) tv[slot][r] = *reinterpret_cast<const uint4v *>(q0 + (int64_t)32 * r * ld_bytes + (int64_t)sc * 128);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sv[slot][j] = *reinterpret_cast<const uint4v *>(p0 + (int64_t)8 * j * ld_bytes + (int64_t)sc * 128);
+    };
+#pragma unroll
+    for (int u = 0; u < D - 1; ++u) fetch(u, u);
+    uint4v acc = {0, 0, 0, 0};
+    for (int s = 0; s < steps; s += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            fetch((u + D - 1) % D, s + u + D - 1);
+            if (L2) {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) acc ^= tv[u][r];
+            }
+            if (LDS) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4v *>(my + wr_off[j]) = sv[u][j];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc ^= *reinterpret_cast<const uint4v *>(my + rd_off[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc ^= sv[u][j];
+            }
+            if (BAR) __syncthreads();                        // steps is the same for every wavefront
+        }
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345u) out[gw] = 1;
+}
+
 template <int RPI, bool NT>
 void launch(const unsigned char *buf, int rows, int row_bytes, unsigned *out, hipStream_t s)
 {
@@ -57,7 +119,8 @@ void launch(const unsigned char *buf, int rows, int row_bytes, unsigned *out, hi
 }  // namespace
 
 // Streams `rows` x `row_bytes` bytes of `buf` (device; rows a multiple of 128, row_bytes a multiple of 1024) `iters`
-// times after two warm-up launches and returns the rate in GB/s through gbps_out (host).  rows_per_load: 8, 4, 2 or 1.
+// times after two warm-up launches and returns the rate in GB/s through gbps_out (host).  rows_per_load: 8, 4, 2 or 1;
+// or 100 + flags for stream_parts_kernel (rows must then be at least 96, the shared rows are the buffer's first 96).
 // `sink` is device scratch of rows / 32 * 4 bytes.  Synchronises the stream.  Returns 0, or a negative number:
 // -1 null pointer, -2 bad shape, -7 a HIP call failed.
 extern "C" int hkprobe_read_rate(int32_t rows_per_load, int32_t nontemporal, const void *buf, int32_t rows, int32_t row_bytes,
@@ -68,9 +131,22 @@ extern "C" int hkprobe_read_rate(int32_t rows_per_load, int32_t nontemporal, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned char *b = static_cast<const unsigned char *>(buf);
     unsigned *o = static_cast<unsigned *>(sink);
+    auto parts = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3(rows / 128), dim3(256), 0, s, b, (int64_t)row_bytes, row_bytes, rows, b, o);
+        return true;
+    };
     auto go = [&]() {
         const bool nt = nontemporal != 0;
         switch (rows_per_load) {
+        // 100 + flags: the 8 x 128-byte stream with parts of a streaming MFMA kernel added (1 barrier, 2 shared loads, 4 LDS)
+        case 100: return parts(stream_parts_kernel<false, false, false>);
+        case 101: return parts(stream_parts_kernel<true, false, false>);
+        case 102: return parts(stream_parts_kernel<false, true, false>);
+        case 103: return parts(stream_parts_kernel<true, true, false>);
+        case 104: return parts(stream_parts_kernel<false, false, true>);
+        case 105: return parts(stream_parts_kernel<true, false, true>);
+        case 106: return parts(stream_parts_kernel<false, true, true>);
+        case 107: return parts(stream_parts_kernel<true, true, true>);
         case 8: nt ? launch<8, true>(b, rows, row_bytes, o, s) : launch<8, false>(b, rows, row_bytes, o, s); return true;
         case 4: nt ? launch<4, true>(b, rows, row_bytes, o, s) : launch<4, false>(b, rows, row_bytes, o, s); return true;
         case 2: nt ? launch<2, true>(b, rows, row_bytes, o, s) : launch<2, false>(b, rows, row_bytes, o, s); return true;
