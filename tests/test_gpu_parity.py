@@ -259,7 +259,9 @@ FULL = [
 def test_full_size_configs_sampled(hk, oracle, cfg):
     print("case", cfg, flush=True)
     torch.cuda.empty_cache()
-    _sampled_oracle_check(hk, oracle, cfg, n_rows=16, n_pairs=2, prepared=True)
+    # the benchmark's workload gets about a hundred rows (28 placed by the tile walk, 70 random, 2 corners)
+    bench_workload = cfg.name == "opt66b" and cfg.L_kv == 0
+    _sampled_oracle_check(hk, oracle, cfg, n_rows=70 if bench_workload else 16, n_pairs=2, prepared=True)
     torch.cuda.empty_cache()
 
 
