@@ -8,7 +8,8 @@ the commands that produced them.
     python3 -m paper_2501_01792_amd.profile_summary measure -- paged --config opt66b ... > profiles/paged_step_....txt
 
 This process never touches the GPU: every pass is a child process `rocprofv3 ... -- python3 <program> ...` with a
-time limit of its own, and a pass that fails ends the run.  Raw profiler output goes to gpurun_out/prof/<tag>/.
+time limit of its own, and a pass that fails ends the run.  Raw profiler output goes to a scratch folder beside the
+sources (SCRATCH below), one sub-folder per program and pass; only the printed summary is meant to be kept.
 """
 from __future__ import annotations
 
@@ -23,6 +24,7 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SCRATCH = os.path.join("gpurun_out", "prof")      # raw profiler output, relative to ROOT
 
 KERNELS = ("column_product|paged_scores|paged_index|paged_prefix|paged_append|row_stats|absorbed_scores_block|"
            "absorbed_scores|absorbed_softmax|absorbed_project_block|absorbed_project|absorbed_join|absorbed_stream|"
@@ -52,7 +54,7 @@ def short(name):
 
 
 def run_pass(tag, name, prof_args, prog, limit):
-    out_dir = os.path.join(ROOT, "gpurun_out", "prof", tag, name)
+    out_dir = os.path.join(ROOT, SCRATCH, tag, name)
     shutil.rmtree(out_dir, ignore_errors=True)
     os.makedirs(out_dir, exist_ok=True)
     cmd = ["rocprofv3"] + prof_args + ["--output-format", "csv", "-d", out_dir, "-o", "p", "--"] + prog
