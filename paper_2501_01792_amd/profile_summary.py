@@ -40,7 +40,9 @@ GROUPS = [
 ]
 
 
-CALIBRATION = "device copy (calibration)"     # the runtime's buffer-copy kernel; the 1 GiB copy is its largest dispatch
+CALIBRATION = "device copy (runtime)"         # the runtime's buffer-copy kernel (tensor copies of the measured program); in
+                                              # hybrid mode the program also makes one 1 GiB copy, its largest dispatch, which
+                                              # calibrates the traffic counters
 
 
 def short(name):
