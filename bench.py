@@ -11,7 +11,7 @@ sweep {0, .25, .5, .75, 1} of the same layer (Sec. 4.3: where recomputation and 
 balance) and the CPU oracle timed on a bounded sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config opt66b] [--ratio R]
-                    [--no-sweep] [--no-cpu-baseline] [--no-variants]
+                    [--no-sweep] [--no-cpu-baseline] [--no-variants] [--traffic auto|live|profiles|none]
     python bench.py --sweep [--config opt66b]      only the sweep, as its own JSON line
 """
 import argparse
@@ -205,6 +205,11 @@ def main():
     ap.add_argument("--unprepared", action="store_true",
                     help="do not call hk_prepare_layer: the library prepares the layer inside every step")
     ap.add_argument("--sweep", action="store_true", help="only the KV-fraction sweep of --config, as its own JSON line")
+    ap.add_argument("--traffic", choices=["auto", "live", "profiles", "none"], default="auto",
+                    help="where roofline.traffic (HBM-side bytes per launch) comes from: live = measured now, before this "
+                         "process touches the GPU, by two short child runs of this program under rocprofv3 --pmc (FETCH_SIZE, "
+                         "WRITE_SIZE, scaled by a 1 GiB copy); profiles = the committed summary of the workload; auto = live "
+                         "for the benchmark's own line when rocprofv3 is there, else profiles")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of 1 GiB (3 launches) so that profiler byte counters "
                          "can be scaled against a kernel of known traffic")
@@ -213,6 +218,21 @@ def main():
         print("bench.py: this build runs on one GPU only (the step has no cross-GPU part); "
               "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
         return 2
+
+    # roofline.traffic measured in this run: child processes under the profiler, started before this process has
+    # loaded anything that touches the GPU
+    live_traffic, live_note = None, None
+    main_line = not (args.sweep or args.absorbed or args.calibrate_copy)
+    if args.traffic == "live" or (args.traffic == "auto" and main_line):
+        import shutil
+        if shutil.which("rocprofv3") is None:
+            live_note = "rocprofv3 not found"
+        else:
+            try:
+                from paper_2501_01792_amd import profile_summary
+                live_traffic = profile_summary.measure_traffic(args.config, args.ratio, args.dtype)
+            except (SystemExit, Exception) as e:                      # a failed pass must not cost the bench line
+                live_note = "live measurement failed: %s" % (str(e).splitlines()[0] if str(e) else type(e).__name__)
 
     import numpy as np
     import torch
@@ -328,8 +348,17 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     gemm_flops, attn_bytes = algorithmic_counts(cfg)
-    traffic = profiled_traffic(cfg.name) if args.ratio is None else {}
-    traffic_source = "profiles/hybrid_step_%s.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE per launch, scaled by a 1 GiB copy)" % cfg.name
+    if live_traffic:
+        traffic = live_traffic
+        traffic_source = ("measured in this run: two child runs of this program under rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, "
+                          "KiB per dispatch), scaled by what the same counters read for a 1 GiB device copy (factors %.3f and %.3f)"
+                          % live_traffic["_scale_factors"])
+    elif args.traffic == "none":
+        traffic, traffic_source = {}, None
+    else:
+        traffic = profiled_traffic(cfg.name) if args.ratio is None else {}
+        traffic_source = ("profiles/hybrid_step_%s.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE per launch, scaled by a 1 GiB copy)%s"
+                          % (cfg.name, "; " + live_note if live_note else ""))
     gemm_kernel = "kv_gemm_fold"
     roofline = None
     if cfg.M > 0 and dur["kv_gemm"] > 0:

@@ -98,6 +98,30 @@ def program_line(out_dir):
     return lines[-1] if lines else None
 
 
+def measure_traffic(config, ratio=None, dtype="f16", limit=150):
+    """HBM-side bytes per launch of the kernels of bench.py's step on `config`, measured now: two short runs of
+    bench.py under `rocprofv3 --pmc` (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same
+    counter reads for the 1 GiB device copy that bench.py adds when asked.  Returns {kernel name without template
+    argument and "_kernel": bytes}.  For a caller that has not touched the GPU itself (the runs are child processes).
+    Raises SystemExit (a pass failed) or RuntimeError (no calibration copy in the counters)."""
+    tag = "live_%s%s" % (config, "_r%s" % ratio if ratio is not None else "")
+    prog = ["python3", "bench.py", "--config", config, "--steps", "2", "--warmup", "1", "--dtype", dtype, "--no-cpu-baseline",
+            "--no-variants", "--no-sweep", "--traffic", "none", "--calibrate-copy"] + (["--ratio", str(ratio)] if ratio is not None else [])
+    df, _ = run_pass(tag, "fetch", ["--pmc", "FETCH_SIZE"], prog, limit)
+    dw, _ = run_pass(tag, "write", ["--pmc", "WRITE_SIZE"], prog, limit)
+    f, w = read_counters(df), read_counters(dw)
+    if CALIBRATION not in f or CALIBRATION not in w:
+        raise RuntimeError("the calibration copy is missing from the counters")
+    sf, sw = 1048576.0 / f[CALIBRATION]["FETCH_SIZE"], 1048576.0 / w[CALIBRATION]["WRITE_SIZE"]
+    out = {}
+    for k in f:
+        if k != CALIBRATION:
+            name = k.split("<")[0].replace("_kernel", "")
+            out[name] = (f[k].get("FETCH_SIZE", 0.0) * sf + w.get(k, {}).get("WRITE_SIZE", 0.0) * sw) * 1024.0
+    out["_scale_factors"] = (sf, sw)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("what", choices=["hybrid", "measure"], help="hybrid: bench.py (the benchmark's step); measure: python3 -m "
@@ -119,7 +143,7 @@ def main():
         tag = "hybrid_%s%s" % (args.config, "_r" + args.ratio if args.ratio else "")
         tag += re.sub(r"[^A-Za-z0-9.]+", "_", " ".join(args.rest)).rstrip("_")
         prog = ["python3", "bench.py", "--config", args.config, "--steps", str(args.steps), "--warmup", "2", "--no-cpu-baseline",
-                "--no-variants", "--no-sweep"] + (["--ratio", args.ratio] if args.ratio else []) + args.rest
+                "--no-variants", "--no-sweep", "--traffic", "profiles"] + (["--ratio", args.ratio] if args.ratio else []) + args.rest
         calib = ["--calibrate-copy"]
         title = "hybrid-cache decode step, workload %s%s%s" % (args.config, " at KV fraction " + args.ratio if args.ratio else "",
                                                               ", bench.py " + " ".join(args.rest) if args.rest else "")
