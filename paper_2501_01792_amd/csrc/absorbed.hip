@@ -401,40 +401,63 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
     c2 = wave_sum(c2);
     const float *r = raw + (int64_t)bh * Lp;
     const float4 *st = stats + (int64_t)b * stats_pitch;
-    auto score = [&](int t, float4 &s4) {
-        s4 = st[t];
-        return sl * (__builtin_fmaf(s4.x, r[t], __builtin_fmaf(s4.z, c1, c2)));
-    };
+    // Every load is unconditional (rows past the end re-read the last row and are masked afterwards) and loads come in
+    // batches of kBatch rows per lane: a load under a per-row test makes the compiler wait for it before the next one
+    // is issued, and the kernel then pays one memory latency per row and lane.
+    const int t_last = L_act > 0 ? L_act - 1 : 0;          // row 0 of the scratch rows is readable even without rows
+    constexpr int kBatch = 8;
+    auto score_of = [&](const float4 &s4, float rv) { return sl * (__builtin_fmaf(s4.x, rv, __builtin_fmaf(s4.z, c1, c2))); };
     // The first 64 kKeep rows stay in registers (score, rstd, mean), so that up to that many rows are read once
     // (the statistics of a row are shared by all heads: re-reading them per pass made this kernel L2-bound);
-    // rows beyond are read again in each of the three passes.
+    // rows beyond are read again in each of the three passes.  (Keeping 64 scores per lane and re-reading the
+    // statistics in the last pass instead was slower: 57 against 32 us on 2048 rows, no faster on 4096.)
     constexpr int kKeep = 32;
     float sc[kKeep], rs[kKeep], mn[kKeep];
     float mx = kNegBig;
 #pragma unroll
-    for (int i = 0; i < kKeep; ++i) {
-        const int t = lane + 64 * i;
-        sc[i] = kNegBig; rs[i] = 0.f; mn[i] = 0.f;
-        if (t < L_act) {
-            float4 s4;
-            sc[i] = score(t, s4);
-            rs[i] = s4.x; mn[i] = s4.y;
-            mx = fmaxf(mx, sc[i]);
+    for (int c = 0; c < kKeep; c += kBatch) {
+        float4 s4[kBatch];
+        float rv[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int t = lane + 64 * (c + u), tc = t < t_last ? t : t_last;
+            s4[u] = st[tc];
+            rv[u] = r[tc];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const bool valid = lane + 64 * (c + u) < L_act;
+            sc[c + u] = valid ? score_of(s4[u], rv[u]) : kNegBig;
+            rs[c + u] = valid ? s4[u].x : 0.f;
+            mn[c + u] = valid ? s4[u].y : 0.f;
+            mx = fmaxf(mx, sc[c + u]);
         }
     }
-    for (int t = lane + 64 * kKeep; t < L_act; t += 64) {
-        float4 s4;
-        mx = fmaxf(mx, score(t, s4));
-    }
+    // rows beyond the kept ones, kBatch per lane at a time: fn(row, valid, score, rstd, mean)
+    auto tail_rows = [&](auto fn, int end) {
+        for (int t0 = lane + 64 * kKeep; t0 - lane < end; t0 += 64 * kBatch) {
+            float4 s4[kBatch];
+            float rv[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int t = t0 + 64 * u, tc = t < t_last ? t : t_last;
+                s4[u] = st[tc];
+                rv[u] = r[tc];
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int t = t0 + 64 * u;
+                fn(t, t < L_act, score_of(s4[u], rv[u]), s4[u].x, s4[u].y);
+            }
+        }
+    };
+    tail_rows([&](int, bool valid, float sv, float, float) { if (valid) mx = fmaxf(mx, sv); }, L_act);
     mx = wave_max(mx);
     float l = 0.f;
 #pragma unroll
     for (int i = 0; i < kKeep; ++i)
         if (lane + 64 * i < L_act) l += __builtin_amdgcn_exp2f(sc[i] - mx);
-    for (int t = lane + 64 * kKeep; t < L_act; t += 64) {
-        float4 s4;
-        l += __builtin_amdgcn_exp2f(score(t, s4) - mx);
-    }
+    tail_rows([&](int, bool valid, float sv, float, float) { if (valid) l += __builtin_amdgcn_exp2f(sv - mx); }, L_act);
     l = wave_sum(l);
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     _Float16 *wr = w + (int64_t)bh * Lp;
@@ -454,16 +477,16 @@ __global__ __launch_bounds__(256) void absorbed_softmax_kernel(const _Float16 *_
             wr[t] = wt;
         }
     }
-    for (int t = lane + 64 * kKeep; t < fill; t += 64) {
-        _Float16 wt = (_Float16)0.f;
-        if (t < L_act) {
-            float4 s4;
-            const float sv = score(t, s4);
-            wt = (_Float16)(__builtin_amdgcn_exp2f(sv - mx) * s4.x * inv);
-            mu = __builtin_fmaf((float)wt, s4.y, mu);
+    tail_rows([&](int t, bool valid, float sv, float rstd, float mean) {
+        if (t < fill) {
+            _Float16 wt = (_Float16)0.f;
+            if (valid) {
+                wt = (_Float16)(__builtin_amdgcn_exp2f(sv - mx) * rstd * inv);
+                mu = __builtin_fmaf((float)wt, mean, mu);
+            }
+            wr[t] = wt;
         }
-        wr[t] = wt;
-    }
+    }, fill);
     mu = wave_sum(mu);
     if (lane == 0) sums[bh] = make_float4(mx, l, mu, 0.f);
 }
