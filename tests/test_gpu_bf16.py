@@ -269,3 +269,39 @@ def test_bf16_absorbed_full_size_opt6p7b_sampled(hk, oracle):
     regen = hk.hybrid_decode_attn(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio)
     torch.cuda.synchronize()
     _check("without regeneration vs regenerating", out, regen.float().cpu().numpy().astype(np.float64))
+
+
+# ---- the two other forms of the regenerating step on bf16 tensors: the same kernels behind another entry point, so
+# each must reproduce hk_hybrid_decode_attn's bf16 result (bit for bit where the arithmetic is the same) and stay
+# within the bf16 bar of the oracle.
+
+def test_bf16_static_scratch_call_matches_the_workspace_call(hk, oracle):
+    cfg = SMALL[2]
+    g, h = _inputs(cfg)
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    ref_gpu = hk.hybrid_decode_attn(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio)
+    out = torch.full_like(ref_gpu, 7.0)
+    hk.hybrid_decode_attn_static(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio, out)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.bfloat16 and torch.equal(out, ref_gpu)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, h)
+    _check("out", out, ref_out)
+
+
+def test_bf16_two_stream_step_matches_oracle(hk, oracle):
+    from paper_2501_01792_amd.hipevents import EventSet
+    cfg = SMALL[2]
+    g, h = _inputs(cfg)
+    lp = tuple(g[k] for k in ("ln_w", "ln_b", "Wkv", "bkv"))
+    ev = EventSet(2)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    one = hk.hybrid_decode_attn_two_stream(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio, None, ev)
+    torch.cuda.synchronize()
+    two = hk.hybrid_decode_attn_two_stream(g["q"], g["K_cache"], g["V_cache"], g["act"], lp, cfg.ratio, side, ev)
+    torch.cuda.synchronize()
+    side.synchronize()
+    ev.destroy()
+    assert two.dtype == torch.bfloat16 and torch.equal(one, two), "the side stream changed the result"
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, h)
+    _check("out", two, ref_out)
