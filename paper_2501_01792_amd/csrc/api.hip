@@ -24,11 +24,10 @@ struct Plan {
     size_t off_k, off_v, off_stats, off_prep, off_partial, total;   // off_prep: per-call prepared layer (0 bytes when unused)
 };
 
-// bf16: only the entry points of the benchmark's path take it (prepare, regenerate, the hybrid step)
-int check_shape(const hk_shape *s, bool allow_bf16 = false)
+int check_shape(const hk_shape *s)
 {
     if (!s) return HK_ERR_NULL;
-    if (s->dtype != HK_DTYPE_F16 && !(allow_bf16 && s->dtype == HK_DTYPE_BF16)) return HK_ERR_DTYPE;
+    if (s->dtype != HK_DTYPE_F16 && s->dtype != HK_DTYPE_BF16) return HK_ERR_DTYPE;
     if (s->d <= 0 || s->n_heads <= 0) return HK_ERR_SHAPE;
     if (s->gemm_tile != 0 && s->gemm_tile != 128 && s->gemm_tile != 256) return HK_ERR_SHAPE;
     if (s->head_dim != 64 && s->head_dim != 128) return HK_ERR_SHAPE;
@@ -46,10 +45,9 @@ PreparedLayout prepared_layout(int d);
 
 // Fills the plan; returns HK_OK or a status.  regen_only: plan of hk_regen_kv (no K/V scratch, no partials).
 // prep_room = false: the caller brings a prepared layer, no room for one is planned.
-int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p, bool allow_bf16 = true,
-              bool prep_room = true)
+int make_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, bool regen_only, Plan *p, bool prep_room = true)
 {
-    int st = check_shape(s, allow_bf16);
+    int st = check_shape(s);
     if (st != HK_OK) return st;
     if (B < 0 || L_kv < 0 || L_act < 0) return HK_ERR_SHAPE;
     if (B > (1 << 24) || L_kv > (1 << 28) || L_act > (1 << 28)) return HK_ERR_SHAPE;
@@ -147,14 +145,14 @@ extern "C" {
 
 size_t hk_prepared_bytes(const hk_shape *shape)
 {
-    if (check_shape(shape, true) != HK_OK) return 0;
+    if (check_shape(shape) != HK_OK) return 0;
     return prepared_layout(shape->d).total;
 }
 
 int hk_prepare_layer(const hk_shape *shape, const hk_layer_params *params, void *prepared, size_t prepared_bytes,
                      void *stream)
 {
-    int st = check_shape(shape, true);
+    int st = check_shape(shape);
     if (st != HK_OK) return st;
     st = check_params(params);
     if (st != HK_OK) return st;
@@ -290,7 +288,7 @@ int hybrid_step(const hk_shape *shape, const void *q,
                 void **events, int32_t n_events)
 {
     Plan p;
-    int st = make_plan(shape, B, L_kv, L_act, false, &p, true, !(static_scratch && params && params->prepared));
+    int st = make_plan(shape, B, L_kv, L_act, false, &p, !(static_scratch && params && params->prepared));
     if (st != HK_OK) return st;
     const int64_t L = (int64_t)L_kv + L_act;
     if (L == 0) return HK_ERR_SHAPE;
@@ -464,7 +462,7 @@ struct AbsorbedPlan {
 int make_absorbed_plan(const hk_shape *s, int64_t B, int64_t L_kv, int64_t L_act, AbsorbedPlan *p)
 {
     Plan base;
-    int st = make_plan(s, B, L_kv, L_act, false, &base, true);
+    int st = make_plan(s, B, L_kv, L_act, false, &base);
     if (st != HK_OK) return st;
     if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
     p->M = base.M; p->BH = base.BH; p->scale = base.scale;
@@ -581,7 +579,7 @@ int hk_hybrid_decode_attn_absorbed(const hk_shape *shape, const void *q,
 
 size_t hk_qkv_workspace_bytes(const hk_shape *shape, int32_t B)
 {
-    if (check_shape(shape, true) != HK_OK || B < 0 || B > (1 << 24)) return 0;
+    if (check_shape(shape) != HK_OK || B < 0 || B > (1 << 24)) return 0;
     return kAlign;                                             // the call is one kernel that needs no scratch; the argument stays
 }
 
@@ -596,7 +594,7 @@ int qkv_impl(const hk_shape *shape, const void *x_cur, int32_t B,
              void *act_dst, int32_t act_cap, int32_t act_pos, const hk_paged_cache *paged, const int32_t *store_mask,
              void *workspace, size_t workspace_bytes, void *stream)
 {
-    int st = check_shape(shape, true);
+    int st = check_shape(shape);
     if (st != HK_OK) return st;
     if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
     int blk_log2 = 0;
@@ -691,9 +689,9 @@ struct PagedPlan {
     size_t off_k, off_v, off_stats, off_prep, off_partial, total;
 };
 
-int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p, bool allow_bf16 = false)
+int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedPlan *p)
 {
-    int st = check_shape(s, allow_bf16);
+    int st = check_shape(s);
     if (st != HK_OK) return st;
     if (!c) return HK_ERR_NULL;
     if (B < 0 || B > (1 << 24)) return HK_ERR_SHAPE;
@@ -725,7 +723,7 @@ int make_paged_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, Paged
 size_t hk_paged_workspace_bytes(const hk_shape *shape, int32_t B, const hk_paged_cache *cache)
 {
     PagedPlan p;
-    if (make_paged_plan(shape, B, cache, &p, true) != HK_OK) return 0;
+    if (make_paged_plan(shape, B, cache, &p) != HK_OK) return 0;
     return p.total > 0 ? p.total : kAlign;
 }
 
@@ -734,7 +732,7 @@ int hk_paged_decode_attn(const hk_shape *shape, const void *q, int32_t B, const 
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     PagedPlan p;
-    int st = make_paged_plan(shape, B, cache, &p, true);
+    int st = make_paged_plan(shape, B, cache, &p);
     if (st != HK_OK) return st;
     if (B == 0) return HK_OK;
     if (!q || !out || !workspace || !cache->block_table || !cache->seq_len || !cache->cu_tokens) return HK_ERR_NULL;
@@ -789,7 +787,7 @@ struct PagedAbsorbedPlan {
 int make_paged_absorbed_plan(const hk_shape *s, int64_t B, const hk_paged_cache *c, PagedAbsorbedPlan *p)
 {
     PagedPlan base;                                        // the checks of the paged step
-    int st = make_paged_plan(s, B, c, &base, true);
+    int st = make_paged_plan(s, B, c, &base);
     if (st != HK_OK) return st;
     if (s->n_heads > hk::kAbsorbMaxHeads || B > 65535) return HK_ERR_SHAPE;
     const int64_t max_rows = (int64_t)c->max_blocks * c->block_tokens;     // the most checkpoint rows a request can have
