@@ -345,7 +345,8 @@ def measure_read(args):
     cfg = synth.CONFIGS[args.config]
     rows = cfg.B * (cfg.L_act if cfg.L_act else cfg.L) // 128 * 128
     row_bytes = cfg.d * 2 // 1024 * 1024
-    buf = torch.ones(rows * row_bytes, dtype=torch.uint8, device="cuda")
+    # normally distributed fp16 values: with MFMAs in the loop the clock, and with it the rate, depends on the data
+    buf = torch.randn(rows * row_bytes // 2, dtype=torch.float16, device="cuda").view(torch.uint8)
     table = []
     for nt in (False, True):
         for rpl in (8, 4, 2, 1):
@@ -355,7 +356,8 @@ def measure_read(args):
     for flags, what in ((0, "stream alone, 5 steps of 4 loads in flight"), (1, "+ a workgroup barrier per step"),
                         (2, "+ 3 loads per thread and step from rows every workgroup shares (L2)"), (3, "+ barrier + shared loads"),
                         (4, "+ every piece through a private LDS block"), (5, "+ barrier + LDS"), (6, "+ shared loads + LDS"),
-                        (7, "+ barrier + shared loads + LDS")):
+                        (7, "+ barrier + shared loads + LDS"), (15, "+ barrier + shared loads + LDS + 12 MFMAs per step"),
+                        (23, "+ barrier + shared loads + LDS + MFMAs + the shared operand through an LDS tile")):
         parts.append({"what": what, "GBps": probe.read_rate(buf, rows, row_bytes, 100 + flags, False, iters=args.iters)})
     print(json.dumps({"entry": "probe.read_rate (20 loads of 16 bytes per lane in flight per wavefront, 32 rows per wavefront)",
                       "workload": "%s: %d rows x %d bytes = %.2f GB" % (cfg.name, rows, row_bytes, rows * row_bytes / 1e9),

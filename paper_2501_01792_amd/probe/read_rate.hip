@@ -11,6 +11,8 @@
 namespace {
 
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
 
 constexpr int kDepth = 20;                                   // loads in flight per wavefront
 
@@ -52,12 +54,16 @@ __global__ __launch_bounds__(256) void read_rate_kernel(const unsigned char *bas
 // flight) with, one by one, what a streaming MFMA kernel adds around it, so that each addition's cost in read rate
 // can be seen: BAR a workgroup barrier per step; L2 three more 16-byte loads per thread and step from a small
 // region every workgroup shares (the shared operand's tile, an L2 hit); LDS every piece written to a private
-// 4 KiB LDS block and read back in MFMA operand layout.
-template <bool BAR, bool L2, bool LDS>
+// 4 KiB LDS block and read back in MFMA operand layout; MMA the 12 MFMAs (3 row blocks of the shared operand x 4 k
+// pieces) a streaming product issues per step, on the pieces as they are; TILE the shared operand written to a
+// double-buffered LDS tile and read from there as 12 more fragments per step.  (With MMA the rate depends on the
+// data: operands that toggle lower the clock.)
+template <bool BAR, bool L2, bool LDS, bool MMA = false, bool TILE = false>
 __global__ __launch_bounds__(256) void stream_parts_kernel(const unsigned char *base, int64_t ld_bytes, int row_bytes,
                                                            int rows_total, const unsigned char *shared_rows, unsigned *out)
 {
     __shared__ __align__(16) unsigned char blocks[4 * 4096];
+    __shared__ __align__(16) unsigned char tile[TILE ? 2 * 3 * 4096 : 16];     // TILE: the shared operand goes through LDS as well
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int gw = blockIdx.x * 4 + wave;
     const int row0 = gw * 32;                                // rows_total is a multiple of 128: every wavefront has rows
@@ -87,10 +93,37 @@ __global__ __launch_bounds__(256) void stream_parts_kernel(const unsigned char *
 #pragma unroll
     for (int u = 0; u < D - 1; ++u) fetch(u, u);
     uint4v acc = {0, 0, 0, 0};
+    float16v facc[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) facc[r][e] = 0.f;
     for (int s = 0; s < steps; s += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             fetch((u + D - 1) % D, s + u + D - 1);
+            if (MMA) {                                       // 3 row blocks of the shared operand x 4 k pieces, as a streaming product issues them
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4v *>(my + wr_off[j]) = sv[u][j];
+                if (TILE) {                                 // written for the next step, read for this one (the barrier orders them)
+                    const int t_row = tid >> 3, t_chunk = tid & 7;
+                    const int t_wr = t_row * 128 + ((t_chunk ^ ((t_row >> 1) & 7)) << 4);
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) *reinterpret_cast<uint4v *>(tile + (((s + u + 1) & 1) * 3 + r) * 4096 + t_wr) = tv[(u + 1) % D][r];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint4v w = *reinterpret_cast<const uint4v *>(my + rd_off[j]);
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        const uint4v a = TILE ? *reinterpret_cast<const uint4v *>(tile + (((s + u) & 1) * 3 + r) * 4096 + rd_off[j]) : tv[u][r];
+                        facc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, w),
+                                                                         facc[r], 0, 0, 0);
+                    }
+                }
+                if (BAR) __syncthreads();
+                continue;
+            }
             if (L2) {
 #pragma unroll
                 for (int r = 0; r < 3; ++r) acc ^= tv[u][r];
@@ -106,6 +139,14 @@ __global__ __launch_bounds__(256) void stream_parts_kernel(const unsigned char *
             }
             if (BAR) __syncthreads();                        // steps is the same for every wavefront
         }
+    }
+    if (MMA) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) t += facc[r][e];
+        if (t == 12345.f) out[gw] = 2;
     }
     if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345u) out[gw] = 1;
 }
@@ -138,7 +179,8 @@ extern "C" int hkprobe_read_rate(int32_t rows_per_load, int32_t nontemporal, con
     auto go = [&]() {
         const bool nt = nontemporal != 0;
         switch (rows_per_load) {
-        // 100 + flags: the 8 x 128-byte stream with parts of a streaming MFMA kernel added (1 barrier, 2 shared loads, 4 LDS)
+        // 100 + flags: the 8 x 128-byte stream with parts of a streaming MFMA kernel added (1 barrier, 2 shared loads, 4 LDS;
+        // on top of all three: 8 MFMAs, 16 shared operand through an LDS tile)
         case 100: return parts(stream_parts_kernel<false, false, false>);
         case 101: return parts(stream_parts_kernel<true, false, false>);
         case 102: return parts(stream_parts_kernel<false, true, false>);
@@ -147,6 +189,8 @@ extern "C" int hkprobe_read_rate(int32_t rows_per_load, int32_t nontemporal, con
         case 105: return parts(stream_parts_kernel<true, false, true>);
         case 106: return parts(stream_parts_kernel<false, true, true>);
         case 107: return parts(stream_parts_kernel<true, true, true>);
+        case 115: return parts(stream_parts_kernel<true, true, true, true>);         // 8: + the MFMAs
+        case 123: return parts(stream_parts_kernel<true, true, true, true, true>);   // 16: + the shared operand's LDS tile
         case 8: nt ? launch<8, true>(b, rows, row_bytes, o, s) : launch<8, false>(b, rows, row_bytes, o, s); return true;
         case 4: nt ? launch<4, true>(b, rows, row_bytes, o, s) : launch<4, false>(b, rows, row_bytes, o, s); return true;
         case 2: nt ? launch<2, true>(b, rows, row_bytes, o, s) : launch<2, false>(b, rows, row_bytes, o, s); return true;
