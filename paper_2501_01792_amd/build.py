@@ -16,6 +16,8 @@ LIB = os.path.join(HERE, "libhybridkv.so")
 PROBE_SRC = [os.path.join(HERE, "probe", "mfma_rate.hip"),     # measurement aids: a library of their own
              os.path.join(HERE, "probe", "read_rate.hip")]
 PROBE_LIB = os.path.join(HERE, "probe", "libhkprobe.so")
+PROBE_LT_SRC = os.path.join(HERE, "probe", "library_gemm.hip")  # the vendor GEMM's candidate kernels, timed (links hipBLASLt)
+PROBE_LT_LIB = os.path.join(HERE, "probe", "libhkprobe_lt.so")
 SOURCES = ["api.hip", "device_info.hip", "ln_stats.hip", "kv_gemm.hip", "kv_gemm_fold.hip", "flash_decode.hip", "paged_decode.hip", "paged_append.hip", "qkv_current.hip", "absorbed.hip", "policy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -51,6 +53,11 @@ def build(verbose: bool = False) -> str:
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (PROBE_SRC, r.stdout, r.stderr))
     os.replace(tmp, PROBE_LIB)
+    tmp = PROBE_LT_LIB + ".tmp%d" % os.getpid()
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", PROBE_LT_SRC, "-o", tmp, "-lhipblaslt"], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (PROBE_LT_SRC, r.stdout, r.stderr))
+    os.replace(tmp, PROBE_LT_LIB)
     return LIB
 
 

@@ -333,8 +333,17 @@ def measure_gemm(args):
     for _ in range(4):
         t1, t2 = timed(ours), timed(lib)
         rounds.append({"hk_regen_kv_tflops": flop / t1 / 1e9, "library_gemm_tflops": flop / t2 / 1e9})
-    print(json.dumps({"entry": "hk_regen_kv against torch.addmm (hipBLASLt), alternating, %d launches per figure" % args.iters,
-                      "workload": "%s: M=%d K=%d N=%d" % (cfg.name, B * L, d, 2 * d), "peak_tflops": 2500.0, "rounds": rounds}))
+    line = {"entry": "hk_regen_kv against torch.addmm (hipBLASLt), alternating, %d launches per figure" % args.iters,
+            "workload": "%s: M=%d K=%d N=%d" % (cfg.name, B * L, d, 2 * d), "peak_tflops": 2500.0, "rounds": rounds}
+    if args.candidates > 0:
+        # every kernel the library offers for the plain GEMM (no bias, no LayerNorm, row-major output), its own order
+        from . import probe
+        ms = probe.library_gemm_candidates(a2, W, out, args.candidates, iters=3)
+        tf = [round(flop / t / 1e9) if t > 0 else None for t in ms]
+        line["library_candidates_tflops"] = tf
+        line["library_candidates_best_tflops"] = max(x for x in tf if x is not None)
+        line["hk_regen_kv_tflops_after_candidates"] = flop / timed(ours) / 1e9
+    print(json.dumps(line))
     return 0
 
 
@@ -375,6 +384,8 @@ def main():
     ap.add_argument("--ragged", action="store_true")
     ap.add_argument("--absorbed", action="store_true", help="paged: the entry point that does not regenerate K/V")
     ap.add_argument("--graph", action="store_true", help="paged: time the step replayed from a HIP graph")
+    ap.add_argument("--candidates", type=int, default=0,
+                    help="gemm: also time up to this many kernels the vendor library offers for the shape (its heuristic's list)")
     ap.add_argument("--free-cus", type=int, default=None, help="overlap: only this carve-out (compute units left to the side stream)")
     args = ap.parse_args()
     import torch

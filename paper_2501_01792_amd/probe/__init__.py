@@ -10,7 +10,9 @@ import ctypes
 import os
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhkprobe.so")
+LT_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhkprobe_lt.so")
 _lib = None
+_lt_lib = None
 
 
 def _load():
@@ -58,3 +60,36 @@ def mfma_rate(random_operands: bool, iters: int = 10000) -> float:
     if st != 0:
         raise RuntimeError("hkprobe_mfma_rate failed: %d" % st)
     return float(out.value)
+
+
+def library_gemm_candidates(a, w, out, max_candidates: int = 32, iters: int = 3, workspace_bytes: int = 512 << 20):
+    """Mean milliseconds of each kernel the vendor GEMM library offers for ``out[M, N] = a[M, K] @ w[N, K].T`` (fp16 or
+    bf16 GPU tensors, fp32 accumulation), in the library's own order of preference; 0.0 for a candidate it refuses or
+    whose workspace does not fit.  libhkprobe_lt.so is a library of its own: only this function loads it."""
+    import torch
+    global _lt_lib
+    if _lt_lib is None:
+        if not os.path.exists(LT_LIB_PATH):
+            raise RuntimeError("%s is missing: run `python -m paper_2501_01792_amd.build` first" % LT_LIB_PATH)
+        _lt_lib = ctypes.CDLL(LT_LIB_PATH)
+        _lt_lib.hkprobe_library_gemm_candidates.restype = ctypes.c_int
+        _lt_lib.hkprobe_library_gemm_candidates.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
+            ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+    M, K = a.shape
+    N = w.shape[0]
+    if not (a.is_cuda and w.is_cuda and out.is_cuda and a.is_contiguous() and w.is_contiguous() and out.is_contiguous()):
+        raise ValueError("a, w, out: contiguous GPU tensors")
+    if w.shape[1] != K or tuple(out.shape) != (M, N) or not (a.dtype == w.dtype == out.dtype) or a.dtype not in (torch.float16, torch.bfloat16):
+        raise ValueError("a [M, K], w [N, K], out [M, N], all fp16 or all bf16")
+    ws = torch.empty(workspace_bytes, dtype=torch.uint8, device="cuda")
+    ms = (ctypes.c_float * max_candidates)()
+    n = ctypes.c_int32()
+    st = _lt_lib.hkprobe_library_gemm_candidates(
+        ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(w.data_ptr()), ctypes.c_void_p(out.data_ptr()), M, N, K,
+        1 if a.dtype == torch.bfloat16 else 0, ctypes.c_void_p(ws.data_ptr()), workspace_bytes, max_candidates, iters, ms,
+        ctypes.byref(n), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != 0:
+        raise RuntimeError("hkprobe_library_gemm_candidates failed: %d" % st)
+    return [float(ms[i]) for i in range(n.value)]
