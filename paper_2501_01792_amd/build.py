@@ -56,8 +56,10 @@ def build(verbose: bool = False) -> str:
     tmp = PROBE_LT_LIB + ".tmp%d" % os.getpid()
     r = subprocess.run([HIPCC, *FLAGS, "-shared", PROBE_LT_SRC, "-o", tmp, "-lhipblaslt"], capture_output=True, text=True)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (PROBE_LT_SRC, r.stdout, r.stderr))
-    os.replace(tmp, PROBE_LT_LIB)
+        # only `measure gemm --candidates` needs it: a toolchain without the vendor GEMM library still builds the rest
+        print("build: %s not built (hipcc: %s)" % (PROBE_LT_LIB, (r.stderr.strip().splitlines() or ["?"])[-1]), file=sys.stderr)
+    else:
+        os.replace(tmp, PROBE_LT_LIB)
     return LIB
 
 
