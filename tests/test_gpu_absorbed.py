@@ -92,6 +92,22 @@ def test_absorbed_rows_with_large_mean(hk, oracle, prepared):
     _check("out", out, ref_out)
 
 
+@pytest.mark.parametrize("cfg", [_cfg("outliers_slab", 1024, 8, 2, 130, 0.0, 21), _cfg("outliers_block", 256, 4, 64, 1030, 0.0, 26)],
+                         ids=lambda c: c.name)
+def test_absorbed_rows_with_outlier_features(hk, oracle, cfg):
+    """A few feature channels that are 60 to 200 times the others in every row, the first channel among them (the
+    rows enter the score product minus their first element): both forms of the score kernel, and the regenerating
+    step beside them."""
+    batch = synth.make_batch(cfg)
+    act = batch["act"].astype(np.float32)
+    for c, mag in ((0, 200.0), (3, -60.0), (cfg.d - 7, 60.0)):
+        act[..., c] += mag
+    batch["act"] = act.astype(np.float16)
+    ref_out, _, _ = _oracle_hybrid(oracle, cfg, batch)
+    _check("absorbed", _run_absorbed(hk, cfg, batch), ref_out)
+    _check("regenerating", _run_hybrid(hk, cfg, batch)[0], ref_out)
+
+
 def test_absorbed_repeatable_and_workspace_reuse(hk, oracle):
     """Two different problems through one workspace, larger first: the second result must not depend on
     what the first left behind (the padded tail of the weight rows is rewritten every call)."""
