@@ -49,6 +49,7 @@ CASES = [
     synth.CONFIGS["opt13b"],                                         # B = 64, d = 5120
     synth.CONFIGS["opt30b"],                                         # B = 128, d = 7168
     synth.CONFIGS["opt66b"],                                         # B = 64, d = 9216: the reduction axis in 2 parts
+    synth.LayerConfig("rows96_d9216", 9216, 72, 96, 8, 0.5, 45),     # three row blocks at the widest layer
 ]
 
 
