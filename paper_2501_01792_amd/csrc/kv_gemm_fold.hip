@@ -69,6 +69,12 @@ struct Frags {
 
 __device__ __forceinline__ int next2(int s) { s += 2; return s >= kSlots ? s - kSlots : s; }
 
+// Column block of the q-th MFMA of a sub-step (row block q / 8): odd row blocks run backwards, so that every MFMA
+// shares one operand register set with the one before it, across row blocks too.  The sums are the same (every
+// accumulator block still takes its k pieces in order); the launch runs against the power limit and the order with
+// fewer operand changes is 0.5 % faster (63.38 -> 63.03 ms on the OPT-66B-shaped layer, three alternating runs).
+__device__ __forceinline__ constexpr int snake(int q) { return ((q >> 3) & 1) ? 7 - (q & 7) : (q & 7); }
+
 
 // acc[i][j][r] is MFMA block (i, j), register r: tile row wrow0 + 16 i + 4 (lane / 16) + r, output feature
 // nb + j with nb = n0 + wcol0 + TN * (lane % 16): a lane holds TN = 8 consecutive features of every row.
@@ -248,7 +254,8 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
             if (q == 0) __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): every fragment of f0, read long ago, in one wait
-            acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f0.a[q >> 3], f0.b[q & 7], FIRST ? zero : acc[q >> 3][q & 7]);
+            const int qi = q >> 3, qj = snake(q);
+            acc[qi][qj] = Elem<DT>::mfma_16x16x32(f0.a[qi], f0.b[qj], FIRST ? zero : acc[qi][qj]);
             if (q < 32 && (q & 1) == 0) read_frag(f1, sA, sB, 1, q >> 1);
             if ((q & 7) == 7) kWeightsFirst ? issue_b(early, q >> 3) : issue_a(early, q >> 3);
             __builtin_amdgcn_sched_barrier(0);
@@ -257,7 +264,8 @@ __global__ __launch_bounds__(FNT) void kv_gemm_fold_kernel(
 #pragma unroll
         for (int q = 0; q < 64; ++q) {
             if (q == 0) __builtin_amdgcn_s_waitcnt(0xC07F);    // lgkmcnt(0): likewise f1
-            acc[q >> 3][q & 7] = Elem<DT>::mfma_16x16x32(f1.a[q >> 3], f1.b[q & 7], acc[q >> 3][q & 7]);
+            const int qi = q >> 3, qj = snake(q);
+            acc[qi][qj] = Elem<DT>::mfma_16x16x32(f1.a[qi], f1.b[qj], acc[qi][qj]);
             if (q == 3) {
                 // Every LDS read of block g has come back (the wait at the top of this sub-step).  Wait for this
                 // wavefront's loads of block g+1 (the 8 early loads of block g+2 may fly), then meet the others: after
